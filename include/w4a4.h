@@ -1,0 +1,141 @@
+/*
+ * libw4a4 -- W4A4 quantized linear layer for AMD MI355X (gfx950), C ABI.
+ *
+ * The layer is the INT4-weight / INT4-activation linear of a BERT-style encoder
+ * (arxiv 2301.12017): activations are quantized per token at run time, weights
+ * per output channel or per K-group offline, two 4-bit codes travel per byte,
+ * the contraction is an integer GEMM with int32 accumulation, and dequantize,
+ * bias, GELU and the next layer's quantize are fused behind the GEMM.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or synchronizes; each call enqueues its kernels on
+ *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ *     returns.  Outputs are valid once the stream reaches that point.
+ *   - Return value only (w4a4_status); no exceptions, no errno.  Argument errors
+ *     are detected before anything is launched and leave the outputs untouched.
+ *   - Matrices are row-major.  Packed code matrices hold element 2j of a row in
+ *     bits 0..3 and element 2j+1 in bits 4..7 of byte j; signed codes are 4-bit
+ *     two's complement in [-8,7], unsigned codes are in [0,15].
+ *   - Base pointers must be 16-byte aligned, K and N multiples of 32 and 8
+ *     (row strides multiples of 16 bytes).  Anything else returns
+ *     W4A4_ERR_UNSUPPORTED_SHAPE.  M is arbitrary (M == 0 is a no-op).
+ *   - NaN / Inf inputs: results unspecified, never a fault.
+ *   - Calls are re-entrant; two calls that share a workspace must be ordered on
+ *     one stream.
+ */
+#ifndef W4A4_H
+#define W4A4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    W4A4_OK = 0,
+    W4A4_ERR_INVALID_ARG = -1,        /* null required pointer, negative size, mode mismatch ... */
+    W4A4_ERR_UNSUPPORTED_SHAPE = -2,  /* alignment / divisibility contract not met */
+    W4A4_ERR_WORKSPACE = -3,          /* workspace missing or smaller than w4a4_workspace_bytes() */
+    W4A4_ERR_HIP = -4                 /* a launch failed (hipGetLastError) */
+} w4a4_status;
+
+/* Sec. 3.1: the symmetric mapping (signed codes, scale only) or the asymmetric
+ * mapping (unsigned codes, scale and real-valued zero = the minimum). b = 4. */
+typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
+
+/* Sec. 4.2: GELU (erf form) may sit between the GEMM and the next quantize. */
+typedef enum { W4A4_ACT_NONE = 0, W4A4_ACT_GELU = 1 } w4a4_act_fn;
+
+/* A token-wise quantized activation matrix (App. A, activation quantization). */
+typedef struct {
+    const uint8_t *q;      /* [M, lda] bytes, first K/2 bytes of a row are codes          */
+    const float   *scale;  /* [M]   S of each token                                       */
+    const float   *zero;   /* [M]   x_zero of each token; NULL when mode == SYM           */
+    const int32_t *gsum;   /* [M, ng] sum of the codes of a token inside each weight
+                              K-group; required when mode == ASYM, else may be NULL      */
+    int M, K;
+    int lda;               /* row stride of q in BYTES (>= K/2, multiple of 16): lets a
+                              GEMM read a column slice of a wider packed matrix in place */
+    int group;             /* K-group length the gsum was taken over (0 = whole row)     */
+    int mode;              /* w4a4_mode */
+} w4a4_act;
+
+/* A weight matrix quantized offline (App. A, weight quantization), row n = output
+ * channel n, groups = contiguous runs of `group` elements along K. ng = K/group. */
+typedef struct {
+    const uint8_t *q;          /* [N, K/2]                                               */
+    const float   *scale;      /* [N, ng]                                                */
+    const float   *zero;       /* [N, ng]; NULL when mode == SYM                         */
+    const float   *rowsum_deq; /* [N] sum over k of the dequantized weight; ASYM only    */
+    int N, K;
+    int group;                 /* 0 = one group per output channel, else multiple of 128 */
+    int mode;                  /* w4a4_mode */
+} w4a4_weight;
+
+/* What happens between the int32 accumulators and memory (Sec. 4.2). */
+typedef struct {
+    const void *bias_f16;   /* [N] fp16, may be NULL                                      */
+    int act;                /* w4a4_act_fn                                                */
+    int requant;            /* 0: store fp16 [M,N].  1: quantize each fp32 output row per
+                               token and store packed codes [M,N/2] + scale (+ zero,gsum) */
+    int requant_mode;       /* w4a4_mode of the requantized output                        */
+    int requant_group;      /* K-group of the NEXT layer's weights, for out_gsum (0=row) */
+    int schedule;           /* 0 = pick the tile schedule from the built-in shape table
+                               (Sec. 4.2: schedules are pre-tuned per shape); > 0 forces
+                               schedule number `schedule` (see w4a4_schedule_count)       */
+} w4a4_epilogue;
+
+const char *w4a4_version(void);
+const char *w4a4_status_string(int status);
+
+/* Number of GEMM tile schedules compiled in, and a short name of schedule i (1-based). */
+int         w4a4_schedule_count(void);
+const char *w4a4_schedule_name(int schedule);
+
+/* Bytes of device workspace w4a4_linear / w4a4_dequant_epilogue need for this shape
+ * and epilogue (0 when none is needed). */
+size_t w4a4_workspace_bytes(int M, int N, int K, const w4a4_epilogue *ep);
+
+/* Step a0 (offline): App. A weight quantization of W_f16[N,K] with the Sec. 3.1 mapping.
+ * Outputs: q[N,K/2], scale[N,ng], zero[N,ng] (ASYM; may be NULL for SYM),
+ * gsum[N,ng] code sums (may be NULL), rowsum_deq[N] (may be NULL; needed for ASYM layers).
+ * group: 0 or a multiple of 32 that divides K. */
+int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
+                         uint8_t *q, float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
+                         void *stream);
+
+/* Step a1: token-wise dynamic quantization (App. A) of X_f16[M,K] (row stride ldx
+ * ELEMENTS) with the Sec. 3.1 mapping, packed two codes per byte (Sec. 4.2).
+ * Outputs: q[M,K/2] (dense rows), scale[M], zero[M] (ASYM only, else may be NULL),
+ * gsum[M, K/group] (may be NULL).  K <= 16384. */
+int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
+                      uint8_t *q, float *scale, float *zero, int32_t *gsum, void *stream);
+
+/* Steps a2+a3 fused: INT4 x INT4 -> INT32 GEMM (Sec. 4.1 shapes, activations [M,K],
+ * weights [N,K]) with the dequantize / zero-point terms / bias / GELU epilogue and
+ * either an fp16 store or a per-token requantize (Sec. 4.2) behind it.
+ *   out:       fp16 [M,N] (requant == 0) or u8 [M,N/2] (requant == 1)
+ *   out_scale: [M], out_zero: [M] (requant_mode ASYM), out_gsum: [M, N/requant_group]
+ *              (may be NULL); all ignored when requant == 0.
+ * A->mode must equal W->mode, A->K == W->K, and for ASYM A->group == W->group. */
+int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
+                void *out, float *out_scale, float *out_zero, int32_t *out_gsum,
+                void *workspace, size_t workspace_bytes, void *stream);
+
+/* Step a2 alone (parity / debugging export): acc[ng, M, N] int32, one plane per
+ * weight K-group (ng == 1 for per-channel weights). */
+int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream);
+
+/* Step a3 alone: the same epilogue applied to int32 accumulators acc[ng, M, N] that
+ * are already in memory.  Outputs as for w4a4_linear.  Needs no workspace. */
+int w4a4_dequant_epilogue(const int32_t *acc, const w4a4_act *A, const w4a4_weight *W,
+                          const w4a4_epilogue *ep, void *out, float *out_scale, float *out_zero,
+                          int32_t *out_gsum, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* W4A4_H */

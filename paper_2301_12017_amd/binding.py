@@ -1,0 +1,247 @@
+"""ctypes binding of libw4a4.so: argument marshalling only.
+
+Every step of the W4A4 linear layer runs in the HIP kernels behind the C ABI
+declared in include/w4a4.h; PyTorch appears here only as the owner of device
+memory and of the stream the kernels are enqueued on.  There is no CPU or
+PyTorch fallback: if the shared object is missing, loading fails.
+"""
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+SYM, ASYM = 0, 1
+ACT_NONE, ACT_GELU = 0, 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libw4a4.so")
+
+
+class W4A4Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+class _Act(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
+                ("gsum", ctypes.c_void_p), ("M", ctypes.c_int), ("K", ctypes.c_int),
+                ("lda", ctypes.c_int), ("group", ctypes.c_int), ("mode", ctypes.c_int)]
+
+
+class _Weight(ctypes.Structure):
+    _fields_ = [("q", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
+                ("rowsum_deq", ctypes.c_void_p), ("N", ctypes.c_int), ("K", ctypes.c_int),
+                ("group", ctypes.c_int), ("mode", ctypes.c_int)]
+
+
+class _Epilogue(ctypes.Structure):
+    _fields_ = [("bias_f16", ctypes.c_void_p), ("act", ctypes.c_int), ("requant", ctypes.c_int),
+                ("requant_mode", ctypes.c_int), ("requant_group", ctypes.c_int),
+                ("schedule", ctypes.c_int)]
+
+
+_lib = None
+
+_vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+_SIGNATURES = {
+    "w4a4_version": (ctypes.c_char_p, []),
+    "w4a4_status_string": (ctypes.c_char_p, [_i]),
+    "w4a4_schedule_count": (_i, []),
+    "w4a4_schedule_name": (ctypes.c_char_p, [_i]),
+    "w4a4_workspace_bytes": (_sz, [_i, _i, _i, ctypes.POINTER(_Epilogue)]),
+    "w4a4_quantize_weight": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
+                         _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
+    "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
+                                   ctypes.POINTER(_Epilogue), _vp, _vp, _vp, _vp, _vp]),
+}
+EXPORTS = tuple(_SIGNATURES)
+
+
+def lib():
+    """Load libw4a4.so (built by paper_2301_12017_amd/build.py).  Fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2301_12017_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().w4a4_version().decode()
+
+
+def status_string(status: int) -> str:
+    return lib().w4a4_status_string(int(status)).decode()
+
+
+def schedule_names():
+    L = lib()
+    return [L.w4a4_schedule_name(i + 1).decode() for i in range(L.w4a4_schedule_count())]
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise W4A4Error(rc, where)
+
+
+@dataclass
+class QAct:
+    """Token-wise quantized activations on the device (see w4a4_act in include/w4a4.h)."""
+    q: torch.Tensor
+    scale: torch.Tensor
+    zero: Optional[torch.Tensor]
+    gsum: Optional[torch.Tensor]
+    M: int
+    K: int
+    lda: int
+    group: int
+    mode: int
+    q_offset_bytes: int = 0     # column-slice view: start this many bytes into each row
+
+    def c(self) -> _Act:
+        return _Act(self.q.data_ptr() + self.q_offset_bytes, self.scale.data_ptr(),
+                    None if self.zero is None else self.zero.data_ptr(),
+                    None if self.gsum is None else self.gsum.data_ptr(),
+                    self.M, self.K, self.lda, self.group, self.mode)
+
+
+@dataclass
+class QWeight:
+    """Offline-quantized weights on the device (see w4a4_weight in include/w4a4.h)."""
+    q: torch.Tensor
+    scale: torch.Tensor
+    zero: Optional[torch.Tensor]
+    gsum: Optional[torch.Tensor]
+    rowsum_deq: Optional[torch.Tensor]
+    N: int
+    K: int
+    group: int
+    mode: int
+
+    def c(self) -> _Weight:
+        return _Weight(self.q.data_ptr(), self.scale.data_ptr(),
+                       None if self.zero is None else self.zero.data_ptr(),
+                       None if self.rowsum_deq is None else self.rowsum_deq.data_ptr(),
+                       self.N, self.K, self.group, self.mode)
+
+
+def _ng(K, group):
+    return 1 if group == 0 else K // group
+
+
+def quantize_weight(W: torch.Tensor, mode=SYM, group=0) -> QWeight:
+    assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
+    N, K = W.shape
+    ng = _ng(K, group)
+    dev = W.device
+    q = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    scale = torch.empty((N, ng), dtype=torch.float32, device=dev)
+    zero = torch.empty((N, ng), dtype=torch.float32, device=dev) if mode == ASYM else None
+    gsum = torch.empty((N, ng), dtype=torch.int32, device=dev)
+    c = torch.empty((N,), dtype=torch.float32, device=dev)
+    rc = lib().w4a4_quantize_weight(_ptr(W), N, K, mode, group, _ptr(q), _ptr(scale), _ptr(zero),
+                                    _ptr(gsum), _ptr(c), _stream())
+    _check(rc, "w4a4_quantize_weight")
+    return QWeight(q, scale, zero, gsum, c, N, K, group, mode)
+
+
+def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None) -> QAct:
+    assert X.is_cuda and X.dtype == torch.float16 and X.stride(1) == 1
+    M, K = X.shape
+    ng = _ng(K, group)
+    dev = X.device
+    if out is None:
+        out = QAct(torch.empty((M, K // 2), dtype=torch.uint8, device=dev),
+                   torch.empty((M,), dtype=torch.float32, device=dev),
+                   torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
+                   torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
+                   M, K, K // 2, group, mode)
+    rc = lib().w4a4_quantize_act(_ptr(X), M, K, X.stride(0), mode, group, _ptr(out.q), _ptr(out.scale),
+                                 _ptr(out.zero), _ptr(out.gsum), _stream())
+    _check(rc, "w4a4_quantize_act")
+    return out
+
+
+def workspace_bytes(M, N, K, requant=False) -> int:
+    ep = _Epilogue(None, 0, int(requant), 0, 0, 0)
+    return int(lib().w4a4_workspace_bytes(M, N, K, ctypes.byref(ep)))
+
+
+def _epilogue(bias, act, requant, requant_mode, requant_group, schedule):
+    return _Epilogue(None if bias is None else bias.data_ptr(), act, int(bool(requant)), requant_mode,
+                     requant_group, schedule)
+
+
+def _alloc_out(A: QAct, W: QWeight, requant, requant_mode, requant_group):
+    dev = A.q.device
+    if not requant:
+        return torch.empty((A.M, W.N), dtype=torch.float16, device=dev), None, None, None
+    rng = _ng(W.N, requant_group)
+    return (torch.empty((A.M, W.N // 2), dtype=torch.uint8, device=dev),
+            torch.empty((A.M,), dtype=torch.float32, device=dev),
+            torch.empty((A.M,), dtype=torch.float32, device=dev) if requant_mode == ASYM else None,
+            torch.empty((A.M, rng), dtype=torch.int32, device=dev) if requant_mode == ASYM else None)
+
+
+def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NONE, requant=False,
+           requant_mode=SYM, requant_group=0, schedule=0, out=None, workspace: Optional[torch.Tensor] = None):
+    """w4a4_linear.  Returns an fp16 tensor [M,N], or a QAct holding the requantized output."""
+    ep = _epilogue(bias, act, requant, requant_mode, requant_group, schedule)
+    if out is None:
+        out = _alloc_out(A, W, requant, requant_mode, requant_group)
+    o, os_, oz, og = out
+    need = int(lib().w4a4_workspace_bytes(A.M, W.N, A.K, ctypes.byref(ep)))
+    if need and workspace is None:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=A.q.device)
+    a, w = A.c(), W.c()
+    rc = lib().w4a4_linear(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), _ptr(o), _ptr(os_), _ptr(oz),
+                           _ptr(og), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
+    _check(rc, "w4a4_linear")
+    if not requant:
+        return o
+    return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)
+
+
+def gemm_i32(A: QAct, W: QWeight, schedule=0) -> torch.Tensor:
+    """w4a4_gemm_i32: int32 accumulators [ng, M, N]."""
+    ng = _ng(W.K, W.group)
+    acc = torch.empty((ng, A.M, W.N), dtype=torch.int32, device=A.q.device)
+    a, w = A.c(), W.c()
+    rc = lib().w4a4_gemm_i32(ctypes.byref(a), ctypes.byref(w), _ptr(acc), schedule, _stream())
+    _check(rc, "w4a4_gemm_i32")
+    return acc
+
+
+def dequant_epilogue(acc: torch.Tensor, A: QAct, W: QWeight, bias=None, act=ACT_NONE, requant=False,
+                     requant_mode=SYM, requant_group=0):
+    """w4a4_dequant_epilogue on accumulators from gemm_i32."""
+    ep = _epilogue(bias, act, requant, requant_mode, requant_group, 0)
+    o, os_, oz, og = _alloc_out(A, W, requant, requant_mode, requant_group)
+    a, w = A.c(), W.c()
+    rc = lib().w4a4_dequant_epilogue(_ptr(acc), ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), _ptr(o),
+                                     _ptr(os_), _ptr(oz), _ptr(og), _stream())
+    _check(rc, "w4a4_dequant_epilogue")
+    if not requant:
+        return o
+    return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)

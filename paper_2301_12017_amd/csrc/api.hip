@@ -1,0 +1,15 @@
+// Version and status strings of libw4a4.
+#include "common.hpp"
+
+extern "C" const char *w4a4_version(void) { return "w4a4 0.1 (gfx950)"; }
+
+extern "C" const char *w4a4_status_string(int status) {
+    switch (status) {
+        case W4A4_OK: return "ok";
+        case W4A4_ERR_INVALID_ARG: return "invalid argument";
+        case W4A4_ERR_UNSUPPORTED_SHAPE: return "unsupported shape or alignment";
+        case W4A4_ERR_WORKSPACE: return "workspace missing or too small";
+        case W4A4_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,77 @@
+// Shared device helpers of libw4a4 (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "../../include/w4a4.h"
+
+namespace w4a4 {
+
+constexpr int kWave = 64;
+
+// ---- wavefront reductions (64 lanes) -------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+// ---- the Sec. 3.1 mappings, b = 4 ----------------------------------------------------
+// A vector's range is summarised as (lo, inv, S): code = rne(clamp((x - lo) * inv)).
+// The reciprocal is one correctly rounded fp32 divide per vector; the per-element
+// multiply and the round-to-nearest-even are separate fp32 operations (the library is
+// compiled without FMA contraction), so codes are reproducible bit for bit.
+struct Range {
+    float lo;    // 0 for the symmetric mapping, min(x) for the asymmetric one
+    float inv;   // 7/absmax or 15/(max-min); 0 for a constant vector
+    float S;     // absmax/7 or (max-min)/15; 1 for a constant vector
+};
+
+__device__ __forceinline__ Range range_sym(float amax) {
+    Range r;
+    r.lo = 0.0f;
+    if (amax == 0.0f) { r.inv = 0.0f; r.S = 1.0f; }
+    else { r.inv = 7.0f / amax; r.S = amax / 7.0f; }
+    return r;
+}
+__device__ __forceinline__ Range range_asym(float lo, float hi) {
+    Range r;
+    r.lo = lo;
+    if (hi == lo) { r.inv = 0.0f; r.S = 1.0f; }
+    else { float d = hi - lo; r.inv = 15.0f / d; r.S = d / 15.0f; }
+    return r;
+}
+template <int MODE>
+__device__ __forceinline__ int code_of(float x, const Range &r) {
+    if (MODE == W4A4_SYM) {
+        float t = x * r.inv;
+        t = fminf(fmaxf(t, -8.0f), 7.0f);
+        return (int)rintf(t);
+    } else {
+        float d = x - r.lo;
+        float t = d * r.inv;
+        t = fminf(fmaxf(t, 0.0f), 15.0f);
+        return (int)rintf(t);
+    }
+}
+
+// erf-form GELU (Sec. 4.2 names GELU; BERT's is the erf form).
+__device__ __forceinline__ float gelu_erf(float y) {
+    return 0.5f * y * (1.0f + erff(y * 0.70710678118654752440f));
+}
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline int launch_status() {
+    return hipGetLastError() == hipSuccess ? W4A4_OK : W4A4_ERR_HIP;
+}
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace w4a4

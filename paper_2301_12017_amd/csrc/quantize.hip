@@ -1,0 +1,217 @@
+// Row-wise INT4 quantization kernels: token-wise activations (step a1), offline weights
+// (step a0) and the requantize of fp32 rows used behind the GEMM.
+//
+// One wavefront owns one row.  The row is read once with 16-byte loads, kept in
+// registers, reduced with wave shuffles (absmax, or min and max), mapped to codes with
+// the Sec. 3.1 formulas and written as one dword (eight codes) per lane per step, so
+// both the read and the write are fully coalesced.  HBM traffic is the algorithmic
+// minimum: 2 bytes in and half a byte out per element.
+#include "common.hpp"
+
+namespace w4a4 {
+
+constexpr int kRowsPerBlock = 4;      // four waves, one row each
+constexpr int kMaxGroups = 512;       // code-sum slots per row held in LDS
+
+template <typename T> struct Load8;
+template <> struct Load8<__half> {
+    // eight consecutive fp16 -> fp32
+    static __device__ __forceinline__ void load(const __half *p, float (&v)[8]) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(p);
+        const __half2 *h = reinterpret_cast<const __half2 *>(&raw);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float2 f = __half22float2(h[i]);
+            v[2 * i] = f.x;
+            v[2 * i + 1] = f.y;
+        }
+    }
+};
+template <> struct Load8<float> {
+    static __device__ __forceinline__ void load(const float *p, float (&v)[8]) {
+        float4 a = *reinterpret_cast<const float4 *>(p);
+        float4 b = *reinterpret_cast<const float4 *>(p + 4);
+        v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+        v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+    }
+};
+
+// X: [rows, ldx] elements, first K used.  q: [rows, K/2] bytes.  s,z: [rows].
+// gsum: [rows, ng] code sums over runs of G elements (NULL = not wanted).
+// ITERS = ceil(K / 512): every lane holds ITERS chunks of eight elements.
+template <int MODE, typename T, int ITERS>
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
+    const T *__restrict__ X, long ldx, int rows, int K, int G, uint8_t *__restrict__ q,
+    float *__restrict__ s, float *__restrict__ z, int32_t *__restrict__ gsum, int ng) {
+    __shared__ int32_t gs[kRowsPerBlock][kMaxGroups];
+    const int wave = threadIdx.x / kWave;
+    const int lane = threadIdx.x % kWave;
+    const long row = (long)blockIdx.x * kRowsPerBlock + wave;
+    if (row >= rows) return;                       // whole wave leaves; no block barrier below
+    const int nchunks = K / 8;
+    const T *xr = X + row * ldx;
+
+    float v[ITERS][8];
+    float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int c = lane + it * kWave;
+        if (c < nchunks) {
+            Load8<T>::load(xr + (long)c * 8, v[it]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                if (MODE == W4A4_SYM) hi = fmaxf(hi, fabsf(v[it][e]));
+                else { hi = fmaxf(hi, v[it][e]); lo = fminf(lo, v[it][e]); }
+            }
+        }
+    }
+    Range r;
+    if (MODE == W4A4_SYM) {
+        r = range_sym(wave_max(hi));
+    } else {
+        r = range_asym(wave_min(lo), wave_max(hi));
+    }
+    if (lane == 0) {
+        s[row] = r.S;
+        if (MODE == W4A4_ASYM) z[row] = r.lo;
+    }
+    if (gsum) {
+        for (int g = lane; g < ng; g += kWave) gs[wave][g] = 0;
+        // lanes of one wave run in lockstep and LDS operations of a wave complete in
+        // order, so the zeroes land before the adds below.
+        __builtin_amdgcn_wave_barrier();
+    }
+    const int cpg = G / 8;                         // chunks per code-sum group
+    uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int c = lane + it * kWave;
+        if (c < nchunks) {
+            uint32_t packed = 0;
+            int sum = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int code = code_of<MODE>(v[it][e], r);
+                sum += code;
+                packed |= (uint32_t)(code & 0xF) << (4 * e);
+            }
+            qr[c] = packed;
+            if (gsum) atomicAdd(&gs[wave][c / cpg], sum);
+        }
+    }
+    if (gsum) {
+        __builtin_amdgcn_wave_barrier();
+        for (int g = lane; g < ng; g += kWave) gsum[row * (long)ng + g] = gs[wave][g];
+    }
+}
+
+// c[n] = sum over k of the dequantized weight, group by group in fp32:
+// c = c + (S*RW + G*zero), each operation separately rounded.
+__global__ void weight_rowsum_kernel(const float *__restrict__ scale, const float *__restrict__ zero,
+                                     const int32_t *__restrict__ gsum, int N, int ng, int G,
+                                     float *__restrict__ c) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    float acc = 0.0f;
+    for (int g = 0; g < ng; ++g) {
+        float S = scale[(long)n * ng + g];
+        float Z = zero ? zero[(long)n * ng + g] : 0.0f;
+        float t = S * (float)gsum[(long)n * ng + g];
+        float u = (float)G * Z;
+        float w = t + u;
+        acc = acc + w;
+    }
+    c[n] = acc;
+}
+
+template <int MODE, typename T>
+static int launch_rows(const T *X, long ldx, int rows, int K, int G, uint8_t *q, float *s, float *z,
+                       int32_t *gsum, int ng, hipStream_t st) {
+    if (rows == 0) return W4A4_OK;
+    const int iters = (K / 8 + kWave - 1) / kWave;
+    dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock), block(kRowsPerBlock * kWave);
+#define W4A4_QL(I)                                                                                  \
+    hipLaunchKernelGGL((quantize_rows_kernel<MODE, T, I>), grid, block, 0, st, X, ldx, rows, K, G, q, \
+                       s, z, gsum, ng)
+    if (iters <= 1) W4A4_QL(1);
+    else if (iters <= 2) W4A4_QL(2);
+    else if (iters <= 4) W4A4_QL(4);
+    else if (iters <= 8) W4A4_QL(8);
+    else if (iters <= 16) W4A4_QL(16);
+    else if (iters <= 32) W4A4_QL(32);
+    else return W4A4_ERR_UNSUPPORTED_SHAPE;
+#undef W4A4_QL
+    return launch_status();
+}
+
+// Shared argument checks for a row quantizer.  elem_bytes: 2 (fp16) or 4 (fp32).
+static int check_rows(const void *X, int rows, int K, long ldx, int mode, int group, const void *q,
+                      const void *s, const void *z, int elem_bytes, int *ng_out) {
+    if (rows < 0 || K <= 0 || ldx < K) return W4A4_ERR_INVALID_ARG;
+    if (mode != W4A4_SYM && mode != W4A4_ASYM) return W4A4_ERR_INVALID_ARG;
+    if (group < 0) return W4A4_ERR_INVALID_ARG;
+    if (rows > 0 && (!X || !q || !s || (mode == W4A4_ASYM && !z))) return W4A4_ERR_INVALID_ARG;
+    if (K % 32 || (ldx * elem_bytes) % 16 || !aligned16(X) || !aligned16(q)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (K > 16384) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    const int G = group == 0 ? K : group;
+    if (G % 32 || K % G) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (K / G > kMaxGroups) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    *ng_out = K / G;
+    return W4A4_OK;
+}
+
+// Requantize of fp32 rows (used behind the GEMM); same mapping as quantize_act.
+int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int group, uint8_t *q,
+                      float *s, float *z, int32_t *gsum, hipStream_t st) {
+    int ng = 0;
+    int rc = check_rows(Y, rows, K, ld, mode, group, q, s, z, 4, &ng);
+    if (rc) return rc;
+    const int G = group == 0 ? K : group;
+    return mode == W4A4_SYM ? launch_rows<W4A4_SYM, float>(Y, ld, rows, K, G, q, s, z, gsum, ng, st)
+                            : launch_rows<W4A4_ASYM, float>(Y, ld, rows, K, G, q, s, z, gsum, ng, st);
+}
+
+}  // namespace w4a4
+
+using namespace w4a4;
+
+extern "C" int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
+                                 uint8_t *q, float *scale, float *zero, int32_t *gsum, void *stream) {
+    int ng = 0;
+    int rc = check_rows(X_f16, M, K, ldx, mode, group, q, scale, zero, 2, &ng);
+    if (rc) return rc;
+    const int G = group == 0 ? K : group;
+    const __half *X = static_cast<const __half *>(X_f16);
+    return mode == W4A4_SYM
+               ? launch_rows<W4A4_SYM, __half>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream))
+               : launch_rows<W4A4_ASYM, __half>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream));
+}
+
+extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group, uint8_t *q,
+                                    float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
+                                    void *stream) {
+    // A weight matrix [N,K] with groups of G along K is the row matrix [N*ng, G]:
+    // every (channel, group) pair is one independent vector (App. A).
+    if (N < 0 || K <= 0 || group < 0) return W4A4_ERR_INVALID_ARG;
+    const int G = group == 0 ? K : group;
+    if (K % 32 || G % 32 || K % G) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    const int ng = K / G;
+    if (rowsum_deq && N > 0 && !gsum) return W4A4_ERR_INVALID_ARG;   // c[n] is built from the code sums
+    long rows = (long)N * ng;
+    if (rows > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    int one = 0;
+    int rc = check_rows(W_f16, (int)rows, G, G, mode, 0, q, scale, zero, 2, &one);
+    if (rc) return rc;
+    hipStream_t st = as_stream(stream);
+    const __half *W = static_cast<const __half *>(W_f16);
+    rc = mode == W4A4_SYM
+             ? launch_rows<W4A4_SYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st)
+             : launch_rows<W4A4_ASYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st);
+    if (rc) return rc;
+    if (rowsum_deq && N > 0) {
+        hipLaunchKernelGGL(weight_rowsum_kernel, dim3((N + 255) / 256), dim3(256), 0, st, scale,
+                           mode == W4A4_ASYM ? zero : nullptr, gsum, N, ng, G, rowsum_deq);
+        rc = launch_status();
+    }
+    return rc;
+}

@@ -1,0 +1,89 @@
+"""Device-side harness for the synthetic workloads: uploads the seeded tensors, quantizes
+the weights once (offline step) and strings the library calls together the way an encoder
+layer would (Sec. 4.1 shapes, Sec. 4.2 fusion).  All arithmetic happens in libw4a4.so; this
+module only owns tensors and call order.  Used by the tests, the smoke check and bench.py.
+"""
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import synth
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@dataclass
+class Layer:
+    spec: synth.LinearSpec
+    W: B.QWeight
+    bias: torch.Tensor
+    act: int
+    host_W: Optional[np.ndarray] = None
+    host_b: Optional[np.ndarray] = None
+
+
+def make_layer(spec: synth.LinearSpec, cfg: int, index: int, seed: int = 0, keep_host: bool = True) -> Layer:
+    w = synth.weights(spec.N, spec.K, seed, cfg, 10 * index + 1)
+    b = synth.bias(spec.N, seed, cfg, 10 * index + 2)
+    Wq = B.quantize_weight(dev(w), spec.mode, spec.group)
+    return Layer(spec, Wq, dev(b), B.ACT_GELU if spec.gelu else B.ACT_NONE,
+                 w if keep_host else None, b if keep_host else None)
+
+
+def make_input(spec: synth.LinearSpec, cfg: int, index: int, seed: int = 0, M: Optional[int] = None) -> np.ndarray:
+    return synth.activations(spec.M if M is None else M, spec.K, seed, cfg, 10 * index,
+                             outlier_channels=8 if cfg == 4 else 0)
+
+
+def run_linear(X: torch.Tensor, layer: Layer, schedule: int = 0, qact: Optional[B.QAct] = None,
+               out=None) -> torch.Tensor:
+    """quantize_act followed by the fused linear with an fp16 store."""
+    A = B.quantize_act(X, layer.spec.mode, layer.spec.group, out=qact)
+    return B.linear(A, layer.W, layer.bias, layer.act, schedule=schedule, out=out)
+
+
+# ------------------------------------------------------------------ the chained stack
+@dataclass
+class ChainLayer:
+    qkv: Layer
+    out: Layer
+    ffn1: Layer
+    ffn2: Layer
+
+
+def make_chain(n_layers: int, h: int = 1024, ffn: int = 4096, M: int = 32768, cfg: int = 5, seed: int = 0,
+               keep_host: bool = True) -> List[ChainLayer]:
+    layers = []
+    for l in range(n_layers):
+        specs = [synth.LinearSpec("qkv", M, 3 * h, h), synth.LinearSpec("attn_out", M, h, h),
+                 synth.LinearSpec("ffn1", M, ffn, h, True), synth.LinearSpec("ffn2", M, h, ffn)]
+        layers.append(ChainLayer(*[make_layer(s, cfg, 4 * l + j, seed, keep_host) for j, s in enumerate(specs)]))
+    return layers
+
+
+def v_slice(qkv: B.QAct, h: int) -> B.QAct:
+    """The V third of a requantized QKV output, read in place: columns [2h, 3h) of every
+    packed row, i.e. byte offset h, row stride 3h/2, with the QKV output's per-token scale."""
+    return B.QAct(qkv.q, qkv.scale, qkv.zero, None, qkv.M, h, qkv.lda, 0, qkv.mode, q_offset_bytes=h)
+
+
+def run_chain(A: B.QAct, layers: List[ChainLayer], workspace: Optional[torch.Tensor] = None, record=None,
+              schedule: int = 0) -> B.QAct:
+    """quantize -> GEMM -> dequant+bias(+GELU) -> requantize, four GEMMs per layer, without
+    an fp16 activation tensor in between.  `record` (a list) receives (name, input, output)."""
+    h = layers[0].out.spec.K
+    for li, L in enumerate(layers):
+        steps = (("qkv", L.qkv, None), ("attn_out", L.out, h), ("ffn1", L.ffn1, None), ("ffn2", L.ffn2, None))
+        for name, lay, slice_h in steps:
+            a_in = v_slice(A, slice_h) if slice_h else A
+            out = B.linear(a_in, lay.W, lay.bias, lay.act, requant=True, requant_mode=B.SYM, schedule=schedule,
+                           workspace=workspace)
+            if record is not None:
+                record.append((li, name, a_in, out, lay))
+            A = out
+    return A

@@ -1,0 +1,106 @@
+"""CPU-side checks of the C-ABI library: it loads without a GPU, exports every symbol the
+header declares, and rejects bad arguments before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def b():
+    from paper_2301_12017_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2301_12017_amd import build
+        build.build(verbose=False)
+    return binding
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "w4a4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(w4a4_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(b):
+    names = _declared_symbols()
+    assert {"w4a4_quantize_act", "w4a4_linear", "w4a4_dequant_epilogue", "w4a4_quantize_weight",
+            "w4a4_gemm_i32", "w4a4_workspace_bytes"} <= set(names)
+    L = ctypes.CDLL(b.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(b.EXPORTS)
+
+
+def test_version_and_status_strings(b):
+    assert "gfx950" in b.version()
+    assert b.status_string(0) == "ok"
+    for s in (-1, -2, -3, -4):
+        assert b.status_string(s) not in ("ok", "unknown status")
+    assert len(b.schedule_names()) == b.lib().w4a4_schedule_count() >= 1
+
+
+def _act(b, M=4, K=64, lda=None, mode=0, group=0, ptr=0x1000):
+    return b._Act(ptr, ptr, ptr, ptr, M, K, K // 2 if lda is None else lda, group, mode)
+
+
+def _wt(b, N=8, K=64, mode=0, group=0, ptr=0x1000):
+    return b._Weight(ptr, ptr, ptr, ptr, N, K, group, mode)
+
+
+def test_argument_errors_are_reported_before_any_launch(b):
+    """Pointers here are fake (never dereferenced): every call must fail in validation."""
+    L = b.lib()
+    ep = b._Epilogue(None, 0, 0, 0, 0, 0)
+    out = ctypes.c_void_p(0x2000)
+
+    def lin(a, w, e=ep, o=out, ws=None, wsb=0, os_=None):
+        return L.w4a4_linear(ctypes.byref(a), ctypes.byref(w), ctypes.byref(e), o, os_, None, None, ws, wsb, None)
+
+    assert lin(_act(b, K=64), _wt(b, K=128)) == -1                    # K mismatch
+    assert lin(_act(b, mode=0), _wt(b, mode=1)) == -1                 # mode mismatch
+    assert lin(_act(b, K=48), _wt(b, K=48)) == -2                     # K % 32
+    assert lin(_act(b), _wt(b, N=12)) == -2                           # N % 8
+    assert lin(_act(b, lda=16), _wt(b)) == -1                         # lda < K/2
+    assert lin(_act(b, lda=40), _wt(b)) == -2                         # lda % 16
+    assert lin(_act(b, K=256), _wt(b, K=256, group=64)) == -2         # GEMM groups are multiples of 128
+    assert lin(_act(b, K=256), _wt(b, K=256, group=96)) == -2         # group must divide K
+    assert lin(_act(b, ptr=None), _wt(b)) == -1                       # null operand
+    assert lin(_act(b), _wt(b), o=None) == -1                         # null output
+    assert lin(_act(b, ptr=0x1004), _wt(b)) == -2                     # misaligned
+    bad_act = b._Epilogue(None, 7, 0, 0, 0, 0)
+    assert lin(_act(b), _wt(b), e=bad_act) == -1
+    rq = b._Epilogue(None, 0, 1, 0, 0, 0)
+    assert lin(_act(b), _wt(b, N=32), e=rq, os_=None) == -1           # requant needs out_scale
+    assert lin(_act(b), _wt(b, N=32), e=rq, os_=out) == -3            # and a workspace
+    assert lin(_act(b), _wt(b, N=8), e=rq, os_=out) == -2             # requant N % 32
+    # asymmetric operands need zero points, code sums and the weight row sums
+    a = _act(b, K=128, mode=1, group=128); a.gsum = None
+    assert lin(a, _wt(b, K=128, mode=1, group=128)) == -1
+    assert lin(_act(b, K=256, mode=1, group=0), _wt(b, K=256, mode=1, group=128)) == -1   # group mismatch
+    # M == 0 is a successful no-op
+    assert lin(_act(b, M=0), _wt(b)) == 0
+    assert L.w4a4_gemm_i32(ctypes.byref(_act(b)), ctypes.byref(_wt(b)), None, 0, None) == -1
+    assert L.w4a4_gemm_i32(ctypes.byref(_act(b)), ctypes.byref(_wt(b)), out, 99, None) == -1
+
+
+def test_quantize_argument_errors(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    assert L.w4a4_quantize_act(None, 4, 64, 64, 0, 0, p, p, None, None, None) == -1
+    assert L.w4a4_quantize_act(p, 4, 48, 48, 0, 0, p, p, None, None, None) == -2
+    assert L.w4a4_quantize_act(p, 4, 64, 32, 0, 0, p, p, None, None, None) == -1      # ldx < K
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 1, 0, p, p, None, None, None) == -1      # ASYM needs zero
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 24, p, p, None, None, None) == -2     # group % 32
+    assert L.w4a4_quantize_act(p, 4, 32768, 32768, 0, 0, p, p, None, None, None) == -2
+    assert L.w4a4_quantize_act(p, 0, 64, 64, 0, 0, p, p, None, None, None) == 0
+    assert L.w4a4_quantize_weight(p, 4, 64, 0, 48, p, p, None, None, None, None) == -2
+    assert L.w4a4_quantize_weight(p, 4, 64, 0, 0, p, p, None, None, p, None) == -1    # rowsum needs gsum
+    assert L.w4a4_quantize_weight(p, 0, 64, 0, 0, p, p, None, None, None, None) == 0
+
+
+def test_workspace_bytes(b):
+    assert b.workspace_bytes(128, 768, 768, requant=False) == 0
+    assert b.workspace_bytes(128, 768, 768, requant=True) == 128 * 768 * 4
