@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A4 linear hot path on one MI355X.
+
+A step is one pass of the whole path -- token-wise quantize_act, then the fused
+INT4 GEMM + dequantize/bias(/GELU) epilogue with an fp16 store -- over the four
+encoder linears of BERT-large at batch 32 x seq 384 (M = 12288; Sec. 4.1 shapes),
+with fp16 activations, quantized weights and biases already resident in HBM.
+`value` is 2*M*N*K summed over the four GEMMs divided by the step time (so the
+quantize kernels count against it).  The line also carries the latency of the
+BERT-base layer linears at batch 1 x seq 128, the roofline position of the GEMM
+kernel (HIP events around every w4a4_linear launch inside the timed region) and the
+CPU oracle timed on a sample of token rows of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix peak, 5.0 POP/s
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--warmup", type=int, default=10)
+    p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped)")
+    p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--cpu-rows", type=int, default=96, help="token rows per GEMM the oracle is timed on")
+    return p.parse_args()
+
+
+def cpu_baseline(specs, cfg, rows):
+    """The oracle as it stands (single thread, plain C) on `rows` token rows of every GEMM."""
+    import numpy as np
+    import oracle
+    from paper_2301_12017_amd import synth
+    ops = 0
+    prepared = []
+    for i, s in enumerate(specs):
+        X = synth.activations(rows, s.K, 0, cfg, 10 * i, outlier_channels=8 if cfg == 4 else 0)
+        W = synth.weights(s.N, s.K, 0, cfg, 10 * i + 1)
+        b = synth.bias(s.N, 0, cfg, 10 * i + 2)
+        Q = oracle.quantize_weight(W, s.mode, s.group)            # offline step, not timed
+        prepared.append((s, X, Q, b))
+        ops += 2 * rows * s.N * s.K
+    t0 = time.perf_counter()
+    for s, X, Q, b in prepared:
+        A = oracle.quantize_act(X, s.mode, s.group)
+        oracle.linear(A, Q, s.mode, s.group, b, oracle.ACT_GELU if s.gelu else oracle.ACT_NONE)
+    dt = time.perf_counter() - t0
+    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": 1, "kind": "oracle",
+            "sample": f"{rows} of {specs[0].M} token rows of each of the {len(specs)} GEMMs "
+                      f"(all N, all K), {dt:.1f} s; rows are independent, so the whole workload "
+                      f"would take about {dt * specs[0].M / rows:.0f} s",
+            "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the path is token-parallel with no "
+              "exchange; see DESIGN.md); --gpus N with N > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2301_12017_amd import binding as B, synth, workloads as WL
+    B.lib()
+    torch.cuda.set_device(0)
+    cfg = args.config
+    specs = synth.config_linears(cfg)
+    layers = [WL.make_layer(s, cfg, i, keep_host=False) for i, s in enumerate(specs)]
+    Xs = [WL.dev(WL.make_input(s, cfg, i)) for i, s in enumerate(specs)]
+    # everything the step touches is allocated once, outside the timed region
+    qacts = [B.quantize_act(X, s.mode, s.group) for X, s in zip(Xs, specs)]
+    outs = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(qacts, layers)]
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in specs]
+          for _ in range(args.steps)]
+
+    def step(events=None):
+        for i, (X, L, qa, o) in enumerate(zip(Xs, layers, qacts, outs)):
+            B.quantize_act(X, L.spec.mode, L.spec.group, out=qa)
+            if events:
+                events[i][0].record()
+            B.linear(qa, L.W, L.bias, L.act, schedule=args.schedule, out=o)
+            if events:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    ops = sum(2 * s.M * s.N * s.K for s in specs)
+    tops = ops / (ms_per_step * 1e-3) / 1e12
+
+    gemm_ms = [sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps
+               for i in range(len(specs))]
+    gemm_tops = [2 * s.M * s.N * s.K / (t * 1e-3) / 1e12 for s, t in zip(specs, gemm_ms)]
+    achieved = ops / (sum(gemm_ms) * 1e-3) / 1e12
+
+    # ---- latency leg: BERT-base layer linears at batch 1 x seq 128 (launch/latency-bound)
+    lat = {}
+    if cfg == 3:
+        s2 = synth.config_linears(2)
+        l2 = [WL.make_layer(s, 2, i, keep_host=False) for i, s in enumerate(s2)]
+        x2 = [WL.dev(WL.make_input(s, 2, i)) for i, s in enumerate(s2)]
+        q2 = [B.quantize_act(X, s.mode, s.group) for X, s in zip(x2, s2)]
+        o2 = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(q2, l2)]
+
+        def layer2():
+            for X, L, qa, o in zip(x2, l2, q2, o2):
+                B.quantize_act(X, L.spec.mode, L.spec.group, out=qa)
+                B.linear(qa, L.W, L.bias, L.act, out=o)
+        for _ in range(20):
+            layer2()
+        torch.cuda.synchronize()
+        reps = 200
+        t1 = time.perf_counter()
+        for _ in range(reps):
+            layer2()
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t1) * 1e6 / reps
+        bytes2 = sum(s.M * s.K * 2 + s.M * s.K // 2 * 2 + s.N * s.K // 2 + s.M * s.N * 2 for s in s2)
+        lat = {"bert_base_layer_b1_s128_us": us, "algorithmic_bytes": bytes2,
+               "achieved_GBps_warm": bytes2 / (us * 1e-6) / 1e9,
+               "note": "4 x (quantize_act + w4a4_linear), eager launches, weights warm in cache; "
+                       "attention, LayerNorm and residuals are outside the path"}
+
+    line = {
+        "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 operands, int8 MFMA, int32 accumulate, fp32 epilogue, fp16 out",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{cfg - 1}]: " + ", ".join(f"{s.name} {s.M}x{s.N}x{s.K}" for s in specs)
+                   + ("; symmetric per-token / per-channel INT4" if cfg != 4 else
+                      "; asymmetric INT4, weight groups of 128, 8 outlier channels x20"),
+                   "step": "quantize_act + w4a4_linear (fused GEMM, dequant, bias, GELU on ffn1, fp16 store) x 4",
+                   "schedule": args.schedule},
+        "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
+        "per_gemm": [{"name": s.name, "ms": t, "TOPS": g} for s, t, g in zip(specs, gemm_ms, gemm_tops)],
+        "latency": lat,
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "kernel": "gemm_kernel (w4a4_linear), all four shapes of the step",
+                     "ops_per_step": ops, "kernel_ms_per_step": sum(gemm_ms)},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(specs, cfg, args.cpu_rows)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

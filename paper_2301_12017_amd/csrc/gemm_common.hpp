@@ -1,0 +1,257 @@
+// Pieces shared by the GEMM kernels of libw4a4: argument block, the nibble widening and
+// the fused epilogue (dequantize, zero-point terms, bias, GELU, store).
+#pragma once
+#include <type_traits>
+
+#include "common.hpp"
+
+namespace w4a4 {
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+constexpr int kBK = 128;           // codes per K step
+constexpr int kRowB = 80;          // LDS row pitch in bytes: 64 of codes + 16 of padding
+constexpr int kXcd = 8;
+
+enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
+
+struct GemmArgs {
+    const uint8_t *Aq; long lda;
+    const uint8_t *Wq; long ldw;
+    int M, N, K;
+    int ng, steps_per_group;       // K-groups of the weights, K steps per group
+    const float *sa, *za; const int32_t *RA;
+    const float *sw, *zw, *c;
+    const __half *bias; int act;
+    void *out;                     // fp16 [M,N] | fp32 [M,N] | int32 [ng,M,N]
+    int tiles_m, tiles_n;
+};
+
+// Widening of packed codes to int8 without sign extension.  For a packed dword d (codes
+// k0..k7, low nibble first) of SIGNED codes, (d << 4) & 0xF0F0F0F0 holds 16*k0,16*k2,16*k4,
+// 16*k6 and d & 0xF0F0F0F0 holds 16*k1,16*k3,16*k5,16*k7 as int8.  Both GEMM operands are
+// widened the same way, so an int8 MFMA accumulates 256 * sum(qa*qw) exactly and the k
+// permutation is common to both.  UNSIGNED codes use the 0x0F0F0F0F masks, unscaled.
+// One 16-byte LDS read feeds two MFMA K-slices: (x,y) -> lo, (z,w) -> hi.
+template <bool SIGNED_>
+__device__ __forceinline__ v4i widen2(uint32_t x, uint32_t y) {
+    if (SIGNED_) {
+        constexpr uint32_t m = 0xF0F0F0F0u;
+        return v4i{(int)((x << 4) & m), (int)(x & m), (int)((y << 4) & m), (int)(y & m)};
+    } else {
+        constexpr uint32_t m = 0x0F0F0F0Fu;
+        return v4i{(int)(x & m), (int)((x >> 4) & m), (int)(y & m), (int)((y >> 4) & m)};
+    }
+}
+template <bool SIGNED_>
+__device__ __forceinline__ void widen(const uint4 &p, v4i &lo, v4i &hi) {
+    lo = widen2<SIGNED_>(p.x, p.y);
+    hi = widen2<SIGNED_>(p.z, p.w);
+}
+
+// XCD x (workgroup id % 8) gets a contiguous range of tiles, so the tiles that share an
+// activation row panel run on one XCD and hit its L2.
+__device__ __forceinline__ int xcd_tile(int bid, int total) {
+    const int x = bid % kXcd, i = bid / kXcd;
+    const int per = total / kXcd, rem = total % kXcd;
+    return x * per + (x < rem ? x : rem) + i;
+}
+
+// Row of the output tile held in accumulator register r of fragment row i (32x32 MFMA
+// layout: lane l holds column l%32 and rows 8*(r/4) + 4*(l/32) + r%4).
+__device__ __forceinline__ int frag_row(int i, int r, int lane) {
+    return i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+}
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), (short)0, (int)bytes, 0x00020000);
+}
+
+// Store FN consecutive 32-bit or 16-bit values through a buffer descriptor: offsets past the
+// end of the buffer (rows >= M, or the poisoned offset of a lane whose channels are >= N) are
+// dropped by the hardware, so the epilogue needs no branches.
+template <int FN>
+__device__ __forceinline__ void store_words(__amdgpu_buffer_rsrc_t rs, uint32_t off, const uint32_t (&w)[FN]) {
+    if constexpr (FN == 1) __builtin_amdgcn_raw_buffer_store_b32(w[0], rs, off, 0, 0);
+    else if constexpr (FN == 2) __builtin_amdgcn_raw_buffer_store_b64(u32x2{w[0], w[1]}, rs, off, 0, 0);
+    else if constexpr (FN == 4) __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[0], w[1], w[2], w[3]}, rs, off, 0, 0);
+    else {
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[0], w[1], w[2], w[3]}, rs, off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[4], w[5], w[6], w[7]}, rs, off + 16, 0, 0);
+    }
+}
+template <int FN>
+__device__ __forceinline__ void store_halves(__amdgpu_buffer_rsrc_t rs, uint32_t off, const float (&y)[FN]) {
+    if constexpr (FN == 1) {
+        __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(y[0])), rs, off, 0, 0);
+    } else {
+        uint32_t w[FN / 2];
+#pragma unroll
+        for (int j = 0; j < FN / 2; ++j) {
+            __half2 h = __floats2half2_rn(y[2 * j], y[2 * j + 1]);
+            w[j] = *reinterpret_cast<uint32_t *>(&h);
+        }
+        store_words<FN / 2>(rs, off, w);
+    }
+}
+
+constexpr uint32_t kPoison = 0x80000000u;     // an offset no output buffer reaches (M*N*4 < 2^31)
+
+// Per-lane constants of the epilogue, fetched before the main loop so that their latency
+// is hidden: the FN output channels of this lane start at n_lane.
+template <int FN>
+struct EpiLane {
+    float sw[FN];      // per-channel weight scale (ungrouped layers), pre-divided by 256 for
+                       // signed codes (the accumulators hold 256 * P; a power of two, so exact)
+    float bias[FN];
+    float c[FN];       // weight row sums (asymmetric layers)
+    uint32_t col_off;  // byte offset of channel n_lane in an output row, or kPoison
+    int nc;            // n_lane clamped into range, for loads
+};
+
+template <int FN, int MODE, bool GROUPED, int OUT>
+__device__ __forceinline__ EpiLane<FN> epilogue_prefetch(const GemmArgs &g, int n_lane) {
+    constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
+    EpiLane<FN> e;
+    const bool n_ok = n_lane < g.N;
+    e.nc = n_ok ? n_lane : 0;
+    e.col_off = n_ok ? (uint32_t)n_lane * ESZ : kPoison;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        e.sw[j] = (!GROUPED && OUT != OUT_I32) ? g.sw[e.nc + j] * (MODE == W4A4_SYM ? 0.00390625f : 1.0f) : 0.0f;
+        e.bias[j] = (OUT != OUT_I32 && g.bias) ? __half2float(g.bias[e.nc + j]) : 0.0f;
+        e.c[j] = (MODE == W4A4_ASYM && OUT != OUT_I32) ? g.c[e.nc + j] : 0.0f;
+    }
+    return e;
+}
+
+// Stage the per-token scales (and zero points) of the BM rows of a tile in LDS; rows past M
+// read as zero.  Call before a workgroup barrier that precedes the epilogue.
+template <int BM, int NT, int MODE>
+__device__ __forceinline__ void stage_token_params(const GemmArgs &g, int m0, float *sa_lds, float *za_lds, int tid) {
+    for (int r = tid; r < BM; r += NT) {
+        const int m = m0 + r;
+        sa_lds[r] = m < g.M ? g.sa[m] : 0.0f;
+        if (MODE == W4A4_ASYM) za_lds[r] = m < g.M ? g.za[m] : 0.0f;
+    }
+}
+
+// The fused epilogue of one wave.  The lane holds, for every (i, r), FN consecutive
+// output channels n_lane..n_lane+FN-1 of token m0 + row_w + frag_row(i, r), row_w being the
+// wave's first row inside the workgroup tile.  Operation order (every operation separately
+// rounded):
+//   SYM, per-channel:  y = ((float)P * sa[m]) * sw[n]     (evaluated on 256*P and sw/256)
+//   grouped:           y = sa[m] * t1,  t1 = sum_g sw[n,g]*(float)P_g  (kept in facc)
+//   ASYM adds:         t2 = sum_g zw[n,g]*(float)RA[m,g];  y = y + sa*t2;  y = y + za*c[n]
+//   then + bias[n], then GELU; store fp16 / fp32 / (OUT_I32: the raw integer sums).
+// Token parameters come from LDS, channel parameters from registers, and stores go through a
+// bounds-checked buffer descriptor (rows >= M and poisoned columns are dropped by the
+// hardware), so the epilogue is straight-line code.
+template <int FM, int FN, int MODE, bool GROUPED, int OUT>
+__device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM][FN],
+                                              float (&facc)[GROUPED ? FM : 1][GROUPED ? FN : 1][16],
+                                              const EpiLane<FN> &e, int m0, int row_w, int lane,
+                                              const float *sa_lds, const float *za_lds) {
+    constexpr bool SGN = MODE == W4A4_SYM;
+    constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
+    if (GROUPED && OUT == OUT_I32) return;                       // planes were stored group by group
+    const __amdgpu_buffer_rsrc_t o_rsrc = make_rsrc(g.out, (uint32_t)((long)g.M * g.N * ESZ));
+    const uint32_t row_bytes = (uint32_t)g.N * ESZ;
+    // offset of (row m0 + row_w + 4*(lane/32), channel n_lane); the per-(i,r) part is uniform
+    const uint32_t lane_off = (uint32_t)(m0 + row_w + 4 * (lane >> 5)) * row_bytes + e.col_off;
+
+    if constexpr (OUT == OUT_I32) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                uint32_t w[FN];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) w[j] = (uint32_t)(SGN ? (acc[i][j][r] >> 8) : acc[i][j][r]);
+                store_words<FN>(o_rsrc, lane_off + (uint32_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * row_bytes, w);
+            }
+    } else {
+        const bool has_bias = g.bias != nullptr;
+        auto body = [&](auto gelu_tag) {
+            constexpr bool GELU = decltype(gelu_tag)::value;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int rl = row_w + i * 32 + 8 * q + 4 * (lane >> 5);      // 4 consecutive rows
+                    const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
+                    float4 za4 = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if constexpr (MODE == W4A4_ASYM) za4 = *reinterpret_cast<const float4 *>(za_lds + rl);
+                    const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w}, zav[4] = {za4.x, za4.y, za4.z, za4.w};
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        const int r = q * 4 + rr;
+                        const float sam = sav[rr];
+                        float y[FN];
+                        if constexpr (!GROUPED) {
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) {
+                                float t = (float)acc[i][j][r] * sam;
+                                y[j] = t * e.sw[j];
+                            }
+                        } else {
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) y[j] = sam * facc[GROUPED ? i : 0][GROUPED ? j : 0][r];
+                            if constexpr (MODE == W4A4_ASYM) {
+                                const int m = m0 + rl + rr;
+                                const int mc = m < g.M ? m : g.M - 1;
+                                float t2[FN];
+#pragma unroll
+                                for (int j = 0; j < FN; ++j) t2[j] = 0.0f;
+                                for (int grp = 0; grp < g.ng; ++grp) {
+                                    const float ra_f = (float)g.RA[(long)mc * g.ng + grp];
+#pragma unroll
+                                    for (int j = 0; j < FN; ++j) {
+                                        float w = g.zw[(long)(e.nc + j) * g.ng + grp] * ra_f;
+                                        t2[j] = t2[j] + w;
+                                    }
+                                }
+#pragma unroll
+                                for (int j = 0; j < FN; ++j) {
+                                    float p = sam * t2[j];
+                                    float z = zav[rr] * e.c[j];
+                                    y[j] = y[j] + p;
+                                    y[j] = y[j] + z;
+                                }
+                            }
+                        }
+                        if (has_bias) {
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) y[j] = y[j] + e.bias[j];
+                        }
+                        if constexpr (GELU) {
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) y[j] = gelu_erf(y[j]);
+                        }
+                        const uint32_t off = lane_off + (uint32_t)(i * 32 + 8 * q + rr) * row_bytes;
+                        if constexpr (OUT == OUT_F32) {
+                            uint32_t w[FN];
+#pragma unroll
+                            for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[j]);
+                            store_words<FN>(o_rsrc, off, w);
+                        } else {
+                            store_halves<FN>(o_rsrc, off, y);
+                        }
+                    }
+                }
+        };
+        if (g.act == W4A4_ACT_GELU) body(std::true_type{});
+        else body(std::false_type{});
+    }
+}
+
+// Launchers of the two kernel families (defined in gemm_generic.hip / gemm_pipe.hip).
+// `variant` selects the tile shape; both return a w4a4_status.
+int launch_generic(int variant, int mode, bool grouped, int out_kind, GemmArgs &g, hipStream_t st);
+int launch_pipe(int variant, int out_kind, GemmArgs &g, hipStream_t st);
+
+}  // namespace w4a4

@@ -6,7 +6,7 @@ bit for bit.  fp16 outputs must satisfy |gpu - oracle| <= 1e-2*|oracle| + 1e-3*r
 both sides perform the same separately rounded fp32 operations, so those outputs are
 additionally required to be identical.  Requantized codes behind a GELU may differ by one
 step only where the oracle's pre-rounding value sits within 1e-3 of a half-integer (the
-device erf and libm's differ in the last bits).
+device GELU and the oracle's differ by a few 1e-6 relative).
 """
 import numpy as np
 import pytest
@@ -110,24 +110,34 @@ def _operands(B, orc, rng, M, N, K, mode, group, outliers=0):
     return X, W, A, Q
 
 
-def _schedules(B, grouped):
-    """Schedule numbers to exercise: all of them, or the ones built for K-grouped weights."""
-    return [3, 5, 6, 7] if grouped else list(range(1, len(B.schedule_names()) + 1))
+def _schedules(B, grouped, K=128):
+    """Schedule numbers to exercise: every one that supports the layer (the pipelined kernels
+    take symmetric per-channel layers with K % 128 == 0; some generic tiles are ungrouped only)."""
+    out = []
+    for i, name in enumerate(B.schedule_names()):
+        if name.startswith("pipe") and (grouped or K % 128):
+            continue
+        if grouped and name == "generic_256x256":
+            continue
+        out.append(i + 1)
+    return out
 
 
 @pytest.mark.parametrize("mode,group", [(SYM, 0), (SYM, 128), (ASYM, 128), (ASYM, 0)])
 def test_gemm_i32_bit_exact_every_schedule(B, orc, mode, group):
     """Several tiles in both directions with ragged tails in M, N and (ungrouped) K."""
     rng = np.random.default_rng(300 + mode + group)
-    K = 416 if (mode == SYM and group == 0) else 384
     M, N = 301, 520
-    X, W, A, Q = _operands(B, orc, rng, M, N, K, mode, group)
-    want = orc.gemm_i32(host(A.q), host(Q.q), mode, group)
     grouped = not (mode == SYM and group == 0)
-    for sch in _schedules(B, grouped):
-        got = host(B.gemm_i32(A, Q, schedule=sch))
-        assert got.shape == want.shape
-        assert np.array_equal(got, want), f"schedule {sch} ({B.schedule_names()[sch - 1]})"
+    for K in ((416, 384) if not grouped else (384,)):
+        X, W, A, Q = _operands(B, orc, rng, M, N, K, mode, group)
+        want = orc.gemm_i32(host(A.q), host(Q.q), mode, group)
+        scheds = _schedules(B, grouped, K)
+        assert len(scheds) >= 4
+        for sch in scheds:
+            got = host(B.gemm_i32(A, Q, schedule=sch))
+            assert got.shape == want.shape
+            assert np.array_equal(got, want), f"K={K} schedule {sch} ({B.schedule_names()[sch - 1]})"
 
 
 def test_gemm_i32_extreme_codes(B, orc):
@@ -139,7 +149,7 @@ def test_gemm_i32_extreme_codes(B, orc):
         one = torch.ones(max(M, N), dtype=torch.float32, device="cuda")
         A = B.QAct(Aq, one, None, None, M, K, K // 2, 0, SYM)
         Q = B.QWeight(Wq, one.reshape(-1, 1), None, None, None, N, K, 0, SYM)
-        for sch in (1, 7):
+        for sch in (1, 2, 4, 7):
             P = host(B.gemm_i32(A, Q, schedule=sch))
             assert (P == val).all()
     Aq = torch.full((M, K // 2), 0xFF, dtype=torch.uint8, device="cuda")
@@ -164,7 +174,7 @@ def test_linear_fp16_every_schedule(B, orc, mode, group, act):
     bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
     want = _oracle_layer(orc, A, Q, mode, group, bias, act)
     grouped = not (mode == SYM and group == 0)
-    for sch in _schedules(B, grouped):
+    for sch in _schedules(B, grouped, K):
         got = host(B.linear(A, Q, dev(bias), act, schedule=sch))
         ok, ratio = f16_close(got, want["out"])
         assert ok, f"schedule {sch}: tolerance ratio {ratio}"
@@ -236,10 +246,11 @@ def test_linear_requant(B, orc, mode, group, rmode):
     if rmode == ASYM:
         assert np.array_equal(host(got.zero).view(np.uint32), want["z"].view(np.uint32))
         assert np.array_equal(host(got.gsum), want["gsum"])
-    # GELU: device erf vs libm erf -> scales to 1e-6, codes equal off near-ties
+    # GELU: the device evaluates the erf form to ~5e-6 relative (the oracle uses libm's erf in
+    # double) -> scales agree to 2e-5, codes are equal off near-ties
     want = _oracle_layer(orc, A, Q, mode, group, bias, 1, requant=True, requant_mode=rmode, requant_group=128)
     got = B.linear(A, Q, dev(bias), 1, requant=True, requant_mode=rmode, requant_group=128)
-    np.testing.assert_allclose(host(got.scale), want["s"], rtol=1e-6)
+    np.testing.assert_allclose(host(got.scale), want["s"], rtol=2e-5)
     nd = _requant_codes_agree(orc, host(got.q), want, want["y"], rmode)
     assert nd <= 0.002 * M * N
 
@@ -265,7 +276,7 @@ def test_degenerate_and_tiny_shapes(B, orc):
     for M, N, K in ((1, 8, 32), (2, 40, 64), (31, 8, 160), (257, 24, 32)):
         X, W, A, Q = _operands(B, orc, rng, M, N, K, SYM, 0)
         want = _oracle_layer(orc, A, Q, SYM, 0, None, 0)
-        for sch in (0, 1, 7):
+        for sch in (0, 4, 7):
             got = host(B.linear(A, Q, schedule=sch))
             assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16)), (M, N, K, sch)
     # M == 0: nothing is launched, nothing fails
