@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix peak, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0
+# HBM-side bytes of the four w4a4_linear launches of one step of configs[2], from the rocprofv3 --pmc
+# runs summarised in profiles/gemm_config3_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
+# factors a 256 MiB device copy gave in the same runs).  Not measured live; None for other workloads.
+PROFILED_TRAFFIC_BYTES = {3: int((25.79 + 25.85 + 49.84 + 25.85 + 72.0 + 24.0 + 96.0 + 24.0) * 2 ** 20)}
 
 
 def parse():
@@ -33,7 +37,10 @@ def parse():
     p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--cpu-rows", type=int, default=96, help="token rows per GEMM the oracle is timed on")
+    p.add_argument("--copy-probe-mb", type=int, default=0,
+                   help="also run one plain device copy of this many MiB (a kernel of known traffic, used to "
+                        "calibrate the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    p.add_argument("--cpu-rows", type=int, default=1024, help="token rows per GEMM the oracle is timed on")
     return p.parse_args()
 
 
@@ -131,11 +138,36 @@ def main():
             layer2()
         torch.cuda.synchronize()
         us = (time.perf_counter() - t1) * 1e6 / reps
+        # the same eight launches replayed from a HIP graph (Sec. 4.2: a captured graph removes the
+        # launch overhead that dominates at small batch x sequence)
+        graph_us = None
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                layer2()
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                layer2()
+            for _ in range(5):
+                gr.replay()
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+            for _ in range(reps):
+                gr.replay()
+            torch.cuda.synchronize()
+            graph_us = (time.perf_counter() - t2) * 1e6 / reps
+        except Exception as ex:                                   # report, never hide
+            graph_us = f"graph capture failed: {ex}"
         bytes2 = sum(s.M * s.K * 2 + s.M * s.K // 2 * 2 + s.N * s.K // 2 + s.M * s.N * 2 for s in s2)
-        lat = {"bert_base_layer_b1_s128_us": us, "algorithmic_bytes": bytes2,
+        lat = {"bert_base_layer_b1_s128_us": us, "bert_base_layer_b1_s128_graph_us": graph_us,
+               "algorithmic_bytes": bytes2,
                "achieved_GBps_warm": bytes2 / (us * 1e-6) / 1e9,
-               "note": "4 x (quantize_act + w4a4_linear), eager launches, weights warm in cache; "
-                       "attention, LayerNorm and residuals are outside the path"}
+               "note": "4 x (quantize_act + w4a4_linear); eager launches from Python, and the same launches "
+                       "replayed from a HIP graph; weights warm in cache; attention, LayerNorm and residuals "
+                       "are outside the path"}
 
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
@@ -152,10 +184,17 @@ def main():
         "per_gemm": [{"name": s.name, "ms": t, "TOPS": g} for s, t, g in zip(specs, gemm_ms, gemm_tops)],
         "latency": lat,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "frac": achieved / INT8_MFMA_PEAK_TOPS,
+                     "traffic": PROFILED_TRAFFIC_BYTES.get(cfg) if args.schedule == 0 else None,
+                     "traffic_unit": "bytes per step (the four launches), profiled separately",
                      "kernel": "gemm_kernel (w4a4_linear), all four shapes of the step",
                      "ops_per_step": ops, "kernel_ms_per_step": sum(gemm_ms)},
     }
+    if args.copy_probe_mb:
+        src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(specs, cfg, args.cpu_rows)
     print(json.dumps(line))

@@ -31,11 +31,16 @@ static bool pipe_ok(const GemmArgs &g, bool grouped) {
     return !grouped && g.K % kBK == 0 && (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL;
 }
 
-// Built-in shape table: large problems take the big pipelined tiles, small ones the tiles
-// that still give every CU something to do.
+// Built-in shape table: large problems take the pipelined tiles (192 x 128 when the output is
+// narrow, so that a 12288-token problem splits into a whole number of rounds of two
+// workgroups per CU; 128 x 256 otherwise), small ones the generic tiles that still give every
+// CU something to do.
 static int pick_schedule(const GemmArgs &g, bool grouped) {
     const long big = (long)((g.M + 127) / 128) * ((g.N + 255) / 256);
-    if (big >= 256) return pipe_ok(g, grouped) ? 1 : 3;
+    if (big >= 256) {
+        if (!pipe_ok(g, grouped)) return 3;
+        return g.N <= 1024 ? 8 : 1;
+    }
     const long mid = (long)((g.M + 63) / 64) * ((g.N + 127) / 128);
     if (mid >= 256) return 5;
     const long small = (long)((g.M + 63) / 64) * ((g.N + 63) / 64);

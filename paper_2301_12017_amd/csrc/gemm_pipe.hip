@@ -16,9 +16,6 @@
 //   * Two workgroups fit on a CU (128 accumulator registers per lane each) so that the
 //     epilogue and the prologue of one tile overlap the main loop of another.
 #include "gemm_common.hpp"
-#ifndef W4A4_ABL
-#define W4A4_ABL 0
-#endif
 
 namespace w4a4 {
 
@@ -131,16 +128,16 @@ void gemm_pipe_kernel(GemmArgs g) {
 #pragma unroll
         for (int k = 0; k < NM; ++k) {
             W4A4_SLOT_BEGIN(U0, k)
-            if (!(W4A4_ABL & 4)) if (k < NF) U1[k] = widen2<true>(P0[k].z, P0[k].w);
-            if (!(W4A4_ABL & 2)) if (k < NF) P1[k] = read_frag(k, cur, 1);
-            if (!(W4A4_ABL & 1)) if (k < LD) { store_one(k, cur ^ 1); load_one(k, so); }
+            if (k < NF) U1[k] = widen2<true>(P0[k].z, P0[k].w);
+            if (k < NF) P1[k] = read_frag(k, cur, 1);
+            if (k < LD) { store_one(k, cur ^ 1); load_one(k, so); }
             __builtin_amdgcn_sched_barrier(0);
         }
         // sub-step 1: multiply (ks 0, high); widen (ks 1, low) -> U0
 #pragma unroll
         for (int k = 0; k < NM; ++k) {
             W4A4_SLOT_BEGIN(U1, k)
-            if (!(W4A4_ABL & 4)) if (k < NF) U0[k] = widen2<true>(P1[k].x, P1[k].y);
+            if (k < NF) U0[k] = widen2<true>(P1[k].x, P1[k].y);
             __builtin_amdgcn_sched_barrier(0);
         }
         // sub-step 2: multiply (ks 1, low); widen (ks 1, high) -> U1; once every wave has passed
@@ -148,16 +145,16 @@ void gemm_pipe_kernel(GemmArgs g) {
 #pragma unroll
         for (int k = 0; k < NM; ++k) {
             W4A4_SLOT_BEGIN(U0, k)
-            if (!(W4A4_ABL & 4)) if (k < NF) U1[k] = widen2<true>(P1[k].z, P1[k].w);
-            if (!(W4A4_ABL & 8)) if (k == kBarSlot) lds_barrier();
-            if (!(W4A4_ABL & 2)) if (k >= kBarSlot) P0[k - kBarSlot] = read_frag(k - kBarSlot, cur ^ 1, 0);
+            if (k < NF) U1[k] = widen2<true>(P1[k].z, P1[k].w);
+            if (k == kBarSlot) lds_barrier();
+            if (k >= kBarSlot) P0[k - kBarSlot] = read_frag(k - kBarSlot, cur ^ 1, 0);
             __builtin_amdgcn_sched_barrier(0);
         }
         // sub-step 3: multiply (ks 1, high); widen (next step's ks 0, low) -> U0
 #pragma unroll
         for (int k = 0; k < NM; ++k) {
             W4A4_SLOT_BEGIN(U1, k)
-            if (!(W4A4_ABL & 4)) if (k < NF) U0[k] = widen2<true>(P0[k].x, P0[k].y);
+            if (k < NF) U0[k] = widen2<true>(P0[k].x, P0[k].y);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
