@@ -8,7 +8,9 @@ namespace w4a4 {
 // names a kernel family and a tile variant of it.
 struct Schedule {
     const char *name;
-    int family;          // 0 = pipelined kernel (symmetric, per-channel, K % 128 == 0), 1 = generic
+    int family;          // 0 = pipelined kernel, codes widened per wave (symmetric, per-channel, K % 128 == 0),
+                         // 1 = generic, 2 = pipelined kernel, codes widened once into LDS (K % 64 == 0),
+                         // 3 = pipelined kernel with direct global->LDS loads (K % 128 == 0)
     int variant;
     bool grouped_ok;     // usable for K-grouped / asymmetric layers
 };
@@ -23,12 +25,16 @@ static const Schedule kSchedules[] = {
     {"generic_32x32", 1, 4, true},
     {"pipe_192x128", 0, 2, false},
     {"pipe_192x256", 0, 3, false},
+    {"pipe8_128x256", 2, 0, false},
+    {"pipe8_256x256", 2, 1, false},
+    {"dma_128x256", 3, 0, false},
+    {"dma_256x256", 3, 1, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 
-static bool pipe_ok(const GemmArgs &g, bool grouped) {
+static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
     // 32-bit buffer offsets and whole K steps
-    return !grouped && g.K % kBK == 0 && (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL;
+    return !grouped && g.K % kstep == 0 && (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL;
 }
 
 // Built-in shape table: large problems take the pipelined tiles (192 x 128 when the output is
@@ -38,7 +44,7 @@ static bool pipe_ok(const GemmArgs &g, bool grouped) {
 static int pick_schedule(const GemmArgs &g, bool grouped) {
     const long big = (long)((g.M + 127) / 128) * ((g.N + 255) / 256);
     if (big >= 256) {
-        if (!pipe_ok(g, grouped)) return 3;
+        if (!pipe_ok(g, grouped)) return 5;      // grouped layers: the 64 x 128 tile leaves LDS for the group tables
         return g.N <= 1024 ? 8 : 1;
     }
     const long mid = (long)((g.M + 63) / 64) * ((g.N + 127) / 128);
@@ -58,6 +64,14 @@ static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int sched
     if (s.family == 0) {
         if (!pipe_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
         return launch_pipe(s.variant, out_kind, g, st);
+    }
+    if (s.family == 3) {
+        if (!pipe_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        return launch_dma(s.variant, out_kind, g, st);
+    }
+    if (s.family == 2) {
+        if (!pipe_ok(g, grouped, 64)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        return launch_pipe8(s.variant, out_kind, g, st);
     }
     return launch_generic(s.variant, mode, grouped, out_kind, g, st);
 }

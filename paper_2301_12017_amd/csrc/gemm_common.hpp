@@ -148,14 +148,17 @@ __device__ __forceinline__ void stage_token_params(const GemmArgs &g, int m0, fl
 //   grouped:           y = sa[m] * t1,  t1 = sum_g sw[n,g]*(float)P_g  (kept in facc)
 //   ASYM adds:         t2 = sum_g zw[n,g]*(float)RA[m,g];  y = y + sa*t2;  y = y + za*c[n]
 //   then + bias[n], then GELU; store fp16 / fp32 / (OUT_I32: the raw integer sums).
-// Token parameters come from LDS, channel parameters from registers, and stores go through a
+// Token parameters and (asymmetric layers) the group zero points / code sums come from LDS,
+// channel parameters from registers, and stores go through a
 // bounds-checked buffer descriptor (rows >= M and poisoned columns are dropped by the
 // hardware), so the epilogue is straight-line code.
 template <int FM, int FN, int MODE, bool GROUPED, int OUT>
 __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM][FN],
                                               float (&facc)[GROUPED ? FM : 1][GROUPED ? FN : 1][16],
                                               const EpiLane<FN> &e, int m0, int row_w, int lane,
-                                              const float *sa_lds, const float *za_lds) {
+                                              const float *sa_lds, const float *za_lds,
+                                              const float *zw_lds = nullptr, const float *ra_lds = nullptr,
+                                              int n_local = 0, int BMt = 0, int BNt = 0) {
     constexpr bool SGN = MODE == W4A4_SYM;
     constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
     if (GROUPED && OUT == OUT_I32) return;                       // planes were stored group by group
@@ -202,16 +205,16 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM]
 #pragma unroll
                             for (int j = 0; j < FN; ++j) y[j] = sam * facc[GROUPED ? i : 0][GROUPED ? j : 0][r];
                             if constexpr (MODE == W4A4_ASYM) {
-                                const int m = m0 + rl + rr;
-                                const int mc = m < g.M ? m : g.M - 1;
+                                // zero points and code sums of the tile were staged in LDS as
+                                // zw_lds[g][channel in tile] and ra_lds[g][row in tile] (as floats)
                                 float t2[FN];
 #pragma unroll
                                 for (int j = 0; j < FN; ++j) t2[j] = 0.0f;
                                 for (int grp = 0; grp < g.ng; ++grp) {
-                                    const float ra_f = (float)g.RA[(long)mc * g.ng + grp];
+                                    const float ra_f = ra_lds[grp * BMt + rl + rr];
 #pragma unroll
                                     for (int j = 0; j < FN; ++j) {
-                                        float w = g.zw[(long)(e.nc + j) * g.ng + grp] * ra_f;
+                                        float w = zw_lds[grp * BNt + n_local + j] * ra_f;
                                         t2[j] = t2[j] + w;
                                     }
                                 }
@@ -249,9 +252,11 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM]
     }
 }
 
-// Launchers of the two kernel families (defined in gemm_generic.hip / gemm_pipe.hip).
+// Launchers of the kernel families (defined in gemm_generic.hip / gemm_pipe.hip / gemm_pipe8.hip).
 // `variant` selects the tile shape; both return a w4a4_status.
 int launch_generic(int variant, int mode, bool grouped, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_pipe(int variant, int out_kind, GemmArgs &g, hipStream_t st);
+int launch_pipe8(int variant, int out_kind, GemmArgs &g, hipStream_t st);
+int launch_dma(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 
 }  // namespace w4a4

@@ -34,6 +34,10 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_kernel(GemmArgs g) {
     uint8_t *Bs = smem + 2 * A_STAGE;
     float *sa_lds = reinterpret_cast<float *>(smem + 2 * A_STAGE + 2 * B_STAGE);   // token scales
     float *za_lds = sa_lds + BM;                                                   // token zero points
+    // K-group parameters of the tile, staged once: sw_lds[g][n], zw_lds[g][n], ra_lds[g][m]
+    float *sw_lds = za_lds + BM;
+    float *zw_lds = sw_lds + (GROUPED ? g.ng * BN : 0);
+    float *ra_lds = zw_lds + (MODE == W4A4_ASYM ? g.ng * BN : 0);
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
@@ -135,13 +139,14 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_kernel(GemmArgs g) {
     // output coordinates of this lane
     const int n_lane = n0 + wn * FN * 32 + (lane & 31) * FN;     // FN consecutive channels from here
     const bool n_ok = n_lane < g.N;
+    const int n_local = wn * FN * 32 + (lane & 31) * FN;
     auto m_of = [&](int i, int r) { return m0 + wm * FM * 32 + frag_row(i, r, lane); };
 
     // Rescale at a group boundary:  t1 += sw[n,g] * (float)P_g   (one mul, one add).
     auto fold_group = [&](int grp) {
         float swg[FN];
 #pragma unroll
-        for (int j = 0; j < FN; ++j) swg[j] = n_ok ? g.sw[(long)(n_lane + j) * g.ng + grp] : 0.0f;
+        for (int j = 0; j < FN; ++j) swg[j] = sw_lds[grp * BN + n_local + j];
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -165,6 +170,19 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_kernel(GemmArgs g) {
     const int KT = (g.K + kBK - 1) / kBK;
     const EpiLane<FN> epi = epilogue_prefetch<FN, MODE, GROUPED, OUT>(g, n_lane);
     stage_token_params<BM, NT, MODE>(g, m0, sa_lds, za_lds, tid);     // visible after the first barrier
+    if constexpr (GROUPED) {
+        for (int e = tid; e < BN * g.ng; e += NT) {                   // global [N][ng] -> LDS [ng][BN]
+            const int nl = e / g.ng, grp = e % g.ng, n = n0 + nl;
+            sw_lds[grp * BN + nl] = n < g.N ? g.sw[(long)n * g.ng + grp] : 0.0f;
+            if (MODE == W4A4_ASYM) zw_lds[grp * BN + nl] = n < g.N ? g.zw[(long)n * g.ng + grp] : 0.0f;
+        }
+        if (MODE == W4A4_ASYM) {
+            for (int e = tid; e < BM * g.ng; e += NT) {
+                const int ml = e / g.ng, grp = e % g.ng, m = m0 + ml;
+                ra_lds[grp * BM + ml] = m < g.M ? (float)g.RA[(long)m * g.ng + grp] : 0.0f;
+            }
+        }
+    }
     gload(0);
     lstore(0);
     __syncthreads();
@@ -178,22 +196,25 @@ __global__ __launch_bounds__(WM *WN * 64) void gemm_kernel(GemmArgs g) {
     }
 
     // ---- epilogue -------------------------------------------------------------------------
-    tile_epilogue<FM, FN, MODE, GROUPED, OUT>(g, acc, facc, epi, m0, wm * FM * 32, lane, sa_lds, za_lds);
+    tile_epilogue<FM, FN, MODE, GROUPED, OUT>(g, acc, facc, epi, m0, wm * FM * 32, lane, sa_lds, za_lds, zw_lds, ra_lds,
+                                              n_local, BM, BN);
 }
 
 template <int FM, int FN, int WM, int WN, int MODE, bool GROUPED, int OUT>
 static int launch_one(GemmArgs &g, hipStream_t st) {
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowB + 2 * BM * sizeof(float);
+    size_t lds = 2 * (size_t)(BM + BN) * kRowB + 2 * BM * sizeof(float);
+    if (GROUPED) lds += (size_t)g.ng * (BN * (MODE == W4A4_ASYM ? 2 : 1) + (MODE == W4A4_ASYM ? BM : 0)) * sizeof(float);
+    if (lds > 160 * 1024) return W4A4_ERR_UNSUPPORTED_SHAPE;      // K-group tables do not fit next to this tile
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     auto kern = gemm_kernel<FM, FN, WM, WN, MODE, GROUPED, OUT>;
-    static bool attr_set = false;          // benign race: the attribute call is idempotent
-    if (!attr_set) {
+    static size_t attr_lds = 0;            // benign race: the attribute call is idempotent
+    if (lds > attr_lds) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)lds) != hipSuccess)
             return W4A4_ERR_HIP;
-        attr_set = true;
+        attr_lds = lds;
     }
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
