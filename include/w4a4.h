@@ -95,9 +95,21 @@ const char *w4a4_status_string(int status);
 int         w4a4_schedule_count(void);
 const char *w4a4_schedule_name(int schedule);
 
-/* Bytes of device workspace w4a4_linear / w4a4_dequant_epilogue need for this shape
- * and epilogue (0 when none is needed). */
+/* Bytes of device workspace that are enough for w4a4_linear on ANY layer of this shape and
+ * epilogue (0 when none is needed; M*N*4 for a requantizing epilogue). */
 size_t w4a4_workspace_bytes(int M, int N, int K, const w4a4_epilogue *ep);
+
+/* Bytes of workspace w4a4_linear needs for exactly this layer.  A symmetric, per-channel
+ * layer with K % 128 == 0 that requantizes to symmetric codes without code sums
+ * (want_gsum == 0) runs fused in one kernel and needs only (M + M/128 + 4) words: the
+ * column tiles of a row panel exchange per-token maxima through it (Sec. 4.2: quantize
+ * fused behind bias-add / GELU).  Every other requantizing layer needs M*N*4 bytes: the
+ * GEMM leaves fp32 rows there and a second kernel packs them.  After the stream has been
+ * synchronized the LAST 32-bit word of a fused layer's workspace is non-zero if a workgroup
+ * gave up waiting for its siblings (outputs are then invalid; this does not happen when a
+ * row panel's tiles are co-resident, which the library's tile order ensures). */
+size_t w4a4_linear_workspace_bytes(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
+                                   int want_gsum);
 
 /* Step a0 (offline): App. A weight quantization of W_f16[N,K] with the Sec. 3.1 mapping.
  * Outputs: q[N,K/2], scale[N,ng], zero[N,ng] (ASYM; may be NULL for SYM),

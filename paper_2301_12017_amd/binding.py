@@ -52,6 +52,7 @@ _SIGNATURES = {
     "w4a4_schedule_count": (_i, []),
     "w4a4_schedule_name": (ctypes.c_char_p, [_i]),
     "w4a4_workspace_bytes": (_sz, [_i, _i, _i, ctypes.POINTER(_Epilogue)]),
+    "w4a4_linear_workspace_bytes": (_sz, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _i]),
     "w4a4_quantize_weight": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
     "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
@@ -188,6 +189,18 @@ def workspace_bytes(M, N, K, requant=False) -> int:
     return int(lib().w4a4_workspace_bytes(M, N, K, ctypes.byref(ep)))
 
 
+def linear_workspace_bytes(A: "QAct", W: "QWeight", requant=True, requant_mode=SYM, requant_group=0,
+                           want_gsum=False, schedule=0) -> int:
+    ep = _Epilogue(None, 0, int(requant), requant_mode, requant_group, schedule)
+    a, w = A.c(), W.c()
+    return int(lib().w4a4_linear_workspace_bytes(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), int(want_gsum)))
+
+
+def fused_fault(workspace: torch.Tensor, nbytes: int) -> int:
+    """Last word of a fused requantize workspace (0 = the row-maximum exchange completed)."""
+    return int(workspace[:nbytes].view(torch.int32)[-1].item())
+
+
 def _epilogue(bias, act, requant, requant_mode, requant_group, schedule):
     return _Epilogue(None if bias is None else bias.data_ptr(), act, int(bool(requant)), requant_mode,
                      requant_group, schedule)
@@ -211,10 +224,11 @@ def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NON
     if out is None:
         out = _alloc_out(A, W, requant, requant_mode, requant_group)
     o, os_, oz, og = out
-    need = int(lib().w4a4_workspace_bytes(A.M, W.N, A.K, ctypes.byref(ep)))
+    a, w = A.c(), W.c()
+    need = int(lib().w4a4_linear_workspace_bytes(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep),
+                                                 0 if og is None else 1))
     if need and workspace is None:
         workspace = torch.empty((need,), dtype=torch.uint8, device=A.q.device)
-    a, w = A.c(), W.c()
     rc = lib().w4a4_linear(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), _ptr(o), _ptr(os_), _ptr(oz),
                            _ptr(og), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
     _check(rc, "w4a4_linear")

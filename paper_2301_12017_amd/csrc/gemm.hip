@@ -138,6 +138,7 @@ static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int 
     g.sw = W->scale; g.zw = W->zero; g.c = W->rowsum_deq;
     g.bias = nullptr; g.act = W4A4_ACT_NONE; g.out = nullptr;
     g.tiles_m = g.tiles_n = 0;
+    g.rowmax = nullptr; g.arrived = nullptr; g.fault = nullptr; g.out_scale = nullptr;
 }
 
 }  // namespace w4a4
@@ -150,10 +151,35 @@ extern "C" const char *w4a4_schedule_name(int schedule) {
     return (schedule >= 1 && schedule <= kNumSchedules) ? kSchedules[schedule - 1].name : "";
 }
 
+// Fused requantize: symmetric per-channel layer on the pipelined kernel, symmetric output codes,
+// no code sums wanted, and few enough column tiles that a row panel's workgroups are co-resident.
+static bool fused_requant_ok(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
+    if (!ep->requant || ep->requant_mode != W4A4_SYM || want_gsum) return false;
+    if (A->mode != W4A4_SYM || W->group != 0) return false;
+    if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return false;
+    if (ep->schedule != 0 && ep->schedule != 1) return false;
+    return (W->N + 255) / 256 <= 32;
+}
+static size_t fused_workspace_bytes(int M) {
+    return ((size_t)M + (size_t)(M + 127) / 128 + 4) * sizeof(uint32_t);
+}
+
 extern "C" size_t w4a4_workspace_bytes(int M, int N, int K, const w4a4_epilogue *ep) {
     (void)K;
     if (!ep || !ep->requant || M <= 0 || N <= 0) return 0;
     return (size_t)M * (size_t)N * sizeof(float);          // fp32 rows awaiting their per-token range
+}
+
+extern "C" size_t w4a4_linear_workspace_bytes(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
+                                              int want_gsum) {
+    if (!A || !W || !ep || !ep->requant || A->M <= 0 || W->N <= 0) return 0;
+    if (fused_requant_ok(A, W, ep, want_gsum != 0)) return fused_workspace_bytes(A->M);
+    return (size_t)A->M * (size_t)W->N * sizeof(float);
+}
+
+__global__ void zero_words_kernel(uint32_t *p, int n) {
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
 }
 
 extern "C" int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream) {
@@ -177,7 +203,7 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
     int rc = check_layer(A, W, ep, out, out_scale, out_zero, &ng, &rng);
     if (rc) return rc;
     if (A->M == 0) return W4A4_OK;
-    const size_t need = w4a4_workspace_bytes(A->M, W->N, A->K, ep);
+    const size_t need = w4a4_linear_workspace_bytes(A, W, ep, out_gsum != nullptr);
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return W4A4_ERR_WORKSPACE;
     hipStream_t st = as_stream(stream);
     GemmArgs g;
@@ -188,6 +214,19 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
     if (!ep->requant) {
         g.out = out;
         return run_gemm(g, A->mode, grouped, OUT_F16, ep->schedule, st);
+    }
+    if (fused_requant_ok(A, W, ep, out_gsum != nullptr)) {
+        // One kernel: the column tiles of a row panel exchange their row maxima through the
+        // workspace (zeroed here) and pack the codes from registers.
+        const int words = (int)(fused_workspace_bytes(A->M) / sizeof(uint32_t));
+        uint32_t *wsp = static_cast<uint32_t *>(workspace);
+        hipLaunchKernelGGL(zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st, wsp, words);
+        g.rowmax = wsp;
+        g.arrived = reinterpret_cast<int *>(wsp + A->M);
+        g.fault = reinterpret_cast<int *>(wsp + words - 1);
+        g.out_scale = out_scale;
+        g.out = out;
+        return run_gemm(g, A->mode, false, OUT_Q4, 1, st);
     }
     // Requantize: the per-token range needs the whole output row, which no single tile
     // sees.  The GEMM leaves the fp32 rows in the workspace and the row quantizer turns

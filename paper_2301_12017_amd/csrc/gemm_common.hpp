@@ -14,7 +14,7 @@ constexpr int kBK = 128;           // codes per K step
 constexpr int kRowB = 80;          // LDS row pitch in bytes: 64 of codes + 16 of padding
 constexpr int kXcd = 8;
 
-enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2 };
+enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2, OUT_Q4 = 3 };   // Q4: per-token requantized codes
 
 struct GemmArgs {
     const uint8_t *Aq; long lda;
@@ -26,6 +26,11 @@ struct GemmArgs {
     const __half *bias; int act;
     void *out;                     // fp16 [M,N] | fp32 [M,N] | int32 [ng,M,N]
     int tiles_m, tiles_n;
+    // fused requantize (OUT_Q4): row maxima and arrival counters live in the caller's workspace
+    uint32_t *rowmax;              // [M]       bit pattern of max |y| of the row, zeroed before the launch
+    int *arrived;                  // [tiles_m] tiles of the row panel that have published their maxima
+    int *fault;                    // [1]       set if a workgroup gave up waiting for its siblings
+    float *out_scale;              // [M]
 };
 
 // Widening of packed codes to int8 without sign extension.  For a packed dword d (codes
@@ -250,6 +255,131 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM]
         if (g.act == W4A4_ACT_GELU) body(std::true_type{});
         else body(std::false_type{});
     }
+}
+
+
+// max over the 16 lanes of a DPP row, result in every lane (butterfly of quad swaps and mirrors)
+__device__ __forceinline__ float row16_max(float v) {
+    int x;
+    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false)));   // lanes ^1
+    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false)));   // lanes ^2
+    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x141, 0xF, 0xF, false)));  // half mirror
+    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x140, 0xF, 0xF, false)));  // row mirror
+    return v;
+}
+
+// Fused per-token requantize of one wave's part of the tile (symmetric output codes, Sec. 4.2:
+// the next layer's quantize rides behind bias-add / GELU).  The range of a token needs the
+// whole output row, which is spread over the tiles_n workgroups of the row panel, so:
+//   1. every lane turns its accumulators into the fp32 outputs y (same operation order as the
+//      fp32 store path) and keeps them in the accumulator registers;
+//   2. per row, max|y| is reduced over the lane's channels and the 32 lanes that share the row
+//      (DPP butterfly + one cross-row exchange) and published with an atomic max on rowmax[m]
+//      (non-negative floats order like integers);
+//   3. the workgroup announces itself on arrived[panel] and waits until all tiles_n siblings
+//      have done so (they are co-resident: consecutive workgroup ids of one XCD; the wait is
+//      bounded and raises *fault instead of hanging);
+//   4. each lane fetches ONE row maximum, derives scale = max/7 and 7/max for that row and
+//      shares the reciprocal with the 31 other lanes of the row through `scratch` (LDS, 64
+//      floats per wave); codes = rne(clamp(y * (7/max))) as in quantize_act, eight codes per
+//      dword assembled from two neighbouring lanes.  The wave that owns channel 0 writes the
+//      scales.
+template <int FM, int FN>
+__device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&acc)[FM][FN], const EpiLane<FN> &e,
+                                                       int m0, int row_w, int lane, int tid, int panel,
+                                                       const float *sa_lds, float *scratch) {
+    static_assert(FN == 4 && FM == 2, "32 rows per half wave; two lanes assemble one dword of eight codes");
+    const bool has_bias = g.bias != nullptr, gelu = g.act == W4A4_ACT_GELU;
+    const int h = lane >> 5, c = lane & 31;
+    // 1. outputs in fp32, kept in place
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rl = row_w + i * 32 + 8 * q + 4 * h;
+            const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
+            const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = q * 4 + rr;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    float t = (float)acc[i][j][r] * sav[rr];
+                    float y = t * e.sw[j];
+                    if (has_bias) y = y + e.bias[j];
+                    if (gelu) y = gelu_erf(y);
+                    acc[i][j][r] = __float_as_int(y);
+                }
+            }
+        }
+    // 2. row maxima -> global
+    const bool n_ok = e.col_off != kPoison;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float v = 0.0f;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) v = fmaxf(v, fabsf(__int_as_float(acc[i][j][r])));
+            if (!n_ok) v = 0.0f;                                  // channels past N do not count
+            v = row16_max(v);
+            v = fmaxf(v, __shfl_xor(v, 16, kWave));
+            const int m = m0 + row_w + frag_row(i, r, lane);
+            if (c == 0 && m < g.M) atomicMax(g.rowmax + m, __float_as_uint(v));
+        }
+    // 3. wait for the siblings of the row panel.  Only relaxed device-scope atomics are used
+    //    (they are performed at the coherence point and bypass the L1): a release / acquire
+    //    FENCE at device scope would write back and invalidate the whole L2 on every poll.
+    //    Ordering comes from waiting for this wave's atomics to be acknowledged (vmcnt) before
+    //    the workgroup barrier that precedes the counter increment.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_fetch_add(g.arrived + panel, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0;
+        while (__hip_atomic_load(g.arrived + panel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.tiles_n) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > (1 << 22)) { *g.fault = 1; break; }     // never hang: report and carry on
+        }
+    }
+    __syncthreads();
+    // 4. ranges: lane (c, h) owns row index c = i*16 + r of its half wave
+    {
+        const int m = m0 + row_w + frag_row(c >> 4, c & 15, lane);
+        const __amdgpu_buffer_rsrc_t mx_rsrc = make_rsrc(g.rowmax, (uint32_t)g.M * 4u);
+        // an ordinary load that bypasses the non-coherent cache levels (sc0 | sc1); rows >= M read 0
+        const float amax = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(mx_rsrc, m * 4, 0, 17));
+        const Range rg = range_sym(amax);
+        if (m < g.M && __shfl(e.col_off, lane & 32, kWave) == 0)
+            g.out_scale[m] = rg.S;                                // this wave holds channel 0 of the row
+        scratch[(tid & ~63) + lane] = rg.inv;
+        __builtin_amdgcn_wave_barrier();
+    }
+    uint8_t *outq = static_cast<uint8_t *>(g.out);
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 iv4 = *reinterpret_cast<const float4 *>(scratch + (tid & ~63) + h * 32 + i * 16 + q * 4);
+            const float ivv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = q * 4 + rr;
+                const int m = m0 + row_w + frag_row(i, r, lane);
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    // code + 8 in [0, 15]; the final xor turns offset binary into two's complement
+                    float t = __int_as_float(acc[i][j][r]) * ivv[rr];
+                    t = rintf(fminf(fmaxf(t, -8.0f), 7.0f)) + 8.0f;
+                    packed |= (uint32_t)t << (4 * j);
+                }
+                packed ^= 0x8888u;
+                const uint32_t other = __shfl_down(packed, 1, kWave);   // the next lane holds the next four channels
+                if ((lane & 1) == 0 && n_ok && m < g.M)
+                    *reinterpret_cast<uint32_t *>(outq + (long)m * (g.N / 2) + (e.nc >> 1)) = packed | (other << 16);
+            }
+        }
 }
 
 // Launchers of the kernel families (defined in gemm_generic.hip / gemm_pipe.hip / gemm_pipe8.hip).

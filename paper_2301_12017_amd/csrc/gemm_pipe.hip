@@ -161,8 +161,13 @@ void gemm_pipe_kernel(GemmArgs g) {
 #undef W4A4_SLOT_BEGIN
 
     // ---- epilogue ---------------------------------------------------------------------------------
-    float none[1][1][16];
-    tile_epilogue<FM, FN, W4A4_SYM, false, OUT>(g, acc, none, epi, m0, wm * FM * 32, lane, sa_lds, nullptr);
+    if constexpr (OUT == OUT_Q4) {
+        tile_epilogue_requant<FM, FN>(g, acc, epi, m0, wm * FM * 32, lane, tid, tile / g.tiles_n, sa_lds,
+                                      reinterpret_cast<float *>(smem));
+    } else {
+        float none[1][1][16];
+        tile_epilogue<FM, FN, W4A4_SYM, false, OUT>(g, acc, none, epi, m0, wm * FM * 32, lane, sa_lds, nullptr);
+    }
 }
 
 template <int FM, int FN, int WM, int WN, int OCC, int OUT>
@@ -198,6 +203,8 @@ static int launch_variant(int variant, GemmArgs &g, hipStream_t st) {
 
 // Requires: symmetric codes, per-channel weight scales, K % 128 == 0, M*lda and N*ldw < 2^31.
 int launch_pipe(int variant, int out_kind, GemmArgs &g, hipStream_t st) {
+    if (out_kind == OUT_Q4)                                     // fused requantize: the 128 x 256 tile only
+        return variant == 0 ? launch_one<2, 4, 2, 2, 2, OUT_Q4>(g, st) : W4A4_ERR_INVALID_ARG;
     switch (out_kind) {
         case OUT_F16: return launch_variant<OUT_F16>(variant, g, st);
         case OUT_F32: return launch_variant<OUT_F32>(variant, g, st);

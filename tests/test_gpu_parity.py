@@ -258,6 +258,32 @@ def test_linear_requant(B, orc, mode, group, rmode):
     assert nd <= 0.002 * M * N
 
 
+def test_fused_requant_many_column_tiles(B, orc):
+    """Symmetric per-channel layers requantize inside the GEMM kernel: the 16 column tiles of a
+    row panel exchange per-token maxima through a workspace of a few words per token."""
+    rng = np.random.default_rng(51)
+    M, N, K = 700, 4096, 256
+    X, W, A, Q = _operands(B, orc, rng, M, N, K, SYM, 0)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    need = B.linear_workspace_bytes(A, Q)
+    assert need < 8 * M                                           # not the M*N*4 bytes of the two-kernel path
+    assert B.linear_workspace_bytes(A, Q, requant_mode=ASYM) == M * N * 4
+    assert B.linear_workspace_bytes(A, Q, want_gsum=True) == M * N * 4
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    want = _oracle_layer(orc, A, Q, SYM, 0, bias, 0, requant=True, requant_mode=SYM)
+    for _ in range(2):                                            # the workspace is re-zeroed by every call
+        got = B.linear(A, Q, dev(bias), 0, requant=True, requant_mode=SYM, workspace=ws)
+        torch.cuda.synchronize()
+        assert B.fused_fault(ws, need) == 0
+        assert np.array_equal(host(got.q), want["q"])
+        assert np.array_equal(host(got.scale).view(np.uint32), want["s"].view(np.uint32))
+    # an all-zero token keeps scale 1 and codes 0 through the fused path as well
+    Xz = X.copy(); Xz[5, :] = 0
+    Az = B.quantize_act(dev(Xz), SYM)
+    gz = B.linear(Az, Q, None, 0, requant=True, requant_mode=SYM, workspace=ws)
+    assert float(host(gz.scale)[5]) == 1.0 and not host(gz.q)[5].any()
+
+
 def test_linear_reads_a_column_slice_in_place(B, orc):
     """lda > K/2: the GEMM reads the last third of a wider packed matrix (as the chained stack does)."""
     rng = np.random.default_rng(43)
