@@ -258,40 +258,36 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM]
 }
 
 
-// max over the 16 lanes of a DPP row, result in every lane (butterfly of quad swaps and mirrors)
-__device__ __forceinline__ float row16_max(float v) {
-    int x;
-    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0xB1, 0xF, 0xF, false)));   // lanes ^1
-    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x4E, 0xF, 0xF, false)));   // lanes ^2
-    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x141, 0xF, 0xF, false)));  // half mirror
-    x = __float_as_int(v); v = fmaxf(v, __int_as_float(__builtin_amdgcn_update_dpp(x, x, 0x140, 0xF, 0xF, false)));  // row mirror
-    return v;
-}
-
 // Fused per-token requantize of one wave's part of the tile (symmetric output codes, Sec. 4.2:
 // the next layer's quantize rides behind bias-add / GELU).  The range of a token needs the
 // whole output row, which is spread over the tiles_n workgroups of the row panel, so:
 //   1. every lane turns its accumulators into the fp32 outputs y (same operation order as the
-//      fp32 store path) and keeps them in the accumulator registers;
-//   2. per row, max|y| is reduced over the lane's channels and the 32 lanes that share the row
-//      (DPP butterfly + one cross-row exchange) and published with an atomic max on rowmax[m]
-//      (non-negative floats order like integers);
+//      fp32 store path), keeps them in the accumulator registers and notes max|y| of its four
+//      channels for each of its 32 rows;
+//   2. a butterfly over the 32 lanes that share the rows (exchange with lane^16, ^8, ... while
+//      halving the set of rows a lane is responsible for) leaves lane c with the maximum of
+//      row c, which it publishes with ONE atomic max on rowmax[m] (non-negative floats order
+//      like integers);
 //   3. the workgroup announces itself on arrived[panel] and waits until all tiles_n siblings
 //      have done so (they are co-resident: consecutive workgroup ids of one XCD; the wait is
 //      bounded and raises *fault instead of hanging);
-//   4. each lane fetches ONE row maximum, derives scale = max/7 and 7/max for that row and
-//      shares the reciprocal with the 31 other lanes of the row through `scratch` (LDS, 64
-//      floats per wave); codes = rne(clamp(y * (7/max))) as in quantize_act, eight codes per
-//      dword assembled from two neighbouring lanes.  The wave that owns channel 0 writes the
-//      scales.
+//   4. lane c fetches the final maximum of row c, derives scale = max/7 and 7/max and shares
+//      the reciprocal with the other lanes of the row through `scratch` (LDS, 64 floats per
+//      wave).  code = rne(y * (7/max)) as in quantize_act: |y * (7/max)| <= 7(1+2^-23), so the
+//      clamp of the definition cannot bind and the rounding is done by adding 1.5*2^23 + 8
+//      (round-to-nearest-even of the fp32 add), which leaves code+8 in the low four bits.
+//      Eight codes per dword are assembled from two neighbouring lanes.  The wave that owns
+//      channel 0 writes the scales.
 template <int FM, int FN>
 __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&acc)[FM][FN], const EpiLane<FN> &e,
                                                        int m0, int row_w, int lane, int tid, int panel,
                                                        const float *sa_lds, float *scratch) {
     static_assert(FN == 4 && FM == 2, "32 rows per half wave; two lanes assemble one dword of eight codes");
-    const bool has_bias = g.bias != nullptr, gelu = g.act == W4A4_ACT_GELU;
+    const bool gelu = g.act == W4A4_ACT_GELU;
+    const bool n_ok = e.col_off != kPoison;
     const int h = lane >> 5, c = lane & 31;
-    // 1. outputs in fp32, kept in place
+    // 1. outputs in fp32, kept in place; vmax[i*16 + r] = max over this lane's channels
+    float vmax[32];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -299,34 +295,46 @@ __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&
             const int rl = row_w + i * 32 + 8 * q + 4 * h;
             const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
             const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+            float y[4][FN];
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                const int r = q * 4 + rr;
+            for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    float t = (float)acc[i][j][r] * sav[rr];
-                    float y = t * e.sw[j];
-                    if (has_bias) y = y + e.bias[j];
-                    if (gelu) y = gelu_erf(y);
-                    acc[i][j][r] = __float_as_int(y);
+                    float t = (float)acc[i][j][q * 4 + rr] * sav[rr];
+                    t = t * e.sw[j];
+                    y[rr][j] = t + e.bias[j];                     // 0 without a bias: changes at most the sign of a zero
                 }
+            if (gelu) {                                           // uniform branch around 16 straight-line evaluations
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) y[rr][j] = gelu_erf(y[rr][j]);
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                float v = 0.0f;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    acc[i][j][q * 4 + rr] = __float_as_int(y[rr][j]);
+                    v = fmaxf(v, fabsf(y[rr][j]));
+                }
+                vmax[i * 16 + q * 4 + rr] = n_ok ? v : 0.0f;      // channels past N do not count
             }
         }
-    // 2. row maxima -> global
-    const bool n_ok = e.col_off != kPoison;
+    // 2. butterfly: after the step with offset o a lane keeps the rows whose index bit o equals
+    //    its own lane bit o; after five steps lane c holds the maximum of row c.
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int o = 16; o > 0; o >>= 1) {
+        const bool up = (lane & o) != 0;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            float v = 0.0f;
-#pragma unroll
-            for (int j = 0; j < FN; ++j) v = fmaxf(v, fabsf(__int_as_float(acc[i][j][r])));
-            if (!n_ok) v = 0.0f;                                  // channels past N do not count
-            v = row16_max(v);
-            v = fmaxf(v, __shfl_xor(v, 16, kWave));
-            const int m = m0 + row_w + frag_row(i, r, lane);
-            if (c == 0 && m < g.M) atomicMax(g.rowmax + m, __float_as_uint(v));
+        for (int k = 0; k < o; ++k) {
+            const float keep = up ? vmax[k + o] : vmax[k];
+            const float send = up ? vmax[k] : vmax[k + o];
+            vmax[k] = fmaxf(keep, __shfl_xor(send, o, kWave));
         }
+    }
+    const int m_c = m0 + row_w + frag_row(c >> 4, c & 15, lane);  // the row this lane is responsible for
+    if (m_c < g.M) atomicMax(g.rowmax + m_c, __float_as_uint(vmax[0]));
     // 3. wait for the siblings of the row panel.  Only relaxed device-scope atomics are used
     //    (they are performed at the coherence point and bypass the L1): a release / acquire
     //    FENCE at device scope would write back and invalidate the whole L2 on every poll.
@@ -343,19 +351,24 @@ __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&
         }
     }
     __syncthreads();
-    // 4. ranges: lane (c, h) owns row index c = i*16 + r of its half wave
+    // 4. ranges
     {
-        const int m = m0 + row_w + frag_row(c >> 4, c & 15, lane);
         const __amdgpu_buffer_rsrc_t mx_rsrc = make_rsrc(g.rowmax, (uint32_t)g.M * 4u);
         // an ordinary load that bypasses the non-coherent cache levels (sc0 | sc1); rows >= M read 0
-        const float amax = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(mx_rsrc, m * 4, 0, 17));
+        const float amax = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(mx_rsrc, m_c * 4, 0, 17));
         const Range rg = range_sym(amax);
-        if (m < g.M && __shfl(e.col_off, lane & 32, kWave) == 0)
-            g.out_scale[m] = rg.S;                                // this wave holds channel 0 of the row
+        if (m_c < g.M && __shfl(e.col_off, lane & 32, kWave) == 0)
+            g.out_scale[m_c] = rg.S;                              // this wave holds channel 0 of the row
         scratch[(tid & ~63) + lane] = rg.inv;
         __builtin_amdgcn_wave_barrier();
     }
-    uint8_t *outq = static_cast<uint8_t *>(g.out);
+    // packed rows are N/2 bytes; even lanes store a dword of eight codes, everything else is
+    // sent to an offset the bounds check of the descriptor drops
+    const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(g.out, (uint32_t)((long)g.M * (g.N / 2)));
+    const uint32_t row_b = (uint32_t)g.N / 2;
+    const uint32_t lane_q = ((lane & 1) == 0 && n_ok)
+                                ? (uint32_t)(m0 + row_w + 4 * h) * row_b + (uint32_t)(e.nc >> 1) : kPoison;
+    constexpr float kMagic = 12582912.0f + 8.0f;                  // 1.5 * 2^23 + 8
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -365,19 +378,17 @@ __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = q * 4 + rr;
-                const int m = m0 + row_w + frag_row(i, r, lane);
                 uint32_t packed = 0;
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    // code + 8 in [0, 15]; the final xor turns offset binary into two's complement
                     float t = __int_as_float(acc[i][j][r]) * ivv[rr];
-                    t = rintf(fminf(fmaxf(t, -8.0f), 7.0f)) + 8.0f;
-                    packed |= (uint32_t)t << (4 * j);
+                    float u = t + kMagic;                         // low mantissa bits = rne(t) + 8
+                    packed |= (__float_as_uint(u) & 0xFu) << (4 * j);
                 }
-                packed ^= 0x8888u;
+                packed ^= 0x8888u;                                // offset binary -> two's complement
                 const uint32_t other = __shfl_down(packed, 1, kWave);   // the next lane holds the next four channels
-                if ((lane & 1) == 0 && n_ok && m < g.M)
-                    *reinterpret_cast<uint32_t *>(outq + (long)m * (g.N / 2) + (e.nc >> 1)) = packed | (other << 16);
+                __builtin_amdgcn_raw_buffer_store_b32(packed | (other << 16), q_rsrc,
+                                                      lane_q + (uint32_t)(i * 32 + 8 * q + rr) * row_b, 0, 0);
             }
         }
 }
