@@ -16,7 +16,11 @@
  *     are detected before anything is launched and leave the outputs untouched.
  *   - Matrices are row-major.  Packed code matrices hold element 2j of a row in
  *     bits 0..3 and element 2j+1 in bits 4..7 of byte j; signed codes are 4-bit
- *     two's complement in [-8,7], unsigned codes are in [0,15].
+ *     two's complement in [-8,7], unsigned codes are in [0,15].  This is the
+ *     canonical layout (W4A4_LAYOUT_CANONICAL).  Symmetric operands may instead be
+ *     kept in the MFMA operand layout (W4A4_LAYOUT_MFMA, see w4a4_layout), a
+ *     byte-wise bijection of the canonical one that halves the unpacking work of
+ *     the GEMM.
  *   - Base pointers must be 16-byte aligned, K and N multiples of 32 and 8
  *     (row strides multiples of 16 bytes).  Anything else returns
  *     W4A4_ERR_UNSUPPORTED_SHAPE.  M is arbitrary (M == 0 is a no-op).
@@ -46,6 +50,24 @@ typedef enum {
  * mapping (unsigned codes, scale and real-valued zero = the minimum). b = 4. */
 typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
 
+/* Sec. 4.2 packs two INT4 codes per byte and leaves the nibble encoding open.  Two encodings
+ * of SYMMETRIC codes are understood:
+ *   CANONICAL  both nibbles are two's complement; element 2j in bits 0..3, 2j+1 in bits 4..7.
+ *   MFMA       chosen so that ONE bitwise AND per register turns packed codes into int8 MFMA
+ *              operands.  The int8 value of (byte & 0xF0) is 16*code for a two's-complement
+ *              high nibble, and (byte & 0x0F) is code+8 for an offset-binary low nibble, so
+ *                activations: low nibble = element 2j   + 8 (offset binary), high nibble =
+ *                             element 2j+1 (two's complement)   [= canonical byte XOR 0x08]
+ *                weights:     low nibble = element 2j+1 + 8 (offset binary), high nibble =
+ *                             element 2j   (two's complement)
+ *              and low(A) meets high(W), high(A) meets low(W) in the contraction, which then
+ *              yields 16*P + 128*(esum[n] + osum[m]) with
+ *                osum[m] = sum of the ODD-position codes of token m   (kept beside the codes),
+ *                esum[n] = sum of the EVEN-position codes of channel n (kept beside the codes);
+ *              the GEMM removes both terms exactly, in integer arithmetic.
+ * The MFMA layout needs mode == SYM, per-channel weight scales (group == 0) and K % 128 == 0. */
+typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1 } w4a4_layout;
+
 /* Sec. 4.2: GELU (erf form) may sit between the GEMM and the next quantize. */
 typedef enum { W4A4_ACT_NONE = 0, W4A4_ACT_GELU = 1 } w4a4_act_fn;
 
@@ -61,6 +83,11 @@ typedef struct {
                               GEMM read a column slice of a wider packed matrix in place */
     int group;             /* K-group length the gsum was taken over (0 = whole row)     */
     int mode;              /* w4a4_mode */
+    int layout;            /* w4a4_layout of q                                           */
+    const int32_t *osum;   /* layout == MFMA: osum[m*ldo] = sum of the odd-position codes
+                              of the K codes of token m that this view covers; else NULL */
+    int ldo;               /* stride of osum in ELEMENTS (>= 1): a column slice of a wider
+                              matrix points into a [M, slices] array of partial sums     */
 } w4a4_act;
 
 /* A weight matrix quantized offline (App. A, weight quantization), row n = output
@@ -73,6 +100,9 @@ typedef struct {
     int N, K;
     int group;                 /* 0 = one group per output channel, else multiple of 128 */
     int mode;                  /* w4a4_mode */
+    int layout;                /* w4a4_layout of q                                       */
+    const int32_t *esum;       /* [N] layout == MFMA: sum of the even-position codes of a
+                                  channel; else NULL                                     */
 } w4a4_weight;
 
 /* What happens between the int32 accumulators and memory (Sec. 4.2). */
@@ -82,7 +112,12 @@ typedef struct {
     int requant;            /* 0: store fp16 [M,N].  1: quantize each fp32 output row per
                                token and store packed codes [M,N/2] + scale (+ zero,gsum) */
     int requant_mode;       /* w4a4_mode of the requantized output                        */
-    int requant_group;      /* K-group of the NEXT layer's weights, for out_gsum (0=row) */
+    int requant_group;      /* K-group of the NEXT layer's weights, for out_gsum (0=row);
+                               with requant_layout == MFMA: length of the column slices
+                               the odd-position sums are kept for (0 = whole row, else a
+                               multiple of 256 that divides N)                            */
+    int requant_layout;     /* w4a4_layout of the requantized codes (MFMA needs
+                               requant_mode == SYM)                                       */
     int schedule;           /* 0 = pick the tile schedule from the built-in shape table
                                (Sec. 4.2: schedules are pre-tuned per shape); > 0 forces
                                schedule number `schedule` (see w4a4_schedule_count)       */
@@ -114,25 +149,30 @@ size_t w4a4_linear_workspace_bytes(const w4a4_act *A, const w4a4_weight *W, cons
 /* Step a0 (offline): App. A weight quantization of W_f16[N,K] with the Sec. 3.1 mapping.
  * Outputs: q[N,K/2], scale[N,ng], zero[N,ng] (ASYM; may be NULL for SYM),
  * gsum[N,ng] code sums (may be NULL), rowsum_deq[N] (may be NULL; needed for ASYM layers).
- * group: 0 or a multiple of 32 that divides K. */
+ * group: 0 or a multiple of 32 that divides K.
+ * layout == W4A4_LAYOUT_MFMA (SYM, group == 0 only) also needs esum[N]; else esum is ignored. */
 int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
                          uint8_t *q, float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
-                         void *stream);
+                         int layout, int32_t *esum, void *stream);
 
 /* Step a1: token-wise dynamic quantization (App. A) of X_f16[M,K] (row stride ldx
  * ELEMENTS) with the Sec. 3.1 mapping, packed two codes per byte (Sec. 4.2).
  * Outputs: q[M,K/2] (dense rows), scale[M], zero[M] (ASYM only, else may be NULL),
- * gsum[M, K/group] (may be NULL).  K <= 16384. */
+ * gsum[M, K/group] (may be NULL).  K <= 16384.
+ * layout == W4A4_LAYOUT_MFMA (SYM only) also needs osum[M]; else osum is ignored. */
 int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
-                      uint8_t *q, float *scale, float *zero, int32_t *gsum, void *stream);
+                      uint8_t *q, float *scale, float *zero, int32_t *gsum,
+                      int layout, int32_t *osum, void *stream);
 
 /* Steps a2+a3 fused: INT4 x INT4 -> INT32 GEMM (Sec. 4.1 shapes, activations [M,K],
  * weights [N,K]) with the dequantize / zero-point terms / bias / GELU epilogue and
  * either an fp16 store or a per-token requantize (Sec. 4.2) behind it.
  *   out:       fp16 [M,N] (requant == 0) or u8 [M,N/2] (requant == 1)
  *   out_scale: [M], out_zero: [M] (requant_mode ASYM), out_gsum: [M, N/requant_group]
- *              (may be NULL); all ignored when requant == 0.
- * A->mode must equal W->mode, A->K == W->K, and for ASYM A->group == W->group. */
+ *              (may be NULL; with requant_layout == MFMA it is REQUIRED and receives the
+ *              odd-position code sums of each column slice); all ignored when requant == 0.
+ * A->mode must equal W->mode, A->layout == W->layout, A->K == W->K, and for ASYM
+ * A->group == W->group. */
 int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
                 void *out, float *out_scale, float *out_zero, int32_t *out_gsum,
                 void *workspace, size_t workspace_bytes, void *stream);

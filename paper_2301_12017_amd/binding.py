@@ -14,6 +14,7 @@ import torch
 
 SYM, ASYM = 0, 1
 ACT_NONE, ACT_GELU = 0, 1
+LAYOUT_CANONICAL, LAYOUT_MFMA = 0, 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw4a4.so")
@@ -28,19 +29,21 @@ class W4A4Error(RuntimeError):
 class _Act(ctypes.Structure):
     _fields_ = [("q", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
                 ("gsum", ctypes.c_void_p), ("M", ctypes.c_int), ("K", ctypes.c_int),
-                ("lda", ctypes.c_int), ("group", ctypes.c_int), ("mode", ctypes.c_int)]
+                ("lda", ctypes.c_int), ("group", ctypes.c_int), ("mode", ctypes.c_int),
+                ("layout", ctypes.c_int), ("osum", ctypes.c_void_p), ("ldo", ctypes.c_int)]
 
 
 class _Weight(ctypes.Structure):
     _fields_ = [("q", ctypes.c_void_p), ("scale", ctypes.c_void_p), ("zero", ctypes.c_void_p),
                 ("rowsum_deq", ctypes.c_void_p), ("N", ctypes.c_int), ("K", ctypes.c_int),
-                ("group", ctypes.c_int), ("mode", ctypes.c_int)]
+                ("group", ctypes.c_int), ("mode", ctypes.c_int), ("layout", ctypes.c_int),
+                ("esum", ctypes.c_void_p)]
 
 
 class _Epilogue(ctypes.Structure):
     _fields_ = [("bias_f16", ctypes.c_void_p), ("act", ctypes.c_int), ("requant", ctypes.c_int),
                 ("requant_mode", ctypes.c_int), ("requant_group", ctypes.c_int),
-                ("schedule", ctypes.c_int)]
+                ("requant_layout", ctypes.c_int), ("schedule", ctypes.c_int)]
 
 
 _lib = None
@@ -53,8 +56,8 @@ _SIGNATURES = {
     "w4a4_schedule_name": (ctypes.c_char_p, [_i]),
     "w4a4_workspace_bytes": (_sz, [_i, _i, _i, ctypes.POINTER(_Epilogue)]),
     "w4a4_linear_workspace_bytes": (_sz, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _i]),
-    "w4a4_quantize_weight": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp]),
-    "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "w4a4_quantize_weight": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
+    "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
                          _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
@@ -119,12 +122,19 @@ class QAct:
     group: int
     mode: int
     q_offset_bytes: int = 0     # column-slice view: start this many bytes into each row
+    layout: int = LAYOUT_CANONICAL
+    osum: Optional[torch.Tensor] = None   # [M, slices] odd-position code sums (MFMA operand layout)
+    osum_index: int = 0         # which slice of osum this view covers
 
     def c(self) -> _Act:
+        osum, ldo = None, 1
+        if self.osum is not None:
+            ldo = 1 if self.osum.dim() == 1 else self.osum.shape[1]
+            osum = self.osum.data_ptr() + 4 * self.osum_index
         return _Act(self.q.data_ptr() + self.q_offset_bytes, self.scale.data_ptr(),
                     None if self.zero is None else self.zero.data_ptr(),
                     None if self.gsum is None else self.gsum.data_ptr(),
-                    self.M, self.K, self.lda, self.group, self.mode)
+                    self.M, self.K, self.lda, self.group, self.mode, self.layout, osum, ldo)
 
 
 @dataclass
@@ -139,19 +149,22 @@ class QWeight:
     K: int
     group: int
     mode: int
+    layout: int = LAYOUT_CANONICAL
+    esum: Optional[torch.Tensor] = None   # [N] even-position code sums (MFMA operand layout)
 
     def c(self) -> _Weight:
         return _Weight(self.q.data_ptr(), self.scale.data_ptr(),
                        None if self.zero is None else self.zero.data_ptr(),
                        None if self.rowsum_deq is None else self.rowsum_deq.data_ptr(),
-                       self.N, self.K, self.group, self.mode)
+                       self.N, self.K, self.group, self.mode, self.layout,
+                       None if self.esum is None else self.esum.data_ptr())
 
 
 def _ng(K, group):
     return 1 if group == 0 else K // group
 
 
-def quantize_weight(W: torch.Tensor, mode=SYM, group=0) -> QWeight:
+def quantize_weight(W: torch.Tensor, mode=SYM, group=0, layout=LAYOUT_CANONICAL) -> QWeight:
     assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
     N, K = W.shape
     ng = _ng(K, group)
@@ -161,13 +174,15 @@ def quantize_weight(W: torch.Tensor, mode=SYM, group=0) -> QWeight:
     zero = torch.empty((N, ng), dtype=torch.float32, device=dev) if mode == ASYM else None
     gsum = torch.empty((N, ng), dtype=torch.int32, device=dev)
     c = torch.empty((N,), dtype=torch.float32, device=dev)
+    esum = torch.empty((N,), dtype=torch.int32, device=dev) if layout == LAYOUT_MFMA else None
     rc = lib().w4a4_quantize_weight(_ptr(W), N, K, mode, group, _ptr(q), _ptr(scale), _ptr(zero),
-                                    _ptr(gsum), _ptr(c), _stream())
+                                    _ptr(gsum), _ptr(c), layout, _ptr(esum), _stream())
     _check(rc, "w4a4_quantize_weight")
-    return QWeight(q, scale, zero, gsum, c, N, K, group, mode)
+    return QWeight(q, scale, zero, gsum, c, N, K, group, mode, layout, esum)
 
 
-def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None) -> QAct:
+def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None,
+                 layout=LAYOUT_CANONICAL) -> QAct:
     assert X.is_cuda and X.dtype == torch.float16 and X.stride(1) == 1
     M, K = X.shape
     ng = _ng(K, group)
@@ -177,21 +192,23 @@ def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None)
                    torch.empty((M,), dtype=torch.float32, device=dev),
                    torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
                    torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
-                   M, K, K // 2, group, mode)
+                   M, K, K // 2, group, mode, 0, layout,
+                   torch.empty((M,), dtype=torch.int32, device=dev) if layout == LAYOUT_MFMA else None)
     rc = lib().w4a4_quantize_act(_ptr(X), M, K, X.stride(0), mode, group, _ptr(out.q), _ptr(out.scale),
-                                 _ptr(out.zero), _ptr(out.gsum), _stream())
+                                 _ptr(out.zero), _ptr(out.gsum), out.layout, _ptr(out.osum), _stream())
     _check(rc, "w4a4_quantize_act")
     return out
 
 
 def workspace_bytes(M, N, K, requant=False) -> int:
-    ep = _Epilogue(None, 0, int(requant), 0, 0, 0)
+    ep = _Epilogue(None, 0, int(requant), 0, 0, 0, 0)
     return int(lib().w4a4_workspace_bytes(M, N, K, ctypes.byref(ep)))
 
 
 def linear_workspace_bytes(A: "QAct", W: "QWeight", requant=True, requant_mode=SYM, requant_group=0,
-                           want_gsum=False, schedule=0) -> int:
-    ep = _Epilogue(None, 0, int(requant), requant_mode, requant_group, schedule)
+                           want_gsum=False, schedule=0, requant_layout=LAYOUT_CANONICAL) -> int:
+    ep = _Epilogue(None, 0, int(requant), requant_mode, requant_group, requant_layout, schedule)
+    want_gsum = want_gsum or requant_layout == LAYOUT_MFMA
     a, w = A.c(), W.c()
     return int(lib().w4a4_linear_workspace_bytes(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), int(want_gsum)))
 
@@ -201,28 +218,30 @@ def fused_fault(workspace: torch.Tensor, nbytes: int) -> int:
     return int(workspace[:nbytes].view(torch.int32)[-1].item())
 
 
-def _epilogue(bias, act, requant, requant_mode, requant_group, schedule):
+def _epilogue(bias, act, requant, requant_mode, requant_group, schedule, requant_layout=LAYOUT_CANONICAL):
     return _Epilogue(None if bias is None else bias.data_ptr(), act, int(bool(requant)), requant_mode,
-                     requant_group, schedule)
+                     requant_group, requant_layout, schedule)
 
 
-def _alloc_out(A: QAct, W: QWeight, requant, requant_mode, requant_group):
+def _alloc_out(A: QAct, W: QWeight, requant, requant_mode, requant_group, requant_layout=LAYOUT_CANONICAL):
     dev = A.q.device
     if not requant:
         return torch.empty((A.M, W.N), dtype=torch.float16, device=dev), None, None, None
     rng = _ng(W.N, requant_group)
+    sums = requant_mode == ASYM or requant_layout == LAYOUT_MFMA
     return (torch.empty((A.M, W.N // 2), dtype=torch.uint8, device=dev),
             torch.empty((A.M,), dtype=torch.float32, device=dev),
             torch.empty((A.M,), dtype=torch.float32, device=dev) if requant_mode == ASYM else None,
-            torch.empty((A.M, rng), dtype=torch.int32, device=dev) if requant_mode == ASYM else None)
+            torch.empty((A.M, rng), dtype=torch.int32, device=dev) if sums else None)
 
 
 def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NONE, requant=False,
-           requant_mode=SYM, requant_group=0, schedule=0, out=None, workspace: Optional[torch.Tensor] = None):
+           requant_mode=SYM, requant_group=0, schedule=0, out=None, workspace: Optional[torch.Tensor] = None,
+           requant_layout=LAYOUT_CANONICAL):
     """w4a4_linear.  Returns an fp16 tensor [M,N], or a QAct holding the requantized output."""
-    ep = _epilogue(bias, act, requant, requant_mode, requant_group, schedule)
+    ep = _epilogue(bias, act, requant, requant_mode, requant_group, schedule, requant_layout)
     if out is None:
-        out = _alloc_out(A, W, requant, requant_mode, requant_group)
+        out = _alloc_out(A, W, requant, requant_mode, requant_group, requant_layout)
     o, os_, oz, og = out
     a, w = A.c(), W.c()
     need = int(lib().w4a4_linear_workspace_bytes(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep),
@@ -234,6 +253,8 @@ def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NON
     _check(rc, "w4a4_linear")
     if not requant:
         return o
+    if requant_layout == LAYOUT_MFMA:
+        return QAct(o, os_, oz, None, A.M, W.N, W.N // 2, requant_group, requant_mode, 0, LAYOUT_MFMA, og)
     return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)
 
 

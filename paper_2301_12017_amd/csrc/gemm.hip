@@ -10,7 +10,8 @@ struct Schedule {
     const char *name;
     int family;          // 0 = pipelined kernel, codes widened per wave (symmetric, per-channel, K % 128 == 0),
                          // 1 = generic, 2 = pipelined kernel, codes widened once into LDS (K % 64 == 0),
-                         // 3 = pipelined kernel with direct global->LDS loads (K % 128 == 0)
+                         // 3 = pipelined kernel with direct global->LDS loads (K % 128 == 0),
+                         // 4 = persistent kernel on operands in the MFMA operand layout
     int variant;
     bool grouped_ok;     // usable for K-grouped / asymmetric layers
 };
@@ -29,6 +30,7 @@ static const Schedule kSchedules[] = {
     {"pipe8_256x256", 2, 1, false},
     {"dma_128x256", 3, 0, false},
     {"dma_256x256", 3, 1, false},
+    {"olay_128x256", 4, 0, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 
@@ -54,13 +56,21 @@ static int pick_schedule(const GemmArgs &g, bool grouped) {
     return 7;
 }
 
+constexpr int kOlaySchedule = 14;
+
 static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int schedule, hipStream_t st) {
     // the epilogue addresses the output with 32-bit byte offsets below 2^31
     if (((long)g.M + 512) * g.N * 4 >= 0x80000000L) return W4A4_ERR_UNSUPPORTED_SHAPE;   // (tile overhang included)
-    if (schedule == 0) schedule = pick_schedule(g, grouped);
+    const bool olay = g.osum != nullptr;                        // operands in the MFMA operand layout
+    if (schedule == 0) schedule = olay ? kOlaySchedule : pick_schedule(g, grouped);
     if (schedule < 1 || schedule > kNumSchedules) return W4A4_ERR_INVALID_ARG;
     const Schedule &s = kSchedules[schedule - 1];
     if (grouped && !s.grouped_ok) return W4A4_ERR_INVALID_ARG;
+    if (olay != (s.family == 4)) return W4A4_ERR_INVALID_ARG;   // a kernel family understands one layout
+    if (s.family == 4) {
+        if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        return launch_olay(s.variant, out_kind, g, st);
+    }
     if (s.family == 0) {
         if (!pipe_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
         return launch_pipe(s.variant, out_kind, g, st);
@@ -83,6 +93,14 @@ static int check_operands(const w4a4_act *A, const w4a4_weight *W, int *ng_out) 
     if (A->M < 0 || A->K <= 0 || W->N <= 0 || W->K != A->K) return W4A4_ERR_INVALID_ARG;
     if (A->mode != W->mode || (A->mode != W4A4_SYM && A->mode != W4A4_ASYM)) return W4A4_ERR_INVALID_ARG;
     if (W->group < 0 || A->group < 0) return W4A4_ERR_INVALID_ARG;
+    if (A->layout != W->layout) return W4A4_ERR_INVALID_ARG;
+    if (A->layout != W4A4_LAYOUT_CANONICAL && A->layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
+    if (A->layout == W4A4_LAYOUT_MFMA) {
+        if (A->mode != W4A4_SYM || A->ldo < 1) return W4A4_ERR_INVALID_ARG;
+        if (A->M > 0 && (!A->osum || !W->esum)) return W4A4_ERR_INVALID_ARG;
+        if (W->group != 0 && W->group != W->K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (A->K % kBK || A->K < 2 * kBK) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    }
     const int K = A->K;
     if (K % 32 || W->N % 8) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const int G = W->group == 0 ? K : W->group;
@@ -113,6 +131,8 @@ int check_layer(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
     if (ep->requant) {
         if (ep->requant_mode != W4A4_SYM && ep->requant_mode != W4A4_ASYM) return W4A4_ERR_INVALID_ARG;
         if (ep->requant_group < 0) return W4A4_ERR_INVALID_ARG;
+        if (ep->requant_layout != W4A4_LAYOUT_CANONICAL && ep->requant_layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
+        if (ep->requant_layout == W4A4_LAYOUT_MFMA && ep->requant_mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
         const int N = W->N;
         if (N % 32 || N > 8192) return W4A4_ERR_UNSUPPORTED_SHAPE;
         const int rG = ep->requant_group == 0 ? N : ep->requant_group;
@@ -128,7 +148,7 @@ int check_layer(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
 }
 
 int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int group, uint8_t *q,
-                      float *s, float *z, int32_t *gsum, hipStream_t st);
+                      float *s, float *z, int32_t *gsum, hipStream_t st, int layout = 0);
 
 static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int ng) {
     g.Aq = A->q; g.lda = A->lda; g.Wq = W->q; g.ldw = W->K / 2;
@@ -139,6 +159,9 @@ static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int 
     g.bias = nullptr; g.act = W4A4_ACT_NONE; g.out = nullptr;
     g.tiles_m = g.tiles_n = 0;
     g.rowmax = nullptr; g.arrived = nullptr; g.fault = nullptr; g.out_scale = nullptr;
+    const bool olay = A->layout == W4A4_LAYOUT_MFMA;
+    g.osum = olay ? A->osum : nullptr; g.ldo = olay ? A->ldo : 0; g.esum = olay ? W->esum : nullptr;
+    g.out_osum = nullptr; g.osum_slices = 1; g.slice_tiles = 0;
 }
 
 }  // namespace w4a4
@@ -155,6 +178,7 @@ extern "C" const char *w4a4_schedule_name(int schedule) {
 // no code sums wanted, and few enough column tiles that a row panel's workgroups are co-resident.
 static bool fused_requant_ok(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
     if (!ep->requant || ep->requant_mode != W4A4_SYM || want_gsum) return false;
+    if (A->layout != W4A4_LAYOUT_CANONICAL || ep->requant_layout != W4A4_LAYOUT_CANONICAL) return false;
     if (A->mode != W4A4_SYM || W->group != 0) return false;
     if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return false;
     if (ep->schedule != 0 && ep->schedule != 1) return false;
@@ -215,6 +239,10 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
         g.out = out;
         return run_gemm(g, A->mode, grouped, OUT_F16, ep->schedule, st);
     }
+    if (ep->requant_layout == W4A4_LAYOUT_MFMA) {
+        if (!out_gsum) return W4A4_ERR_INVALID_ARG;            // receives the odd-position code sums
+        if (ep->requant_group != 0 && ep->requant_group != W->N) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    }
     if (fused_requant_ok(A, W, ep, out_gsum != nullptr)) {
         // One kernel: the column tiles of a row panel exchange their row maxima through the
         // workspace (zeroed here) and pack the codes from registers.
@@ -235,5 +263,6 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
     rc = run_gemm(g, A->mode, grouped, OUT_F32, ep->schedule, st);
     if (rc) return rc;
     return quantize_rows_f32(static_cast<const float *>(workspace), A->M, W->N, W->N, ep->requant_mode,
-                             ep->requant_group, static_cast<uint8_t *>(out), out_scale, out_zero, out_gsum, st);
+                             ep->requant_group, static_cast<uint8_t *>(out), out_scale, out_zero, out_gsum, st,
+                             ep->requant_layout);
 }

@@ -31,6 +31,11 @@ struct GemmArgs {
     int *arrived;                  // [tiles_m] tiles of the row panel that have published their maxima
     int *fault;                    // [1]       set if a workgroup gave up waiting for its siblings
     float *out_scale;              // [M]
+    // MFMA operand layout: code sums that the contraction picks up (see w4a4_layout)
+    const int32_t *osum; long ldo; // [M * ldo]  odd-position code sums of the tokens
+    const int32_t *esum;           // [N]        even-position code sums of the channels
+    int32_t *out_osum; int osum_slices, slice_tiles;   // requantized output: [M, osum_slices] sums, column
+                                                       // tiles per slice
 };
 
 // Widening of packed codes to int8 without sign extension.  For a packed dword d (codes
@@ -399,5 +404,6 @@ int launch_generic(int variant, int mode, bool grouped, int out_kind, GemmArgs &
 int launch_pipe(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_pipe8(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_dma(int variant, int out_kind, GemmArgs &g, hipStream_t st);
+int launch_olay(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 
 }  // namespace w4a4

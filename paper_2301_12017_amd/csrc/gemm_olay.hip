@@ -1,0 +1,389 @@
+// Persistent INT4 x INT4 -> INT32 GEMM on operands kept in the MFMA operand layout
+// (symmetric codes, per-channel weight scales, K a multiple of 128, K >= 256).
+//
+// What bounds this GEMM on gfx950 is the vector-ALU issue port of a SIMD: an int8
+// 32x32x32 MFMA occupies it for about half of its 32 cycles, and every ordinary VALU
+// instruction for four more.  So the design removes VALU work wherever it can:
+//   * Operand layout (see w4a4_layout in w4a4.h): one v_and_b32 per MFMA operand register
+//     instead of a shift and a mask (3 instead of 4.5 VALU per MFMA for a 64 x 128 wave
+//     tile).  The contraction then yields 16*P + 128*(esum[n] + osum[m]); the two code-sum
+//     terms are taken out with one integer v_add3 per accumulator.
+//   * Tiles travel HBM -> LDS with `buffer_load_dwordx4 ... lds` (no staging registers, no
+//     LDS-write instructions); all DMA addressing is scalar: the per-lane offsets are fixed
+//     for the whole kernel, the tile origin lives in the buffer descriptor (SGPRs) and the
+//     K offset in the instruction's scalar offset.  Rows past M / channels past N fall
+//     outside the descriptor and read as zero.
+//   * LDS rows are unpadded; bank conflicts are avoided by an XOR swizzle of the 16-byte
+//     slots of a row (physical slot = logical chunk ^ ((row >> 2) & 3)).
+//   * Workgroups are persistent and the K steps of successive tiles form ONE stream through
+//     the three LDS stages: while the last two K steps of a tile are multiplied, the first
+//     two of the next tile are already being fetched, so a tile has no load prologue.
+//     Token scales / odd sums go to LDS by 4-byte DMA, channel constants to registers, at
+//     the start of the tile whose epilogue uses them.
+//   * Two workgroups share a CU (2 x 74 KB of LDS), four waves of 64 x 128 each, so one
+//     workgroup's epilogue stores overlap the other's main loop.
+#include "gemm_common.hpp"
+
+namespace w4a4 {
+
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+// s_waitcnt immediate for "vmcnt <= n", lgkmcnt and expcnt unconstrained (gfx9 encoding)
+constexpr int vmcnt_only(int n) { return (n & 0xF) | (0x7 << 4) | (0xF << 8) | (((n >> 4) & 0x3) << 14); }
+
+// One v_and per register: activations give (even codes + 8, 16 * odd codes), weights give
+// (16 * even codes, odd codes + 8); register r of one meets register r of the other.
+__device__ __forceinline__ v4i widen_act(uint32_t x, uint32_t y) {
+    return v4i{(int)(x & 0x0F0F0F0Fu), (int)(x & 0xF0F0F0F0u), (int)(y & 0x0F0F0F0Fu), (int)(y & 0xF0F0F0F0u)};
+}
+__device__ __forceinline__ v4i widen_wgt(uint32_t x, uint32_t y) {
+    return v4i{(int)(x & 0xF0F0F0F0u), (int)(x & 0x0F0F0F0Fu), (int)(y & 0xF0F0F0F0u), (int)(y & 0x0F0F0F0Fu)};
+}
+
+template <int FN>
+struct ChanParams {
+    float sw[FN];      // weight scale / 16 (the accumulators hold 16 * P; a power of two, so exact)
+    float bias[FN];
+    int ne[FN];        // -128 * esum[n]
+};
+
+// Epilogue of one wave for the fp16 / fp32 / int32 outputs.  v = acc - 128*(esum + osum) = 16*P
+// exactly; then y = ((float)v * sa[m]) * (sw[n]/16) (+ bias[n]) (GELU), each operation
+// separately rounded, which equals ((float)P * sa) * sw of the definition bit for bit.
+template <int FM, int FN, int OUT, bool BIAS, bool GELU>
+__device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM][FN], const ChanParams<FN> &cp,
+                                              uint32_t col_off, int m0, int row_w, int lane,
+                                              const float *sa_lds, const int *os_lds) {
+    constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
+    const __amdgpu_buffer_rsrc_t o_rsrc = make_rsrc(g.out, (uint32_t)((long)g.M * g.N * ESZ));
+    const uint32_t row_bytes = (uint32_t)g.N * ESZ;
+    const uint32_t lane_off = (uint32_t)(m0 + row_w + 4 * (lane >> 5)) * row_bytes + col_off;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rl = row_w + i * 32 + 8 * q + 4 * (lane >> 5);          // 4 consecutive rows
+            const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
+            const int4 os4 = *reinterpret_cast<const int4 *>(os_lds + rl);
+            const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+            const int osv[4] = {os4.x, os4.y, os4.z, os4.w};
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = q * 4 + rr;
+                const int no = osv[rr] * -128;
+                const uint32_t off = lane_off + (uint32_t)(i * 32 + 8 * q + rr) * row_bytes;
+                if constexpr (OUT == OUT_I32) {
+                    uint32_t w[FN];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) w[j] = (uint32_t)((acc[i][j][r] + cp.ne[j] + no) >> 4);
+                    store_words<FN>(o_rsrc, off, w);
+                } else {
+                    float y[FN];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        float t = (float)(acc[i][j][r] + cp.ne[j] + no) * sav[rr];
+                        y[j] = t * cp.sw[j];
+                        if constexpr (BIAS) y[j] = y[j] + cp.bias[j];
+                        if constexpr (GELU) y[j] = gelu_erf(y[j]);
+                    }
+                    if constexpr (OUT == OUT_F32) {
+                        uint32_t w[FN];
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[j]);
+                        store_words<FN>(o_rsrc, off, w);
+                    } else {
+                        store_halves<FN>(o_rsrc, off, y);
+                    }
+                }
+            }
+        }
+}
+
+template <int FM, int FN, int WM, int WN, int OCC, int OUT>
+__global__ __attribute__((amdgpu_flat_work_group_size(WM *WN * 64, WM *WN * 64), amdgpu_waves_per_eu(OCC, OCC)))
+void gemm_olay_kernel(GemmArgs g) {
+    constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN;
+    constexpr int ROWB = kBK / 2;                               // 64 bytes of codes per row per K step
+    constexpr int STAGE = (BM + BN) * ROWB, NS = 3;
+    constexpr int BLOCKS = (BM + BN) / 16;                      // 1 KB DMA blocks per stage
+    constexpr int LD = BLOCKS / NW;                             // tile DMA instructions per wave per K step
+    constexpr int A_LD = (BM / 16) / NW;                        // the first A_LD of them fetch activations
+    constexpr int NF = FM + FN, NM = FM * FN;
+    constexpr int PB = (BM / 64 <= NW / 2) ? BM / 64 : 0;       // waves that fetch token scales (and as many odd sums)
+    static_assert(BLOCKS % NW == 0 && (BM / 16) % NW == 0, "DMA blocks must split evenly over the waves");
+    static_assert(NF <= NM && LD <= NM, "not enough MFMA slots to hide the memory operations");
+    static_assert(BM % 64 == 0 && PB > 0, "token parameters are fetched 64 rows per wave");
+
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
+    // token parameters of the tile, double buffered by tile parity: [2][ sa[BM] | osum[BM] ]
+    uint8_t *par = smem + NS * STAGE;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int total = g.tiles_m * g.tiles_n, stride = gridDim.x;
+    const int KT = g.K / kBK;
+
+    // ---- global -> LDS plan (fixed for the whole kernel) -------------------------------------------
+    // DMA instruction i of this wave fills block b = wave + i*NW of a stage: tile rows 16b..16b+15.
+    // Lane l supplies physical slot (r = l>>2, pc = l&3) of the block = logical chunk pc ^ ((row>>2)&3).
+    int voff[LD];
+#pragma unroll
+    for (int i = 0; i < LD; ++i) {
+        const int row = (wave + i * NW) * 16 + (lane >> 2);
+        const int c = (lane & 3) ^ ((row >> 2) & 3);
+        if (i < A_LD) {
+            voff[i] = row * (int)g.lda + c * 16;
+        } else {
+            // LDS row p of the weight tile holds output channel nl: MFMA column cc of fragment f
+            // is channel cc*FN + f of the wave's span, so a lane ends up with FN adjacent channels.
+            const int p = row - BM;
+            const int w = p / (FN * 32), rem = p % (FN * 32), f = rem / 32, cc = rem % 32;
+            const int nl = w * (FN * 32) + cc * FN + f;
+            voff[i] = nl * (int)g.ldw + c * 16;
+        }
+    }
+    // Descriptors of a tile: base at the tile origin, size = its valid rows.
+    auto a_desc = [&](int m0) {
+        const int rows = min(BM, g.M - m0);
+        return make_rsrc(g.Aq + (long)m0 * g.lda, (uint32_t)((long)(rows - 1) * g.lda + g.K / 2));
+    };
+    auto b_desc = [&](int n0) {
+        const int rows = min(BN, g.N - n0);
+        return make_rsrc(g.Wq + (long)n0 * g.ldw, (uint32_t)((long)rows * g.ldw));
+    };
+    auto dma_one = [&](int i, int stage, __amdgpu_buffer_rsrc_t ra, __amdgpu_buffer_rsrc_t rb, int so) {
+        uint8_t *dst = smem + stage * STAGE + (wave + i * NW) * 1024;
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the kernel's signature; it rejects the LDS cast
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(i < A_LD ? ra : rb, (lds_ptr_t)dst, 16, voff[i], so, 0, 0);
+#else
+        (void)dst; (void)ra; (void)rb; (void)so;
+#endif
+    };
+    // Token parameters by 4-byte DMA: waves [0, PB) fetch 64 scales each, waves [PB, 2 PB) the odd sums.
+    const __amdgpu_buffer_rsrc_t sa_rsrc = make_rsrc(g.sa, (uint32_t)g.M * 4u);
+    const __amdgpu_buffer_rsrc_t os_rsrc = make_rsrc(g.osum, (uint32_t)(((long)(g.M - 1) * g.ldo + 1) * 4));
+    const __amdgpu_buffer_rsrc_t sw_rsrc = make_rsrc(g.sw, (uint32_t)g.N * 4u);
+    const __amdgpu_buffer_rsrc_t es_rsrc = make_rsrc(g.esum, (uint32_t)g.N * 4u);
+    const __amdgpu_buffer_rsrc_t bias_rsrc = make_rsrc(g.bias, g.bias ? (uint32_t)g.N * 2u : 0u);   // no bias: zeros
+    auto dma_params = [&](int m0, int parity) {
+        if (wave < 2 * PB) {
+            const bool is_sa = wave < PB;
+            const int blk = is_sa ? wave : wave - PB;
+            uint8_t *dst = par + parity * (2 * BM * 4) + (is_sa ? 0 : BM * 4) + blk * 256;
+            const int m = m0 + blk * 64 + lane;
+            const int vo = is_sa ? m * 4 : m * (int)g.ldo * 4;
+#if defined(__HIP_DEVICE_COMPILE__)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_sa ? sa_rsrc : os_rsrc, (lds_ptr_t)dst, 4, vo, 0, 0, 0);
+#else
+            (void)dst; (void)vo;
+#endif
+        }
+    };
+
+    // ---- operand fragments -----------------------------------------------------------------------
+    // lane (r = lane&31, h = lane>>5) reads logical chunk ks*2 + h of its row
+    const int swz = ((lane & 31) >> 2) & 3;
+    const int rd0 = (lane & 31) * ROWB + (((lane >> 5) ^ swz) << 4);   // ks = 0;  ks = 1 is rd0 ^ 32
+    int frag_off[NF];
+#pragma unroll
+    for (int f = 0; f < FM; ++f) frag_off[f] = (wm * FM * 32 + f * 32) * ROWB + rd0;
+#pragma unroll
+    for (int f = 0; f < FN; ++f) frag_off[FM + f] = (BM + wn * FN * 32 + f * 32) * ROWB + rd0;
+    auto read_frag = [&](int f, int stage, int ks) {
+        return *reinterpret_cast<const u32x4 *>(smem + stage * STAGE + (frag_off[f] ^ (ks << 5)));
+    };
+    auto widen_lo = [&](int f, const u32x4 &p) { return f < FM ? widen_act(p.x, p.y) : widen_wgt(p.x, p.y); };
+    auto widen_hi = [&](int f, const u32x4 &p) { return f < FM ? widen_act(p.z, p.w) : widen_wgt(p.z, p.w); };
+
+    v16i acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+    // ---- first tile: its first two K steps and parameters --------------------------------------------
+    int vb = blockIdx.x;                                        // virtual block id of the current tile
+    int tile = xcd_tile(vb, total);
+    int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
+    __amdgpu_buffer_rsrc_t a_cur = a_desc(m0), b_cur = b_desc(n0);
+#pragma unroll
+    for (int i = 0; i < LD; ++i) dma_one(i, 0, a_cur, b_cur, 0);
+#pragma unroll
+    for (int i = 0; i < LD; ++i) dma_one(i, 1, a_cur, b_cur, ROWB);
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    u32x4 P0[NF], P1[NF];
+    v4i U0[NF], U1[NF];
+
+    int cur = 0;                                                // LDS stage of the current K step
+    int parity = 0;
+    for (;;) {
+        // first fragments of the tile (its first two K steps are in LDS and published)
+#pragma unroll
+        for (int f = 0; f < NF; ++f) P0[f] = read_frag(f, cur, 0);
+        // ---- tile start: parameters of this tile, origin of the next one ---------------------------
+        dma_params(m0, parity);
+        // channel constants of this lane's FN adjacent channels: raw loads now (channels past N read
+        // as zero), converted when the epilogue starts
+        const int n_lane = n0 + wn * FN * 32 + (lane & 31) * FN;
+        static_assert(FN == 4, "channel constants are fetched four at a time");
+        const u32x4 sw_raw = __builtin_amdgcn_raw_buffer_load_b128(sw_rsrc, n_lane * 4, 0, 0);
+        const u32x4 es_raw = __builtin_amdgcn_raw_buffer_load_b128(es_rsrc, n_lane * 4, 0, 0);
+        const u32x2 bias_raw = __builtin_amdgcn_raw_buffer_load_b64(bias_rsrc, n_lane * 2, 0, 0);
+        const int vb_next = vb + stride;
+        const bool has_next = vb_next < total;
+        const int tile_next = xcd_tile(has_next ? vb_next : vb, total);
+        const int m0n = (tile_next / g.tiles_n) * BM, n0n = (tile_next % g.tiles_n) * BN;
+        const __amdgpu_buffer_rsrc_t a_nxt = a_desc(m0n), b_nxt = b_desc(n0n);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) U0[f] = widen_lo(f, P0[f]);
+
+        // ---- main loop: one iteration = 128 codes of K = four sub-steps of NM MFMAs -------------
+        // The instruction order below is the intended issue order; the scheduling barriers keep
+        // the compiler from regrouping it.  Slot k of a sub-step issues MFMA k and, behind it, the
+        // widening of fragment k for the NEXT sub-step plus at most one LDS read and one DMA.
+#define W4A4_SLOT_BEGIN(Ucur, k)                                                                          \
+    acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
+                                                                   acc[(k) / FN][(k) % FN], 0, 0, 0);    \
+    __builtin_amdgcn_sched_barrier(0);
+        constexpr int kBarSlot = NM - NF;                      // LDS reads of the next stage start here
+        auto k_step = [&](auto last_tag, int kt) {
+            constexpr bool LAST = decltype(last_tag)::value;   // last K step of the tile
+            const int nxt = cur == NS - 1 ? 0 : cur + 1;       // stage of stream step +1
+            const int nx2 = nxt == NS - 1 ? 0 : nxt + 1;       // stage of stream step +2 (= step -1)
+            // stream step +2 is K step kt+2 of this tile, or K step kt+2-KT of the next one (when there
+            // is none: a harmless in-bounds re-read, so that the load counting stays uniform)
+            const bool own = !LAST && kt + 2 < KT;
+            const __amdgpu_buffer_rsrc_t ra = own ? a_cur : a_nxt, rb = own ? b_cur : b_nxt;
+            const int so = (own ? kt + 2 : kt + 2 - KT) * ROWB;
+            // sub-step 0: multiply (ks 0, low); widen (ks 0, high) -> U1; fetch ks 1 -> P1; request
+            //             stream step +2 into the stage every wave finished reading before the last barrier.
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                W4A4_SLOT_BEGIN(U0, k)
+                if (k < NF) U1[k] = widen_hi(k, P0[k]);
+                if (k < NF) P1[k] = read_frag(k, cur, 1);
+                if (k < LD) dma_one(k, nx2, ra, rb, so);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // sub-step 1: multiply (ks 0, high); widen (ks 1, low) -> U0
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                W4A4_SLOT_BEGIN(U1, k)
+                if (k < NF) U0[k] = widen_lo(k, P1[k]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // sub-step 2: multiply (ks 1, low); widen (ks 1, high) -> U1; this wave's loads of stream
+            //             step +1 have landed (vmcnt), and after the barrier everyone's have: fetch its ks 0.
+            //             At the end of a tile BOTH prefetched steps of the next tile are waited for, so
+            //             that the next tile's first barrier does not have to wait for this tile's stores;
+            //             the next tile reads its first fragments itself.
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                W4A4_SLOT_BEGIN(U0, k)
+                if (k < NF) U1[k] = widen_hi(k, P1[k]);
+                if (k == kBarSlot) {
+                    __builtin_amdgcn_s_waitcnt(vmcnt_only(LAST ? 0 : LD));
+                    __builtin_amdgcn_s_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+                }
+                if (!LAST && k >= kBarSlot) P0[k - kBarSlot] = read_frag(k - kBarSlot, nxt, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // sub-step 3: multiply (ks 1, high); widen (next step's ks 0, low) -> U0
+#pragma unroll
+            for (int k = 0; k < NM; ++k) {
+                W4A4_SLOT_BEGIN(U1, k)
+                if (!LAST && k < NF) U0[k] = widen_lo(k, P0[k]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            cur = nxt;
+        };
+        for (int kt = 0; kt < KT - 1; ++kt) k_step(std::false_type{}, kt);
+        k_step(std::true_type{}, KT - 1);
+#undef W4A4_SLOT_BEGIN
+
+        // ---- epilogue of this tile ------------------------------------------------------------------
+        {
+            constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
+            const uint32_t col_off = n_lane < g.N ? (uint32_t)n_lane * ESZ : kPoison;
+            ChanParams<FN> cp;
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                cp.sw[j] = __uint_as_float(sw_raw[j]) * 0.0625f;
+                cp.ne[j] = (int)es_raw[j] * -128;
+                const uint32_t b2 = bias_raw[j >> 1];
+                cp.bias[j] = __half2float(__ushort_as_half((unsigned short)((j & 1) ? b2 >> 16 : b2 & 0xFFFFu)));
+            }
+            const float *sa_lds = reinterpret_cast<const float *>(par + parity * (2 * BM * 4));
+            const int *os_lds = reinterpret_cast<const int *>(par + parity * (2 * BM * 4) + BM * 4);
+            const int row_w = wm * FM * 32;
+            const bool bias = g.bias != nullptr, gelu = g.act == W4A4_ACT_GELU;
+            if (OUT == OUT_I32 || (!bias && !gelu)) olay_epilogue<FM, FN, OUT, false, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
+            else if (bias && !gelu) olay_epilogue<FM, FN, OUT, true, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
+            else if (!bias && gelu) olay_epilogue<FM, FN, OUT, false, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
+            else olay_epilogue<FM, FN, OUT, true, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
+        }
+        if (!has_next) break;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+        vb = vb_next; m0 = m0n; n0 = n0n; a_cur = a_nxt; b_cur = b_nxt; parity ^= 1;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_only(0));                  // no DMA may outlive the workgroup's LDS
+}
+
+template <int FM, int FN, int WM, int WN, int OCC, int OUT>
+static int launch_one(GemmArgs &g, hipStream_t st) {
+    constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+    constexpr size_t lds = 3 * (size_t)(BM + BN) * (kBK / 2) + 2 * 2 * BM * 4;
+    g.tiles_m = (g.M + BM - 1) / BM;
+    g.tiles_n = (g.N + BN - 1) / BN;
+    auto kern = gemm_olay_kernel<FM, FN, WM, WN, OCC, OUT>;
+    static bool attr_set = false;          // benign race: the attribute call is idempotent
+    static int slots = 0;                  // workgroups that are resident at once on this device
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)lds) != hipSuccess)
+            return W4A4_ERR_HIP;
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            return W4A4_ERR_HIP;
+        slots = cus * OCC;
+        attr_set = true;
+    }
+    const long tiles = (long)g.tiles_m * g.tiles_n;
+    if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
+    return launch_status();
+}
+
+template <int OUT>
+static int launch_variant(int variant, GemmArgs &g, hipStream_t st) {
+    switch (variant) {
+        case 0: return launch_one<2, 4, 2, 2, 2, OUT>(g, st);   // 128 x 256, two workgroups per CU
+        default: return W4A4_ERR_INVALID_ARG;
+    }
+}
+
+// Requires: MFMA operand layout on both sides (symmetric codes, per-channel weight scales),
+// K % 128 == 0, K >= 256, M*lda and N*ldw < 2^31, M*ldo*4 < 2^31.
+int launch_olay(int variant, int out_kind, GemmArgs &g, hipStream_t st) {
+    switch (out_kind) {
+        case OUT_F16: return launch_variant<OUT_F16>(variant, g, st);
+        case OUT_F32: return launch_variant<OUT_F32>(variant, g, st);
+        case OUT_I32: return launch_variant<OUT_I32>(variant, g, st);
+        default: return W4A4_ERR_INVALID_ARG;
+    }
+}
+
+}  // namespace w4a4

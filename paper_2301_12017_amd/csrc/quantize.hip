@@ -39,10 +39,15 @@ template <> struct Load8<float> {
 // X: [rows, ldx] elements, first K used.  q: [rows, K/2] bytes.  s,z: [rows].
 // gsum: [rows, ng] code sums over runs of G elements (NULL = not wanted).
 // ITERS = ceil(K / 512): every lane holds ITERS chunks of eight elements.
-template <int MODE, typename T, int ITERS>
+// LAYOUT: 0 = canonical nibbles; 1 = MFMA operand layout of activations (even elements in
+// offset binary, psum[row] = sum of the odd-position codes); 2 = MFMA operand layout of
+// weights (nibbles of a byte swapped, odd elements in offset binary, psum[row] = sum of
+// the even-position codes).  Layouts 1 and 2 exist for symmetric codes only.
+template <int MODE, typename T, int ITERS, int LAYOUT>
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
     const T *__restrict__ X, long ldx, int rows, int K, int G, uint8_t *__restrict__ q,
-    float *__restrict__ s, float *__restrict__ z, int32_t *__restrict__ gsum, int ng) {
+    float *__restrict__ s, float *__restrict__ z, int32_t *__restrict__ gsum, int ng,
+    int32_t *__restrict__ psum) {
     __shared__ int32_t gs[kRowsPerBlock][kMaxGroups];
     const int wave = threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
@@ -83,6 +88,7 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
     }
     const int cpg = G / 8;                         // chunks per code-sum group
     uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
+    int part = 0;                                  // this lane's share of psum
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int c = lane + it * kWave;
@@ -93,11 +99,24 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
             for (int e = 0; e < 8; ++e) {
                 int code = code_of<MODE>(v[it][e], r);
                 sum += code;
-                packed |= (uint32_t)(code & 0xF) << (4 * e);
+                if (LAYOUT == 0) {
+                    packed |= (uint32_t)(code & 0xF) << (4 * e);
+                } else if (LAYOUT == 1) {
+                    if (e & 1) part += code;
+                    packed |= (uint32_t)((code + ((e & 1) ? 0 : 8)) & 0xF) << (4 * e);
+                } else {
+                    if (!(e & 1)) part += code;
+                    packed |= (uint32_t)((code + ((e & 1) ? 8 : 0)) & 0xF) << (4 * (e ^ 1));
+                }
             }
             qr[c] = packed;
             if (gsum) atomicAdd(&gs[wave][c / cpg], sum);
         }
+    }
+    if (LAYOUT != 0) {
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
+        if (lane == 0) psum[row] = part;
     }
     if (gsum) {
         __builtin_amdgcn_wave_barrier();
@@ -124,15 +143,15 @@ __global__ void weight_rowsum_kernel(const float *__restrict__ scale, const floa
     c[n] = acc;
 }
 
-template <int MODE, typename T>
+template <int MODE, typename T, int LAYOUT = 0>
 static int launch_rows(const T *X, long ldx, int rows, int K, int G, uint8_t *q, float *s, float *z,
-                       int32_t *gsum, int ng, hipStream_t st) {
+                       int32_t *gsum, int ng, hipStream_t st, int32_t *psum = nullptr) {
     if (rows == 0) return W4A4_OK;
     const int iters = (K / 8 + kWave - 1) / kWave;
     dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock), block(kRowsPerBlock * kWave);
 #define W4A4_QL(I)                                                                                  \
-    hipLaunchKernelGGL((quantize_rows_kernel<MODE, T, I>), grid, block, 0, st, X, ldx, rows, K, G, q, \
-                       s, z, gsum, ng)
+    hipLaunchKernelGGL((quantize_rows_kernel<MODE, T, I, LAYOUT>), grid, block, 0, st, X, ldx, rows, K, G, q, \
+                       s, z, gsum, ng, psum)
     if (iters <= 1) W4A4_QL(1);
     else if (iters <= 2) W4A4_QL(2);
     else if (iters <= 4) W4A4_QL(4);
@@ -161,14 +180,28 @@ static int check_rows(const void *X, int rows, int K, long ldx, int mode, int gr
 }
 
 // Requantize of fp32 rows (used behind the GEMM); same mapping as quantize_act.
+// layout 1: codes in the MFMA operand layout of activations, gsum[rows] = odd-position sums.
 int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int group, uint8_t *q,
-                      float *s, float *z, int32_t *gsum, hipStream_t st) {
+                      float *s, float *z, int32_t *gsum, hipStream_t st, int layout) {
     int ng = 0;
     int rc = check_rows(Y, rows, K, ld, mode, group, q, s, z, 4, &ng);
     if (rc) return rc;
     const int G = group == 0 ? K : group;
+    if (layout == W4A4_LAYOUT_MFMA)
+        return launch_rows<W4A4_SYM, float, 1>(Y, ld, rows, K, K, q, s, z, nullptr, 1, st, gsum);
     return mode == W4A4_SYM ? launch_rows<W4A4_SYM, float>(Y, ld, rows, K, G, q, s, z, gsum, ng, st)
                             : launch_rows<W4A4_ASYM, float>(Y, ld, rows, K, G, q, s, z, gsum, ng, st);
+}
+
+// Layout check shared by the two quantizer entry points.
+static int check_layout(int layout, int mode, int group, int K, const void *psum, int rows) {
+    if (layout != W4A4_LAYOUT_CANONICAL && layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
+    if (layout == W4A4_LAYOUT_MFMA) {
+        if (mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+        if (group != 0 && group != K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (rows > 0 && !psum) return W4A4_ERR_INVALID_ARG;
+    }
+    return W4A4_OK;
 }
 
 }  // namespace w4a4
@@ -176,12 +209,17 @@ int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int gr
 using namespace w4a4;
 
 extern "C" int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
-                                 uint8_t *q, float *scale, float *zero, int32_t *gsum, void *stream) {
+                                 uint8_t *q, float *scale, float *zero, int32_t *gsum, int layout,
+                                 int32_t *osum, void *stream) {
     int ng = 0;
     int rc = check_rows(X_f16, M, K, ldx, mode, group, q, scale, zero, 2, &ng);
     if (rc) return rc;
+    rc = check_layout(layout, mode, group, K, osum, M);
+    if (rc) return rc;
     const int G = group == 0 ? K : group;
     const __half *X = static_cast<const __half *>(X_f16);
+    if (layout == W4A4_LAYOUT_MFMA)
+        return launch_rows<W4A4_SYM, __half, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream), osum);
     return mode == W4A4_SYM
                ? launch_rows<W4A4_SYM, __half>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream))
                : launch_rows<W4A4_ASYM, __half>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream));
@@ -189,7 +227,7 @@ extern "C" int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int m
 
 extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group, uint8_t *q,
                                     float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
-                                    void *stream) {
+                                    int layout, int32_t *esum, void *stream) {
     // A weight matrix [N,K] with groups of G along K is the row matrix [N*ng, G]:
     // every (channel, group) pair is one independent vector (App. A).
     if (N < 0 || K <= 0 || group < 0) return W4A4_ERR_INVALID_ARG;
@@ -202,11 +240,16 @@ extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, i
     int one = 0;
     int rc = check_rows(W_f16, (int)rows, G, G, mode, 0, q, scale, zero, 2, &one);
     if (rc) return rc;
+    rc = check_layout(layout, mode, group, K, esum, N);
+    if (rc) return rc;
     hipStream_t st = as_stream(stream);
     const __half *W = static_cast<const __half *>(W_f16);
-    rc = mode == W4A4_SYM
-             ? launch_rows<W4A4_SYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st)
-             : launch_rows<W4A4_ASYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st);
+    if (layout == W4A4_LAYOUT_MFMA)
+        rc = launch_rows<W4A4_SYM, __half, 2>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st, esum);
+    else
+        rc = mode == W4A4_SYM
+                 ? launch_rows<W4A4_SYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st)
+                 : launch_rows<W4A4_ASYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st);
     if (rc) return rc;
     if (rowsum_deq && N > 0) {
         hipLaunchKernelGGL(weight_rowsum_kernel, dim3((N + 255) / 256), dim3(256), 0, st, scale,

@@ -42,18 +42,18 @@ def test_version_and_status_strings(b):
     assert len(b.schedule_names()) == b.lib().w4a4_schedule_count() >= 1
 
 
-def _act(b, M=4, K=64, lda=None, mode=0, group=0, ptr=0x1000):
-    return b._Act(ptr, ptr, ptr, ptr, M, K, K // 2 if lda is None else lda, group, mode)
+def _act(b, M=4, K=64, lda=None, mode=0, group=0, ptr=0x1000, layout=0, osum=None, ldo=1):
+    return b._Act(ptr, ptr, ptr, ptr, M, K, K // 2 if lda is None else lda, group, mode, layout, osum, ldo)
 
 
-def _wt(b, N=8, K=64, mode=0, group=0, ptr=0x1000):
-    return b._Weight(ptr, ptr, ptr, ptr, N, K, group, mode)
+def _wt(b, N=8, K=64, mode=0, group=0, ptr=0x1000, layout=0, esum=None):
+    return b._Weight(ptr, ptr, ptr, ptr, N, K, group, mode, layout, esum)
 
 
 def test_argument_errors_are_reported_before_any_launch(b):
     """Pointers here are fake (never dereferenced): every call must fail in validation."""
     L = b.lib()
-    ep = b._Epilogue(None, 0, 0, 0, 0, 0)
+    ep = b._Epilogue(None, 0, 0, 0, 0, 0, 0)
     out = ctypes.c_void_p(0x2000)
 
     def lin(a, w, e=ep, o=out, ws=None, wsb=0, os_=None):
@@ -70,9 +70,9 @@ def test_argument_errors_are_reported_before_any_launch(b):
     assert lin(_act(b, ptr=None), _wt(b)) == -1                       # null operand
     assert lin(_act(b), _wt(b), o=None) == -1                         # null output
     assert lin(_act(b, ptr=0x1004), _wt(b)) == -2                     # misaligned
-    bad_act = b._Epilogue(None, 7, 0, 0, 0, 0)
+    bad_act = b._Epilogue(None, 7, 0, 0, 0, 0, 0)
     assert lin(_act(b), _wt(b), e=bad_act) == -1
-    rq = b._Epilogue(None, 0, 1, 0, 0, 0)
+    rq = b._Epilogue(None, 0, 1, 0, 0, 0, 0)
     assert lin(_act(b), _wt(b, N=32), e=rq, os_=None) == -1           # requant needs out_scale
     assert lin(_act(b), _wt(b, N=32), e=rq, os_=out) == -3            # and a workspace
     assert lin(_act(b), _wt(b, N=8), e=rq, os_=out) == -2             # requant N % 32
@@ -80,6 +80,16 @@ def test_argument_errors_are_reported_before_any_launch(b):
     a = _act(b, K=128, mode=1, group=128); a.gsum = None
     assert lin(a, _wt(b, K=128, mode=1, group=128)) == -1
     assert lin(_act(b, K=256, mode=1, group=0), _wt(b, K=256, mode=1, group=128)) == -1   # group mismatch
+    # operands in the MFMA operand layout: both sides, symmetric, with their code sums, K % 128, K >= 256
+    o = 0x3000
+    assert lin(_act(b, K=256, layout=1, osum=o), _wt(b, K=256)) == -1                     # layouts differ
+    assert lin(_act(b, K=256, layout=1), _wt(b, K=256, layout=1, esum=o)) == -1           # osum missing
+    assert lin(_act(b, K=256, layout=1, osum=o), _wt(b, K=256, layout=1)) == -1           # esum missing
+    assert lin(_act(b, K=256, layout=1, osum=o, ldo=0), _wt(b, K=256, layout=1, esum=o)) == -1
+    assert lin(_act(b, K=128, layout=1, osum=o), _wt(b, K=128, layout=1, esum=o)) == -2   # K < 256
+    assert lin(_act(b, K=256, layout=7, osum=o), _wt(b, K=256, layout=7, esum=o)) == -1
+    rq_bad = b._Epilogue(None, 0, 1, 1, 0, 1, 0)                                          # ASYM codes in the operand layout
+    assert lin(_act(b), _wt(b, N=32), e=rq_bad, os_=out) == -1
     # M == 0 is a successful no-op
     assert lin(_act(b, M=0), _wt(b)) == 0
     assert L.w4a4_gemm_i32(ctypes.byref(_act(b)), ctypes.byref(_wt(b)), None, 0, None) == -1
@@ -89,16 +99,22 @@ def test_argument_errors_are_reported_before_any_launch(b):
 def test_quantize_argument_errors(b):
     L = b.lib()
     p = ctypes.c_void_p(0x1000)
-    assert L.w4a4_quantize_act(None, 4, 64, 64, 0, 0, p, p, None, None, None) == -1
-    assert L.w4a4_quantize_act(p, 4, 48, 48, 0, 0, p, p, None, None, None) == -2
-    assert L.w4a4_quantize_act(p, 4, 64, 32, 0, 0, p, p, None, None, None) == -1      # ldx < K
-    assert L.w4a4_quantize_act(p, 4, 64, 64, 1, 0, p, p, None, None, None) == -1      # ASYM needs zero
-    assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 24, p, p, None, None, None) == -2     # group % 32
-    assert L.w4a4_quantize_act(p, 4, 32768, 32768, 0, 0, p, p, None, None, None) == -2
-    assert L.w4a4_quantize_act(p, 0, 64, 64, 0, 0, p, p, None, None, None) == 0
-    assert L.w4a4_quantize_weight(p, 4, 64, 0, 48, p, p, None, None, None, None) == -2
-    assert L.w4a4_quantize_weight(p, 4, 64, 0, 0, p, p, None, None, p, None) == -1    # rowsum needs gsum
-    assert L.w4a4_quantize_weight(p, 0, 64, 0, 0, p, p, None, None, None, None) == 0
+    assert L.w4a4_quantize_act(None, 4, 64, 64, 0, 0, p, p, None, None, 0, None, None) == -1
+    assert L.w4a4_quantize_act(p, 4, 48, 48, 0, 0, p, p, None, None, 0, None, None) == -2
+    assert L.w4a4_quantize_act(p, 4, 64, 32, 0, 0, p, p, None, None, 0, None, None) == -1      # ldx < K
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 1, 0, p, p, None, None, 0, None, None) == -1      # ASYM needs zero
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 24, p, p, None, None, 0, None, None) == -2     # group % 32
+    assert L.w4a4_quantize_act(p, 4, 32768, 32768, 0, 0, p, p, None, None, 0, None, None) == -2
+    assert L.w4a4_quantize_act(p, 0, 64, 64, 0, 0, p, p, None, None, 0, None, None) == 0
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 0, p, p, None, None, 1, None, None) == -1      # operand layout needs osum
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 1, 0, p, p, p, None, 1, p, None) == -1            # ... and symmetric codes
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 32, p, p, None, None, 1, p, None) == -2        # ... and no K-groups
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 0, p, p, None, None, 5, p, None) == -1
+    assert L.w4a4_quantize_weight(p, 4, 64, 0, 48, p, p, None, None, None, 0, None, None) == -2
+    assert L.w4a4_quantize_weight(p, 4, 64, 0, 0, p, p, None, None, p, 0, None, None) == -1    # rowsum needs gsum
+    assert L.w4a4_quantize_weight(p, 0, 64, 0, 0, p, p, None, None, None, 0, None, None) == 0
+    assert L.w4a4_quantize_weight(p, 4, 64, 0, 0, p, p, None, None, None, 1, None, None) == -1 # operand layout needs esum
+    assert L.w4a4_quantize_weight(p, 4, 64, 0, 32, p, p, None, None, None, 1, p, None) == -2
 
 
 def test_workspace_bytes(b):

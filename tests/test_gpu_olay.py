@@ -1,0 +1,183 @@
+"""GPU-vs-oracle parity for operands kept in the MFMA operand layout (w4a4_layout in w4a4.h).
+
+The oracle knows one packing only (canonical two's-complement nibbles).  The operand layout is
+a byte-wise bijection of it, so every comparison here first maps the device bytes back to
+canonical bytes with the two functions below (bit operations only) and then asks for equality:
+codes, scales, code sums and int32 accumulators bit for bit, fp16 outputs identical without
+GELU and within the fp16 bar with it.
+"""
+import numpy as np
+import pytest
+import torch
+
+from tests.gpu_util import dev, f16_close, has_gpu, host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
+
+SYM = 0
+MFMA = 1
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2301_12017_amd import binding
+    binding.lib()
+    return binding
+
+
+def act_to_canonical(q):
+    """activations: low nibble is offset binary -> flip its top bit"""
+    return q ^ np.uint8(0x08)
+
+
+def wgt_to_canonical(q):
+    """weights: nibbles swapped, low nibble (the odd element) offset binary"""
+    return (q >> 4) | ((((q & 0x0F) ^ 0x08) << 4).astype(np.uint8))
+
+
+def _codes(orc, q_canonical):
+    return orc.unpack(q_canonical, SYM).astype(np.int64)
+
+
+def _rand_x(rng, M, K):
+    return rng.standard_normal((M, K)).astype(np.float32).astype(np.float16)
+
+
+def _rand_w(rng, N, K):
+    return (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+
+
+def _qhost(A, Q):
+    a = dict(q=act_to_canonical(host(A.q)), s=host(A.scale), z=np.zeros(A.M, np.float32), gsum=None)
+    w = dict(q=wgt_to_canonical(host(Q.q)), s=host(Q.scale), gsum=host(Q.gsum), c=host(Q.rowsum_deq))
+    w["z"] = np.zeros_like(w["s"])
+    return a, w
+
+
+@pytest.mark.parametrize("M,K", [(1, 256), (130, 768), (67, 1024), (33, 4096), (3, 8192)])
+def test_quantize_act_operand_layout(B, orc, M, K):
+    rng = np.random.default_rng(900 + M + K)
+    X = _rand_x(rng, M, K)
+    X[0, :] = 0
+    want = orc.quantize_act(X, SYM)
+    A = B.quantize_act(dev(X), SYM, layout=MFMA)
+    assert np.array_equal(act_to_canonical(host(A.q)), want["q"])
+    assert np.array_equal(host(A.scale).view(np.uint32), want["s"].view(np.uint32))
+    codes = _codes(orc, want["q"])
+    assert np.array_equal(host(A.osum).astype(np.int64), codes[:, 1::2].sum(axis=1))
+
+
+def test_quantize_weight_operand_layout(B, orc):
+    rng = np.random.default_rng(901)
+    W = _rand_w(rng, 72, 768)
+    W[3, :] = 0
+    want = orc.quantize_weight(W, SYM, 0)
+    Q = B.quantize_weight(dev(W), SYM, 0, layout=MFMA)
+    assert np.array_equal(wgt_to_canonical(host(Q.q)), want["q"])
+    assert np.array_equal(host(Q.scale).view(np.uint32), want["s"].view(np.uint32))
+    assert np.array_equal(host(Q.gsum), want["gsum"])
+    codes = _codes(orc, want["q"])
+    assert np.array_equal(host(Q.esum).astype(np.int64), codes[:, 0::2].sum(axis=1))
+
+
+def test_layout_argument_errors(B):
+    X = torch.zeros((4, 256), dtype=torch.float16, device="cuda")
+    with pytest.raises(B.W4A4Error):
+        B.quantize_act(X, 1, 0, layout=MFMA)                       # asymmetric codes have no operand layout
+    A = B.quantize_act(X, SYM, layout=MFMA)
+    Wc = B.quantize_weight(torch.zeros((8, 256), dtype=torch.float16, device="cuda"), SYM, 0)
+    with pytest.raises(B.W4A4Error):
+        B.gemm_i32(A, Wc)                                          # layouts of the two operands differ
+    Wm = B.quantize_weight(torch.zeros((8, 256), dtype=torch.float16, device="cuda"), SYM, 0, layout=MFMA)
+    with pytest.raises(B.W4A4Error):
+        B.gemm_i32(A, Wm, schedule=1)                              # that kernel reads canonical codes
+
+
+@pytest.mark.parametrize("M,N,K", [(301, 520, 384), (128, 256, 256), (1, 8, 256), (700, 1032, 1024), (257, 264, 4096)])
+def test_gemm_i32_bit_exact(B, orc, M, N, K):
+    """Several tiles per workgroup, ragged tails in M and N, short and long K streams."""
+    rng = np.random.default_rng(910 + M + N + K)
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    want = orc.gemm_i32(act_to_canonical(host(A.q)), wgt_to_canonical(host(Q.q)), SYM, 0)
+    got = host(B.gemm_i32(A, Q))
+    assert got.shape == want.shape and np.array_equal(got, want)
+
+
+def test_gemm_i32_extreme_codes(B):
+    """All-(-8), all-(+7) and mixed operands at K = 4096: the largest magnitudes the accumulators
+    and the code sums see."""
+    K, M, N = 4096, 200, 264
+
+    def enc_a(c):   # canonical byte of two equal codes -> activation operand byte
+        return ((c & 0xF) | ((c & 0xF) << 4)) ^ 0x08
+
+    def enc_w(c):
+        return (((c + 8) & 0xF) | ((c & 0xF) << 4))
+
+    one = torch.ones(max(M, N), dtype=torch.float32, device="cuda")
+    for ca, cw in ((-8, -8), (7, 7), (7, -8), (-8, 7)):
+        Aq = torch.full((M, K // 2), enc_a(ca), dtype=torch.uint8, device="cuda")
+        Wq = torch.full((N, K // 2), enc_w(cw), dtype=torch.uint8, device="cuda")
+        osum = torch.full((M,), ca * K // 2, dtype=torch.int32, device="cuda")
+        esum = torch.full((N,), cw * K // 2, dtype=torch.int32, device="cuda")
+        A = B.QAct(Aq, one, None, None, M, K, K // 2, 0, SYM, 0, MFMA, osum)
+        Q = B.QWeight(Wq, one.reshape(-1, 1), None, None, None, N, K, 0, SYM, MFMA, esum)
+        P = host(B.gemm_i32(A, Q))
+        assert (P == ca * cw * K).all(), (ca, cw)
+
+
+@pytest.mark.parametrize("act,with_bias", [(0, True), (1, True), (0, False), (1, False)])
+def test_linear_fp16(B, orc, act, with_bias):
+    rng = np.random.default_rng(920 + act + 2 * with_bias)
+    M, N, K = 419, 776, 512
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16) if with_bias else None
+    a, w = _qhost(A, Q)
+    want = orc.linear(a, w, SYM, 0, bias, act)
+    got = host(B.linear(A, Q, None if bias is None else dev(bias), act))
+    ok, ratio = f16_close(got, want["out"])
+    assert ok, f"tolerance ratio {ratio}"
+    if act == 0:
+        assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16))
+    else:
+        assert np.mean(got.view(np.uint16) == want["out"].view(np.uint16)) > 0.98
+
+
+def test_many_tiles_per_workgroup(B, orc):
+    """More tiles than resident workgroups (2 x 256 CUs): every workgroup walks several tiles, so the
+    K stream crosses tile boundaries; sampled rows are checked against the oracle."""
+    rng = np.random.default_rng(930)
+    M, N, K = 128 * 40, 256 * 30, 256                               # 1200 tiles
+    X = _rand_x(rng, M, K)
+    A = B.quantize_act(dev(X), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    got = host(B.linear(A, Q, dev(bias), 0))
+    rows = np.sort(rng.choice(M, 48, replace=False))
+    a, w = _qhost(A, Q)
+    a = dict(q=a["q"][rows], s=a["s"][rows], z=a["z"][rows], gsum=None)
+    want = orc.linear(a, w, SYM, 0, bias, 0)
+    assert np.array_equal(got[rows].view(np.uint16), want["out"].view(np.uint16))
+    # untouched rows would show up as the fill pattern: every output row was written
+    P = host(B.gemm_i32(A, Q))
+    wantP = orc.gemm_i32(a["q"], w["q"], SYM, 0)
+    assert np.array_equal(P[0][rows], wantP[0])
+
+
+def test_requantized_output_in_operand_layout(B, orc):
+    """The requantizing epilogue can emit the next layer's operand layout directly."""
+    rng = np.random.default_rng(940)
+    M, N, K = 150, 512, 512
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    a, w = _qhost(A, Q)
+    want = orc.linear(a, w, SYM, 0, bias, 0, requant=True, requant_mode=SYM)
+    out = B.linear(A, Q, dev(bias), 0, requant=True, requant_mode=SYM, requant_layout=MFMA)
+    assert out.layout == MFMA
+    assert np.array_equal(act_to_canonical(host(out.q)), want["q"])
+    assert np.array_equal(host(out.scale).view(np.uint32), want["s"].view(np.uint32))
+    codes = _codes(orc, want["q"])
+    assert np.array_equal(host(out.osum).reshape(M).astype(np.int64), codes[:, 1::2].sum(axis=1))

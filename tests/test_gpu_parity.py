@@ -115,6 +115,8 @@ def _schedules(B, grouped, K=128):
     take symmetric per-channel layers with K % 128 == 0; some generic tiles are ungrouped only)."""
     out = []
     for i, name in enumerate(B.schedule_names()):
+        if name.startswith("olay"):                 # reads the MFMA operand layout only (tests/test_gpu_olay.py)
+            continue
         if name.startswith("pipe8"):
             if grouped or K % 64:
                 continue
