@@ -130,6 +130,12 @@ const char *w4a4_status_string(int status);
 int         w4a4_schedule_count(void);
 const char *w4a4_schedule_name(int schedule);
 
+/* The layout in which w4a4_linear is fastest for a layer of this shape (Sec. 4.2: the GEMM
+ * schedule, and with it the operand layout it reads, is fixed per shape ahead of time).  Both
+ * operands of a layer must use the same layout; every layout a layer supports gives identical
+ * results. */
+int w4a4_preferred_layout(int M, int N, int K, int mode, int group);
+
 /* Bytes of device workspace that are enough for w4a4_linear on ANY layer of this shape and
  * epilogue (0 when none is needed; M*N*4 for a requantizing epilogue). */
 size_t w4a4_workspace_bytes(int M, int N, int K, const w4a4_epilogue *ep);

@@ -54,6 +54,7 @@ _SIGNATURES = {
     "w4a4_status_string": (ctypes.c_char_p, [_i]),
     "w4a4_schedule_count": (_i, []),
     "w4a4_schedule_name": (ctypes.c_char_p, [_i]),
+    "w4a4_preferred_layout": (_i, [_i, _i, _i, _i, _i]),
     "w4a4_workspace_bytes": (_sz, [_i, _i, _i, ctypes.POINTER(_Epilogue)]),
     "w4a4_linear_workspace_bytes": (_sz, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _i]),
     "w4a4_quantize_weight": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
@@ -94,6 +95,10 @@ def status_string(status: int) -> str:
 def schedule_names():
     L = lib()
     return [L.w4a4_schedule_name(i + 1).decode() for i in range(L.w4a4_schedule_count())]
+
+
+def preferred_layout(M: int, N: int, K: int, mode=SYM, group=0) -> int:
+    return int(lib().w4a4_preferred_layout(M, N, K, mode, group))
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -256,6 +261,51 @@ def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NON
     if requant_layout == LAYOUT_MFMA:
         return QAct(o, os_, oz, None, A.M, W.N, W.N // 2, requant_group, requant_mode, 0, LAYOUT_MFMA, og)
     return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)
+
+
+class PreparedLinear:
+    """A w4a4_linear call with every argument marshalled once: calling the object only makes the
+    C call on the current stream.  For loops that must not be slowed down by Python (benchmarks,
+    graph capture).  The tensors it was built from are kept alive."""
+
+    def __init__(self, A: QAct, W: QWeight, bias=None, act=ACT_NONE, requant=False, requant_mode=SYM,
+                 requant_group=0, schedule=0, out=None, workspace=None, requant_layout=LAYOUT_CANONICAL):
+        self.keep = (A, W, bias, out, workspace)
+        self.ep = _epilogue(bias, act, requant, requant_mode, requant_group, schedule, requant_layout)
+        if out is None:
+            out = _alloc_out(A, W, requant, requant_mode, requant_group, requant_layout)
+        self.out = out
+        self.a, self.w = A.c(), W.c()
+        need = int(lib().w4a4_linear_workspace_bytes(ctypes.byref(self.a), ctypes.byref(self.w),
+                                                     ctypes.byref(self.ep), 0 if out[3] is None else 1))
+        if need and workspace is None:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=A.q.device)
+        self.workspace = workspace
+        self.args = (ctypes.byref(self.a), ctypes.byref(self.w), ctypes.byref(self.ep), _ptr(out[0]), _ptr(out[1]),
+                     _ptr(out[2]), _ptr(out[3]), _ptr(workspace), 0 if workspace is None else workspace.numel())
+        self.fn = lib().w4a4_linear
+
+    def __call__(self, stream=None):
+        rc = self.fn(*self.args, _stream() if stream is None else stream)
+        if rc:
+            raise W4A4Error(rc, "w4a4_linear")
+
+
+class PreparedQuantizeAct:
+    """A w4a4_quantize_act call with its arguments marshalled once (see PreparedLinear)."""
+
+    def __init__(self, X: torch.Tensor, out: QAct):
+        assert X.is_cuda and X.dtype == torch.float16 and X.stride(1) == 1
+        self.keep = (X, out)
+        M, K = X.shape
+        self.args = (_ptr(X), M, K, X.stride(0), out.mode, out.group, _ptr(out.q), _ptr(out.scale), _ptr(out.zero),
+                     _ptr(out.gsum), out.layout, _ptr(out.osum))
+        self.fn = lib().w4a4_quantize_act
+
+    def __call__(self, stream=None):
+        rc = self.fn(*self.args, _stream() if stream is None else stream)
+        if rc:
+            raise W4A4Error(rc, "w4a4_quantize_act")
 
 
 def gemm_i32(A: QAct, W: QWeight, schedule=0) -> torch.Tensor:

@@ -31,6 +31,7 @@ static const Schedule kSchedules[] = {
     {"dma_128x256", 3, 0, false},
     {"dma_256x256", 3, 1, false},
     {"olay_128x256", 4, 0, false},
+    {"olay_192x128", 4, 1, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 
@@ -56,13 +57,26 @@ static int pick_schedule(const GemmArgs &g, bool grouped) {
     return 7;
 }
 
-constexpr int kOlaySchedule = 14;
+constexpr int kOlaySchedule = 14;                             // olay_128x256; +1 = olay_192x128
+
+// Tile choice of the persistent kernel: two workgroups share a CU's matrix pipe, so what counts is
+// the largest number of tiles any CU ends up with (workgroups b and b + 256 share a CU) times the
+// tile area; the 192 x 128 tile unpacks 11 % more operand registers per MFMA.
+static int pick_olay(const GemmArgs &g) {
+    const long cus = 256;
+    auto cost = [&](int bm, int bn, double penalty) {
+        const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
+        const long per_cu = (tiles + cus - 1) / cus;
+        return (double)per_cu * bm * bn * penalty;
+    };
+    return cost(128, 256, 1.0) <= cost(192, 128, 1.08) ? kOlaySchedule : kOlaySchedule + 1;
+}
 
 static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int schedule, hipStream_t st) {
     // the epilogue addresses the output with 32-bit byte offsets below 2^31
     if (((long)g.M + 512) * g.N * 4 >= 0x80000000L) return W4A4_ERR_UNSUPPORTED_SHAPE;   // (tile overhang included)
     const bool olay = g.osum != nullptr;                        // operands in the MFMA operand layout
-    if (schedule == 0) schedule = olay ? kOlaySchedule : pick_schedule(g, grouped);
+    if (schedule == 0) schedule = olay ? pick_olay(g) : pick_schedule(g, grouped);
     if (schedule < 1 || schedule > kNumSchedules) return W4A4_ERR_INVALID_ARG;
     const Schedule &s = kSchedules[schedule - 1];
     if (grouped && !s.grouped_ok) return W4A4_ERR_INVALID_ARG;
@@ -169,6 +183,14 @@ static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int 
 using namespace w4a4;
 
 extern "C" int w4a4_schedule_count(void) { return kNumSchedules; }
+
+extern "C" int w4a4_preferred_layout(int M, int N, int K, int mode, int group) {
+    (void)N;
+    // the operand layout exists for symmetric per-channel layers whose K the persistent kernel accepts;
+    // small token counts (latency-bound, a handful of 128-row tiles) stay on the canonical kernels
+    if (mode != W4A4_SYM || (group != 0 && group != K) || K % kBK || K < 2 * kBK) return W4A4_LAYOUT_CANONICAL;
+    return M >= 2048 ? W4A4_LAYOUT_MFMA : W4A4_LAYOUT_CANONICAL;
+}
 
 extern "C" const char *w4a4_schedule_name(int schedule) {
     return (schedule >= 1 && schedule <= kNumSchedules) ? kSchedules[schedule - 1].name : "";

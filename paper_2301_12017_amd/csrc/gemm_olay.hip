@@ -109,10 +109,10 @@ void gemm_olay_kernel(GemmArgs g) {
     constexpr int LD = BLOCKS / NW;                             // tile DMA instructions per wave per K step
     constexpr int A_LD = (BM / 16) / NW;                        // the first A_LD of them fetch activations
     constexpr int NF = FM + FN, NM = FM * FN;
-    constexpr int PB = (BM / 64 <= NW / 2) ? BM / 64 : 0;       // waves that fetch token scales (and as many odd sums)
+    constexpr int PB = BM / 64;                                 // 64-row blocks of token scales (and as many of odd sums)
     static_assert(BLOCKS % NW == 0 && (BM / 16) % NW == 0, "DMA blocks must split evenly over the waves");
     static_assert(NF <= NM && LD <= NM, "not enough MFMA slots to hide the memory operations");
-    static_assert(BM % 64 == 0 && PB > 0, "token parameters are fetched 64 rows per wave");
+    static_assert(BM % 64 == 0, "token parameters are fetched 64 rows per DMA instruction");
 
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     // token parameters of the tile, double buffered by tile parity: [2][ sa[BM] | osum[BM] ]
@@ -167,17 +167,21 @@ void gemm_olay_kernel(GemmArgs g) {
     const __amdgpu_buffer_rsrc_t es_rsrc = make_rsrc(g.esum, (uint32_t)g.N * 4u);
     const __amdgpu_buffer_rsrc_t bias_rsrc = make_rsrc(g.bias, g.bias ? (uint32_t)g.N * 2u : 0u);   // no bias: zeros
     auto dma_params = [&](int m0, int parity) {
-        if (wave < 2 * PB) {
-            const bool is_sa = wave < PB;
-            const int blk = is_sa ? wave : wave - PB;
-            uint8_t *dst = par + parity * (2 * BM * 4) + (is_sa ? 0 : BM * 4) + blk * 256;
-            const int m = m0 + blk * 64 + lane;
-            const int vo = is_sa ? m * 4 : m * (int)g.ldo * 4;
+#pragma unroll
+        for (int b0 = 0; b0 < 2 * PB; b0 += NW) {
+            const int b = b0 + wave;                            // block b: scales of rows 64b.. (b < PB), else odd sums
+            if (b < 2 * PB) {
+                const bool is_sa = b < PB;
+                const int blk = is_sa ? b : b - PB;
+                uint8_t *dst = par + parity * (2 * BM * 4) + (is_sa ? 0 : BM * 4) + blk * 256;
+                const int m = m0 + blk * 64 + lane;
+                const int vo = is_sa ? m * 4 : m * (int)g.ldo * 4;
 #if defined(__HIP_DEVICE_COMPILE__)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(is_sa ? sa_rsrc : os_rsrc, (lds_ptr_t)dst, 4, vo, 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(is_sa ? sa_rsrc : os_rsrc, (lds_ptr_t)dst, 4, vo, 0, 0, 0);
 #else
-            (void)dst; (void)vo;
+                (void)dst; (void)vo;
 #endif
+            }
         }
     };
 
@@ -230,10 +234,20 @@ void gemm_olay_kernel(GemmArgs g) {
         // channel constants of this lane's FN adjacent channels: raw loads now (channels past N read
         // as zero), converted when the epilogue starts
         const int n_lane = n0 + wn * FN * 32 + (lane & 31) * FN;
-        static_assert(FN == 4, "channel constants are fetched four at a time");
-        const u32x4 sw_raw = __builtin_amdgcn_raw_buffer_load_b128(sw_rsrc, n_lane * 4, 0, 0);
-        const u32x4 es_raw = __builtin_amdgcn_raw_buffer_load_b128(es_rsrc, n_lane * 4, 0, 0);
-        const u32x2 bias_raw = __builtin_amdgcn_raw_buffer_load_b64(bias_rsrc, n_lane * 2, 0, 0);
+        static_assert(FN == 4 || FN == 2, "channel constants are fetched two or four at a time");
+        u32x4 sw_raw, es_raw;
+        u32x2 bias_raw;
+        if constexpr (FN == 4) {
+            sw_raw = __builtin_amdgcn_raw_buffer_load_b128(sw_rsrc, n_lane * 4, 0, 0);
+            es_raw = __builtin_amdgcn_raw_buffer_load_b128(es_rsrc, n_lane * 4, 0, 0);
+            bias_raw = __builtin_amdgcn_raw_buffer_load_b64(bias_rsrc, n_lane * 2, 0, 0);
+        } else {
+            const u32x2 s2 = __builtin_amdgcn_raw_buffer_load_b64(sw_rsrc, n_lane * 4, 0, 0);
+            const u32x2 e2 = __builtin_amdgcn_raw_buffer_load_b64(es_rsrc, n_lane * 4, 0, 0);
+            sw_raw = u32x4{s2[0], s2[1], 0, 0};
+            es_raw = u32x4{e2[0], e2[1], 0, 0};
+            bias_raw = u32x2{__builtin_amdgcn_raw_buffer_load_b32(bias_rsrc, n_lane * 2, 0, 0), 0};
+        }
         const int vb_next = vb + stride;
         const bool has_next = vb_next < total;
         const int tile_next = xcd_tile(has_next ? vb_next : vb, total);
@@ -371,6 +385,7 @@ template <int OUT>
 static int launch_variant(int variant, GemmArgs &g, hipStream_t st) {
     switch (variant) {
         case 0: return launch_one<2, 4, 2, 2, 2, OUT>(g, st);   // 128 x 256, two workgroups per CU
+        case 1: return launch_one<3, 2, 2, 2, 2, OUT>(g, st);   // 192 x 128, two workgroups per CU
         default: return W4A4_ERR_INVALID_ARG;
     }
 }

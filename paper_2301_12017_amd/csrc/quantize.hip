@@ -124,6 +124,118 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
     }
 }
 
+// Streaming form of the row quantizer for fp16 activations (step a1, the run-time one).
+// The kernel above is latency-bound: a wave loads its row, waits, reduces, converts, stores,
+// and only then does the next wave of the block slot start.  Here a wave owns `rpw` rows
+// (rows w, w + W, w + 2W ... for W waves in the grid, chosen so that all W are resident) and
+// requests row i+1 before it touches row i, so that nearly the whole input is in flight at
+// once and HBM streams without gaps.  A row stays in registers as raw fp16 (16 bytes per lane
+// per chunk) and is converted twice (range, then codes), which halves the registers of the
+// two row buffers.  Loads go through a buffer descriptor of the row (chunks past K read as
+// zero).  Code sums per K-group are segmented wave reductions (cpg = chunks per group must be
+// a power of two <= 64, or the group is the whole row).
+template <int MODE, int ITERS, int LAYOUT>
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
+    const __half *__restrict__ X, long ldx, int rows, int K, uint8_t *__restrict__ q,
+    float *__restrict__ s, float *__restrict__ z, int32_t *__restrict__ gsum, int ng, int cpg,
+    int32_t *__restrict__ psum) {
+    const int lane = threadIdx.x % kWave;
+    const int nwaves = gridDim.x * kRowsPerBlock;
+    const int nchunks = K / 8;
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    auto load_row = [&](long row, u4 (&raw)[ITERS]) {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<__half *>(X + row * ldx), (short)0, K * 2, 0x00020000);
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it)
+            raw[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, (lane + it * kWave) * 16, 0, 0);
+    };
+    auto unpack8 = [&](const u4 &r, float (&v)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const __half2 h = *reinterpret_cast<const __half2 *>(&reinterpret_cast<const uint32_t *>(&r)[i]);
+            const float2 f = __half22float2(h);
+            v[2 * i] = f.x;
+            v[2 * i + 1] = f.y;
+        }
+    };
+    long row = (long)blockIdx.x * kRowsPerBlock + __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    u4 cur[ITERS], nxt[ITERS];
+    if (row < rows) load_row(row, cur);
+    while (row < rows) {
+        const long next = row + nwaves;
+        if (next < rows) load_row(next, nxt);
+        // ---- range of the row
+        float lo = INFINITY, hi = -INFINITY;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            float v[8];
+            unpack8(cur[it], v);
+            float clo = v[0], chi = MODE == W4A4_SYM ? fabsf(v[0]) : v[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) {
+                if (MODE == W4A4_SYM) chi = fmaxf(chi, fabsf(v[e]));
+                else { chi = fmaxf(chi, v[e]); clo = fminf(clo, v[e]); }
+            }
+            const bool in = lane + it * kWave < nchunks;        // chunks past K hold zeros: keep them out of min/max
+            if (MODE == W4A4_SYM) hi = fmaxf(hi, chi);
+            else { hi = fmaxf(hi, in ? chi : -INFINITY); lo = fminf(lo, in ? clo : INFINITY); }
+        }
+        Range r;
+        if (MODE == W4A4_SYM) r = range_sym(wave_max(hi));
+        else r = range_asym(wave_min(lo), wave_max(hi));
+        if (lane == 0) {
+            s[row] = r.S;
+            if (MODE == W4A4_ASYM) z[row] = r.lo;
+        }
+        // ---- codes
+        uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
+        int part = 0, total = 0;
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int c = lane + it * kWave;
+            float v[8];
+            unpack8(cur[it], v);
+            uint32_t packed = 0;
+            int sum = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int code = code_of<MODE>(v[e], r);
+                sum += code;
+                if (LAYOUT == 0) {
+                    packed |= (uint32_t)(code & 0xF) << (4 * e);
+                } else {
+                    if (e & 1) part += code;
+                    packed |= (uint32_t)((code + ((e & 1) ? 0 : 8)) & 0xF) << (4 * e);
+                }
+            }
+            if (c < nchunks) {
+                qr[c] = packed;
+                total += sum;
+            } else {
+                sum = 0;
+            }
+            if (gsum && ng > 1) {                               // groups of cpg lanes, all inside this `it`
+                for (int o = 1; o < cpg; o <<= 1) sum += __shfl_xor(sum, o, kWave);
+                if ((lane & (cpg - 1)) == 0 && c < nchunks) gsum[row * (long)ng + c / cpg] = sum;
+            }
+        }
+        if (gsum && ng == 1) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) total += __shfl_xor(total, o, kWave);
+            if (lane == 0) gsum[row] = total;
+        }
+        if (LAYOUT != 0) {
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
+            if (lane == 0) psum[row] = part;
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) cur[it] = nxt[it];
+        row = next;
+    }
+}
+
 // c[n] = sum over k of the dequantized weight, group by group in fp32:
 // c = c + (S*RW + G*zero), each operation separately rounded.
 __global__ void weight_rowsum_kernel(const float *__restrict__ scale, const float *__restrict__ zero,
@@ -160,6 +272,40 @@ static int launch_rows(const T *X, long ldx, int rows, int K, int G, uint8_t *q,
     else if (iters <= 32) W4A4_QL(32);
     else return W4A4_ERR_UNSUPPORTED_SHAPE;
 #undef W4A4_QL
+    return launch_status();
+}
+
+// Streaming launch for fp16 activations; returns -100 when the shape needs the general kernel
+// (K-groups whose chunk count is not a power of two <= 64).
+template <int MODE, int LAYOUT>
+static int launch_stream(const __half *X, long ldx, int rows, int K, int G, uint8_t *q, float *s, float *z,
+                         int32_t *gsum, int ng, hipStream_t st, int32_t *psum) {
+    if (rows == 0) return W4A4_OK;
+    const int cpg = G / 8;
+    if (gsum && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return -100;
+    const int iters = (K / 8 + kWave - 1) / kWave;
+    static int cus = 0;
+    if (!cus) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+            return W4A4_ERR_HIP;
+    }
+    // all waves resident at once: 8 per SIMD while the two row buffers are small, fewer for long rows
+    const int occ = iters <= 2 ? 8 : iters <= 4 ? 6 : 3;
+    const long target = (long)cus * 4 * occ;
+    const long rpw = (rows + target - 1) / target;              // rows per wave
+    const long waves = (rows + rpw - 1) / rpw;
+    dim3 grid((unsigned)((waves + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowsPerBlock * kWave);
+#define W4A4_QS(I)                                                                                       \
+    hipLaunchKernelGGL((quantize_stream_kernel<MODE, I, LAYOUT>), grid, block, 0, st, X, ldx, rows, K, q, s, z, \
+                       gsum, ng, cpg, psum)
+    if (iters <= 1) W4A4_QS(1);
+    else if (iters <= 2) W4A4_QS(2);
+    else if (iters <= 4) W4A4_QS(4);
+    else if (iters <= 8) W4A4_QS(8);
+    else return -100;
+#undef W4A4_QS
     return launch_status();
 }
 
@@ -218,6 +364,11 @@ extern "C" int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int m
     if (rc) return rc;
     const int G = group == 0 ? K : group;
     const __half *X = static_cast<const __half *>(X_f16);
+    hipStream_t st = as_stream(stream);
+    rc = layout == W4A4_LAYOUT_MFMA ? launch_stream<W4A4_SYM, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, osum)
+         : mode == W4A4_SYM         ? launch_stream<W4A4_SYM, 0>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, nullptr)
+                                    : launch_stream<W4A4_ASYM, 0>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, nullptr);
+    if (rc != -100) return rc;                                  // else: a shape only the general kernel takes
     if (layout == W4A4_LAYOUT_MFMA)
         return launch_rows<W4A4_SYM, __half, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream), osum);
     return mode == W4A4_SYM

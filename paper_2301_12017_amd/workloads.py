@@ -27,10 +27,15 @@ class Layer:
     host_b: Optional[np.ndarray] = None
 
 
-def make_layer(spec: synth.LinearSpec, cfg: int, index: int, seed: int = 0, keep_host: bool = True) -> Layer:
+def make_layer(spec: synth.LinearSpec, cfg: int, index: int, seed: int = 0, keep_host: bool = True,
+               layout: Optional[int] = None) -> Layer:
+    """Weights of one linear, quantized offline in the layout the library prefers for the shape
+    (or the one asked for)."""
     w = synth.weights(spec.N, spec.K, seed, cfg, 10 * index + 1)
     b = synth.bias(spec.N, seed, cfg, 10 * index + 2)
-    Wq = B.quantize_weight(dev(w), spec.mode, spec.group)
+    if layout is None:
+        layout = B.preferred_layout(spec.M, spec.N, spec.K, spec.mode, spec.group)
+    Wq = B.quantize_weight(dev(w), spec.mode, spec.group, layout=layout)
     return Layer(spec, Wq, dev(b), B.ACT_GELU if spec.gelu else B.ACT_NONE,
                  w if keep_host else None, b if keep_host else None)
 
@@ -43,7 +48,7 @@ def make_input(spec: synth.LinearSpec, cfg: int, index: int, seed: int = 0, M: O
 def run_linear(X: torch.Tensor, layer: Layer, schedule: int = 0, qact: Optional[B.QAct] = None,
                out=None) -> torch.Tensor:
     """quantize_act followed by the fused linear with an fp16 store."""
-    A = B.quantize_act(X, layer.spec.mode, layer.spec.group, out=qact)
+    A = B.quantize_act(X, layer.spec.mode, layer.spec.group, out=qact, layout=layer.W.layout)
     return B.linear(A, layer.W, layer.bias, layer.act, schedule=schedule, out=out)
 
 
@@ -57,12 +62,12 @@ class ChainLayer:
 
 
 def make_chain(n_layers: int, h: int = 1024, ffn: int = 4096, M: int = 32768, cfg: int = 5, seed: int = 0,
-               keep_host: bool = True) -> List[ChainLayer]:
+               keep_host: bool = True, layout: int = B.LAYOUT_CANONICAL) -> List[ChainLayer]:
     layers = []
     for l in range(n_layers):
         specs = [synth.LinearSpec("qkv", M, 3 * h, h), synth.LinearSpec("attn_out", M, h, h),
                  synth.LinearSpec("ffn1", M, ffn, h, True), synth.LinearSpec("ffn2", M, h, ffn)]
-        layers.append(ChainLayer(*[make_layer(s, cfg, 4 * l + j, seed, keep_host) for j, s in enumerate(specs)]))
+        layers.append(ChainLayer(*[make_layer(s, cfg, 4 * l + j, seed, keep_host, layout) for j, s in enumerate(specs)]))
     return layers
 
 

@@ -15,16 +15,31 @@ def host(t):
     return None if t is None else t.detach().cpu().numpy()
 
 
+def act_to_canonical(q):
+    """Bytes of activations in the MFMA operand layout -> canonical bytes (the low nibble is
+    offset binary: flip its top bit).  A pure re-encoding; no arithmetic of the method."""
+    return q ^ np.uint8(0x08)
+
+
+def wgt_to_canonical(q):
+    """Bytes of weights in the MFMA operand layout -> canonical bytes (the nibbles are swapped
+    and the low one, the odd element, is offset binary)."""
+    return ((q >> 4) | (((q & 0x0F) ^ 0x08) << 4)).astype(np.uint8)
+
+
 def qact_host(A):
-    """QAct (device) -> the dict layout the oracle uses."""
-    d = dict(q=host(A.q), s=host(A.scale))
+    """QAct (device) -> the dict layout the oracle uses (codes in the canonical packing)."""
+    q = host(A.q)
+    d = dict(q=act_to_canonical(q) if getattr(A, "layout", 0) == 1 else q, s=host(A.scale))
     d["z"] = host(A.zero) if A.zero is not None else np.zeros(A.M, np.float32)
     d["gsum"] = host(A.gsum) if A.gsum is not None else None
     return d
 
 
 def qweight_host(W):
-    d = dict(q=host(W.q), s=host(W.scale), gsum=host(W.gsum), c=host(W.rowsum_deq))
+    q = host(W.q)
+    d = dict(q=wgt_to_canonical(q) if getattr(W, "layout", 0) == 1 else q, s=host(W.scale),
+             gsum=host(W.gsum), c=host(W.rowsum_deq))
     d["z"] = host(W.zero) if W.zero is not None else np.zeros_like(d["s"])
     return d
 

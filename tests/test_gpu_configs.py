@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import dev, f16_close, has_gpu, host, qact_host, qweight_host
+from tests.gpu_util import act_to_canonical, dev, f16_close, has_gpu, host, qact_host, qweight_host
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -55,7 +55,7 @@ def test_small_workloads_whole(env, orc, cfg):
     for i, spec in enumerate(synth.config_linears(cfg)):
         layer = WL.make_layer(spec, cfg, i)
         X = WL.make_input(spec, cfg, i)
-        A = B.quantize_act(dev(X), spec.mode, spec.group)
+        A = B.quantize_act(dev(X), spec.mode, spec.group, layout=layer.W.layout)
         Y = B.linear(A, layer.W, layer.bias, layer.act)
         rows = np.arange(spec.M)
         oa, ow = _check_linear_rows(orc, B, spec, layer, X, A, Y, rows, exact=True)
@@ -70,13 +70,15 @@ def test_large_workloads_sampled_rows(env, orc, cfg, nrows):
     for i, spec in enumerate(synth.config_linears(cfg)):
         layer = WL.make_layer(spec, cfg, i)
         X = WL.make_input(spec, cfg, i)
-        A = B.quantize_act(dev(X), spec.mode, spec.group)
+        A = B.quantize_act(dev(X), spec.mode, spec.group, layout=layer.W.layout)
         Y = B.linear(A, layer.W, layer.bias, layer.act)
         rows = np.sort(np.concatenate([[0, spec.M - 1], rng.choice(spec.M, nrows - 2, replace=False)]))
         oa, ow = _check_linear_rows(orc, B, spec, layer, X, A, Y, rows, exact=True)
         # int32 accumulators of the sampled rows, through the export entry point
-        sub = B.QAct(A.q[torch.from_numpy(rows).cuda()].contiguous(), A.scale, A.zero, A.gsum, len(rows), spec.K,
-                     spec.K // 2, spec.group, spec.mode)
+        rt = torch.from_numpy(rows).cuda()
+        sub = B.QAct(A.q[rt].contiguous(), A.scale, A.zero, A.gsum, len(rows), spec.K,
+                     spec.K // 2, spec.group, spec.mode, 0, A.layout,
+                     None if A.osum is None else A.osum[rt].contiguous())
         P = host(B.gemm_i32(sub, layer.W))
         assert np.array_equal(P, orc.gemm_i32(oa["q"], ow["q"], spec.mode, spec.group))
         del Y, A, layer

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import dev, f16_close, has_gpu, host
+from tests.gpu_util import act_to_canonical, dev, f16_close, has_gpu, host, wgt_to_canonical
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -23,16 +23,6 @@ def B():
     from paper_2301_12017_amd import binding
     binding.lib()
     return binding
-
-
-def act_to_canonical(q):
-    """activations: low nibble is offset binary -> flip its top bit"""
-    return q ^ np.uint8(0x08)
-
-
-def wgt_to_canonical(q):
-    """weights: nibbles swapped, low nibble (the odd element) offset binary"""
-    return (q >> 4) | ((((q & 0x0F) ^ 0x08) << 4).astype(np.uint8))
 
 
 def _codes(orc, q_canonical):
@@ -93,6 +83,10 @@ def test_layout_argument_errors(B):
         B.gemm_i32(A, Wm, schedule=1)                              # that kernel reads canonical codes
 
 
+def _olay_schedules(B):
+    return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("olay")]
+
+
 @pytest.mark.parametrize("M,N,K", [(301, 520, 384), (128, 256, 256), (1, 8, 256), (700, 1032, 1024), (257, 264, 4096)])
 def test_gemm_i32_bit_exact(B, orc, M, N, K):
     """Several tiles per workgroup, ragged tails in M and N, short and long K streams."""
@@ -100,8 +94,11 @@ def test_gemm_i32_bit_exact(B, orc, M, N, K):
     A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
     Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
     want = orc.gemm_i32(act_to_canonical(host(A.q)), wgt_to_canonical(host(Q.q)), SYM, 0)
-    got = host(B.gemm_i32(A, Q))
-    assert got.shape == want.shape and np.array_equal(got, want)
+    scheds = _olay_schedules(B)
+    assert len(scheds) >= 2
+    for sch in [0] + scheds:
+        got = host(B.gemm_i32(A, Q, schedule=sch))
+        assert got.shape == want.shape and np.array_equal(got, want), sch
 
 
 def test_gemm_i32_extreme_codes(B):
@@ -123,8 +120,9 @@ def test_gemm_i32_extreme_codes(B):
         esum = torch.full((N,), cw * K // 2, dtype=torch.int32, device="cuda")
         A = B.QAct(Aq, one, None, None, M, K, K // 2, 0, SYM, 0, MFMA, osum)
         Q = B.QWeight(Wq, one.reshape(-1, 1), None, None, None, N, K, 0, SYM, MFMA, esum)
-        P = host(B.gemm_i32(A, Q))
-        assert (P == ca * cw * K).all(), (ca, cw)
+        for sch in _olay_schedules(B):
+            P = host(B.gemm_i32(A, Q, schedule=sch))
+            assert (P == ca * cw * K).all(), (ca, cw, sch)
 
 
 @pytest.mark.parametrize("act,with_bias", [(0, True), (1, True), (0, False), (1, False)])
@@ -136,13 +134,14 @@ def test_linear_fp16(B, orc, act, with_bias):
     bias = (rng.standard_normal(N) * 0.01).astype(np.float16) if with_bias else None
     a, w = _qhost(A, Q)
     want = orc.linear(a, w, SYM, 0, bias, act)
-    got = host(B.linear(A, Q, None if bias is None else dev(bias), act))
-    ok, ratio = f16_close(got, want["out"])
-    assert ok, f"tolerance ratio {ratio}"
-    if act == 0:
-        assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16))
-    else:
-        assert np.mean(got.view(np.uint16) == want["out"].view(np.uint16)) > 0.98
+    for sch in _olay_schedules(B):
+        got = host(B.linear(A, Q, None if bias is None else dev(bias), act, schedule=sch))
+        ok, ratio = f16_close(got, want["out"])
+        assert ok, f"schedule {sch}: tolerance ratio {ratio}"
+        if act == 0:
+            assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16)), sch
+        else:
+            assert np.mean(got.view(np.uint16) == want["out"].view(np.uint16)) > 0.98
 
 
 def test_many_tiles_per_workgroup(B, orc):
@@ -154,12 +153,13 @@ def test_many_tiles_per_workgroup(B, orc):
     A = B.quantize_act(dev(X), SYM, layout=MFMA)
     Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
     bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
-    got = host(B.linear(A, Q, dev(bias), 0))
     rows = np.sort(rng.choice(M, 48, replace=False))
     a, w = _qhost(A, Q)
     a = dict(q=a["q"][rows], s=a["s"][rows], z=a["z"][rows], gsum=None)
     want = orc.linear(a, w, SYM, 0, bias, 0)
-    assert np.array_equal(got[rows].view(np.uint16), want["out"].view(np.uint16))
+    for sch in _olay_schedules(B):
+        got = host(B.linear(A, Q, dev(bias), 0, schedule=sch))
+        assert np.array_equal(got[rows].view(np.uint16), want["out"].view(np.uint16)), sch
     # untouched rows would show up as the fill pattern: every output row was written
     P = host(B.gemm_i32(A, Q))
     wantP = orc.gemm_i32(a["q"], w["q"], SYM, 0)
