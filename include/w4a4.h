@@ -188,7 +188,8 @@ int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
 int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream);
 
 /* Step a3 alone: the same epilogue applied to int32 accumulators acc[ng, M, N] that
- * are already in memory.  Outputs as for w4a4_linear.  Needs no workspace. */
+ * are already in memory.  Outputs as for w4a4_linear (requantized codes in the canonical
+ * layout only).  Needs no workspace. */
 int w4a4_dequant_epilogue(const int32_t *acc, const w4a4_act *A, const w4a4_weight *W,
                           const w4a4_epilogue *ep, void *out, float *out_scale, float *out_zero,
                           int32_t *out_gsum, void *stream);

@@ -158,6 +158,7 @@ extern "C" int w4a4_dequant_epilogue(const int32_t *acc, const w4a4_act *A, cons
     int ng = 0, rng = 0;
     int rc = check_layer(A, W, ep, out, out_scale, out_zero, &ng, &rng);
     if (rc) return rc;
+    if (ep->requant && ep->requant_layout != W4A4_LAYOUT_CANONICAL) return W4A4_ERR_UNSUPPORTED_SHAPE;   // canonical codes only
     if (A->M == 0) return W4A4_OK;
     if (!acc) return W4A4_ERR_INVALID_ARG;
     if (!aligned16(acc)) return W4A4_ERR_UNSUPPORTED_SHAPE;

@@ -196,15 +196,30 @@ extern "C" const char *w4a4_schedule_name(int schedule) {
     return (schedule >= 1 && schedule <= kNumSchedules) ? kSchedules[schedule - 1].name : "";
 }
 
-// Fused requantize: symmetric per-channel layer on the pipelined kernel, symmetric output codes,
-// no code sums wanted, and few enough column tiles that a row panel's workgroups are co-resident.
-static bool fused_requant_ok(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
-    if (!ep->requant || ep->requant_mode != W4A4_SYM || want_gsum) return false;
-    if (A->layout != W4A4_LAYOUT_CANONICAL || ep->requant_layout != W4A4_LAYOUT_CANONICAL) return false;
-    if (A->mode != W4A4_SYM || W->group != 0) return false;
-    if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return false;
-    if (ep->schedule != 0 && ep->schedule != 1) return false;
-    return (W->N + 255) / 256 <= 32;
+// Fused requantize (one kernel: the column tiles of a row panel exchange per-token maxima and pack
+// the codes from registers).  Two kernels can do it:
+//   1 = the pipelined kernel on canonical operands, canonical symmetric codes out, no code sums;
+//   2 = the persistent kernel on operands in the MFMA operand layout; symmetric codes out in either
+//       layout (the operand layout with odd-position sums per column slice of requant_group, which
+//       must be whole 256-column tiles).
+// 0 = not fusable: the GEMM stores fp32 rows and the row quantizer packs them.
+static int fused_requant_kind(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
+    if (!ep->requant || ep->requant_mode != W4A4_SYM) return 0;
+    if (A->mode != W4A4_SYM || (W->group != 0 && W->group != W->K)) return 0;
+    if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return 0;
+    const int tn = (W->N + 255) / 256;
+    if (A->layout == W4A4_LAYOUT_MFMA) {
+        if (ep->schedule != 0 && ep->schedule != kOlaySchedule) return 0;
+        if (tn > 32 || A->K < 2 * kBK) return 0;
+        if (ep->requant_layout == W4A4_LAYOUT_MFMA) {
+            const int rg = ep->requant_group == 0 ? W->N : ep->requant_group;
+            return (rg % 256 == 0 || rg == W->N) && W->N % rg == 0 && (rg == W->N || W->N % 256 == 0) ? 2 : 0;
+        }
+        return want_gsum ? 0 : 2;
+    }
+    if (ep->requant_layout != W4A4_LAYOUT_CANONICAL || want_gsum) return 0;
+    if (ep->schedule != 0 && ep->schedule != 1) return 0;
+    return tn <= 32 ? 1 : 0;
 }
 static size_t fused_workspace_bytes(int M) {
     return ((size_t)M + (size_t)(M + 127) / 128 + 4) * sizeof(uint32_t);
@@ -219,13 +234,15 @@ extern "C" size_t w4a4_workspace_bytes(int M, int N, int K, const w4a4_epilogue 
 extern "C" size_t w4a4_linear_workspace_bytes(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
                                               int want_gsum) {
     if (!A || !W || !ep || !ep->requant || A->M <= 0 || W->N <= 0) return 0;
-    if (fused_requant_ok(A, W, ep, want_gsum != 0)) return fused_workspace_bytes(A->M);
+    if (fused_requant_kind(A, W, ep, want_gsum != 0)) return fused_workspace_bytes(A->M);
     return (size_t)A->M * (size_t)W->N * sizeof(float);
 }
 
-__global__ void zero_words_kernel(uint32_t *p, int n) {
+// Clears two word ranges (a fill kernel rather than a memset, so that the call can be captured in a graph).
+__global__ void zero_words_kernel(uint32_t *p, int n, uint32_t *p2, int n2) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
+    else if (i - n < n2) p2[i - n] = 0;
 }
 
 extern "C" int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream) {
@@ -261,22 +278,31 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
         g.out = out;
         return run_gemm(g, A->mode, grouped, OUT_F16, ep->schedule, st);
     }
+    const int fused = fused_requant_kind(A, W, ep, out_gsum != nullptr);
     if (ep->requant_layout == W4A4_LAYOUT_MFMA) {
         if (!out_gsum) return W4A4_ERR_INVALID_ARG;            // receives the odd-position code sums
-        if (ep->requant_group != 0 && ep->requant_group != W->N) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (!fused && ep->requant_group != 0 && ep->requant_group != W->N) return W4A4_ERR_UNSUPPORTED_SHAPE;
     }
-    if (fused_requant_ok(A, W, ep, out_gsum != nullptr)) {
+    if (fused) {
         // One kernel: the column tiles of a row panel exchange their row maxima through the
         // workspace (zeroed here) and pack the codes from registers.
         const int words = (int)(fused_workspace_bytes(A->M) / sizeof(uint32_t));
         uint32_t *wsp = static_cast<uint32_t *>(workspace);
-        hipLaunchKernelGGL(zero_words_kernel, dim3((words + 255) / 256), dim3(256), 0, st, wsp, words);
+        const bool sums = fused == 2 && ep->requant_layout == W4A4_LAYOUT_MFMA;
+        const int rg = ep->requant_group == 0 ? W->N : ep->requant_group;
+        const int slices = sums ? W->N / rg : 1;
+        const long n2 = sums ? (long)A->M * slices : 0;
+        if (n2 + words > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + n2 + 255) / 256)), dim3(256), 0, st, wsp, words,
+                           reinterpret_cast<uint32_t *>(out_gsum), (int)n2);
         g.rowmax = wsp;
         g.arrived = reinterpret_cast<int *>(wsp + A->M);
         g.fault = reinterpret_cast<int *>(wsp + words - 1);
         g.out_scale = out_scale;
         g.out = out;
-        return run_gemm(g, A->mode, false, OUT_Q4, 1, st);
+        g.out_osum = out_gsum; g.osum_slices = slices; g.slice_tiles = sums && slices > 1 ? rg / 256 : 0x40000000;
+        if (fused == 1) return run_gemm(g, A->mode, false, OUT_Q4, 1, st);
+        return run_gemm(g, A->mode, false, sums ? OUT_Q4M : OUT_Q4, kOlaySchedule, st);
     }
     // Requantize: the per-token range needs the whole output row, which no single tile
     // sees.  The GEMM leaves the fp32 rows in the workspace and the row quantizer turns

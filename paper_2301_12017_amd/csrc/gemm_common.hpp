@@ -14,7 +14,7 @@ constexpr int kBK = 128;           // codes per K step
 constexpr int kRowB = 80;          // LDS row pitch in bytes: 64 of codes + 16 of padding
 constexpr int kXcd = 8;
 
-enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2, OUT_Q4 = 3 };   // Q4: per-token requantized codes
+enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2, OUT_Q4 = 3, OUT_Q4M = 4 };   // Q4: per-token requantized codes, canonical; Q4M: in the MFMA operand layout
 
 struct GemmArgs {
     const uint8_t *Aq; long lda;

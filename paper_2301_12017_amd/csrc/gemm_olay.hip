@@ -99,6 +99,160 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
         }
 }
 
+// Fused per-token requantize of one wave's part of the tile (symmetric output codes; Sec. 4.2:
+// the next layer's quantize rides behind bias-add / GELU).  The range of a token needs the whole
+// output row, which is spread over the tiles_n workgroups that hold the row panel's column
+// tiles at this moment (all workgroups of the grid are resident), so:
+//   1. every lane turns its accumulators into the fp32 outputs y (the operation order of the
+//      fp32 store path), keeps them in the accumulator registers and notes max|y| of its four
+//      channels for each of its 32 rows;
+//   2. a butterfly over the 32 lanes that share the rows leaves lane c with the maximum of row
+//      c, which it publishes with ONE atomic max on rowmax[m] (non-negative floats order like
+//      integers);
+//   3. the workgroup announces itself on arrived[panel] and waits until all tiles_n siblings
+//      have (bounded; on expiry *fault is raised instead of hanging);
+//   4. lane c fetches the final maximum of row c, derives scale = max/7 and 7/max and shares the
+//      reciprocal through `scratch` (LDS, 64 floats per wave).  code = rne(y * (7/max)) as in
+//      quantize_act: |y * (7/max)| <= 7(1+2^-23), so the clamp of the definition cannot bind and
+//      the rounding is done by adding 1.5*2^23 + 8 (round-to-nearest-even of the fp32 add), which
+//      leaves code+8 in the low four bits.  Eight codes per dword come from two neighbouring
+//      lanes.  MFMA==true writes the operand layout of activations (even positions stay offset
+//      binary, odd ones become two's complement) and accumulates the odd-position code sums of the
+//      tile's column slice with one atomic add per row and wave; otherwise canonical nibbles.
+template <int FM, int FN, bool MFMA>
+__device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&acc)[FM][FN], const ChanParams<FN> &cp,
+                                                       bool n_ok, int n_lane, int m0, int row_w, int lane, int tid,
+                                                       int panel, int slice, bool first_cols, const float *sa_lds,
+                                                       const int *os_lds, float *scratch) {
+    static_assert(FN == 4 && FM == 2, "32 rows per half wave; two lanes assemble one dword of eight codes");
+    const bool gelu = g.act == W4A4_ACT_GELU;
+    const int h = lane >> 5, c = lane & 31;
+    // 1. outputs in fp32, kept in place; vmax[i*16 + r] = max over this lane's channels
+    float vmax[32];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rl = row_w + i * 32 + 8 * q + 4 * h;
+            const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
+            const int4 os4 = *reinterpret_cast<const int4 *>(os_lds + rl);
+            const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+            const int osv[4] = {os4.x, os4.y, os4.z, os4.w};
+            float y[4][FN];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int no = osv[rr] * -128;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    float t = (float)(acc[i][j][q * 4 + rr] + cp.ne[j] + no) * sav[rr];
+                    t = t * cp.sw[j];
+                    y[rr][j] = t + cp.bias[j];                    // 0 without a bias: changes at most the sign of a zero
+                }
+            }
+            if (gelu) {                                           // uniform branch around 16 straight-line evaluations
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) y[rr][j] = gelu_erf(y[rr][j]);
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                float v = 0.0f;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    acc[i][j][q * 4 + rr] = __float_as_int(y[rr][j]);
+                    v = fmaxf(v, fabsf(y[rr][j]));
+                }
+                vmax[i * 16 + q * 4 + rr] = n_ok ? v : 0.0f;      // channels past N do not count
+            }
+        }
+    // 2. butterfly: after the step with offset o a lane keeps the rows whose index bit o equals
+    //    its own lane bit o; after five steps lane c holds the maximum of row c.
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) {
+        const bool up = (lane & o) != 0;
+#pragma unroll
+        for (int k = 0; k < o; ++k) {
+            const float keep = up ? vmax[k + o] : vmax[k];
+            const float send = up ? vmax[k] : vmax[k + o];
+            vmax[k] = fmaxf(keep, __shfl_xor(send, o, kWave));
+        }
+    }
+    const int m_c = m0 + row_w + frag_row(c >> 4, c & 15, lane);  // the row this lane is responsible for
+    if (m_c < g.M) atomicMax(g.rowmax + m_c, __float_as_uint(vmax[0]));
+    // 3. wait for the siblings of the row panel.  Only relaxed device-scope atomics are used (they
+    //    are performed at the coherence point and bypass the L1): a release / acquire FENCE at
+    //    device scope would write back and invalidate the whole L2 on every poll.  Ordering comes
+    //    from waiting for this wave's atomics to be acknowledged (vmcnt) before the workgroup
+    //    barrier that precedes the counter increment.
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_fetch_add(g.arrived + panel, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0;
+        while (__hip_atomic_load(g.arrived + panel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.tiles_n) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > (1 << 22)) { *g.fault = 1; break; }     // never hang: report and carry on
+        }
+    }
+    __syncthreads();
+    // 4. ranges
+    {
+        const __amdgpu_buffer_rsrc_t mx_rsrc = make_rsrc(g.rowmax, (uint32_t)g.M * 4u);
+        // an ordinary load that bypasses the non-coherent cache levels (sc0 | sc1); rows >= M read 0
+        const float amax = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(mx_rsrc, m_c * 4, 0, 17));
+        const Range rg = range_sym(amax);
+        if (m_c < g.M && first_cols) g.out_scale[m_c] = rg.S;     // the wave that holds channel 0 of the row
+        scratch[(tid & ~63) + lane] = rg.inv;
+        __builtin_amdgcn_wave_barrier();
+    }
+    // packed rows are N/2 bytes; even lanes store a dword of eight codes, everything else is
+    // sent to an offset the bounds check of the descriptor drops
+    const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(g.out, (uint32_t)((long)g.M * (g.N / 2)));
+    const uint32_t row_b = (uint32_t)g.N / 2;
+    const uint32_t lane_q = ((lane & 1) == 0 && n_ok)
+                                ? (uint32_t)(m0 + row_w + 4 * h) * row_b + (uint32_t)(n_lane >> 1) : kPoison;
+    constexpr float kMagic = 12582912.0f + 8.0f;                  // 1.5 * 2^23 + 8
+    int osum[32];                                                 // odd-position code sums + 16 per row (MFMA)
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 iv4 = *reinterpret_cast<const float4 *>(scratch + (tid & ~63) + h * 32 + i * 16 + q * 4);
+            const float ivv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = q * 4 + rr;
+                uint32_t packed = 0;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    float t = __int_as_float(acc[i][j][r]) * ivv[rr];
+                    float u = t + kMagic;                         // low mantissa bits = rne(t) + 8
+                    packed |= (__float_as_uint(u) & 0xFu) << (4 * j);
+                }
+                if (MFMA) osum[i * 16 + r] = n_ok ? (int)(((packed >> 4) & 0xFu) + ((packed >> 12) & 0xFu)) - 16 : 0;
+                packed ^= MFMA ? 0x8080u : 0x8888u;               // offset binary -> two's complement where wanted
+                const uint32_t other = __shfl_down(packed, 1, kWave);   // the next lane holds the next four channels
+                __builtin_amdgcn_raw_buffer_store_b32(packed | (other << 16), q_rsrc,
+                                                      lane_q + (uint32_t)(i * 32 + 8 * q + rr) * row_b, 0, 0);
+            }
+        }
+    if (MFMA) {
+        // the same butterfly with sums: lane c ends with the sum over the wave's 128 channels of row c
+#pragma unroll
+        for (int o = 16; o > 0; o >>= 1) {
+            const bool up = (lane & o) != 0;
+#pragma unroll
+            for (int k = 0; k < o; ++k) {
+                const int keep = up ? osum[k + o] : osum[k];
+                const int send = up ? osum[k] : osum[k + o];
+                osum[k] = keep + __shfl_xor(send, o, kWave);
+            }
+        }
+        if (m_c < g.M) atomicAdd(g.out_osum + (long)m_c * g.osum_slices + slice, osum[0]);
+    }
+}
+
 template <int FM, int FN, int WM, int WN, int OCC, int OUT>
 __global__ __attribute__((amdgpu_flat_work_group_size(WM *WN * 64, WM *WN * 64), amdgpu_waves_per_eu(OCC, OCC)))
 void gemm_olay_kernel(GemmArgs g) {
@@ -209,8 +363,26 @@ void gemm_olay_kernel(GemmArgs g) {
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
     // ---- first tile: its first two K steps and parameters --------------------------------------------
+    // Tile of virtual block id vb (workgroup id + k * grid size; vb % 8 = the XCD it runs on).  Every XCD
+    // owns a contiguous range of tiles, so that the tiles of a row panel run on one XCD and share its
+    // L2.  For the requantizing outputs the ranges are whole row panels: the column tiles of a panel
+    // wait for each other, and a workgroup walks its XCD's tiles in increasing order, which together
+    // rule out a cycle of waits.  Returns false when the XCD has no tile for this id.
+    auto tile_of = [&](int v, int &t) {
+        if constexpr (OUT == OUT_Q4 || OUT == OUT_Q4M) {
+            const int x = v & (kXcd - 1), i = v >> 3;
+            const int per = g.tiles_m / kXcd, rem = g.tiles_m % kXcd;
+            const int cnt = per + (x < rem ? 1 : 0);
+            t = (x * per + (x < rem ? x : rem)) * g.tiles_n + i;
+            return i < cnt * g.tiles_n;
+        } else {
+            t = xcd_tile(v < total ? v : 0, total);
+            return v < total;
+        }
+    };
     int vb = blockIdx.x;                                        // virtual block id of the current tile
-    int tile = xcd_tile(vb, total);
+    int tile;
+    if (!tile_of(vb, tile)) return;                             // (uniform) nothing to do for this workgroup
     int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
     __amdgpu_buffer_rsrc_t a_cur = a_desc(m0), b_cur = b_desc(n0);
 #pragma unroll
@@ -249,8 +421,9 @@ void gemm_olay_kernel(GemmArgs g) {
             bias_raw = u32x2{__builtin_amdgcn_raw_buffer_load_b32(bias_rsrc, n_lane * 2, 0, 0), 0};
         }
         const int vb_next = vb + stride;
-        const bool has_next = vb_next < total;
-        const int tile_next = xcd_tile(has_next ? vb_next : vb, total);
+        int tile_next;
+        const bool has_next = tile_of(vb_next, tile_next);
+        if (!has_next) tile_next = tile;
         const int m0n = (tile_next / g.tiles_n) * BM, n0n = (tile_next % g.tiles_n) * BN;
         const __amdgpu_buffer_rsrc_t a_nxt = a_desc(m0n), b_nxt = b_desc(n0n);
 #pragma unroll
@@ -337,6 +510,14 @@ void gemm_olay_kernel(GemmArgs g) {
             const int *os_lds = reinterpret_cast<const int *>(par + parity * (2 * BM * 4) + BM * 4);
             const int row_w = wm * FM * 32;
             const bool bias = g.bias != nullptr, gelu = g.act == W4A4_ACT_GELU;
+            if constexpr (OUT == OUT_Q4 || OUT == OUT_Q4M) {
+                if constexpr (FM == 2 && FN == 4) {
+                    const int tn = tile % g.tiles_n;
+                    olay_epilogue_requant<FM, FN, OUT == OUT_Q4M>(g, acc, cp, n_lane < g.N, n_lane, m0, row_w, lane, tid,
+                                                                  tile / g.tiles_n, tn / g.slice_tiles, tn == 0 && wn == 0,
+                                                                  sa_lds, os_lds, reinterpret_cast<float *>(par + 2 * 2 * BM * 4));
+                }
+            } else
             if (OUT == OUT_I32 || (!bias && !gelu)) olay_epilogue<FM, FN, OUT, false, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
             else if (bias && !gelu) olay_epilogue<FM, FN, OUT, true, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
             else if (!bias && gelu) olay_epilogue<FM, FN, OUT, false, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
@@ -349,7 +530,7 @@ void gemm_olay_kernel(GemmArgs g) {
             for (int j = 0; j < FN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-        vb = vb_next; m0 = m0n; n0 = n0n; a_cur = a_nxt; b_cur = b_nxt; parity ^= 1;
+        vb = vb_next; tile = tile_next; m0 = m0n; n0 = n0n; a_cur = a_nxt; b_cur = b_nxt; parity ^= 1;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_only(0));                  // no DMA may outlive the workgroup's LDS
 }
@@ -357,7 +538,7 @@ void gemm_olay_kernel(GemmArgs g) {
 template <int FM, int FN, int WM, int WN, int OCC, int OUT>
 static int launch_one(GemmArgs &g, hipStream_t st) {
     constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr size_t lds = 3 * (size_t)(BM + BN) * (kBK / 2) + 2 * 2 * BM * 4;
+    constexpr size_t lds = 3 * (size_t)(BM + BN) * (kBK / 2) + 2 * 2 * BM * 4 + (OUT == OUT_Q4 || OUT == OUT_Q4M ? 1024 : 0);
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     auto kern = gemm_olay_kernel<FM, FN, WM, WN, OCC, OUT>;
@@ -376,7 +557,14 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     }
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
+    unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
+    if (OUT == OUT_Q4 || OUT == OUT_Q4M) {
+        // every XCD walks whole row panels: ids up to 8 * (tiles of the fullest XCD); and the column tiles
+        // of a panel must sit in different workgroups at the same time
+        const long most = (long)((g.tiles_m + kXcd - 1) / kXcd) * g.tiles_n * kXcd;
+        grid = (unsigned)(most < (slots & ~(kXcd - 1)) ? most : (slots & ~(kXcd - 1)));
+        if (g.tiles_n > (int)(grid / kXcd)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    }
     hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
     return launch_status();
 }
@@ -397,6 +585,8 @@ int launch_olay(int variant, int out_kind, GemmArgs &g, hipStream_t st) {
         case OUT_F16: return launch_variant<OUT_F16>(variant, g, st);
         case OUT_F32: return launch_variant<OUT_F32>(variant, g, st);
         case OUT_I32: return launch_variant<OUT_I32>(variant, g, st);
+        case OUT_Q4: return variant == 0 ? launch_one<2, 4, 2, 2, 2, OUT_Q4>(g, st) : W4A4_ERR_INVALID_ARG;
+        case OUT_Q4M: return variant == 0 ? launch_one<2, 4, 2, 2, 2, OUT_Q4M>(g, st) : W4A4_ERR_INVALID_ARG;
         default: return W4A4_ERR_INVALID_ARG;
     }
 }

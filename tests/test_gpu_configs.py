@@ -85,34 +85,44 @@ def test_large_workloads_sampled_rows(env, orc, cfg, nrows):
         torch.cuda.empty_cache()
 
 
-def test_chained_stack_teacher_forced(env, orc):
+@pytest.mark.parametrize("layout,n_layers", [(1, 24), (0, 6)])
+def test_chained_stack_teacher_forced(env, orc, layout, n_layers):
     """Workload 5: 24 layers x (QKV, out, FFN1+GELU, FFN2) at M = 32768, every output requantized
     in the epilogue and fed to the next GEMM as packed codes.  Each GEMM is checked teacher-forced:
-    the oracle receives the GPU's own input codes and scales of that GEMM for a sample of rows."""
+    the oracle receives the GPU's own input codes and scales of that GEMM for a sample of rows.
+    Runs in the layout the library prefers for these shapes (the MFMA operand layout, whole stack)
+    and, for six layers, in the canonical layout."""
     B, synth, WL = env
-    M, h, ffn, n_layers, nrows = 32768, 1024, 4096, 24, 6
+    M, h, ffn, nrows = 32768, 1024, 4096, 6
+    assert B.preferred_layout(M, 3 * h, h) == 1
+    canon = (lambda q: act_to_canonical(q)) if layout == 1 else (lambda q: q)
     rng = np.random.default_rng(5)
     rows = np.sort(np.concatenate([[0, M - 1], rng.choice(M, nrows - 2, replace=False)]))
     rows_t = torch.from_numpy(rows).cuda()
     X = synth.activations(M, h, 0, 5, 0)
-    A0 = B.quantize_act(dev(X), B.SYM)
+    A0 = B.quantize_act(dev(X), B.SYM, layout=layout)
     o0 = orc.quantize_act(np.ascontiguousarray(X[rows]), orc.SYM)
-    assert np.array_equal(host(A0.q[rows_t]), o0["q"])
-    ws = torch.empty(M * ffn * 4, dtype=torch.uint8, device="cuda")
+    assert np.array_equal(canon(host(A0.q[rows_t])), o0["q"])
+    ws = torch.empty(M * 8, dtype=torch.uint8, device="cuda")       # the fused path needs ~4 bytes per token
     A = A0
     mismatched = total = 0
     for l in range(n_layers):
-        layer = WL.make_chain(1, h, ffn, M, 5, seed=l)[0]
+        layer = WL.make_chain(1, h, ffn, M, 5, seed=l, layout=layout)[0]
         rec = []
         A = WL.run_chain(A, [layer], workspace=ws, record=rec)
+        torch.cuda.synchronize()
+        assert int(ws[:(M + M // 128 + 4) * 4].view(torch.int32)[-1].item()) == 0     # no workgroup gave up waiting
         for (_, name, a_in, out, lay) in rec:
             K = lay.spec.K
             off = a_in.q_offset_bytes
-            qin = host(a_in.q[rows_t])[:, off:off + K // 2]
+            qin = canon(host(a_in.q[rows_t]))[:, off:off + K // 2]
             oin = dict(q=np.ascontiguousarray(qin), s=host(a_in.scale[rows_t]), z=np.zeros(nrows, np.float32), gsum=None)
+            if layout == 1:                                         # the odd sums the consumer reads describe these codes
+                osum = host(a_in.osum.reshape(M, -1)[rows_t])[:, a_in.osum_index]
+                assert np.array_equal(osum.astype(np.int64), orc.unpack(oin["q"], 0).astype(np.int64)[:, 1::2].sum(axis=1))
             ow = orc.quantize_weight(lay.host_W, orc.SYM)
             want = orc.linear(oin, ow, orc.SYM, 0, lay.host_b, 1 if lay.spec.gelu else 0, requant=True)
-            gq, gs = host(out.q[rows_t]), host(out.scale[rows_t])
+            gq, gs = canon(host(out.q[rows_t])), host(out.scale[rows_t])
             if lay.spec.gelu:
                 np.testing.assert_allclose(gs, want["s"], rtol=2e-5)
                 gc, wc = orc.unpack(gq, 0).astype(np.int32), orc.unpack(want["q"], 0).astype(np.int32)

@@ -181,3 +181,95 @@ def test_requantized_output_in_operand_layout(B, orc):
     assert np.array_equal(host(out.scale).view(np.uint32), want["s"].view(np.uint32))
     codes = _codes(orc, want["q"])
     assert np.array_equal(host(out.osum).reshape(M).astype(np.int64), codes[:, 1::2].sum(axis=1))
+
+
+def _requant_compare(orc, want, out, gelu, M, N):
+    """Scales and codes of a requantized output against the oracle's (canonical) ones."""
+    gq = host(out.q)
+    if out.layout == MFMA:
+        gq = act_to_canonical(gq)
+    gs = host(out.scale)
+    if not gelu:
+        assert np.array_equal(gs.view(np.uint32), want["s"].view(np.uint32))
+        assert np.array_equal(gq, want["q"])
+        return gq
+    np.testing.assert_allclose(gs, want["s"], rtol=2e-5)
+    gc, wc = orc.unpack(gq, SYM).astype(np.int32), orc.unpack(want["q"], SYM).astype(np.int32)
+    diff = gc != wc
+    t = want["y"].astype(np.float64) / want["s"].astype(np.float64)[:, None]
+    frac = np.abs(t - np.floor(t) - 0.5)
+    assert np.all(np.abs(gc - wc)[diff] == 1) and np.all(frac[diff] < 1e-3)
+    assert diff.mean() < 2e-3
+    return gq
+
+
+@pytest.mark.parametrize("act", [0, 1])
+@pytest.mark.parametrize("M,N,K,group", [(300, 768, 512, 256), (1000, 3072, 256, 1024), (257, 1024, 1024, 0),
+                                         (129, 288, 256, 0)])
+def test_fused_requantize_operand_layout(B, orc, act, M, N, K, group):
+    """One kernel: GEMM, dequantize, bias, (GELU), per-token requantize; codes leave in the operand
+    layout with one odd-position sum per column slice.  Ragged M and (ungrouped) ragged N."""
+    rng = np.random.default_rng(950 + M + N + act)
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    a, w = _qhost(A, Q)
+    want = orc.linear(a, w, SYM, 0, bias, act, requant=True, requant_mode=SYM)
+    need = B.linear_workspace_bytes(A, Q, requant_layout=MFMA, requant_group=group)
+    assert need < M * N                                            # the fused path, not fp32 rows
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    out = B.linear(A, Q, dev(bias), act, requant=True, requant_mode=SYM, requant_layout=MFMA, requant_group=group,
+                   workspace=ws)
+    torch.cuda.synchronize()
+    assert B.fused_fault(ws, need) == 0
+    gq = _requant_compare(orc, want, out, act == 1, M, N)
+    codes = _codes(orc, gq)                                        # the sums must describe the codes that were written
+    G = N if group == 0 else group
+    sums = codes[:, 1::2].reshape(M, N // G, G // 2).sum(axis=2)
+    assert np.array_equal(host(out.osum).reshape(M, -1).astype(np.int64), sums)
+    # the same layer with canonical codes out
+    need_c = B.linear_workspace_bytes(A, Q)
+    ws_c = torch.empty(need_c, dtype=torch.uint8, device="cuda")
+    out_c = B.linear(A, Q, dev(bias), act, requant=True, requant_mode=SYM, workspace=ws_c)
+    torch.cuda.synchronize()
+    assert need_c < M * N and B.fused_fault(ws_c, need_c) == 0 and out_c.layout == 0
+    _requant_compare(orc, want, out_c, act == 1, M, N)
+
+
+def test_fused_requantize_equals_dequant_epilogue(B, orc):
+    """The stand-alone epilogue on exported accumulators reproduces the fused kernel's codes and scales."""
+    rng = np.random.default_rng(960)
+    M, N, K = 391, 1280, 768
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    bias = dev((rng.standard_normal(N) * 0.01).astype(np.float16))
+    P = B.gemm_i32(A, Q)
+    for act in (0, 1):
+        fused = B.linear(A, Q, bias, act, requant=True, requant_mode=SYM, requant_layout=MFMA)
+        alone = B.dequant_epilogue(P, A, Q, bias, act, requant=True, requant_mode=SYM)
+        assert np.array_equal(act_to_canonical(host(fused.q)), host(alone.q)), act
+        assert np.array_equal(host(fused.scale).view(np.uint32), host(alone.scale).view(np.uint32)), act
+
+
+def test_chained_layers_in_operand_layout(B, orc):
+    """Two encoder layers' worth of linears chained through requantized codes in the operand layout,
+    the V third of the QKV output consumed in place; every GEMM teacher-forced against the oracle."""
+    from paper_2301_12017_amd import synth, workloads as WL
+    M, h, ffn = 700, 256, 1024
+    X = synth.activations(M, h, 0, 5, 0)
+    A = B.quantize_act(dev(X), SYM, layout=MFMA)
+    for l in range(2):
+        layer = WL.make_chain(1, h, ffn, M, 5, seed=l, layout=MFMA)[0]
+        rec = []
+        A = WL.run_chain(A, [layer], record=rec)
+        for (_, name, a_in, out, lay) in rec:
+            K = lay.spec.K
+            off = a_in.q_offset_bytes
+            qin = act_to_canonical(host(a_in.q))[:, off:off + K // 2]
+            oin = dict(q=np.ascontiguousarray(qin), s=host(a_in.scale), z=np.zeros(M, np.float32), gsum=None)
+            # the odd sums the consumer reads describe exactly these codes
+            osum = host(a_in.osum).reshape(M, -1)[:, a_in.osum_index]
+            assert np.array_equal(osum.astype(np.int64), _codes(orc, oin["q"])[:, 1::2].sum(axis=1)), (l, name)
+            ow = orc.quantize_weight(lay.host_W, SYM)
+            want = orc.linear(oin, ow, SYM, 0, lay.host_b, 1 if lay.spec.gelu else 0, requant=True)
+            _requant_compare(orc, want, out, lay.spec.gelu, M, lay.spec.N)
