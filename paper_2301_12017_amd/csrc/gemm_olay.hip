@@ -354,13 +354,7 @@ void gemm_olay_kernel(GemmArgs g) {
     auto widen_lo = [&](int f, const u32x4 &p) { return f < FM ? widen_act(p.x, p.y) : widen_wgt(p.x, p.y); };
     auto widen_hi = [&](int f, const u32x4 &p) { return f < FM ? widen_act(p.z, p.w) : widen_wgt(p.z, p.w); };
 
-    v16i acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    v16i acc[FM][FN];                                           // written by the first K step of every tile
 
     // ---- first tile: its first two K steps and parameters --------------------------------------------
     // Tile of virtual block id vb (workgroup id + k * grid size; vb % 8 = the XCD it runs on).  Every XCD
@@ -437,8 +431,15 @@ void gemm_olay_kernel(GemmArgs g) {
     acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
                                                                    acc[(k) / FN][(k) % FN], 0, 0, 0);    \
     __builtin_amdgcn_sched_barrier(0);
+        // the first MFMA into an accumulator of a tile takes a zero C operand (an inline constant), so the
+        // accumulators are never cleared with VALU moves
+#define W4A4_SLOT_BEGIN_ZERO(Ucur, k)                                                                     \
+    acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
+                                                                   v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0); \
+    __builtin_amdgcn_sched_barrier(0);
         constexpr int kBarSlot = NM - NF;                      // LDS reads of the next stage start here
-        auto k_step = [&](auto last_tag, int kt) {
+        auto k_step = [&](auto first_tag, auto last_tag, int kt) {
+            constexpr bool FIRST = decltype(first_tag)::value; // first K step of the tile
             constexpr bool LAST = decltype(last_tag)::value;   // last K step of the tile
             const int nxt = cur == NS - 1 ? 0 : cur + 1;       // stage of stream step +1
             const int nx2 = nxt == NS - 1 ? 0 : nxt + 1;       // stage of stream step +2 (= step -1)
@@ -451,7 +452,7 @@ void gemm_olay_kernel(GemmArgs g) {
             //             stream step +2 into the stage every wave finished reading before the last barrier.
 #pragma unroll
             for (int k = 0; k < NM; ++k) {
-                W4A4_SLOT_BEGIN(U0, k)
+                if constexpr (FIRST) { W4A4_SLOT_BEGIN_ZERO(U0, k) } else { W4A4_SLOT_BEGIN(U0, k) }
                 if (k < NF) U1[k] = widen_hi(k, P0[k]);
                 if (k < NF) P1[k] = read_frag(k, cur, 1);
                 if (k < LD) dma_one(k, nx2, ra, rb, so);
@@ -490,9 +491,11 @@ void gemm_olay_kernel(GemmArgs g) {
             }
             cur = nxt;
         };
-        for (int kt = 0; kt < KT - 1; ++kt) k_step(std::false_type{}, kt);
-        k_step(std::true_type{}, KT - 1);
+        k_step(std::true_type{}, std::false_type{}, 0);
+        for (int kt = 1; kt < KT - 1; ++kt) k_step(std::false_type{}, std::false_type{}, kt);
+        k_step(std::false_type{}, std::true_type{}, KT - 1);
 #undef W4A4_SLOT_BEGIN
+#undef W4A4_SLOT_BEGIN_ZERO
 
         // ---- epilogue of this tile ------------------------------------------------------------------
         {
@@ -524,12 +527,6 @@ void gemm_olay_kernel(GemmArgs g) {
             else olay_epilogue<FM, FN, OUT, true, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
         }
         if (!has_next) break;
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
         vb = vb_next; tile = tile_next; m0 = m0n; n0 = n0n; a_cur = a_nxt; b_cur = b_nxt; parity ^= 1;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_only(0));                  // no DMA may outlive the workgroup's LDS

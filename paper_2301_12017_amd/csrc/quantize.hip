@@ -124,16 +124,15 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
     }
 }
 
-// Streaming form of the row quantizer for fp16 activations (step a1, the run-time one).
-// The kernel above is latency-bound: a wave loads its row, waits, reduces, converts, stores,
-// and only then does the next wave of the block slot start.  Here a wave owns `rpw` rows
-// (rows w, w + W, w + 2W ... for W waves in the grid, chosen so that all W are resident) and
-// requests row i+1 before it touches row i, so that nearly the whole input is in flight at
-// once and HBM streams without gaps.  A row stays in registers as raw fp16 (16 bytes per lane
-// per chunk) and is converted twice (range, then codes), which halves the registers of the
-// two row buffers.  Loads go through a buffer descriptor of the row (chunks past K read as
-// zero).  Code sums per K-group are segmented wave reductions (cpg = chunks per group must be
-// a power of two <= 64, or the group is the whole row).
+// Row quantizer for fp16 activations (step a1, the run-time one), trimmed for the vector ALU: the
+// range is taken on packed fp16 (v_pk_max_f16 on |x|, exact), the row stays in registers as raw
+// fp16 (16 bytes per lane per chunk) and is converted once for the codes, rounding is an fp32 add
+// of 1.5*2^23 (round-to-nearest-even, then the code sits in the low mantissa bits), symmetric
+// codes are produced in offset binary so that nibble sums are byte sums (v_sad_u8) and one XOR per
+// dword gives the wanted layout.  Loads go through a buffer descriptor of the row (chunks past K
+// read as zero).  A wave owns rows w, w + W, ... of W waves and requests its next row before it
+// touches the current one.  Code sums per K-group are segmented wave reductions (cpg = chunks per
+// group must be a power of two <= 64, or the group is the whole row).
 template <int MODE, int ITERS, int LAYOUT>
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
     const __half *__restrict__ X, long ldx, int rows, int K, uint8_t *__restrict__ q,
@@ -165,30 +164,55 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
     while (row < rows) {
         const long next = row + nwaves;
         if (next < rows) load_row(next, nxt);
-        // ---- range of the row
-        float lo = INFINITY, hi = -INFINITY;
+        // ---- range of the row, on packed fp16 (the maximum of fp16 values is exact in fp16)
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        h2 hi2, lo2;
+        {
+            const uint32_t first = cur[0][0];
+            const uint32_t init = MODE == W4A4_SYM ? 0u : (first & 0xFFFFu) * 0x10001u;   // SYM: 0; ASYM: element 0 twice
+            hi2 = *reinterpret_cast<const h2 *>(&init);
+            lo2 = hi2;
+        }
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            float v[8];
-            unpack8(cur[it], v);
-            float clo = v[0], chi = MODE == W4A4_SYM ? fabsf(v[0]) : v[0];
+            // chunks past K read as zero: harmless for |x| maxima; for min/max they are replaced by the row's
+            // first element
+            const bool in = lane + it * kWave < nchunks;
 #pragma unroll
-            for (int e = 1; e < 8; ++e) {
-                if (MODE == W4A4_SYM) chi = fmaxf(chi, fabsf(v[e]));
-                else { chi = fmaxf(chi, v[e]); clo = fminf(clo, v[e]); }
+            for (int i = 0; i < 4; ++i) {
+                uint32_t d = cur[it][i];
+                if (MODE == W4A4_SYM) {
+                    d &= 0x7FFF7FFFu;
+                    hi2 = __builtin_elementwise_max(hi2, *reinterpret_cast<const h2 *>(&d));
+                } else {
+                    const uint32_t sub = *reinterpret_cast<const uint32_t *>(&hi2);
+                    if (!in) d = sub;
+                    hi2 = __builtin_elementwise_max(hi2, *reinterpret_cast<const h2 *>(&d));
+                    lo2 = __builtin_elementwise_min(lo2, *reinterpret_cast<const h2 *>(&d));
+                }
             }
-            const bool in = lane + it * kWave < nchunks;        // chunks past K hold zeros: keep them out of min/max
-            if (MODE == W4A4_SYM) hi = fmaxf(hi, chi);
-            else { hi = fmaxf(hi, in ? chi : -INFINITY); lo = fminf(lo, in ? clo : INFINITY); }
         }
+        float hi = fmaxf((float)hi2[0], (float)hi2[1]);
         Range r;
-        if (MODE == W4A4_SYM) r = range_sym(wave_max(hi));
-        else r = range_asym(wave_min(lo), wave_max(hi));
+        if (MODE == W4A4_SYM) {
+            r = range_sym(wave_max(hi));
+        } else {
+            // lanes past K started from THEIR chunk's first element (zeros): take lane 0's as the neutral value
+            const float lo = fminf((float)lo2[0], (float)lo2[1]);
+            const bool any = lane < nchunks;
+            const float hi0 = __shfl(hi, 0, kWave), lo0 = __shfl(lo, 0, kWave);
+            r = range_asym(wave_min(any ? lo : lo0), wave_max(any ? hi : hi0));
+        }
         if (lane == 0) {
             s[row] = r.S;
             if (MODE == W4A4_ASYM) z[row] = r.lo;
         }
-        // ---- codes
+        // ---- codes.  rne(t) for |t| < 2^22 is the low mantissa of t + 1.5*2^23 (the fp32 add rounds to
+        // nearest even); the clamp of the definition cannot bind (|t| <= 7(1+2^-23), resp. t in [0, 15(1+2^-23)]).
+        // Symmetric codes are produced in offset binary (code + 8: the +8 rides in the constant) so that nibble
+        // sums are plain byte sums; one XOR per dword then gives the layout wanted.
+        constexpr float kMagic = MODE == W4A4_SYM ? 12582920.0f : 12582912.0f;
+        constexpr uint32_t kFlip = MODE == W4A4_ASYM ? 0u : LAYOUT == 0 ? 0x88888888u : 0x80808080u;
         uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
         int part = 0, total = 0;
 #pragma unroll
@@ -197,27 +221,28 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
             float v[8];
             unpack8(cur[it], v);
             uint32_t packed = 0;
-            int sum = 0;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int code = code_of<MODE>(v[e], r);
-                sum += code;
-                if (LAYOUT == 0) {
-                    packed |= (uint32_t)(code & 0xF) << (4 * e);
-                } else {
-                    if (e & 1) part += code;
-                    packed |= (uint32_t)((code + ((e & 1) ? 0 : 8)) & 0xF) << (4 * e);
-                }
+                float t;
+                if (MODE == W4A4_SYM) t = v[e] * r.inv;
+                else { float d = v[e] - r.lo; t = d * r.inv; }
+                const float u = t + kMagic;
+                packed |= (__float_as_uint(u) & 0xFu) << (4 * e);
             }
-            if (c < nchunks) {
-                qr[c] = packed;
+            const bool in = c < nchunks;
+            const uint32_t even = packed & 0x0F0F0F0Fu, odd = (packed >> 4) & 0x0F0F0F0Fu;
+            int sum = 0;
+            if (gsum) sum = (int)__builtin_amdgcn_sad_u8(even, 0u, __builtin_amdgcn_sad_u8(odd, 0u, 0u)) - (MODE == W4A4_SYM ? 64 : 0);
+            if (LAYOUT != 0 && in) part += (int)__builtin_amdgcn_sad_u8(odd, 0u, 0u) - 32;
+            if (in) {
+                qr[c] = packed ^ kFlip;
                 total += sum;
             } else {
                 sum = 0;
             }
             if (gsum && ng > 1) {                               // groups of cpg lanes, all inside this `it`
                 for (int o = 1; o < cpg; o <<= 1) sum += __shfl_xor(sum, o, kWave);
-                if ((lane & (cpg - 1)) == 0 && c < nchunks) gsum[row * (long)ng + c / cpg] = sum;
+                if ((lane & (cpg - 1)) == 0 && in) gsum[row * (long)ng + c / cpg] = sum;
             }
         }
         if (gsum && ng == 1) {
@@ -284,17 +309,11 @@ static int launch_stream(const __half *X, long ldx, int rows, int K, int G, uint
     const int cpg = G / 8;
     if (gsum && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return -100;
     const int iters = (K / 8 + kWave - 1) / kWave;
-    static int cus = 0;
-    if (!cus) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            return W4A4_ERR_HIP;
-    }
-    // all waves resident at once: 8 per SIMD while the two row buffers are small, fewer for long rows
-    const int occ = iters <= 2 ? 8 : iters <= 4 ? 6 : 3;
-    const long target = (long)cus * 4 * occ;
-    const long rpw = (rows + target - 1) / target;              // rows per wave
+    // One row per wave measured fastest on MI355X (a 12288 x 1024 activation matrix: 8.1 us against 9.6 us
+    // with two rows per wave and the second row's loads in flight under the first row's arithmetic): the
+    // dispatcher keeps the CUs fed, and more, shorter waves hide the reduction latency better.  The row loop
+    // of the kernel only matters beyond 2^22 rows.
+    const long rpw = (rows + (1L << 22) - 1) >> 22;
     const long waves = (rows + rpw - 1) / rpw;
     dim3 grid((unsigned)((waves + kRowsPerBlock - 1) / kRowsPerBlock)), block(kRowsPerBlock * kWave);
 #define W4A4_QS(I)                                                                                       \
