@@ -11,7 +11,8 @@ struct Schedule {
     int family;          // 0 = pipelined kernel, codes widened per wave (symmetric, per-channel, K % 128 == 0),
                          // 1 = generic, 2 = pipelined kernel, codes widened once into LDS (K % 64 == 0),
                          // 3 = pipelined kernel with direct global->LDS loads (K % 128 == 0),
-                         // 4 = persistent kernel on operands in the MFMA operand layout
+                         // 4 = persistent kernel on operands in the MFMA operand layout,
+                         // 5 = persistent kernel for K-grouped / asymmetric layers
     int variant;
     bool grouped_ok;     // usable for K-grouped / asymmetric layers
 };
@@ -32,12 +33,22 @@ static const Schedule kSchedules[] = {
     {"dma_256x256", 3, 1, false},
     {"olay_128x256", 4, 0, false},
     {"olay_192x128", 4, 1, false},
+    {"group_128x128", 5, 0, true},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 
 static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
     // 32-bit buffer offsets and whole K steps
     return !grouped && g.K % kstep == 0 && (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL;
+}
+
+constexpr int kOlaySchedule = 14;                             // olay_128x256; +1 = olay_192x128
+constexpr int kGroupSchedule = 16;                            // group_128x128
+
+static bool group_ok(const GemmArgs &g, bool grouped) {
+    return grouped && g.K % kBK == 0 && g.K >= 2 * kBK && (long)g.M * g.lda < 0x7fffffffL &&
+           (long)g.N * g.ldw < 0x7fffffffL && (long)g.N * g.ng * 4 < 0x7fffffffL && (long)g.M * g.ng * 4 < 0x7fffffffL &&
+           (size_t)g.ng * 256 * 4 + 3 * 256 * 64 + 2048 <= 80 * 1024;
 }
 
 // Built-in shape table: large problems take the pipelined tiles (192 x 128 when the output is
@@ -47,6 +58,7 @@ static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
 static int pick_schedule(const GemmArgs &g, bool grouped) {
     const long big = (long)((g.M + 127) / 128) * ((g.N + 255) / 256);
     if (big >= 256) {
+        if (group_ok(g, grouped)) return kGroupSchedule;
         if (!pipe_ok(g, grouped)) return 5;      // grouped layers: the 64 x 128 tile leaves LDS for the group tables
         return g.N <= 1024 ? 8 : 1;
     }
@@ -56,8 +68,6 @@ static int pick_schedule(const GemmArgs &g, bool grouped) {
     if (small >= 256) return 6;
     return 7;
 }
-
-constexpr int kOlaySchedule = 14;                             // olay_128x256; +1 = olay_192x128
 
 // Tile choice of the persistent kernel: two workgroups share a CU's matrix pipe, so what counts is
 // the largest number of tiles any CU ends up with (workgroups b and b + 256 share a CU) times the
@@ -84,6 +94,10 @@ static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int sched
     if (s.family == 4) {
         if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
         return launch_olay(s.variant, out_kind, g, st);
+    }
+    if (s.family == 5) {
+        if (!group_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        return launch_group(mode, out_kind, g, st);
     }
     if (s.family == 0) {
         if (!pipe_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;

@@ -117,6 +117,8 @@ def _schedules(B, grouped, K=128):
     for i, name in enumerate(B.schedule_names()):
         if name.startswith("olay"):                 # reads the MFMA operand layout only (tests/test_gpu_olay.py)
             continue
+        if name.startswith("group") and (not grouped or K % 128 or K < 256):
+            continue
         if name.startswith("pipe8"):
             if grouped or K % 64:
                 continue
@@ -328,3 +330,30 @@ def test_errors_raise(B):
     X = torch.zeros((4, 48), dtype=torch.float16, device="cuda")
     with pytest.raises(B.W4A4Error):
         B.quantize_act(X, SYM)                            # K % 32 != 0
+
+
+@pytest.mark.parametrize("mode,group,K", [(ASYM, 128, 768), (ASYM, 0, 512), (SYM, 128, 512), (ASYM, 256, 1024)])
+def test_grouped_kernel_many_tiles(B, orc, mode, group, K):
+    """The persistent kernel for grouped / asymmetric layers with more tiles than resident workgroups
+    (every workgroup walks several tiles; the group tables in LDS are replaced between tiles), ragged M
+    and N; sampled rows against the oracle, int32 planes and fp16 outputs."""
+    sch = B.schedule_names().index("group_128x128") + 1
+    rng = np.random.default_rng(500 + mode + group + K)
+    M, N = 128 * 11 + 37, 128 * 50 + 24                            # 12 x 51 = 612 tiles
+    X, W, A, Q = _operands(B, orc, rng, M, N, K, mode, group, outliers=4 if mode == ASYM else 0)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    rows = np.sort(np.concatenate([[0, M - 1], rng.choice(M, 30, replace=False)]))
+    a, w = qact_host(A), qweight_host(Q)
+    a = {k: (None if v is None else v[rows]) for k, v in a.items()}
+    for act in (0, 1):
+        want = orc.linear(a, w, mode, group, bias, act)
+        got = host(B.linear(A, Q, dev(bias), act, schedule=sch))[rows]
+        ok, ratio = f16_close(got, want["out"])
+        assert ok, f"act {act}: tolerance ratio {ratio}"
+        if act == 0:
+            assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16))
+    P = host(B.gemm_i32(A, Q, schedule=sch))[:, rows]
+    assert np.array_equal(P, orc.gemm_i32(a["q"], w["q"], mode, group))
+    # the shape table picks this kernel for large grouped layers: same result without naming it
+    auto = host(B.linear(A, Q, dev(bias), 0))[rows]
+    assert np.array_equal(auto, host(B.linear(A, Q, dev(bias), 0, schedule=sch))[rows])
