@@ -84,20 +84,23 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
 // Store FN consecutive 32-bit or 16-bit values through a buffer descriptor: offsets past the
 // end of the buffer (rows >= M, or the poisoned offset of a lane whose channels are >= N) are
 // dropped by the hardware, so the epilogue needs no branches.
-template <int FN>
+// AUX: cache-policy bits of the store (0 = default; kStreamed = non-temporal: the output is written once
+// and not read by this kernel, so it should not displace the operand tiles in L2).
+constexpr int kStreamed = 2;
+template <int FN, int AUX = 0>
 __device__ __forceinline__ void store_words(__amdgpu_buffer_rsrc_t rs, uint32_t off, const uint32_t (&w)[FN]) {
-    if constexpr (FN == 1) __builtin_amdgcn_raw_buffer_store_b32(w[0], rs, off, 0, 0);
-    else if constexpr (FN == 2) __builtin_amdgcn_raw_buffer_store_b64(u32x2{w[0], w[1]}, rs, off, 0, 0);
-    else if constexpr (FN == 4) __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[0], w[1], w[2], w[3]}, rs, off, 0, 0);
+    if constexpr (FN == 1) __builtin_amdgcn_raw_buffer_store_b32(w[0], rs, off, 0, AUX);
+    else if constexpr (FN == 2) __builtin_amdgcn_raw_buffer_store_b64(u32x2{w[0], w[1]}, rs, off, 0, AUX);
+    else if constexpr (FN == 4) __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[0], w[1], w[2], w[3]}, rs, off, 0, AUX);
     else {
-        __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[0], w[1], w[2], w[3]}, rs, off, 0, 0);
-        __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[4], w[5], w[6], w[7]}, rs, off + 16, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[0], w[1], w[2], w[3]}, rs, off, 0, AUX);
+        __builtin_amdgcn_raw_buffer_store_b128(u32x4{w[4], w[5], w[6], w[7]}, rs, off + 16, 0, AUX);
     }
 }
-template <int FN>
+template <int FN, int AUX = 0>
 __device__ __forceinline__ void store_halves(__amdgpu_buffer_rsrc_t rs, uint32_t off, const float (&y)[FN]) {
     if constexpr (FN == 1) {
-        __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(y[0])), rs, off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b16(__half_as_ushort(__float2half_rn(y[0])), rs, off, 0, AUX);
     } else {
         uint32_t w[FN / 2];
 #pragma unroll
@@ -105,7 +108,7 @@ __device__ __forceinline__ void store_halves(__amdgpu_buffer_rsrc_t rs, uint32_t
             __half2 h = __floats2half2_rn(y[2 * j], y[2 * j + 1]);
             w[j] = *reinterpret_cast<uint32_t *>(&h);
         }
-        store_words<FN / 2>(rs, off, w);
+        store_words<FN / 2, AUX>(rs, off, w);
     }
 }
 

@@ -360,9 +360,9 @@ void gemm_group_kernel(GemmArgs g) {
                             uint32_t w[FN];
 #pragma unroll
                             for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[rr][j]);
-                            store_words<FN>(o_rsrc, off, w);
+                            store_words<FN, kStreamed>(o_rsrc, off, w);
                         } else {
-                            store_halves<FN>(o_rsrc, off, y[rr]);
+                            store_halves<FN, kStreamed>(o_rsrc, off, y[rr]);
                         }
                     }
                 }

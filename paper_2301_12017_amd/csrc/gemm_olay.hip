@@ -76,7 +76,7 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
                     uint32_t w[FN];
 #pragma unroll
                     for (int j = 0; j < FN; ++j) w[j] = (uint32_t)((acc[i][j][r] + cp.ne[j] + no) >> 4);
-                    store_words<FN>(o_rsrc, off, w);
+                    store_words<FN, kStreamed>(o_rsrc, off, w);
                 } else {
                     float y[FN];
 #pragma unroll
@@ -90,9 +90,9 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
                         uint32_t w[FN];
 #pragma unroll
                         for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[j]);
-                        store_words<FN>(o_rsrc, off, w);
+                        store_words<FN, kStreamed>(o_rsrc, off, w);
                     } else {
-                        store_halves<FN>(o_rsrc, off, y);
+                        store_halves<FN, kStreamed>(o_rsrc, off, y);
                     }
                 }
             }
