@@ -196,13 +196,32 @@ def main():
             graph_us = (time.perf_counter() - t2) * 1e6 / reps
         except Exception as ex:                                   # report, never hide
             graph_us = f"graph capture failed: {ex}"
+        # floor of eight back-to-back launches on this stream: the smallest quantize_act the library accepts
+        # (one token of 32 elements), eight times
+        tiny_x = torch.zeros((1, 32), dtype=torch.float16, device="cuda")
+        tiny = B.PreparedQuantizeAct(tiny_x, B.quantize_act(tiny_x, B.SYM))
+
+        def eight():
+            st = B._stream()
+            for _ in range(8):
+                tiny(st)
+        for _ in range(20):
+            eight()
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for _ in range(reps):
+            eight()
+        torch.cuda.synchronize()
+        floor_us = (time.perf_counter() - t3) * 1e6 / reps
         bytes2 = sum(s.M * s.K * 2 + s.M * s.K // 2 * 2 + s.N * s.K // 2 + s.M * s.N * 2 for s in s2)
         lat = {"bert_base_layer_b1_s128_us": us, "bert_base_layer_b1_s128_graph_us": graph_us,
+               "eight_minimal_launches_us": floor_us,
                "algorithmic_bytes": bytes2,
                "achieved_GBps_warm": bytes2 / (us * 1e-6) / 1e9,
                "note": "4 x (quantize_act + w4a4_linear); eager launches from Python, and the same launches "
                        "replayed from a HIP graph; weights warm in cache; attention, LayerNorm and residuals "
-                       "are outside the path"}
+                       "are outside the path; eight_minimal_launches_us = eight one-token quantize_act launches, "
+                       "the launch floor of this stream"}
 
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",

@@ -79,7 +79,9 @@ __device__ __forceinline__ float gelu_erf(float x) {
     q = __fmaf_rn(q, t, -1.151269197e+00f);
     q = __fmaf_rn(q, t, -9.999943376e-01f);
     const float tail = t * __builtin_amdgcn_exp2f(q);
-    return fmaxf(x, 0.0f) - tail;
+    // max(x, 0) as a signed integer maximum on the bit pattern (one instruction, no NaN canonicalisation)
+    const float relu = __int_as_float(max(__float_as_int(x), 0));
+    return relu - tail;
 }
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }

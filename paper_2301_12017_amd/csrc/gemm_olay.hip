@@ -70,7 +70,7 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = q * 4 + rr;
-                const int no = osv[rr] * -128;
+                const int no = __mul24(osv[rr], -128);
                 const uint32_t off = lane_off + (uint32_t)(i * 32 + 8 * q + rr) * row_bytes;
                 if constexpr (OUT == OUT_I32) {
                     uint32_t w[FN];
@@ -141,7 +141,7 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
             float y[4][FN];
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const int no = osv[rr] * -128;
+                const int no = __mul24(osv[rr], -128);
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
                     float t = (float)(acc[i][j][q * 4 + rr] + cp.ne[j] + no) * sav[rr];
