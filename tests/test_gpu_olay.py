@@ -273,3 +273,74 @@ def test_chained_layers_in_operand_layout(B, orc):
             ow = orc.quantize_weight(lay.host_W, SYM)
             want = orc.linear(oin, ow, SYM, 0, lay.host_b, 1 if lay.spec.gelu else 0, requant=True)
             _requant_compare(orc, want, out, lay.spec.gelu, M, lay.spec.N)
+
+
+def test_edge_shapes(B, orc):
+    """Empty input, a single token, the narrowest output, the longest K the quantizers accept, and an
+    activation matrix read as a column slice of a wider one (row stride > K/2, its own odd sums)."""
+    rng = np.random.default_rng(970)
+    Q = B.quantize_weight(dev(_rand_w(rng, 8, 256)), SYM, 0, layout=MFMA)
+    A0 = B.QAct(torch.empty((0, 128), dtype=torch.uint8, device="cuda"), torch.empty(0, device="cuda"), None, None,
+                0, 256, 128, 0, SYM, 0, MFMA, torch.empty(0, dtype=torch.int32, device="cuda"))
+    assert B.linear(A0, Q).shape == (0, 8)                          # M == 0: a successful no-op
+    for M, N, K in ((1, 8, 256), (3, 40, 16384)):
+        A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+        Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+        a, w = _qhost(A, Q)
+        assert np.array_equal(host(B.gemm_i32(A, Q))[0], orc.gemm_i32(a["q"], w["q"], SYM, 0)[0])
+        want = orc.linear(a, w, SYM, 0, None, 0)
+        assert np.array_equal(host(B.linear(A, Q)).view(np.uint16), want["out"].view(np.uint16))
+    # column slice: quantize a [M, 3K] matrix third by third into one packed buffer, multiply the middle third
+    M, K, N = 200, 512, 136
+    Xw = _rand_x(rng, M, 3 * K)
+    wide = torch.empty((M, 3 * K // 2), dtype=torch.uint8, device="cuda")
+    osum = torch.empty((M, 3), dtype=torch.int32, device="cuda")
+    scales = []
+    for t in range(3):
+        At = B.quantize_act(dev(np.ascontiguousarray(Xw[:, t * K:(t + 1) * K])), SYM, layout=MFMA)
+        wide[:, t * K // 2:(t + 1) * K // 2] = At.q
+        osum[:, t] = At.osum
+        scales.append(At.scale)
+    Amid = B.QAct(wide, scales[1], None, None, M, K, 3 * K // 2, 0, SYM, q_offset_bytes=K // 2, layout=MFMA,
+                  osum=osum, osum_index=1)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    want = orc.quantize_act(np.ascontiguousarray(Xw[:, K:2 * K]), SYM)
+    w = _qhost(B.quantize_act(dev(np.ascontiguousarray(Xw[:, K:2 * K])), SYM, layout=MFMA), Q)[1]
+    assert np.array_equal(host(B.gemm_i32(Amid, Q))[0], orc.gemm_i32(want["q"], w["q"], SYM, 0)[0])
+
+
+def test_non_finite_inputs_do_not_fault(B):
+    """NaN / Inf activations: results are unspecified, but every kernel must run to completion."""
+    M, N, K = 300, 544, 512
+    X = np.ones((M, K), np.float16)
+    X[0, 0] = np.nan
+    X[1, 5] = np.inf
+    X[2, :] = -np.inf
+    A = B.quantize_act(dev(X), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(np.ones((N, K), np.float16)), SYM, 0, layout=MFMA)
+    Y = B.linear(A, Q, None, 1)
+    Z = B.linear(A, Q, None, 1, requant=True, requant_layout=MFMA)
+    torch.cuda.synchronize()
+    assert Y.shape == (M, N) and Z.q.shape == (M, N // 2)
+    assert np.isfinite(host(Y)[3:].astype(np.float32)).all()        # finite rows are unaffected by the others
+
+
+def test_fused_requantize_widest_output(B, orc):
+    """N = 8192 (32 column tiles exchange their maxima), sampled rows against the oracle."""
+    rng = np.random.default_rng(980)
+    M, N, K = 600, 8192, 256
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    need = B.linear_workspace_bytes(A, Q, requant_layout=MFMA, requant_group=2048)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    out = B.linear(A, Q, None, 0, requant=True, requant_layout=MFMA, requant_group=2048, workspace=ws)
+    torch.cuda.synchronize()
+    assert need < M * N and B.fused_fault(ws, need) == 0
+    rows = np.sort(rng.choice(M, 24, replace=False))
+    a, w = _qhost(A, Q)
+    a = dict(q=a["q"][rows], s=a["s"][rows], z=a["z"][rows], gsum=None)
+    want = orc.linear(a, w, SYM, 0, None, 0, requant=True)
+    assert np.array_equal(act_to_canonical(host(out.q))[rows], want["q"])
+    assert np.array_equal(host(out.scale)[rows].view(np.uint32), want["s"].view(np.uint32))
+    sums = _codes(orc, want["q"])[:, 1::2].reshape(len(rows), 4, 1024).sum(axis=2)
+    assert np.array_equal(host(out.osum)[rows].astype(np.int64), sums)
