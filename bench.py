@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0
 # HBM-side bytes of the four w4a4_linear launches of one step of configs[2], from the rocprofv3 --pmc
 # runs summarised in profiles/gemm_config3_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
 # factors a 256 MiB device copy gave in the same runs).  Not measured live; None for other workloads.
-PROFILED_TRAFFIC_BYTES = {3: int((25.79 + 25.85 + 49.84 + 25.85 + 72.0 + 24.0 + 96.0 + 24.0) * 2 ** 20)}
+PROFILED_TRAFFIC_BYTES = {3: int((18.52 + 10.36 + 22.82 + 42.86 + 72.0 + 24.0 + 96.0 + 24.0) * 2 ** 20)}
 
 
 def parse():
