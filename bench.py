@@ -34,7 +34,7 @@ def parse():
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=50)
     p.add_argument("--warmup", type=int, default=10)
-    p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped)")
+    p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped, 5 = one layer of the chained stack)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--copy-probe-mb", type=int, default=0,
@@ -70,12 +70,87 @@ def cpu_baseline(specs, cfg, rows):
             "seconds": dt}
 
 
+def bench_chain(args):
+    """Workload 5: the chained BERT-large linear stack at M = 32768.  A step is one encoder layer's four
+    GEMMs (QKV, out-proj on the V third, FFN1+GELU, FFN2), each with the dequantize / bias (/GELU) /
+    per-token requantize epilogue fused, codes flowing from one GEMM to the next without an fp16 tensor.
+    Four layers with distinct weights are cycled; the step input is the previous layer's output."""
+    import torch
+    from paper_2301_12017_amd import binding as B, synth, workloads as WL
+    B.lib()
+    torch.cuda.set_device(0)
+    M, h, ffn, nl = 32768, 1024, 4096, 4
+    layout = B.preferred_layout(M, 3 * h, h)
+    layers = WL.make_chain(nl, h, ffn, M, 5, keep_host=False, layout=layout)
+    A0 = B.quantize_act(WL.dev(synth.activations(M, h, 0, 5, 0)), B.SYM, layout=layout)
+    ws = torch.empty(M * 8, dtype=torch.uint8, device="cuda")
+    # build the 16 calls once: run the chain eagerly and keep every output as the next call's input
+    calls, names, A = [], [], A0
+    for L in layers:
+        for name, lay, slice_h in (("qkv", L.qkv, None), ("attn_out", L.out, h), ("ffn1", L.ffn1, None), ("ffn2", L.ffn2, None)):
+            a_in = WL.v_slice(A, slice_h) if slice_h else A
+            mfma = lay.W.layout == B.LAYOUT_MFMA
+            out = B._alloc_out(a_in, lay.W, True, B.SYM, h if (mfma and name == "qkv") else 0, lay.W.layout)
+            calls.append(B.PreparedLinear(a_in, lay.W, lay.bias, lay.act, requant=True, requant_mode=B.SYM,
+                                          requant_group=h if (mfma and name == "qkv") else 0, out=out, workspace=ws,
+                                          requant_layout=lay.W.layout))
+            names.append(name)
+            A = B.QAct(out[0], out[1], None, None, M, lay.spec.N, lay.spec.N // 2, 0, B.SYM, 0, lay.W.layout,
+                       out[3] if mfma else None)
+    stream = B._stream()
+    steps = args.steps
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(4)]
+          for _ in range(steps)]
+
+    def step(k, events=None):
+        for j in range(4):
+            if events:
+                events[j][0].record()
+            calls[(k % nl) * 4 + j](stream)
+            if events:
+                events[j][1].record()
+
+    for k in range(args.warmup):
+        step(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        step(k, ev[k])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    assert B.fused_fault(ws, (M + M // 128 + 4) * 4) == 0
+    ms = dt * 1e3 / steps
+    shapes = [(3 * h, h), (h, h), (ffn, h), (h, ffn)]
+    ops = sum(2 * M * n * k for n, k in shapes)
+    gemm_ms = [sum(ev[k][j][0].elapsed_time(ev[k][j][1]) for k in range(steps)) / steps for j in range(4)]
+    achieved = ops / (sum(gemm_ms) * 1e-3) / 1e12
+    line = {
+        "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
+        "value": ops / (ms * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int4 operands, int8 MFMA, int32 accumulate, fp32 epilogue, int4 out", "data": "synthetic",
+        "config": {"workload": f"configs[4]: one layer of the chained BERT-large stack, M={M}: qkv, attn_out (V third in "
+                               f"place), ffn1+GELU, ffn2, every output requantized per token in the GEMM epilogue",
+                   "step": "4 x w4a4_linear(requant)", "layout": layout},
+        "pct_int8_mfma_peak": 100.0 * ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
+        "per_gemm": [{"name": n, "ms": t, "TOPS": 2 * M * nn * kk / (t * 1e-3) / 1e12}
+                     for n, t, (nn, kk) in zip(names[:4], gemm_ms, shapes)],
+        "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "kernel": "gemm_olay_kernel with the fused requantize epilogue, the four launches of the step",
+                     "ops_per_step": ops, "kernel_ms_per_step": sum(gemm_ms)},
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path is token-parallel with no "
               "exchange; see DESIGN.md); --gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
+    if args.config == 5:
+        return bench_chain(args)
     import torch
     from paper_2301_12017_amd import binding as B, synth, workloads as WL
     B.lib()
