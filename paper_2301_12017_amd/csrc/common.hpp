@@ -64,24 +64,46 @@ __device__ __forceinline__ int code_of(float x, const Range &r) {
 // erf-form GELU (Sec. 4.2 names GELU; BERT's is the erf form): gelu(x) = x * Phi(x) with
 // Phi the standard normal CDF.  Evaluated as  max(x,0) - t * Phi(-t),  t = min(|x|, 6), with
 // Phi(-t) = 2^q(t) and q a degree-7 polynomial fitted to log2 Phi(-t) on [0,6].  The form
-// keeps RELATIVE accuracy in the negative tail (where gelu is tiny) and costs seven FMAs and
+// keeps RELATIVE accuracy in the negative tail (where gelu is tiny) and costs eight FMAs and
 // one v_exp_f32, about a third of a libm-grade erff.  Against the float64 erf form: relative
 // error < 5e-6 wherever |gelu| exceeds the smallest fp16 subnormal, absolute error < 7e-7.
-__device__ __forceinline__ float gelu_erf(float x) {
-    const float ax = fabsf(x);
-    const float t = fminf(ax, 6.0f);
+struct GeluParts { float relu, t, p; };                          // gelu(x) = relu - t * p
+__device__ __forceinline__ GeluParts gelu_parts(float x) {
+    GeluParts g;
+    g.t = fminf(fabsf(x), 6.0f);
     float q = -1.889626219e-06f;
-    q = __fmaf_rn(q, t, 6.268139987e-05f);
-    q = __fmaf_rn(q, t, -9.388679173e-04f);
-    q = __fmaf_rn(q, t, 8.539461531e-03f);
-    q = __fmaf_rn(q, t, -5.402068794e-02f);
-    q = __fmaf_rn(q, t, -4.584097862e-01f);
-    q = __fmaf_rn(q, t, -1.151269197e+00f);
-    q = __fmaf_rn(q, t, -9.999943376e-01f);
-    const float tail = t * __builtin_amdgcn_exp2f(q);
+    q = __fmaf_rn(q, g.t, 6.268139987e-05f);
+    q = __fmaf_rn(q, g.t, -9.388679173e-04f);
+    q = __fmaf_rn(q, g.t, 8.539461531e-03f);
+    q = __fmaf_rn(q, g.t, -5.402068794e-02f);
+    q = __fmaf_rn(q, g.t, -4.584097862e-01f);
+    q = __fmaf_rn(q, g.t, -1.151269197e+00f);
+    q = __fmaf_rn(q, g.t, -9.999943376e-01f);
+    g.p = __builtin_amdgcn_exp2f(q);
     // max(x, 0) as a signed integer maximum on the bit pattern (one instruction, no NaN canonicalisation)
-    const float relu = __int_as_float(max(__float_as_int(x), 0));
-    return relu - tail;
+    g.relu = __int_as_float(max(__float_as_int(x), 0));
+    return g;
+}
+__device__ __forceinline__ float gelu_erf(float x) {
+    const GeluParts g = gelu_parts(x);
+    return __fmaf_rn(-g.t, g.p, g.relu);
+}
+// GELU of two values as a pair of fp16 (x0 in the low half).  The last FMA and the conversion are
+// one instruction each half (v_fma_mix*_f16: fp32 sources, the exact fused result rounded ONCE to
+// fp16), so this is not always the same bit pattern as rounding gelu_erf() to fp16: every fp16
+// GELU output of the library goes through here.
+__device__ __forceinline__ uint32_t gelu_erf_half2(float x0, float x1) {
+    const GeluParts a = gelu_parts(x0), b = gelu_parts(x1);
+    uint32_t d;
+    asm("v_fma_mixlo_f16 %0, -%1, %2, %3" : "=v"(d) : "v"(a.t), "v"(a.p), "v"(a.relu));
+    asm("v_fma_mixhi_f16 %0, -%1, %2, %3" : "+v"(d) : "v"(b.t), "v"(b.p), "v"(b.relu));
+    return d;
+}
+__device__ __forceinline__ unsigned short gelu_erf_half(float x) {
+    const GeluParts a = gelu_parts(x);
+    uint32_t d;
+    asm("v_fma_mixlo_f16 %0, -%1, %2, %3" : "=v"(d) : "v"(a.t), "v"(a.p), "v"(a.relu));
+    return (unsigned short)(d & 0xFFFFu);
 }
 
 inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }

@@ -32,8 +32,8 @@ struct EpiArgs {
 //   SYM, ng == 1:  y = ((float)P * sa) * sw
 //   otherwise:     t1 = sum_g sw[n,g]*(float)P_g ; y = sa*t1
 //   ASYM adds:     t2 = sum_g zw[n,g]*(float)RA[m,g] ; y = y + sa*t2 ; y = y + za*c[n]
-// then + bias, then GELU.
-template <int MODE>
+// then + bias, then GELU (GELU32; the fp16 store applies its own, rounded once to fp16).
+template <int MODE, bool GELU32 = true>
 __device__ __forceinline__ void dequant8(const EpiArgs &a, long m, int n0, float (&y)[8]) {
     const float sa = a.sa[m];
     if (MODE == W4A4_SYM && a.ng == 1) {
@@ -80,7 +80,7 @@ __device__ __forceinline__ void dequant8(const EpiArgs &a, long m, int n0, float
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         if (a.bias) y[e] = y[e] + __half2float(a.bias[n0 + e]);
-        if (a.act == W4A4_ACT_GELU) y[e] = gelu_erf(y[e]);
+        if (GELU32 && a.act == W4A4_ACT_GELU) y[e] = gelu_erf(y[e]);
     }
 }
 
@@ -95,11 +95,17 @@ __global__ __launch_bounds__(256) void dequant_rows_kernel(EpiArgs a) {
     float y[8];
     if (REQ < 0) {
         for (int c = lane; c < nchunks; c += kWave) {
-            dequant8<MODE>(a, m, c * 8, y);
-            __half2 h[4];
+            dequant8<MODE, false>(a, m, c * 8, y);
+            uint4 w;
+            if (a.act == W4A4_ACT_GELU) {
+                w = uint4{gelu_erf_half2(y[0], y[1]), gelu_erf_half2(y[2], y[3]), gelu_erf_half2(y[4], y[5]), gelu_erf_half2(y[6], y[7])};
+            } else {
+                __half2 h[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) h[i] = __floats2half2_rn(y[2 * i], y[2 * i + 1]);
-            *reinterpret_cast<uint4 *>(a.out16 + m * a.N + c * 8) = *reinterpret_cast<uint4 *>(h);
+                for (int i = 0; i < 4; ++i) h[i] = __floats2half2_rn(y[2 * i], y[2 * i + 1]);
+                w = *reinterpret_cast<uint4 *>(h);
+            }
+            *reinterpret_cast<uint4 *>(a.out16 + m * a.N + c * 8) = w;
         }
         return;
     }

@@ -112,6 +112,19 @@ __device__ __forceinline__ void store_halves(__amdgpu_buffer_rsrc_t rs, uint32_t
     }
 }
 
+// GELU of FN pre-activations, stored as fp16 (see gelu_erf_half2)
+template <int FN, int AUX = 0>
+__device__ __forceinline__ void store_gelu_halves(__amdgpu_buffer_rsrc_t rs, uint32_t off, const float (&y)[FN]) {
+    if constexpr (FN == 1) {
+        __builtin_amdgcn_raw_buffer_store_b16(gelu_erf_half(y[0]), rs, off, 0, AUX);
+    } else {
+        uint32_t w[FN / 2];
+#pragma unroll
+        for (int j = 0; j < FN / 2; ++j) w[j] = gelu_erf_half2(y[2 * j], y[2 * j + 1]);
+        store_words<FN / 2, AUX>(rs, off, w);
+    }
+}
+
 constexpr uint32_t kPoison = 0x80000000u;     // an offset no output buffer reaches (M*N*4 < 2^31)
 
 // Per-lane constants of the epilogue, fetched before the main loop so that their latency
@@ -244,16 +257,14 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM]
 #pragma unroll
                             for (int j = 0; j < FN; ++j) y[j] = y[j] + e.bias[j];
                         }
-                        if constexpr (GELU) {
-#pragma unroll
-                            for (int j = 0; j < FN; ++j) y[j] = gelu_erf(y[j]);
-                        }
                         const uint32_t off = lane_off + (uint32_t)(i * 32 + 8 * q + rr) * row_bytes;
                         if constexpr (OUT == OUT_F32) {
                             uint32_t w[FN];
 #pragma unroll
-                            for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[j]);
+                            for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(GELU ? gelu_erf(y[j]) : y[j]);
                             store_words<FN>(o_rsrc, off, w);
+                        } else if constexpr (GELU) {
+                            store_gelu_halves<FN>(o_rsrc, off, y);
                         } else {
                             store_halves<FN>(o_rsrc, off, y);
                         }

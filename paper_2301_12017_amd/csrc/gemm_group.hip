@@ -351,16 +351,14 @@ void gemm_group_kernel(GemmArgs g) {
 #pragma unroll
                             for (int j = 0; j < FN; ++j) y[rr][j] = y[rr][j] + bv[j];
                         }
-                        if (gelu) {
-#pragma unroll
-                            for (int j = 0; j < FN; ++j) y[rr][j] = gelu_erf(y[rr][j]);
-                        }
                         const uint32_t off = lane_off + (uint32_t)(i * 32 + 8 * q + rr) * row_bytes;
                         if constexpr (OUT == OUT_F32) {
                             uint32_t w[FN];
 #pragma unroll
-                            for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[rr][j]);
+                            for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(gelu ? gelu_erf(y[rr][j]) : y[rr][j]);
                             store_words<FN, kStreamed>(o_rsrc, off, w);
+                        } else if (gelu) {
+                            store_gelu_halves<FN, kStreamed>(o_rsrc, off, y[rr]);
                         } else {
                             store_halves<FN, kStreamed>(o_rsrc, off, y[rr]);
                         }

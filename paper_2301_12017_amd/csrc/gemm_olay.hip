@@ -6,8 +6,10 @@
 // instruction for four more.  So the design removes VALU work wherever it can:
 //   * Operand layout (see w4a4_layout in w4a4.h): one v_and_b32 per MFMA operand register
 //     instead of a shift and a mask (3 instead of 4.5 VALU per MFMA for a 64 x 128 wave
-//     tile).  The contraction then yields 16*P + 128*(esum[n] + osum[m]); the two code-sum
-//     terms are taken out with one integer v_add3 per accumulator.
+//     tile).  The contraction then yields 16*P + 128*(esum[n] + osum[m]).  The token term
+//     costs nothing per accumulator: the first MFMA of a tile takes -128*osum[m] (sixteen
+//     registers per 32 rows, shared by all column fragments) as its C operand; the channel
+//     term is one integer add per accumulator in the epilogue.
 //   * Tiles travel HBM -> LDS with `buffer_load_dwordx4 ... lds` (no staging registers, no
 //     LDS-write instructions); all DMA addressing is scalar: the per-lane offsets are fixed
 //     for the whole kernel, the tile origin lives in the buffer descriptor (SGPRs) and the
@@ -18,8 +20,8 @@
 //   * Workgroups are persistent and the K steps of successive tiles form ONE stream through
 //     the three LDS stages: while the last two K steps of a tile are multiplied, the first
 //     two of the next tile are already being fetched, so a tile has no load prologue.
-//     Token scales / odd sums go to LDS by 4-byte DMA, channel constants to registers, at
-//     the start of the tile whose epilogue uses them.
+//     Token scales / odd sums go to LDS by 4-byte DMA one tile ahead (the odd sums are needed
+//     by the first MFMAs of the tile), channel constants to registers at the start of the tile.
 //   * Two workgroups share a CU (2 x 74 KB of LDS), four waves of 64 x 128 each, so one
 //     workgroup's epilogue stores overlap the other's main loop.
 #include "gemm_common.hpp"
@@ -47,13 +49,13 @@ struct ChanParams {
     int ne[FN];        // -128 * esum[n]
 };
 
-// Epilogue of one wave for the fp16 / fp32 / int32 outputs.  v = acc - 128*(esum + osum) = 16*P
-// exactly; then y = ((float)v * sa[m]) * (sw[n]/16) (+ bias[n]) (GELU), each operation
+// Epilogue of one wave for the fp16 / fp32 / int32 outputs.  The accumulators already contain
+// -128*osum[m] (C operand of the tile's first MFMAs), so v = acc - 128*esum[n] = 16*P exactly; then y = ((float)v * sa[m]) * (sw[n]/16) (+ bias[n]) (GELU), each operation
 // separately rounded, which equals ((float)P * sa) * sw of the definition bit for bit.
 template <int FM, int FN, int OUT, bool BIAS, bool GELU>
 __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM][FN], const ChanParams<FN> &cp,
                                               uint32_t col_off, int m0, int row_w, int lane,
-                                              const float *sa_lds, const int *os_lds) {
+                                              const float *sa_lds) {
     constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
     const __amdgpu_buffer_rsrc_t o_rsrc = make_rsrc(g.out, (uint32_t)((long)g.M * g.N * ESZ));
     const uint32_t row_bytes = (uint32_t)g.N * ESZ;
@@ -64,33 +66,31 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
         for (int q = 0; q < 4; ++q) {
             const int rl = row_w + i * 32 + 8 * q + 4 * (lane >> 5);          // 4 consecutive rows
             const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
-            const int4 os4 = *reinterpret_cast<const int4 *>(os_lds + rl);
             const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
-            const int osv[4] = {os4.x, os4.y, os4.z, os4.w};
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = q * 4 + rr;
-                const int no = __mul24(osv[rr], -128);
                 const uint32_t off = lane_off + (uint32_t)(i * 32 + 8 * q + rr) * row_bytes;
                 if constexpr (OUT == OUT_I32) {
                     uint32_t w[FN];
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) w[j] = (uint32_t)((acc[i][j][r] + cp.ne[j] + no) >> 4);
+                    for (int j = 0; j < FN; ++j) w[j] = (uint32_t)((acc[i][j][r] + cp.ne[j]) >> 4);
                     store_words<FN, kStreamed>(o_rsrc, off, w);
                 } else {
                     float y[FN];
 #pragma unroll
                     for (int j = 0; j < FN; ++j) {
-                        float t = (float)(acc[i][j][r] + cp.ne[j] + no) * sav[rr];
+                        float t = (float)(acc[i][j][r] + cp.ne[j]) * sav[rr];
                         y[j] = t * cp.sw[j];
                         if constexpr (BIAS) y[j] = y[j] + cp.bias[j];
-                        if constexpr (GELU) y[j] = gelu_erf(y[j]);
                     }
                     if constexpr (OUT == OUT_F32) {
                         uint32_t w[FN];
 #pragma unroll
-                        for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(y[j]);
+                        for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(GELU ? gelu_erf(y[j]) : y[j]);
                         store_words<FN, kStreamed>(o_rsrc, off, w);
+                    } else if constexpr (GELU) {
+                        store_gelu_halves<FN, kStreamed>(o_rsrc, off, y);
                     } else {
                         store_halves<FN, kStreamed>(o_rsrc, off, y);
                     }
@@ -123,7 +123,7 @@ template <int FM, int FN, bool MFMA>
 __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&acc)[FM][FN], const ChanParams<FN> &cp,
                                                        bool n_ok, int n_lane, int m0, int row_w, int lane, int tid,
                                                        int panel, int slice, bool first_cols, const float *sa_lds,
-                                                       const int *os_lds, float *scratch) {
+                                                       float *scratch) {
     static_assert(FN == 4 && FM == 2, "32 rows per half wave; two lanes assemble one dword of eight codes");
     const bool gelu = g.act == W4A4_ACT_GELU;
     const int h = lane >> 5, c = lane & 31;
@@ -135,16 +135,13 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
         for (int q = 0; q < 4; ++q) {
             const int rl = row_w + i * 32 + 8 * q + 4 * h;
             const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
-            const int4 os4 = *reinterpret_cast<const int4 *>(os_lds + rl);
             const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
-            const int osv[4] = {os4.x, os4.y, os4.z, os4.w};
             float y[4][FN];
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                const int no = __mul24(osv[rr], -128);
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    float t = (float)(acc[i][j][q * 4 + rr] + cp.ne[j] + no) * sav[rr];
+                    float t = (float)(acc[i][j][q * 4 + rr] + cp.ne[j]) * sav[rr];
                     t = t * cp.sw[j];
                     y[rr][j] = t + cp.bias[j];                    // 0 without a bias: changes at most the sign of a zero
                 }
@@ -384,6 +381,7 @@ void gemm_olay_kernel(GemmArgs g) {
     for (int i = 0; i < LD; ++i) dma_one(i, 0, a_cur, b_cur, 0);
 #pragma unroll
     for (int i = 0; i < LD; ++i) dma_one(i, 1, a_cur, b_cur, ROWB);
+    dma_params(m0, 0);
     __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
@@ -396,8 +394,22 @@ void gemm_olay_kernel(GemmArgs g) {
         // first fragments of the tile (its first two K steps are in LDS and published)
 #pragma unroll
         for (int f = 0; f < NF; ++f) P0[f] = read_frag(f, cur, 0);
-        // ---- tile start: parameters of this tile, origin of the next one ---------------------------
-        dma_params(m0, parity);
+        // ---- tile start: C operand of the first MFMAs, channel constants, origin of the next tile -----
+        // acc[i][0] = -128 * osum of the rows of fragment row i (accumulator layout: register 4q+rr of
+        // lane (c, h) is row 8q + 4h + rr).  The token parameters of this tile were fetched one tile ago.
+        {
+            const int *os_lds = reinterpret_cast<const int *>(par + parity * (2 * BM * 4) + BM * 4) + wm * FM * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int4 o = *reinterpret_cast<const int4 *>(os_lds + i * 32 + 8 * q);
+                    acc[i][0][4 * q + 0] = __mul24(o.x, -128);
+                    acc[i][0][4 * q + 1] = __mul24(o.y, -128);
+                    acc[i][0][4 * q + 2] = __mul24(o.z, -128);
+                    acc[i][0][4 * q + 3] = __mul24(o.w, -128);
+                }
+        }
         // channel constants of this lane's FN adjacent channels: raw loads now (channels past N read
         // as zero), converted when the epilogue starts
         const int n_lane = n0 + wn * FN * 32 + (lane & 31) * FN;
@@ -432,11 +444,12 @@ void gemm_olay_kernel(GemmArgs g) {
     acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
                                                                    acc[(k) / FN][(k) % FN], 0, 0, 0);    \
     __builtin_amdgcn_sched_barrier(0);
-        // the first MFMA into an accumulator of a tile takes a zero C operand (an inline constant), so the
-        // accumulators are never cleared with VALU moves
-#define W4A4_SLOT_BEGIN_ZERO(Ucur, k)                                                                     \
-    acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
-                                                                   v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0); \
+        // the first MFMA into an accumulator of a tile takes acc[i][0] = -128 * osum as its C operand (column
+        // fragments in descending order, so that fragment 0 is overwritten last): the accumulators are never
+        // cleared and the token term of the layout correction is never added per element
+#define W4A4_SLOT_BEGIN_FIRST(Ucur, k)                                                                    \
+    acc[(k) / FN][FN - 1 - (k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                              \
+        Ucur[(k) / FN], Ucur[FM + FN - 1 - (k) % FN], acc[(k) / FN][0], 0, 0, 0);                          \
     __builtin_amdgcn_sched_barrier(0);
         constexpr int kBarSlot = NM - NF;                      // LDS reads of the next stage start here
         auto k_step = [&](auto first_tag, auto last_tag, int kt) {
@@ -462,7 +475,7 @@ void gemm_olay_kernel(GemmArgs g) {
             //             stream step +2 into the stage every wave finished reading before the last barrier.
 #pragma unroll
             for (int k = 0; k < NM; ++k) {
-                if constexpr (FIRST) { W4A4_SLOT_BEGIN_ZERO(U0, k) } else { W4A4_SLOT_BEGIN(U0, k) }
+                if constexpr (FIRST) { W4A4_SLOT_BEGIN_FIRST(U0, k) } else { W4A4_SLOT_BEGIN(U0, k) }
                 if (k < NF) U1[k] = widen_hi(k, P0[k]);
                 if (k < NF) P1[k] = read_frag(k, cur, 1);
                 if (k < LD) dma_one(k, nx2, ra, rb, so);
@@ -502,10 +515,14 @@ void gemm_olay_kernel(GemmArgs g) {
             cur = nxt;
         };
         k_step(std::true_type{}, std::false_type{}, 0);
+        // every wave has passed a barrier of this tile, so nobody reads the previous tile's parameters
+        // any more: fetch the next tile's into that buffer (complete at this tile's last barrier)
+        dma_params(m0n, parity ^ 1);
+        __builtin_amdgcn_sched_barrier(0);
         for (int kt = 1; kt < KT - 1; ++kt) k_step(std::false_type{}, std::false_type{}, kt);
         k_step(std::false_type{}, std::true_type{}, KT - 1);
 #undef W4A4_SLOT_BEGIN
-#undef W4A4_SLOT_BEGIN_ZERO
+#undef W4A4_SLOT_BEGIN_FIRST
 
         // ---- epilogue of this tile ------------------------------------------------------------------
         {
@@ -520,7 +537,6 @@ void gemm_olay_kernel(GemmArgs g) {
                 cp.bias[j] = __half2float(__ushort_as_half((unsigned short)((j & 1) ? b2 >> 16 : b2 & 0xFFFFu)));
             }
             const float *sa_lds = reinterpret_cast<const float *>(par + parity * (2 * BM * 4));
-            const int *os_lds = reinterpret_cast<const int *>(par + parity * (2 * BM * 4) + BM * 4);
             const int row_w = wm * FM * 32;
             const bool bias = g.bias != nullptr, gelu = g.act == W4A4_ACT_GELU;
             if constexpr (OUT == OUT_Q4 || OUT == OUT_Q4M) {
@@ -528,13 +544,13 @@ void gemm_olay_kernel(GemmArgs g) {
                     const int tn = tile % g.tiles_n;
                     olay_epilogue_requant<FM, FN, OUT == OUT_Q4M>(g, acc, cp, n_lane < g.N, n_lane, m0, row_w, lane, tid,
                                                                   tile / g.tiles_n, tn / g.slice_tiles, tn == 0 && wn == 0,
-                                                                  sa_lds, os_lds, reinterpret_cast<float *>(par + 2 * 2 * BM * 4));
+                                                                  sa_lds, reinterpret_cast<float *>(par + 2 * 2 * BM * 4));
                 }
             } else
-            if (OUT == OUT_I32 || (!bias && !gelu)) olay_epilogue<FM, FN, OUT, false, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
-            else if (bias && !gelu) olay_epilogue<FM, FN, OUT, true, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
-            else if (!bias && gelu) olay_epilogue<FM, FN, OUT, false, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
-            else olay_epilogue<FM, FN, OUT, true, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds, os_lds);
+            if (OUT == OUT_I32 || (!bias && !gelu)) olay_epilogue<FM, FN, OUT, false, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
+            else if (bias && !gelu) olay_epilogue<FM, FN, OUT, true, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
+            else if (!bias && gelu) olay_epilogue<FM, FN, OUT, false, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
+            else olay_epilogue<FM, FN, OUT, true, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
         }
         if (!has_next) break;
         vb = vb_next; tile = tile_next; m0 = m0n; n0 = n0n; a_cur = a_nxt; b_cur = b_nxt; parity ^= 1;
