@@ -130,6 +130,13 @@ const char *w4a4_status_string(int status);
 int         w4a4_schedule_count(void);
 const char *w4a4_schedule_name(int schedule);
 
+/* Measurement hook (no passage of the paper: it serves the roofline figure).  Arms the calling
+ * thread: the GEMM kernel of its NEXT w4a4_linear / w4a4_gemm_i32 call records the two HIP events
+ * (hipEvent_t, created by the caller with timing enabled) at the kernel's own start and end, the
+ * interval a kernel trace reports, free of the dispatch gap that events recorded around the call
+ * include.  The arming is consumed by that one launch; two NULLs disarm.  Returns W4A4_OK. */
+int w4a4_time_next_gemm(void *start_event, void *stop_event);
+
 /* The layout in which w4a4_linear is fastest for a layer of this shape (Sec. 4.2: the GEMM
  * schedule, and with it the operand layout it reads, is fixed per shape ahead of time).  Both
  * operands of a layer must use the same layout; every layout a layer supports gives identical

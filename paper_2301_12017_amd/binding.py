@@ -55,6 +55,7 @@ _SIGNATURES = {
     "w4a4_schedule_count": (_i, []),
     "w4a4_schedule_name": (ctypes.c_char_p, [_i]),
     "w4a4_preferred_layout": (_i, [_i, _i, _i, _i, _i]),
+    "w4a4_time_next_gemm": (_i, [_vp, _vp]),
     "w4a4_workspace_bytes": (_sz, [_i, _i, _i, ctypes.POINTER(_Epilogue)]),
     "w4a4_linear_workspace_bytes": (_sz, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _i]),
     "w4a4_quantize_weight": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
@@ -82,6 +83,51 @@ def lib():
             fn.restype, fn.argtypes = res, args
         _lib = L
     return _lib
+
+
+_hip = None
+
+
+def _hiprt():
+    """The HIP runtime this process already has loaded (for events only)."""
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipEventCreate.argtypes = [ctypes.POINTER(_vp)]
+        _hip.hipEventDestroy.argtypes = [_vp]
+        _hip.hipEventSynchronize.argtypes = [_vp]
+        _hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), _vp, _vp]
+    return _hip
+
+
+class KernelTimer:
+    """A pair of HIP events that w4a4_time_next_gemm stamps with the start and the end of the
+    GEMM kernel of the next linear() / gemm_i32() call of this thread."""
+
+    def __init__(self):
+        self.start, self.stop = _vp(), _vp()
+        for e in (self.start, self.stop):
+            if _hiprt().hipEventCreate(ctypes.byref(e)) != 0:
+                raise RuntimeError("hipEventCreate failed")
+
+    def arm(self):
+        _check(lib().w4a4_time_next_gemm(self.start, self.stop), "w4a4_time_next_gemm")
+
+    def elapsed_ms(self) -> float:
+        """Kernel duration; call after the stream has been synchronized."""
+        ms = ctypes.c_float()
+        rc = _hiprt().hipEventElapsedTime(ctypes.byref(ms), self.start, self.stop)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def __del__(self):
+        try:
+            for e in (self.start, self.stop):
+                if e:
+                    _hiprt().hipEventDestroy(e)
+        except Exception:
+            pass
 
 
 def version() -> str:

@@ -1,4 +1,4 @@
-// Version and status strings of libw4a4.
+// Version and status strings of libw4a4, and the timing hook.
 #include "common.hpp"
 
 extern "C" const char *w4a4_version(void) { return "w4a4 0.1 (gfx950)"; }
@@ -12,4 +12,18 @@ extern "C" const char *w4a4_status_string(int status) {
         case W4A4_ERR_HIP: return "HIP launch failed";
         default: return "unknown status";
     }
+}
+
+namespace w4a4 {
+KernelTimer &kernel_timer() {
+    static thread_local KernelTimer t;
+    return t;
+}
+}  // namespace w4a4
+
+extern "C" int w4a4_time_next_gemm(void *start_event, void *stop_event) {
+    w4a4::KernelTimer &t = w4a4::kernel_timer();
+    t.start = reinterpret_cast<hipEvent_t>(start_event);
+    t.stop = reinterpret_cast<hipEvent_t>(stop_event);
+    return W4A4_OK;
 }

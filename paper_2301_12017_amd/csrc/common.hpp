@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "../../include/w4a4.h"
@@ -110,6 +111,22 @@ inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s);
 
 inline int launch_status() {
     return hipGetLastError() == hipSuccess ? W4A4_OK : W4A4_ERR_HIP;
+}
+
+// Kernel-boundary timestamps for the caller's roofline figure (w4a4_time_next_gemm): when the
+// thread is armed, the GEMM launch goes through hipExtLaunchKernelGGL, which stamps the two events
+// with the start and the end of the kernel itself, and disarms.
+struct KernelTimer { hipEvent_t start = nullptr, stop = nullptr; };
+KernelTimer &kernel_timer();                                     // thread-local, lives in api.hip
+template <typename... KArgs, typename... Args>
+inline void launch_gemm(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t lds, hipStream_t st, Args... args) {
+    KernelTimer &t = kernel_timer();
+    if (t.start || t.stop) {
+        hipExtLaunchKernelGGL(kern, grid, block, (unsigned)lds, st, t.start, t.stop, 0, args...);
+        t = KernelTimer{};
+    } else {
+        hipLaunchKernelGGL(kern, grid, block, lds, st, args...);
+    }
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -399,7 +399,7 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, g);
+    launch_gemm(kern, dim3(grid), dim3(256), lds, st, g);
     return launch_status();
 }
 

@@ -588,7 +588,7 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
         grid = (unsigned)(most < (slots & ~(kXcd - 1)) ? most : (slots & ~(kXcd - 1)));
         if (g.tiles_n > (int)(grid / kXcd)) return W4A4_ERR_UNSUPPORTED_SHAPE;
     }
-    hipLaunchKernelGGL(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
+    launch_gemm(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
     return launch_status();
 }
 

@@ -181,7 +181,7 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     }
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    hipLaunchKernelGGL(kern, dim3((unsigned)tiles), dim3(WM * WN * 64), lds, st, g);
+    launch_gemm(kern, dim3((unsigned)tiles), dim3(WM * WN * 64), lds, st, g);
     return launch_status();
 }
 

@@ -344,3 +344,22 @@ def test_fused_requantize_widest_output(B, orc):
     assert np.array_equal(host(out.scale)[rows].view(np.uint32), want["s"].view(np.uint32))
     sums = _codes(orc, want["q"])[:, 1::2].reshape(len(rows), 4, 1024).sum(axis=2)
     assert np.array_equal(host(out.osum)[rows].astype(np.int64), sums)
+
+
+@pytest.mark.parametrize("layout,M,N,K", [(MFMA, 2048, 512, 512), (0, 300, 256, 384)])
+def test_kernel_timer_stamps_one_gemm(B, layout, M, N, K):
+    """w4a4_time_next_gemm: the armed events bracket the GEMM kernel of the next call only, the
+    arming is consumed by it, and the output does not depend on it."""
+    rng = np.random.default_rng(31)
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=layout)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, layout=layout)
+    plain = host(B.linear(A, Q, None, 0))
+    t = B.KernelTimer()
+    t.arm()
+    timed = host(B.linear(A, Q, None, 0))                         # host() synchronizes
+    ms = t.elapsed_ms()
+    assert 0.0 < ms < 5.0
+    assert np.array_equal(plain.view(np.uint16), timed.view(np.uint16))
+    again = host(B.linear(A, Q, None, 0))                         # not armed any more
+    assert t.elapsed_ms() == ms
+    assert np.array_equal(plain.view(np.uint16), again.view(np.uint16))
