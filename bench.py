@@ -274,6 +274,24 @@ def main():
             graph_us = (time.perf_counter() - t2) * 1e6 / reps
         except Exception as ex:                                   # report, never hide
             graph_us = f"graph capture failed: {ex}"
+        # the same four linears through w4a4_linear_f16act: the activation quantize inside the GEMM kernel,
+        # four launches instead of eight
+        fc2 = [B.PreparedLinearF16Act(X, L.W, L.bias, L.act) for X, L in zip(x2, l2)]
+
+        def layer2_fused():
+            st = B._stream()
+            for fc in fc2:
+                fc(st)
+        for _ in range(20):
+            layer2_fused()
+        torch.cuda.synchronize()
+        for fc, lc in zip(fc2, lc2):                                 # same bits as the two-call path
+            assert torch.equal(fc.out.view(torch.int16), lc.out[0].view(torch.int16))
+        t4 = time.perf_counter()
+        for _ in range(reps):
+            layer2_fused()
+        torch.cuda.synchronize()
+        fused_us = (time.perf_counter() - t4) * 1e6 / reps
         # floor of eight back-to-back launches on this stream: the smallest quantize_act the library accepts
         # (one token of 32 elements), eight times
         tiny_x = torch.zeros((1, 32), dtype=torch.float16, device="cuda")
@@ -292,14 +310,16 @@ def main():
         torch.cuda.synchronize()
         floor_us = (time.perf_counter() - t3) * 1e6 / reps
         bytes2 = sum(s.M * s.K * 2 + s.M * s.K // 2 * 2 + s.N * s.K // 2 + s.M * s.N * 2 for s in s2)
-        lat = {"bert_base_layer_b1_s128_us": us, "bert_base_layer_b1_s128_graph_us": graph_us,
+        lat = {"bert_base_layer_b1_s128_us": fused_us, "bert_base_layer_b1_s128_two_call_us": us,
+               "bert_base_layer_b1_s128_two_call_graph_us": graph_us,
                "eight_minimal_launches_us": floor_us,
                "algorithmic_bytes": bytes2,
-               "achieved_GBps_warm": bytes2 / (us * 1e-6) / 1e9,
-               "note": "4 x (quantize_act + w4a4_linear); eager launches from Python, and the same launches "
-                       "replayed from a HIP graph; weights warm in cache; attention, LayerNorm and residuals "
-                       "are outside the path; eight_minimal_launches_us = eight one-token quantize_act launches, "
-                       "the launch floor of this stream"}
+               "achieved_GBps_warm": bytes2 / (fused_us * 1e-6) / 1e9,
+               "note": "bert_base_layer_b1_s128_us: 4 x w4a4_linear_f16act (quantize_act inside the GEMM kernel, "
+                       "one launch per linear, outputs identical to the two-call path); two_call: 4 x "
+                       "(quantize_act + w4a4_linear), eager and replayed from a HIP graph; weights warm in cache; "
+                       "attention, LayerNorm and residuals are outside the path; eight_minimal_launches_us = eight "
+                       "one-token quantize_act launches, the launch floor of eight launches on this stream"}
 
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",

@@ -190,6 +190,21 @@ int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
                 void *out, float *out_scale, float *out_zero, int32_t *out_gsum,
                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* Steps a1 + a2 + a3 in ONE kernel, for small token counts (Sec. 4.2: at small batch x
+ * sequence the launch overhead and the memory-bound quantize kernels decide the latency):
+ * the result equals w4a4_quantize_act(X, SYM, group 0, canonical layout) followed by
+ * w4a4_linear(requant = 0) bit for bit, but the codes and scales of the activations never
+ * leave the kernel.  Every workgroup re-derives the scales of its 32 tokens, so the cost grows
+ * with N/32 * M * K: meant for M up to a few hundred tokens.
+ *   X_f16 [M, ldx] fp16 (device, 16-byte aligned, ldx >= K elements, ldx*2 % 16 == 0)
+ *   W     symmetric per-channel weights in the canonical layout (K % 64 == 0, K <= 4096,
+ *         N % 8 == 0)
+ *   ep    bias / activation; ep->requant must be 0
+ *   out   fp16 [M, N] (device)
+ * UNSUPPORTED_SHAPE for asymmetric / K-grouped / operand-layout weights and for requant. */
+int w4a4_linear_f16act(const void *X_f16, int M, int K, int ldx, const w4a4_weight *W,
+                       const w4a4_epilogue *ep, void *out, void *stream);
+
 /* Step a2 alone (parity / debugging export): acc[ng, M, N] int32, one plane per
  * weight K-group (ng == 1 for per-channel weights). */
 int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream);

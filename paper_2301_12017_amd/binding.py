@@ -62,6 +62,7 @@ _SIGNATURES = {
     "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
                          _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "w4a4_linear_f16act": (_i, [_vp, _i, _i, _i, ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _vp, _vp]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
     "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
                                    ctypes.POINTER(_Epilogue), _vp, _vp, _vp, _vp, _vp]),
@@ -335,6 +336,39 @@ class PreparedLinear:
         rc = self.fn(*self.args, _stream() if stream is None else stream)
         if rc:
             raise W4A4Error(rc, "w4a4_linear")
+
+
+def linear_f16act(X: torch.Tensor, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NONE,
+                  out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """w4a4_linear_f16act: quantize_act + linear in one kernel, for small token counts.  fp16 [M,N]."""
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, W.N), dtype=torch.float16, device=X.device)
+    ep, w = _epilogue(bias, act, False, SYM, 0, 0, LAYOUT_CANONICAL), W.c()
+    rc = lib().w4a4_linear_f16act(_ptr(X), M, K, X.stride(0), ctypes.byref(w), ctypes.byref(ep), _ptr(out), _stream())
+    _check(rc, "w4a4_linear_f16act")
+    return out
+
+
+class PreparedLinearF16Act:
+    """A w4a4_linear_f16act call with its arguments marshalled once (see PreparedLinear)."""
+
+    def __init__(self, X: torch.Tensor, W: QWeight, bias=None, act=ACT_NONE, out=None):
+        assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+        M, K = X.shape
+        if out is None:
+            out = torch.empty((M, W.N), dtype=torch.float16, device=X.device)
+        self.out = out
+        self.keep = (X, W, bias, out)
+        self.ep, self.w = _epilogue(bias, act, False, SYM, 0, 0, LAYOUT_CANONICAL), W.c()
+        self.args = (_ptr(X), M, K, X.stride(0), ctypes.byref(self.w), ctypes.byref(self.ep), _ptr(out))
+        self.fn = lib().w4a4_linear_f16act
+
+    def __call__(self, stream=None):
+        rc = self.fn(*self.args, _stream() if stream is None else stream)
+        if rc:
+            raise W4A4Error(rc, "w4a4_linear_f16act")
 
 
 class PreparedQuantizeAct:

@@ -117,6 +117,31 @@ def test_quantize_argument_errors(b):
     assert L.w4a4_quantize_weight(p, 4, 64, 0, 32, p, p, None, None, None, 1, p, None) == -2
 
 
+def test_linear_f16act_argument_errors(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    ep = b._Epilogue(None, 0, 0, 0, 0, 0, 0)
+
+    def f(M=4, K=64, ldx=None, w=None, e=ep, x=p, o=p):
+        w = _wt(b, K=K) if w is None else w
+        return L.w4a4_linear_f16act(x, M, K, K if ldx is None else ldx, ctypes.byref(w), ctypes.byref(e), o, None)
+
+    assert f(w=_wt(b, K=128)) == -1                                   # K mismatch
+    assert f(ldx=32) == -1                                            # ldx < K
+    assert f(x=None) == -1 and f(o=None) == -1                        # null pointers
+    assert f(e=b._Epilogue(None, 7, 0, 0, 0, 0, 0)) == -1             # unknown activation
+    assert f(K=96, w=_wt(b, K=96)) == -2                              # K % 64
+    assert f(K=8192, w=_wt(b, K=8192)) == -2                          # K > 4096
+    assert f(w=_wt(b, N=12)) == -2                                    # N % 8
+    assert f(ldx=68) == -2                                            # rows not 16-byte aligned
+    assert f(x=ctypes.c_void_p(0x1004)) == -2                         # misaligned
+    assert f(w=_wt(b, mode=1)) == -2                                  # asymmetric weights
+    assert f(K=256, w=_wt(b, K=256, group=128)) == -2                 # K-grouped weights
+    assert f(K=256, w=_wt(b, K=256, layout=1, esum=0x3000)) == -2     # operand-layout weights
+    assert f(e=b._Epilogue(None, 0, 1, 0, 0, 0, 0)) == -2             # requant is the two-call path's
+    assert f(M=0) == 0
+
+
 def test_workspace_bytes(b):
     assert b.workspace_bytes(128, 768, 768, requant=False) == 0
     assert b.workspace_bytes(128, 768, 768, requant=True) == 128 * 768 * 4
