@@ -122,6 +122,34 @@ def quantize_act(X_f16, mode=SYM, group=0):
     return dict(q=q, s=s, z=z, gsum=gs)
 
 
+def layernorm_quantize(X_f16, R_f16, gamma_f16, beta_f16, eps, mode=SYM, group=0):
+    """LayerNorm(x + r) * gamma + beta per token, then the token-wise quantize of the fp32 result.
+    Returns dict(y16 f16 [M,K], y32 f32 [M,K], q, s, z, gsum)."""
+    X = _c(X_f16, np.float16)
+    M, K = X.shape
+    R = None if R_f16 is None else _c(R_f16, np.float16)
+    g, b = _c(gamma_f16, np.float16), _c(beta_f16, np.float16)
+    assert g.shape == (K,) and b.shape == (K,) and (R is None or R.shape == X.shape)
+    ng = _ng(K, group)
+    y16 = np.empty((M, K), np.float16)
+    y32 = np.empty((M, K), np.float32)
+    q = np.empty((M, K // 2), np.uint8)
+    s = np.empty(M, np.float32)
+    z = np.zeros(M, np.float32)
+    gs = np.empty((M, ng), np.int32)
+    L = lib()
+    L.orc_layernorm_quantize.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int, ctypes.c_int,
+                                         ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                         ctypes.c_void_p, ctypes.c_void_p]
+    rc = L.orc_layernorm_quantize(_p(X.view(np.uint16)), None if R is None else _p(R.view(np.uint16)), M, K, K,
+                                  _p(g.view(np.uint16)), _p(b.view(np.uint16)), float(eps), mode, group,
+                                  _p(y16.view(np.uint16)), _p(y32), _p(q), _p(s), _p(z), _p(gs))
+    if rc:
+        raise ValueError(f"orc_layernorm_quantize rc={rc}")
+    return dict(y16=y16, y32=y32, q=q, s=s, z=z, gsum=gs)
+
+
 def quantize_rows_f32(Y, mode=SYM, group=0):
     Y = _c(Y, np.float32)
     M, K = Y.shape

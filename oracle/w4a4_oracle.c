@@ -241,6 +241,54 @@ int orc_quantize_act(const uint16_t *X, int M, int K, int ldx, int mode, int gro
     return rc;
 }
 
+/* ------------------------------------------- producer fusion: LayerNorm, then step a1 */
+
+/* LayerNorm over the K features of every token of x (+ residual), Sec. 4.2: the quantize of
+ * an activation is fused with the LayerNorm (or bias-add, or GELU) that produces it.
+ *     v    = x + r                         (r may be NULL)
+ *     mean = sum(v) / K,   var = sum((v - mean)^2) / K          (biased, two passes)
+ *     y    = (v - mean) / sqrt(var + eps) * gamma + beta
+ * evaluated in double from the fp16 inputs.  y32 = (float)y is the fused kernel's value: it
+ * is stored as fp16 in Y16 (the residual stream, may be NULL), as fp32 in Y32 (may be NULL;
+ * for tests) and handed to orc_quantize_rows_f32, i.e. the codes come from the fp32 value,
+ * never from its fp16 rounding.  Returns 0, or -1 on bad arguments. */
+int orc_layernorm_quantize(const uint16_t *X, const uint16_t *R, int M, int K, int ldx,
+                           const uint16_t *gamma, const uint16_t *beta, double eps,
+                           int mode, int group, uint16_t *Y16, float *Y32,
+                           uint8_t *q, float *s, float *z, int32_t *gsum)
+{
+    if (M < 0 || K <= 0 || ldx < K || !gamma || !beta || eps < 0.0) return -1;
+    int G = group == 0 ? K : group;
+    if (G <= 0 || K % G) return -1;
+    int ng = K / G;
+    double *v = (double *)malloc(sizeof(double) * (size_t)K);
+    float *y = (float *)malloc(sizeof(float) * (size_t)K);
+    if (!v || !y) { free(v); free(y); return -1; }
+    int rc = 0;
+    for (int m = 0; m < M && rc == 0; ++m) {
+        double sum = 0.0;
+        for (int k = 0; k < K; ++k) {
+            v[k] = (double)orc_h2f(X[(size_t)m * ldx + k]);
+            if (R) v[k] += (double)orc_h2f(R[(size_t)m * ldx + k]);
+            sum += v[k];
+        }
+        const double mean = sum / (double)K;
+        double sq = 0.0;
+        for (int k = 0; k < K; ++k) sq += (v[k] - mean) * (v[k] - mean);
+        const double rstd = 1.0 / sqrt(sq / (double)K + eps);
+        for (int k = 0; k < K; ++k) {
+            const double yy = (v[k] - mean) * rstd * (double)orc_h2f(gamma[k]) + (double)orc_h2f(beta[k]);
+            y[k] = (float)yy;
+            if (Y16) Y16[(size_t)m * K + k] = orc_f2h(y[k]);
+            if (Y32) Y32[(size_t)m * K + k] = y[k];
+        }
+        rc = orc_quantize_rows_f32(y, 1, K, K, mode, group, q + (size_t)m * (K / 2), s + m,
+                                   z ? z + m : NULL, gsum ? gsum + (size_t)m * ng : NULL);
+    }
+    free(v); free(y);
+    return rc;
+}
+
 /* ---------------------------------------------------------------- step a0: weights */
 
 /* App. A weight quantization of W[N, K] (fp16 bits, row n = output channel n).
