@@ -190,6 +190,22 @@ int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
                 void *out, float *out_scale, float *out_zero, int32_t *out_gsum,
                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* Producer fusion (Sec. 4.2: "fuse the quantization operation for activation with its previous
+ * element-bias-add, GELU, or layer normalization"): LayerNorm over the K features of every token
+ * of X (+ R), then step a1 on the result, in one kernel.
+ *     v = X + R;  y = (v - mean(v)) / sqrt(var(v) + eps) * gamma + beta      (fp32, biased variance)
+ * y is quantized per token from its fp32 value exactly as w4a4_quantize_act quantizes a row
+ * (same outputs, same meaning of mode / group / layout / gsum / osum), and stored as fp16 in
+ * Y_f16 when that is not NULL (the residual stream of the encoder).
+ *   X_f16, R_f16  [M, ldx] fp16 (device; R_f16 may be NULL; 16-byte aligned, ldx*2 % 16 == 0)
+ *   gamma_f16, beta_f16  [K] fp16 (device, 16-byte aligned)
+ *   Y_f16  [M, K] fp16 or NULL
+ *   K % 32 == 0, K <= 4096; groups as for w4a4_quantize_act. */
+int w4a4_layernorm_quantize(const void *X_f16, const void *R_f16, int M, int K, int ldx,
+                            const void *gamma_f16, const void *beta_f16, float eps, void *Y_f16,
+                            int mode, int group, uint8_t *q, float *scale, float *zero, int32_t *gsum,
+                            int layout, int32_t *osum, void *stream);
+
 /* Steps a1 + a2 + a3 in ONE kernel, for small token counts (Sec. 4.2: at small batch x
  * sequence the launch overhead and the memory-bound quantize kernels decide the latency):
  * the result equals w4a4_quantize_act(X, SYM, group 0, canonical layout) followed by

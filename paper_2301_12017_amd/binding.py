@@ -62,6 +62,8 @@ _SIGNATURES = {
     "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
                          _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "w4a4_layernorm_quantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, ctypes.c_float, _vp, _i, _i, _vp, _vp, _vp, _vp,
+                                     _i, _vp, _vp]),
     "w4a4_linear_f16act": (_i, [_vp, _i, _i, _i, ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _vp, _vp]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
     "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
@@ -250,6 +252,51 @@ def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None,
                                  _ptr(out.zero), _ptr(out.gsum), out.layout, _ptr(out.osum), _stream())
     _check(rc, "w4a4_quantize_act")
     return out
+
+
+def _new_qact(M, K, mode, group, layout, dev) -> QAct:
+    ng = _ng(K, group)
+    return QAct(torch.empty((M, K // 2), dtype=torch.uint8, device=dev),
+                torch.empty((M,), dtype=torch.float32, device=dev),
+                torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
+                torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
+                M, K, K // 2, group, mode, 0, layout,
+                torch.empty((M,), dtype=torch.int32, device=dev) if layout == LAYOUT_MFMA else None)
+
+
+def layernorm_quantize(X: torch.Tensor, R: Optional[torch.Tensor], gamma: torch.Tensor, beta: torch.Tensor,
+                       eps: float, mode=SYM, group=0, layout=LAYOUT_CANONICAL, want_y=True,
+                       out: Optional[QAct] = None, y: Optional[torch.Tensor] = None):
+    """w4a4_layernorm_quantize: (QAct of LayerNorm(X + R) * gamma + beta, its fp16 copy or None)."""
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    assert R is None or (R.dtype == torch.float16 and R.shape == X.shape and R.stride() == X.stride())
+    M, K = X.shape
+    if out is None:
+        out = _new_qact(M, K, mode, group, layout, X.device)
+    if y is None and want_y:
+        y = torch.empty((M, K), dtype=torch.float16, device=X.device)
+    rc = lib().w4a4_layernorm_quantize(_ptr(X), _ptr(R), M, K, X.stride(0), _ptr(gamma), _ptr(beta), float(eps),
+                                       _ptr(y), mode, group, _ptr(out.q), _ptr(out.scale), _ptr(out.zero),
+                                       _ptr(out.gsum), out.layout, _ptr(out.osum), _stream())
+    _check(rc, "w4a4_layernorm_quantize")
+    return out, y
+
+
+class PreparedLayerNormQuantize:
+    """A w4a4_layernorm_quantize call with its arguments marshalled once (see PreparedLinear)."""
+
+    def __init__(self, X, R, gamma, beta, eps, out: QAct, y=None):
+        M, K = X.shape
+        self.keep = (X, R, gamma, beta, out, y)
+        self.args = (_ptr(X), _ptr(R), M, K, X.stride(0), _ptr(gamma), _ptr(beta), float(eps), _ptr(y), out.mode,
+                     out.group, _ptr(out.q), _ptr(out.scale), _ptr(out.zero), _ptr(out.gsum), out.layout,
+                     _ptr(out.osum))
+        self.fn = lib().w4a4_layernorm_quantize
+
+    def __call__(self, stream=None):
+        rc = self.fn(*self.args, _stream() if stream is None else stream)
+        if rc:
+            raise W4A4Error(rc, "w4a4_layernorm_quantize")
 
 
 def workspace_bytes(M, N, K, requant=False) -> int:

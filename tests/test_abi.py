@@ -142,6 +142,33 @@ def test_linear_f16act_argument_errors(b):
     assert f(M=0) == 0
 
 
+def test_layernorm_quantize_argument_errors(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+
+    def f(M=4, K=64, ldx=None, x=p, r=None, g=p, be=p, eps=1e-5, y=None, mode=0, group=0, q=p, s=p, z=None,
+          gs=None, layout=0, osum=None):
+        return L.w4a4_layernorm_quantize(x, r, M, K, K if ldx is None else ldx, g, be, eps, y, mode, group, q, s, z,
+                                         gs, layout, osum, None)
+
+    assert f(x=None) == -1 and f(g=None) == -1 and f(be=None) == -1 and f(q=None) == -1 and f(s=None) == -1
+    assert f(ldx=32) == -1                                            # ldx < K
+    assert f(eps=-1.0) == -1 and f(eps=float("nan")) == -1
+    assert f(mode=1) == -1                                            # asymmetric needs zero
+    assert f(mode=3) == -1 and f(layout=4) == -1
+    assert f(layout=1) == -1                                          # operand layout needs osum
+    assert f(layout=1, mode=1, z=p, osum=p) == -1                     # ... and symmetric codes
+    assert f(K=48) == -2                                              # K % 32
+    assert f(K=8192) == -2                                            # K > 4096
+    assert f(ldx=68) == -2                                            # rows not 16-byte aligned
+    assert f(group=24) == -2                                          # group % 32
+    assert f(K=96, group=64) == -2                                    # group must divide K
+    assert f(K=192, group=96, mode=1, z=p, gs=p) == -2                # group sums need power-of-two chunk counts
+    assert f(K=128, group=64, layout=1, osum=p) == -2                 # no K-groups in the operand layout
+    assert f(x=ctypes.c_void_p(0x1004)) == -2                         # misaligned
+    assert f(M=0) == 0
+
+
 def test_workspace_bytes(b):
     assert b.workspace_bytes(128, 768, 768, requant=False) == 0
     assert b.workspace_bytes(128, 768, 768, requant=True) == 128 * 768 * 4
