@@ -190,9 +190,9 @@ int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
                 void *out, float *out_scale, float *out_zero, int32_t *out_gsum,
                 void *workspace, size_t workspace_bytes, void *stream);
 
-/* Producer fusion (Sec. 4.2: "fuse the quantization operation for activation with its previous
- * element-bias-add, GELU, or layer normalization"): LayerNorm over the K features of every token
- * of X (+ R), then step a1 on the result, in one kernel.
+/* Producer fusion (Sec. 4.2: the quantize of an activation shares a kernel with the bias-add,
+ * GELU or LayerNorm that produces it): LayerNorm over the K features of every token of X (+ R),
+ * then step a1 on the result, in one kernel.
  *     v = X + R;  y = (v - mean(v)) / sqrt(var(v) + eps) * gamma + beta      (fp32, biased variance)
  * y is quantized per token from its fp32 value exactly as w4a4_quantize_act quantizes a row
  * (same outputs, same meaning of mode / group / layout / gsum / osum), and stored as fp16 in
