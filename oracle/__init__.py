@@ -122,6 +122,47 @@ def quantize_act(X_f16, mode=SYM, group=0):
     return dict(q=q, s=s, z=z, gsum=gs)
 
 
+def quant_sym8(v):
+    """One vector -> (int8 codes, scale): the symmetric mapping with b = 8."""
+    v = _c(v, np.float32)
+    q = np.empty(v.shape[0], np.int8)
+    S = ctypes.c_float()
+    lib().orc_quant_sym8(_p(v), v.shape[0], _p(q), ctypes.byref(S))
+    return q, np.float32(S.value)
+
+
+def quantize_rows8(X_f16):
+    """float16 [M, K] -> dict(q int8 [M,K], s f32 [M]): row-wise INT8 (tokens, or weight channels)."""
+    X = _c(X_f16, np.float16)
+    M, K = X.shape
+    q = np.empty((M, K), np.int8)
+    s = np.empty(M, np.float32)
+    rc = lib().orc_quantize_rows8(_p(X.view(np.uint16)), M, K, K, _p(q), _p(s))
+    if rc:
+        raise ValueError(f"orc_quantize_rows8 rc={rc}")
+    return dict(q=q, s=s)
+
+
+def gemm8_i32(A8, W8):
+    A, W = _c(A8, np.int8), _c(W8, np.int8)
+    M, K = A.shape
+    N = W.shape[0]
+    P = np.empty((M, N), np.int32)
+    rc = lib().orc_gemm8_i32(_p(A), K, _p(W), M, N, K, _p(P))
+    if rc:
+        raise ValueError(f"orc_gemm8_i32 rc={rc}")
+    return P
+
+
+def linear8(a, w, bias_f16=None, act=ACT_NONE):
+    """W8A8 linear: int8 GEMM, then the symmetric per-channel dequantize / bias / GELU / fp16 store of the
+    INT4 path (same C routine).  a, w: dicts from quantize_rows8.  Returns dict(P, y f32, out f16)."""
+    P = gemm8_i32(a["q"], w["q"])
+    M, N = P.shape
+    y = dequant(P.reshape(1, M, N), SYM, a["s"], w["s"], bias_f16=bias_f16, act=act)
+    return dict(P=P, y=y, out=store_f16(y))
+
+
 def layernorm_quantize(X_f16, R_f16, gamma_f16, beta_f16, eps, mode=SYM, group=0):
     """LayerNorm(x + r) * gamma + beta per token, then the token-wise quantize of the fp32 result.
     Returns dict(y16 f16 [M,K], y32 f32 [M,K], q, s, z, gsum)."""

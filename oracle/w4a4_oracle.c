@@ -359,6 +359,62 @@ int orc_gemm_i32(const uint8_t *Aq, int lda, const uint8_t *Wq, int M, int N, in
     return 0;
 }
 
+/* ------------------------------------------------ the INT8 sibling of the path (W8A8) */
+
+/* Sec. 3.1 symmetric mapping with b = 8 (the INT8 pipeline the paper measures INT4 against,
+ * Sec. 4.1 / 4.3): S = absmax / 127, q = clamp(rne(v * (127 / absmax)), -128, 127); a zero
+ * vector gets S = 1 and zero codes.  One code per byte, no packing. */
+void orc_quant_sym8(const float *v, int n, int8_t *q, float *S)
+{
+    float amax = 0.0f;
+    for (int k = 0; k < n; ++k) {
+        float a = fabsf(v[k]);
+        if (a > amax) amax = a;
+    }
+    if (amax == 0.0f) {
+        *S = 1.0f;
+        for (int k = 0; k < n; ++k) q[k] = 0;
+        return;
+    }
+    *S = amax / 127.0f;
+    float inv = 127.0f / amax;
+    for (int k = 0; k < n; ++k) {
+        float t = v[k] * inv;
+        float r = nearbyintf(clampf(t, -128.0f, 127.0f));
+        q[k] = (int8_t)r;
+    }
+}
+
+/* Row-wise INT8 quantization of fp16 rows X[M, ldx] (first K columns): token-wise for
+ * activations, per output channel for weights (App. A with b = 8).  q[M, K], s[M]. */
+int orc_quantize_rows8(const uint16_t *X, int M, int K, int ldx, int8_t *q, float *s)
+{
+    if (M < 0 || K <= 0 || ldx < K) return -1;
+    float *row = (float *)malloc(sizeof(float) * (size_t)K);
+    if (!row) return -1;
+    for (int m = 0; m < M; ++m) {
+        for (int k = 0; k < K; ++k) row[k] = orc_h2f(X[(size_t)m * ldx + k]);
+        orc_quant_sym8(row, K, q + (size_t)m * K, s + m);
+    }
+    free(row);
+    return 0;
+}
+
+/* P[m, n] = sum_k qa[m,k] * qw[n,k] on INT8 codes, 64-bit accumulation. */
+int orc_gemm8_i32(const int8_t *A, int lda, const int8_t *W, int M, int N, int K, int32_t *P)
+{
+    if (M < 0 || N < 0 || K <= 0 || lda < K) return -1;
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int k = 0; k < K; ++k)
+                acc += (int64_t)A[(size_t)m * lda + k] * (int64_t)W[(size_t)n * K + k];
+            if (acc > INT32_MAX || acc < INT32_MIN) return -2;
+            P[(size_t)m * N + n] = (int32_t)acc;
+        }
+    return 0;
+}
+
 /* ---------------------------------------------------------------- step a3: epilogue */
 
 /* erf-form GELU of an fp32 value, evaluated in double and rounded once. */
