@@ -352,6 +352,42 @@ def main():
               "note": "w4a4_layernorm_quantize with residual and fp16 copy; back-to-back launches over four "
                       "rotating buffer sets, launch gaps included"}
 
+    # ---- the INT8 sibling on the same workload (the paper's Sec. 4.1 comparison, on this hardware): the same
+    # step with w8a8_quantize_rows + w8a8_linear, timed the same way
+    i8 = {}
+    if cfg == 3:
+        w8 = [B.quantize_rows8(WL.dev(WL.make_layer(s_, cfg, i, keep_host=True).host_W)) for i, s_ in enumerate(specs)]
+        a8 = [B.quantize_rows8(X) for X in Xs]
+        q8_calls = [B.PreparedQuantizeRows8(X, a[0], a[1]) for X, a in zip(Xs, a8)]
+        l8_calls = [B.PreparedLinear8(a[0], a[1], w[0], w[1], L.bias, L.act, out=o[0])
+                    for a, w, L, o in zip(a8, w8, layers, outs)]
+        t8 = [[B.KernelTimer() for _ in specs] for _ in range(args.steps)]
+
+        def step8(tm=None):
+            for i in range(len(specs)):
+                q8_calls[i](stream)
+                if tm:
+                    tm[i].arm()
+                l8_calls[i](stream)
+        for _ in range(args.warmup):
+            step8()
+        torch.cuda.synchronize()
+        t6 = time.perf_counter()
+        for _ in range(args.steps):
+            step8()
+        torch.cuda.synchronize()
+        ms8 = (time.perf_counter() - t6) * 1e3 / args.steps
+        for k in range(args.steps):
+            step8(t8[k])
+        torch.cuda.synchronize()
+        g8 = [sum(t8[k][i].elapsed_ms() for k in range(args.steps)) / args.steps for i in range(len(specs))]
+        i8 = {"ms_per_step": ms8, "TOPS": ops / (ms8 * 1e-3) / 1e12, "kernel_ms_per_step": sum(g8),
+              "frac_of_int8_mfma_peak": ops / (sum(g8) * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
+              "per_gemm_ms": {s_.name: t for s_, t in zip(specs, g8)},
+              "int4_over_int8_gemm_speedup": sum(g8) / sum(gemm_ms),
+              "note": "w8a8_quantize_rows + w8a8_linear on the same inputs and shapes; both paths use the int8 "
+                      "MFMA, INT4 halves the operand bytes and pays for the nibble widening"}
+
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -367,6 +403,7 @@ def main():
         "per_gemm": [{"name": s.name, "ms": t, "TOPS": g} for s, t, g in zip(specs, gemm_ms, gemm_tops)],
         "latency": lat,
         "producer_fusion": ln,
+        "int8_sibling": i8,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": achieved / INT8_MFMA_PEAK_TOPS,
                      "traffic": PROFILED_TRAFFIC_BYTES.get(cfg) if args.schedule == 0 else None,

@@ -130,6 +130,27 @@ const char *w4a4_status_string(int status);
 int         w4a4_schedule_count(void);
 const char *w4a4_schedule_name(int schedule);
 
+/* ---- the INT8 sibling of the path (W8A8) ------------------------------------------------------
+ * The paper measures its INT4 pipeline against an INT8 one built from the same pieces (Sec. 4.1,
+ * Sec. 4.3).  These three calls are that sibling on this hardware, where INT4 and INT8 share the
+ * int8 MFMA: Sec. 3.1's symmetric mapping with b = 8 (S = absmax / 127, one code per byte), the
+ * INT8 x INT8 -> INT32 GEMM, and the symmetric per-token / per-channel epilogue of w4a4_linear.
+ * All pointers are device pointers; calls are asynchronous on `stream`. */
+
+/* Rows of X_f16 [M, ldx] (first K columns) -> q [M, K] int8, scale [M].  Token-wise for activations;
+ * called on W [N, K] it is the per-output-channel weight quantizer.  K % 32 == 0, K <= 16384. */
+int w8a8_quantize_rows(const void *X_f16, int M, int K, int ldx, int8_t *q, float *scale, void *stream);
+
+/* out[M, N] fp16 = epilogue(Aq[M, K] * Wq[N, K]^T): y = ((float)P * sa[m]) * sw[n] (+ bias) (GELU).
+ * lda = row stride of Aq in bytes (>= K, multiple of 16).  K % 64 == 0, K >= 128, N % 8 == 0.
+ * Of `ep` only bias_f16 and act are used; ep->requant must be 0. */
+int w8a8_linear(const int8_t *Aq, int lda, const float *sa, int M, const int8_t *Wq, const float *sw,
+                int N, int K, const w4a4_epilogue *ep, void *out, void *stream);
+
+/* The int32 accumulators alone (parity export): acc [M, N]. */
+int w8a8_gemm_i32(const int8_t *Aq, int lda, const float *sa, int M, const int8_t *Wq, const float *sw,
+                  int N, int K, int32_t *acc, void *stream);
+
 /* Measurement hook (no passage of the paper: it serves the roofline figure).  Arms the calling
  * thread: the GEMM kernel of its NEXT w4a4_linear / w4a4_gemm_i32 call records the two HIP events
  * (hipEvent_t, created by the caller with timing enabled) at the kernel's own start and end, the

@@ -62,6 +62,9 @@ _SIGNATURES = {
     "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
                          _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "w8a8_quantize_rows": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
+    "w8a8_linear": (_i, [_vp, _i, _vp, _i, _vp, _vp, _i, _i, ctypes.POINTER(_Epilogue), _vp, _vp]),
+    "w8a8_gemm_i32": (_i, [_vp, _i, _vp, _i, _vp, _vp, _i, _i, _vp, _vp]),
     "w4a4_layernorm_quantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, ctypes.c_float, _vp, _i, _i, _vp, _vp, _vp, _vp,
                                      _i, _vp, _vp]),
     "w4a4_linear_f16act": (_i, [_vp, _i, _i, _i, ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _vp, _vp]),
@@ -396,6 +399,69 @@ def linear_f16act(X: torch.Tensor, W: QWeight, bias: Optional[torch.Tensor] = No
     rc = lib().w4a4_linear_f16act(_ptr(X), M, K, X.stride(0), ctypes.byref(w), ctypes.byref(ep), _ptr(out), _stream())
     _check(rc, "w4a4_linear_f16act")
     return out
+
+
+# ---- the INT8 sibling -------------------------------------------------------------------------------
+def quantize_rows8(X: torch.Tensor, q: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None):
+    """w8a8_quantize_rows: (int8 codes [M,K], fp32 scales [M]) of fp16 rows (tokens, or weight channels)."""
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    q = torch.empty((M, K), dtype=torch.int8, device=X.device) if q is None else q
+    scale = torch.empty((M,), dtype=torch.float32, device=X.device) if scale is None else scale
+    _check(lib().w8a8_quantize_rows(_ptr(X), M, K, X.stride(0), _ptr(q), _ptr(scale), _stream()), "w8a8_quantize_rows")
+    return q, scale
+
+
+def linear8(Aq, sa, Wq, sw, bias=None, act=ACT_NONE, out=None):
+    """w8a8_linear: fp16 [M,N]."""
+    M, K = Aq.shape
+    N = Wq.shape[0]
+    out = torch.empty((M, N), dtype=torch.float16, device=Aq.device) if out is None else out
+    ep = _epilogue(bias, act, False, SYM, 0, 0, LAYOUT_CANONICAL)
+    rc = lib().w8a8_linear(_ptr(Aq), Aq.stride(0), _ptr(sa), M, _ptr(Wq), _ptr(sw), N, K, ctypes.byref(ep), _ptr(out),
+                           _stream())
+    _check(rc, "w8a8_linear")
+    return out
+
+
+def gemm8_i32(Aq, sa, Wq, sw):
+    M, K = Aq.shape
+    N = Wq.shape[0]
+    acc = torch.empty((M, N), dtype=torch.int32, device=Aq.device)
+    rc = lib().w8a8_gemm_i32(_ptr(Aq), Aq.stride(0), _ptr(sa), M, _ptr(Wq), _ptr(sw), N, K, _ptr(acc), _stream())
+    _check(rc, "w8a8_gemm_i32")
+    return acc
+
+
+class PreparedLinear8:
+    """A w8a8_linear call with its arguments marshalled once (see PreparedLinear)."""
+
+    def __init__(self, Aq, sa, Wq, sw, bias=None, act=ACT_NONE, out=None):
+        M, K = Aq.shape
+        N = Wq.shape[0]
+        self.out = torch.empty((M, N), dtype=torch.float16, device=Aq.device) if out is None else out
+        self.keep = (Aq, sa, Wq, sw, bias)
+        self.ep = _epilogue(bias, act, False, SYM, 0, 0, LAYOUT_CANONICAL)
+        self.args = (_ptr(Aq), Aq.stride(0), _ptr(sa), M, _ptr(Wq), _ptr(sw), N, K, ctypes.byref(self.ep), _ptr(self.out))
+        self.fn = lib().w8a8_linear
+
+    def __call__(self, stream=None):
+        rc = self.fn(*self.args, _stream() if stream is None else stream)
+        if rc:
+            raise W4A4Error(rc, "w8a8_linear")
+
+
+class PreparedQuantizeRows8:
+    def __init__(self, X, q, scale):
+        M, K = X.shape
+        self.keep = (X, q, scale)
+        self.args = (_ptr(X), M, K, X.stride(0), _ptr(q), _ptr(scale))
+        self.fn = lib().w8a8_quantize_rows
+
+    def __call__(self, stream=None):
+        rc = self.fn(*self.args, _stream() if stream is None else stream)
+        if rc:
+            raise W4A4Error(rc, "w8a8_quantize_rows")
 
 
 class PreparedLinearF16Act:

@@ -21,7 +21,7 @@ def b():
 def _declared_symbols():
     text = open(os.path.join(ROOT, "include", "w4a4.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(w4a4_[a-z0-9_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(w[48]a[48]_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_every_declared_symbol_is_exported(b):
@@ -167,6 +167,30 @@ def test_layernorm_quantize_argument_errors(b):
     assert f(K=128, group=64, layout=1, osum=p) == -2                 # no K-groups in the operand layout
     assert f(x=ctypes.c_void_p(0x1004)) == -2                         # misaligned
     assert f(M=0) == 0
+
+
+def test_int8_sibling_argument_errors(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x1000)
+    ep = b._Epilogue(None, 0, 0, 0, 0, 0, 0)
+
+    def lin(M=4, N=8, K=128, lda=None, a=p, sa=p, w=p, sw=p, e=ep, o=p):
+        return L.w8a8_linear(a, K if lda is None else lda, sa, M, w, sw, N, K, ctypes.byref(e), o, None)
+
+    assert lin(a=None) == -1 and lin(sa=None) == -1 and lin(w=None) == -1 and lin(sw=None) == -1 and lin(o=None) == -1
+    assert lin(lda=64) == -1                                          # lda < K
+    assert lin(e=b._Epilogue(None, 9, 0, 0, 0, 0, 0)) == -1           # unknown activation
+    assert lin(e=b._Epilogue(None, 0, 1, 0, 0, 0, 0)) == -2           # no requantize here
+    assert lin(K=96) == -2 and lin(K=64) == -2                        # K % 64, K >= 128
+    assert lin(N=12) == -2 and lin(lda=136) == -2                     # N % 8, lda % 16
+    assert lin(a=ctypes.c_void_p(0x1004)) == -2                       # misaligned
+    assert lin(M=0) == 0
+    assert L.w8a8_gemm_i32(p, 128, p, 4, p, p, 8, 128, None, None) == -1
+    assert L.w8a8_quantize_rows(None, 4, 64, 64, p, p, None) == -1
+    assert L.w8a8_quantize_rows(p, 4, 64, 32, p, p, None) == -1       # ldx < K
+    assert L.w8a8_quantize_rows(p, 4, 48, 48, p, p, None) == -2       # K % 32
+    assert L.w8a8_quantize_rows(p, 4, 32768, 32768, p, p, None) == -2
+    assert L.w8a8_quantize_rows(p, 0, 64, 64, p, p, None) == 0
 
 
 def test_workspace_bytes(b):
