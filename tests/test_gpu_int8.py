@@ -45,7 +45,8 @@ def test_quantize_strided_rows(B, orc):
 
 
 @pytest.mark.parametrize("M,N,K", [(128, 768, 768), (300, 520, 512), (1, 8, 128), (700, 1024, 1024), (193, 264, 4096),
-                                   (2048, 3072, 256), (4100, 1032, 192)])
+                                   (2048, 3072, 256), (4100, 1032, 192),
+                                   (12288, 4096, 1024), (12288, 1024, 4096)])
 def test_gemm_and_linear(B, orc, M, N, K):
     rng = np.random.default_rng(M + N + K)
     X, W, b = _xw(rng, M, N, K)

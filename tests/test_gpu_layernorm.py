@@ -89,6 +89,18 @@ def test_operand_layout_and_no_fp16_copy(B, orc):
     assert np.isfinite(Y).all()
 
 
+def test_bench_shape_sampled_rows(B, orc):
+    """The shape bench.py times (12288 x 1024, residual, fp16 copy, operand layout): sampled rows."""
+    rng = np.random.default_rng(8)
+    M, K = 12288, 1024
+    x, r, g, b = _inputs(rng, M, K)
+    A, y = B.layernorm_quantize(dev(x), dev(r), dev(g), dev(b), 1e-12, SYM, layout=MFMA)
+    rows = np.sort(np.concatenate([[0, M - 1], rng.choice(M, 62, replace=False)]))
+    want = orc.layernorm_quantize(x[rows], r[rows], g, b, 1e-12, SYM)
+    gc = _check(orc, act_to_canonical(host(A.q)[rows]), host(A.scale)[rows], None, host(y)[rows], want, SYM)
+    assert np.array_equal(host(A.osum)[rows].astype(np.int64), gc[:, 1::2].sum(axis=1))
+
+
 def test_strided_rows_and_untouched_neighbours(B, orc):
     rng = np.random.default_rng(6)
     M, K = 50, 256
