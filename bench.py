@@ -388,6 +388,30 @@ def main():
               "note": "w8a8_quantize_rows + w8a8_linear on the same inputs and shapes; both paths use the int8 "
                       "MFMA, INT4 halves the operand bytes and pays for the nibble widening"}
 
+    # ---- context only: the vendor library's FP16 GEMM (torch.matmul -> hipBLASLt) on the same four shapes, the
+    # precision the paper's speedups are quoted against.  Plain matmul: no bias, no GELU, no quantize.
+    fp16 = {}
+    if cfg == 3:
+        try:
+            Wh = [torch.randn((s_.N, s_.K), device="cuda").half() * 0.02 for s_ in specs]
+            Yh = [torch.empty((s_.M, s_.N), dtype=torch.float16, device="cuda") for s_ in specs]
+            for X, W_, Y_ in zip(Xs, Wh, Yh):
+                torch.matmul(X, W_.t(), out=Y_)
+            torch.cuda.synchronize()
+            t7 = time.perf_counter()
+            for _ in range(args.steps):
+                for X, W_, Y_ in zip(Xs, Wh, Yh):
+                    torch.matmul(X, W_.t(), out=Y_)
+            torch.cuda.synchronize()
+            ms16 = (time.perf_counter() - t7) * 1e3 / args.steps
+            fp16 = {"ms_per_step": ms16, "TFLOPS": ops / (ms16 * 1e-3) / 1e12,
+                    "w4a4_step_speedup": ms16 / ms_per_step,
+                    "note": "four torch.matmul calls (hipBLASLt FP16, fp32 accumulate) on the same activations and "
+                            "shapes, launch gaps included; the W4A4 step it is compared with also contains the four "
+                            "quantize_act kernels, bias and GELU"}
+        except Exception as ex:                                   # context only: never fail the bench over it
+            fp16 = {"error": str(ex)}
+
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -404,6 +428,7 @@ def main():
         "latency": lat,
         "producer_fusion": ln,
         "int8_sibling": i8,
+        "fp16_library_gemm": fp16,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": achieved / INT8_MFMA_PEAK_TOPS,
                      "traffic": PROFILED_TRAFFIC_BYTES.get(cfg) if args.schedule == 0 else None,
