@@ -411,6 +411,22 @@ def main():
                             "quantize_act kernels, bias and GELU"}
         except Exception as ex:                                   # context only: never fail the bench over it
             fp16 = {"error": str(ex)}
+        try:                                                          # and its INT8 GEMM (int32 out, no epilogue)
+            a8l = [a[0] for a in a8]
+            w8l = [w[0].t() for w in w8]
+            for a_, w_ in zip(a8l, w8l):
+                torch._int_mm(a_, w_)
+            torch.cuda.synchronize()
+            t8l = time.perf_counter()
+            for _ in range(args.steps):
+                for a_, w_ in zip(a8l, w8l):
+                    torch._int_mm(a_, w_)
+            torch.cuda.synchronize()
+            ms8l = (time.perf_counter() - t8l) * 1e3 / args.steps
+            fp16["int8_library_gemm_ms_per_step"] = ms8l
+            fp16["int8_library_gemm_TOPS"] = ops / (ms8l * 1e-3) / 1e12
+        except Exception as ex:
+            fp16["int8_library_gemm_error"] = str(ex)[:200]
 
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
