@@ -1,0 +1,73 @@
+"""Seeded random shapes through the one-launch small-token path, the INT8 sibling and the LayerNorm
+kernel: ragged M, N, K inside each entry point's contract, all in one process."""
+import numpy as np
+import pytest
+
+from tests.gpu_util import dev, f16_close, has_gpu, host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2301_12017_amd import binding
+    binding.lib()
+    return binding
+
+
+def test_small_token_path_random_shapes(B, orc):
+    rng = np.random.default_rng(2024)
+    for _ in range(24):
+        M = int(rng.integers(1, 200))
+        N = 8 * int(rng.integers(1, 80))
+        K = 64 * int(rng.integers(1, 65))
+        act = int(rng.integers(0, 2))
+        X = rng.standard_normal((M, K)).astype(np.float32).astype(np.float16)
+        W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+        b = (rng.standard_normal(N) * 0.01).astype(np.float16) if rng.integers(0, 2) else None
+        Q = B.quantize_weight(dev(W), 0)
+        got = host(B.linear_f16act(dev(X), Q, None if b is None else dev(b), act))
+        want = orc.linear(orc.quantize_act(X, 0), orc.quantize_weight(W, 0), 0, 0, b, act)["out"]
+        ok, ratio = f16_close(got, want)
+        assert ok, (M, N, K, act, ratio)
+        if act == 0:
+            assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), (M, N, K)
+
+
+def test_int8_sibling_random_shapes(B, orc):
+    rng = np.random.default_rng(2025)
+    for _ in range(16):
+        M = int(rng.integers(1, 700))
+        N = 8 * int(rng.integers(1, 90))
+        K = 64 * int(rng.integers(2, 40))
+        X = rng.standard_normal((M, K)).astype(np.float32).astype(np.float16)
+        W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+        b = (rng.standard_normal(N) * 0.01).astype(np.float16)
+        Aq, sa = B.quantize_rows8(dev(X))
+        Wq, sw = B.quantize_rows8(dev(W))
+        rows = np.sort(rng.choice(M, min(M, 48), replace=False))
+        a, w = orc.quantize_rows8(X[rows]), orc.quantize_rows8(W)
+        assert np.array_equal(host(Aq)[rows], a["q"]) and np.array_equal(host(Wq), w["q"])
+        assert np.array_equal(host(B.gemm8_i32(Aq, sa, Wq, sw))[rows], orc.gemm8_i32(a["q"], w["q"])), (M, N, K)
+        got = host(B.linear8(Aq, sa, Wq, sw, dev(b), 0))[rows]
+        assert np.array_equal(got.view(np.uint16), orc.linear8(a, w, b, 0)["out"].view(np.uint16)), (M, N, K)
+
+
+def test_layernorm_random_shapes(B, orc):
+    rng = np.random.default_rng(2026)
+    for _ in range(16):
+        M = int(rng.integers(1, 300))
+        K = 32 * int(rng.integers(1, 129))
+        mode = int(rng.integers(0, 2))
+        x = (rng.standard_normal((M, K)) * rng.uniform(0.1, 5)).astype(np.float32).astype(np.float16)
+        r = rng.standard_normal((M, K)).astype(np.float16) if rng.integers(0, 2) else None
+        g = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+        b = (0.1 * rng.standard_normal(K)).astype(np.float16)
+        want = orc.layernorm_quantize(x, r, g, b, 1e-5, mode)
+        A, y = B.layernorm_quantize(dev(x), None if r is None else dev(r), dev(g), dev(b), 1e-5, mode)
+        np.testing.assert_allclose(host(A.scale), want["s"], rtol=1e-5)
+        gc = orc.unpack(host(A.q), mode).astype(np.int32)
+        wc = orc.unpack(want["q"], mode).astype(np.int32)
+        assert np.max(np.abs(gc - wc)) <= 1 and np.mean(gc != wc) <= 2e-3, (M, K, mode)
+        yy, wy = host(y).astype(np.float64), want["y16"].astype(np.float64)
+        assert np.all(np.abs(yy - wy) <= np.maximum(np.abs(wy) * 2.0 ** -10, 2.0 ** -24)), (M, K, mode)
