@@ -148,7 +148,7 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path is token-parallel with no "
-              "exchange; see DESIGN.md); --gpus N with N > 1 is not supported.", file=sys.stderr)
+              "exchange); --gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
     if args.config == 5:
         return bench_chain(args)
