@@ -12,7 +12,8 @@ struct Schedule {
                          // 1 = generic, 2 = pipelined kernel, codes widened once into LDS (K % 64 == 0),
                          // 3 = pipelined kernel with direct global->LDS loads (K % 128 == 0),
                          // 4 = persistent kernel on operands in the MFMA operand layout,
-                         // 5 = persistent kernel for K-grouped / asymmetric layers
+                         // 5 = persistent kernel for K-grouped / asymmetric layers,
+                         // 6 = small-problem kernel: the waves of a workgroup split K (symmetric per-channel, K % 64 == 0)
     int variant;
     bool grouped_ok;     // usable for K-grouped / asymmetric layers
 };
@@ -34,6 +35,7 @@ static const Schedule kSchedules[] = {
     {"olay_128x256", 4, 0, false},
     {"olay_192x128", 4, 1, false},
     {"group_128x128", 5, 0, true},
+    {"small_splitk", 6, 0, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 
@@ -44,6 +46,13 @@ static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
 
 constexpr int kOlaySchedule = 14;                             // olay_128x256; +1 = olay_192x128
 constexpr int kGroupSchedule = 16;                            // group_128x128
+constexpr int kSmallSchedule = 17;                            // small_splitk
+
+// The small-problem kernel: symmetric per-channel layers in the canonical layout, fp16 or int32 output.
+static bool small_ok(const GemmArgs &g, bool grouped, int out_kind) {
+    return !grouped && (out_kind == OUT_F16 || out_kind == OUT_I32) && g.K % 64 == 0 && g.K <= 4096 && g.lda % 16 == 0 &&
+           (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL && ((long)g.M + 32) * g.N * 4 < 0x7fffffffL;
+}
 
 static bool group_ok(const GemmArgs &g, bool grouped) {
     return grouped && g.K % kBK == 0 && g.K >= 2 * kBK && (long)g.M * g.lda < 0x7fffffffL &&
@@ -55,7 +64,9 @@ static bool group_ok(const GemmArgs &g, bool grouped) {
 // narrow, so that a 12288-token problem splits into a whole number of rounds of two
 // workgroups per CU; 128 x 256 otherwise), small ones the generic tiles that still give every
 // CU something to do.
-static int pick_schedule(const GemmArgs &g, bool grouped) {
+static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
+    // a few hundred 32 x 32 tiles at most: latency decides, the waves of a workgroup split K
+    if ((long)((g.M + 31) / 32) * ((g.N + 31) / 32) <= 512 && small_ok(g, grouped, out_kind)) return kSmallSchedule;
     const long big = (long)((g.M + 127) / 128) * ((g.N + 255) / 256);
     if (big >= 256) {
         if (group_ok(g, grouped)) return kGroupSchedule;
@@ -86,7 +97,7 @@ static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int sched
     // the epilogue addresses the output with 32-bit byte offsets below 2^31
     if (((long)g.M + 512) * g.N * 4 >= 0x80000000L) return W4A4_ERR_UNSUPPORTED_SHAPE;   // (tile overhang included)
     const bool olay = g.osum != nullptr;                        // operands in the MFMA operand layout
-    if (schedule == 0) schedule = olay ? pick_olay(g) : pick_schedule(g, grouped);
+    if (schedule == 0) schedule = olay ? pick_olay(g) : pick_schedule(g, grouped, out_kind);
     if (schedule < 1 || schedule > kNumSchedules) return W4A4_ERR_INVALID_ARG;
     const Schedule &s = kSchedules[schedule - 1];
     if (grouped && !s.grouped_ok) return W4A4_ERR_INVALID_ARG;
@@ -94,6 +105,10 @@ static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int sched
     if (s.family == 4) {
         if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
         return launch_olay(s.variant, out_kind, g, st);
+    }
+    if (s.family == 6) {
+        if (!small_ok(g, grouped, out_kind)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        return launch_small_packed(out_kind, g, st);
     }
     if (s.family == 5) {
         if (!group_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;

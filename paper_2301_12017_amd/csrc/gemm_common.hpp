@@ -420,5 +420,6 @@ int launch_pipe8(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_dma(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_olay(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_group(int mode, int out_kind, GemmArgs &g, hipStream_t st);
+int launch_small_packed(int out_kind, GemmArgs &g, hipStream_t st);
 
 }  // namespace w4a4

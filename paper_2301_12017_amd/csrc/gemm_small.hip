@@ -30,7 +30,10 @@
 namespace w4a4 {
 
 struct SmallArgs {
-    const __half *X; long ldx;       // [M, K] fp16, row stride in elements
+    const __half *X; long ldx;       // [M, K] fp16, row stride in elements (fp16-activation form)
+    const uint8_t *Aq; long lda;     // [M, K/2] canonical packed codes, row stride in bytes (packed form)
+    const float *sa;                 // [M] token scales (packed form)
+    int32_t *acc_out;                // packed form only: store the int32 sums P [M, N] instead of fp16 outputs
     const uint8_t *Wq; long ldw;     // canonical packed codes [N, K/2]
     const float *sw;                 // [N]
     const __half *bias; int act;
@@ -63,25 +66,30 @@ __device__ __forceinline__ void codes8(const u32x4 &x, float inv, uint32_t &even
 
 // NW waves, FN column fragments of 32 channels, TM = 32 or 16 tokens per workgroup (with 16 the upper
 // half of the MFMA rows repeats the lower one and is not stored), WLDS: the weight tile is staged in LDS.
-template <int NW, int FN, int TM, bool WLDS>
+// PACKED: the activations arrive already quantized (packed codes + token scales, the output of
+// w4a4_quantize_act or of a producer kernel): pass 1 only parks their tile in LDS, and both operands are
+// widened to 16 * code on their way into the MFMA (the sums hold 256 * P).
+template <int NW, int FN, int TM, bool WLDS, bool PACKED>
 __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     constexpr int NT = NW * 64, LPR = NT / TM;                  // LPR consecutive lanes share a token in pass 1
     constexpr int RV = TM / 2;                                  // accumulator registers per fragment that hold real rows
     constexpr int R = RV * FN;                                  // ... of the tile
     constexpr int RPW = (R + NW - 1) / NW;                      // ... finished by one wave
     constexpr int WCH = WLDS ? small_wchunks(NW) : 1;
-    constexpr int XCH = small_xchunks(TM);
+    constexpr int XCH = PACKED ? 1 : small_xchunks(TM);
+    constexpr int ACH = PACKED ? 4 : 1;                         // 16-byte chunks of the packed activation tile per lane
     static_assert(LPR <= 64 && (LPR & (LPR - 1)) == 0, "a token's lanes sit in one wave");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const int pitch = a.K + 16, wpitch = a.K / 2 + 16;
-    uint8_t *codes = smem;                                      // [TM][pitch] int8 activation codes
+    const int wpitch = a.K / 2 + 16, pitch = PACKED ? wpitch : a.K + 16;
+    uint8_t *codes = smem;                                      // [TM][pitch] int8 activation codes (packed codes if PACKED)
     uint8_t *wt = codes + TM * pitch;                           // [32 FN][wpitch] packed weight codes (WLDS)
     int *s_sum = reinterpret_cast<int *>(wt + (WLDS ? 32 * FN * wpitch : 0));   // [R][64]
     float *s_S = reinterpret_cast<float *>(s_sum + R * 64);     // [TM]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m0 = (blockIdx.x / a.tiles_n) * TM, n0 = (blockIdx.x % a.tiles_n) * (32 * FN);
-    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(a.X, (uint32_t)(((long)(a.M - 1) * a.ldx + a.K) * 2));
+    const __amdgpu_buffer_rsrc_t x_rsrc = PACKED ? make_rsrc(a.Aq, (uint32_t)((long)(a.M - 1) * a.lda + a.K / 2))
+                                                 : make_rsrc(a.X, (uint32_t)(((long)(a.M - 1) * a.ldx + a.K) * 2));
     const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(a.Wq, (uint32_t)((long)a.N * a.ldw));
     const int r = lane & 31, h = lane >> 5;                     // pass 2: token / channel r, K half h
     const int nb = a.K / 64;
@@ -89,16 +97,33 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     // ---- requests, in the order they are needed: activation rows, weights, channel constants ----------------
     const int row = tid / LPR, c0 = tid % LPR;
     const int nchunks = a.K / 8;                                // 16-byte chunks of an activation row
+    const int wcpr = a.K / 32;                                  // 16-byte chunks of a row of packed codes
     u32x4 x[XCH];
-    {
+    u32x4 ast[ACH];
+    int arow_i[ACH];
+    uint32_t adst_i[ACH];
+    if constexpr (!PACKED) {
         const uint32_t base = (uint32_t)min(m0 + row, a.M - 1) * (uint32_t)a.ldx * 2u;
 #pragma unroll
         for (int i = 0; i < XCH; ++i)               // (chunks past the row are requested but never used)
             if (i * LPR < nchunks) x[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, base + (uint32_t)(c0 + i * LPR) * 16, 0, 0);
+    } else {
+        // the packed tile, coalesced like the weight tile below (rows past M fall outside the descriptor: zeros)
+        const int stepq = NT / wcpr, stepr = NT % wcpr;
+        int rw = tid / wcpr, cl = tid % wcpr;
+        uint32_t src = (uint32_t)(m0 + rw) * (uint32_t)a.lda + (uint32_t)cl * 16, dst = (uint32_t)(rw * pitch + cl * 16);
+        const uint32_t src_q = (uint32_t)stepq * (uint32_t)a.lda + (uint32_t)stepr * 16, dst_q = (uint32_t)(stepq * pitch + stepr * 16);
+        const uint32_t src_c = (uint32_t)a.lda - (uint32_t)wcpr * 16, dst_c = (uint32_t)(pitch - wcpr * 16);
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            arow_i[i] = rw; adst_i[i] = dst;
+            if (i * NT < TM * wcpr) ast[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, src, 0, 0);
+            rw += stepq; cl += stepr; src += src_q; dst += dst_q;
+            if (cl >= wcpr) { cl -= wcpr; ++rw; src += src_c; dst += dst_c; }
+        }
     }
     // weights: the whole tile, coalesced (consecutive lanes walk a channel's row), on its way to LDS; when
     // it does not fit there, pass 2 fetches its operands itself (lane (c, h): 16 bytes of channel c)
-    const int wcpr = a.K / 32;                                  // 16-byte chunks of a weight row
     u32x4 wst[WCH];
     // chunk tid + i NT of the tile sits in row wrow_i, column wcol_i: one division, then carries
     int wrow_i[WCH];                                            // its row, or 32 FN and more past the tile
@@ -132,7 +157,12 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     for (int e = tid; e < R * 64; e += NT) s_sum[e] = 0;
 
     // ---- pass 1: ranges, codes into LDS ----------------------------------------------------------------------
-    {
+    if constexpr (PACKED) {
+        if (tid < TM) s_S[tid] = a.sa[min(m0 + tid, a.M - 1)];
+#pragma unroll
+        for (int i = 0; i < ACH; ++i)
+            if (i * NT < TM * wcpr && arow_i[i] < TM) *reinterpret_cast<u32x4 *>(codes + adst_i[i]) = ast[i];
+    } else {
         typedef _Float16 h2 __attribute__((ext_vector_type(2)));
         uint32_t zero = 0;
         h2 mx = *reinterpret_cast<const h2 *>(&zero);
@@ -161,11 +191,11 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
                 *reinterpret_cast<uint2 *>(dst + c * 8) = make_uint2(ev, od);
             }
         }
-        if constexpr (WLDS) {
+    }
+    if constexpr (WLDS) {
 #pragma unroll
-            for (int i = 0; i < WCH; ++i) {
-                if (i * NT < 32 * FN * wcpr && wrow_i[i] < 32 * FN) *reinterpret_cast<u32x4 *>(wt + wdst_i[i]) = wst[i];
-            }
+        for (int i = 0; i < WCH; ++i) {
+            if (i * NT < 32 * FN * wcpr && wrow_i[i] < 32 * FN) *reinterpret_cast<u32x4 *>(wt + wdst_i[i]) = wst[i];
         }
     }
     __syncthreads();
@@ -176,12 +206,19 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[j][q] = 0;
-    const uint8_t *arow = codes + (r % TM) * pitch + h * 32;
+    const uint8_t *arow = codes + (r % TM) * pitch + h * (PACKED ? 16 : 32);
     const uint8_t *wrow = wt + r * wpitch + h * 16;
 #pragma unroll 1
     for (int b = wave; b < nb; b += NW) {
-        const v4i alo = *reinterpret_cast<const v4i *>(arow + b * 64);
-        const v4i ahi = *reinterpret_cast<const v4i *>(arow + b * 64 + 16);
+        v4i alo, ahi;
+        if constexpr (PACKED) {
+            const u32x4 ap = *reinterpret_cast<const u32x4 *>(arow + b * 32);
+            alo = widen2<true>(ap[0], ap[1]);
+            ahi = widen2<true>(ap[2], ap[3]);
+        } else {
+            alo = *reinterpret_cast<const v4i *>(arow + b * 64);
+            ahi = *reinterpret_cast<const v4i *>(arow + b * 64 + 16);
+        }
         u32x4 wv[FN];
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
@@ -206,7 +243,9 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
             for (int q = 0; q < RV; ++q) atomicAdd(&s_sum[(j * RV + q) * 64 + lane], acc[j][q]);
     }
     __syncthreads();
-    const __amdgpu_buffer_rsrc_t o_rsrc = make_rsrc(a.out, (uint32_t)((long)a.M * a.N * 2));
+    const bool ints = PACKED && a.acc_out != nullptr;
+    const __amdgpu_buffer_rsrc_t o_rsrc = ints ? make_rsrc(a.acc_out, (uint32_t)((long)a.M * a.N * 4))
+                                               : make_rsrc(a.out, (uint32_t)((long)a.M * a.N * 2));
 #pragma unroll
     for (int k = 0; k < RPW; ++k) {
         const int qq = wave + k * NW;
@@ -215,7 +254,13 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
         const int n = n0 + 32 * j + r;
         const bool n_ok = n < a.N;
         const int trow = frag_row(0, q, lane);
-        const float swn = __uint_as_float(sw_raw[k]) * 0.0625f;  // the sums hold 16 * P; a power of two, so exact
+        if (ints) {                                              // parity export: P itself
+            const uint32_t ioff = n_ok ? ((uint32_t)(m0 + trow) * (uint32_t)a.N + (uint32_t)n) * 4u : kPoison;
+            __builtin_amdgcn_raw_buffer_store_b32((uint32_t)(s_sum[qq * 64 + lane] >> 8), o_rsrc, ioff, 0, 0);
+            continue;
+        }
+        // the sums hold 16 * P (256 * P if PACKED); a power of two, so the rescaled weight scale is exact
+        const float swn = __uint_as_float(sw_raw[k]) * (PACKED ? 0.00390625f : 0.0625f);
         float y = ((float)s_sum[qq * 64 + lane] * s_S[trow]) * swn;
         if (a.bias) y = y + __half2float(__ushort_as_half(b_raw[k]));
         const uint32_t off = n_ok ? ((uint32_t)(m0 + trow) * (uint32_t)a.N + (uint32_t)n) * 2u : kPoison;   // rows >= M fall off the end
@@ -224,14 +269,14 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     }
 }
 
-template <int NW, int FN, int TM, bool WLDS>
+template <int NW, int FN, int TM, bool WLDS, bool PACKED>
 static int launch_small(SmallArgs &a, hipStream_t st) {
     a.tiles_n = (a.N + 32 * FN - 1) / (32 * FN);
     const long tiles = (long)((a.M + TM - 1) / TM) * a.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const size_t lds = TM * (size_t)(a.K + 16) + (WLDS ? 32 * FN * (size_t)(a.K / 2 + 16) : 0) +
+    const size_t lds = TM * (size_t)((PACKED ? a.K / 2 : a.K) + 16) + (WLDS ? 32 * FN * (size_t)(a.K / 2 + 16) : 0) +
                        (size_t)(TM / 2) * FN * 64 * 4 + TM * 4;
-    auto kern = linear_f16act_kernel<NW, FN, TM, WLDS>;
+    auto kern = linear_f16act_kernel<NW, FN, TM, WLDS, PACKED>;
     static size_t attr_lds = 0;            // benign race: the attribute call is idempotent
     if (lds > attr_lds) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -241,6 +286,50 @@ static int launch_small(SmallArgs &a, hipStream_t st) {
     }
     launch_gemm(kern, dim3((unsigned)tiles), dim3(NW * 64), lds, st, a);
     return launch_status();
+}
+
+// Shape policy.  Waves: enough that none walks more than four blocks of K nor holds more than 16 chunks of
+// a row.  Tile: every column tile re-quantizes (or re-reads) its token rows, so fewer, wider tiles do less
+// redundant work, but a tile is one CU's job: 32 x 32 while that gives at most one workgroup per CU, 32 x 64
+// beyond, and 16-token tiles when 32-token tiles would leave more than half of the CUs idle.  The weight
+// tile is staged in LDS (coalesced loads) whenever it fits beside the activation codes.
+template <bool PACKED>
+static int small_dispatch(SmallArgs &a, hipStream_t st) {
+    const int M = a.M, N = a.N, K = a.K;
+    const long t32 = (long)((M + 31) / 32) * ((N + 31) / 32);
+    const bool wide = t32 > 256, low = t32 <= 128;
+    const size_t code_b = (size_t)(low ? 16 : 32) * ((PACKED ? K / 2 : K) + 16), wt_b = (size_t)(wide ? 64 : 32) * (K / 2 + 16);
+    const int nw = K > 1536 ? 16 : K > 384 ? 8 : 4;
+    const long wchunks = ((long)(wide ? 64 : 32) * (K / 32) + nw * 64 - 1) / (nw * 64);   // per lane
+    const bool wlds = code_b + wt_b <= 144 * 1024 && wchunks <= small_wchunks(nw);   // beside the sums, within a CU's 160 KB
+#define W4A4_SMALL(NW)                                                                                  \
+    do {                                                                                                \
+        if (wide) return wlds ? launch_small<NW, 2, 32, true, PACKED>(a, st) : launch_small<NW, 2, 32, false, PACKED>(a, st); \
+        if (low) return wlds ? launch_small<NW, 1, 16, true, PACKED>(a, st) : launch_small<NW, 1, 16, false, PACKED>(a, st);  \
+        return wlds ? launch_small<NW, 1, 32, true, PACKED>(a, st) : launch_small<NW, 1, 32, false, PACKED>(a, st);     \
+    } while (0)
+    if (K > 1536) W4A4_SMALL(16);
+    if (K > 384) W4A4_SMALL(8);
+    W4A4_SMALL(4);
+#undef W4A4_SMALL
+}
+
+// The same kernel on activations that are already quantized (canonical packed codes + token scales): the
+// small-problem schedule of w4a4_linear / w4a4_gemm_i32.  Requires symmetric per-channel operands,
+// K % 64 == 0, K <= 4096, lda % 16 == 0, 32-bit offsets.
+int launch_small_packed(int out_kind, GemmArgs &g, hipStream_t st) {
+    if (out_kind != OUT_F16 && out_kind != OUT_I32) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (g.K % 64 || g.K > 4096 || g.lda % 16 || (long)g.M * g.lda >= 0x7fffffffL || (long)g.N * g.ldw >= 0x7fffffffL ||
+        ((long)g.M + 32) * g.N * 4 >= 0x7fffffffL)
+        return W4A4_ERR_UNSUPPORTED_SHAPE;
+    SmallArgs a{};
+    a.Aq = g.Aq; a.lda = g.lda; a.sa = g.sa;
+    a.Wq = g.Wq; a.ldw = g.ldw; a.sw = g.sw;
+    a.bias = g.bias; a.act = g.act;
+    if (out_kind == OUT_I32) a.acc_out = static_cast<int32_t *>(g.out);
+    else a.out = static_cast<__half *>(g.out);
+    a.M = g.M; a.N = g.N; a.K = g.K;
+    return small_dispatch<true>(a, st);
 }
 
 }  // namespace w4a4
@@ -260,32 +349,11 @@ extern "C" int w4a4_linear_f16act(const void *X_f16, int M, int K, int ldx, cons
     if (!aligned16(X_f16) || !aligned16(W->q) || !aligned16(out)) return W4A4_ERR_UNSUPPORTED_SHAPE;
     if ((long)M * ldx * 2 >= 0x7fffffffL || (long)W->N * (K / 2) >= 0x7fffffffL || ((long)M + 32) * W->N * 2 >= 0x7fffffffL)
         return W4A4_ERR_UNSUPPORTED_SHAPE;
-    SmallArgs a;
+    SmallArgs a{};
     a.X = static_cast<const __half *>(X_f16); a.ldx = ldx;
     a.Wq = W->q; a.ldw = K / 2; a.sw = W->scale;
     a.bias = static_cast<const __half *>(ep->bias_f16); a.act = ep->act;
     a.out = static_cast<__half *>(out);
     a.M = M; a.N = W->N; a.K = K; a.tiles_n = 0;
-    // Shape policy.  Waves: enough that none walks more than four blocks of K nor holds more than 16
-    // chunks of a row.  Tile: every column tile re-quantizes its token rows, so fewer, wider tiles do less
-    // redundant work, but a tile is one CU's job: 32 x 32 while that gives at most one workgroup per CU,
-    // 32 x 64 beyond, and 16-token tiles when 32-token tiles would leave more than half of the CUs idle.
-    // The weight tile is staged in LDS (coalesced loads) whenever it fits beside the activation codes.
-    hipStream_t st = as_stream(stream);
-    const long t32 = (long)((M + 31) / 32) * ((W->N + 31) / 32);
-    const bool wide = t32 > 256, low = t32 <= 128;
-    const size_t code_b = (size_t)(low ? 16 : 32) * (K + 16), wt_b = (size_t)(wide ? 64 : 32) * (K / 2 + 16);
-    const int nw = K > 1536 ? 16 : K > 384 ? 8 : 4;
-    const long wchunks = ((long)(wide ? 64 : 32) * (K / 32) + nw * 64 - 1) / (nw * 64);   // per lane
-    const bool wlds = code_b + wt_b <= 144 * 1024 && wchunks <= small_wchunks(nw);   // beside the sums, within a CU's 160 KB
-#define W4A4_SMALL(NW)                                                                                  \
-    do {                                                                                                \
-        if (wide) return wlds ? launch_small<NW, 2, 32, true>(a, st) : launch_small<NW, 2, 32, false>(a, st); \
-        if (low) return wlds ? launch_small<NW, 1, 16, true>(a, st) : launch_small<NW, 1, 16, false>(a, st);  \
-        return wlds ? launch_small<NW, 1, 32, true>(a, st) : launch_small<NW, 1, 32, false>(a, st);     \
-    } while (0)
-    if (K > 1536) W4A4_SMALL(16);
-    if (K > 384) W4A4_SMALL(8);
-    W4A4_SMALL(4);
-#undef W4A4_SMALL
+    return small_dispatch<false>(a, as_stream(stream));
 }

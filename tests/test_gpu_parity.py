@@ -119,6 +119,8 @@ def _schedules(B, grouped, K=128):
             continue
         if name.startswith("group") and (not grouped or K % 128 or K < 256):
             continue
+        if name.startswith("small") and (grouped or K % 64 or K > 4096):   # symmetric per-channel, K % 64 == 0
+            continue
         if name.startswith("pipe8"):
             if grouped or K % 64:
                 continue
