@@ -129,6 +129,27 @@ inline void launch_gemm(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t ld
     }
 }
 
+// Per-device launch state of one kernel instantiation: the dynamic-LDS limit already granted and the CU
+// count.  Function attributes and CU counts belong to a device and a process may use several, so both are
+// kept per device (races between threads are benign: the calls are idempotent).
+constexpr int kMaxDevices = 16;
+struct KernelState { size_t lds[kMaxDevices] = {}; int cus[kMaxDevices] = {}; };
+// Lets `kern` use `lds` bytes of dynamic LDS on the current device.  Returns that device's CU count, or -1.
+inline int prepare_kernel(const void *kern, size_t lds, KernelState &ks) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    if (lds > ks.lds[dev]) {
+        if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -1;
+        ks.lds[dev] = lds;
+    }
+    if (!ks.cus[dev]) {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return -1;
+        ks.cus[dev] = cus;
+    }
+    return ks.cus[dev];
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace w4a4

@@ -381,21 +381,10 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     auto kern = gemm_group_kernel<MODE, OUT>;
-    static size_t attr_lds = 0;            // benign race: the attribute call is idempotent
-    static int slots = 0;
-    if (lds > attr_lds) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return W4A4_ERR_HIP;
-        attr_lds = lds;
-    }
-    if (!slots) {
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            return W4A4_ERR_HIP;
-        slots = cus * 2;
-    }
+    static KernelState ks;
+    const int cus = prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks);
+    if (cus < 0) return W4A4_ERR_HIP;
+    const int slots = cus * 2;                                  // workgroups that are resident at once
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);

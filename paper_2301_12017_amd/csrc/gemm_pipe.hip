@@ -177,13 +177,8 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     auto kern = gemm_pipe_kernel<FM, FN, WM, WN, OCC, OUT>;
-    static bool attr_set = false;          // benign race: the attribute call is idempotent
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return W4A4_ERR_HIP;
-        attr_set = true;
-    }
+    static KernelState ks;
+    if (prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks) < 0) return W4A4_ERR_HIP;
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     launch_gemm(kern, dim3((unsigned)tiles), dim3(WM * WN * 64), lds, st, g);

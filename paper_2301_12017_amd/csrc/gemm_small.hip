@@ -277,13 +277,8 @@ static int launch_small(SmallArgs &a, hipStream_t st) {
     const size_t lds = TM * (size_t)((PACKED ? a.K / 2 : a.K) + 16) + (WLDS ? 32 * FN * (size_t)(a.K / 2 + 16) : 0) +
                        (size_t)(TM / 2) * FN * 64 * 4 + TM * 4;
     auto kern = linear_f16act_kernel<NW, FN, TM, WLDS, PACKED>;
-    static size_t attr_lds = 0;            // benign race: the attribute call is idempotent
-    if (lds > attr_lds) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return W4A4_ERR_HIP;
-        attr_lds = lds;
-    }
+    static KernelState ks;
+    if (prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks) < 0) return W4A4_ERR_HIP;
     launch_gemm(kern, dim3((unsigned)tiles), dim3(NW * 64), lds, st, a);
     return launch_status();
 }

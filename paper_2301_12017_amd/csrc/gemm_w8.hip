@@ -306,19 +306,10 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     g.tiles_m = (g.M + BM - 1) / BM;
     g.tiles_n = (g.N + BN - 1) / BN;
     auto kern = gemm_w8_kernel<FM, FN, WM, WN, OCC, OUT>;
-    static bool attr_set = false;          // benign race: the attribute call is idempotent
-    static int slots = 0;                  // workgroups that are resident at once on this device
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return W4A4_ERR_HIP;
-        int dev = 0, cus = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
-            return W4A4_ERR_HIP;
-        slots = cus * OCC;
-        attr_set = true;
-    }
+    static KernelState ks;
+    const int cus = prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks);
+    if (cus < 0) return W4A4_ERR_HIP;
+    const int slots = cus * OCC;                                // workgroups that are resident at once on this device
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
