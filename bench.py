@@ -129,7 +129,7 @@ def bench_chain(args):
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
         "value": ops / (ms * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int4 operands, int8 MFMA, int32 accumulate, fp32 epilogue, int4 out", "data": "synthetic",
+        "dtype": "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, int4 out)", "data": "synthetic",
         "config": {"workload": f"configs[4]: one layer of the chained BERT-large stack, M={M}: qkv, attn_out (V third in "
                                f"place), ffn1+GELU, ffn2, every output requantized per token in the GEMM epilogue",
                    "step": "4 x w4a4_linear(requant)", "layout": layout},
@@ -432,7 +432,7 @@ def main():
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "ms_per_step_graph_replay": graph_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int4 operands, int8 MFMA, int32 accumulate, fp32 epilogue, fp16 out",
+        "dtype": "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, fp16 out)",
         "data": "synthetic",
         "config": {"workload": f"configs[{cfg - 1}]: " + ", ".join(f"{s.name} {s.M}x{s.N}x{s.K}" for s in specs)
                    + ("; symmetric per-token / per-channel INT4" if cfg != 4 else
