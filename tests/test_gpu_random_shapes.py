@@ -71,3 +71,28 @@ def test_layernorm_random_shapes(B, orc):
         assert np.max(np.abs(gc - wc)) <= 1 and np.mean(gc != wc) <= 2e-3, (M, K, mode)
         yy, wy = host(y).astype(np.float64), want["y16"].astype(np.float64)
         assert np.all(np.abs(yy - wy) <= np.maximum(np.abs(wy) * 2.0 ** -10, 2.0 ** -24)), (M, K, mode)
+
+
+def test_operand_layout_gemm_random_shapes(B, orc):
+    """The persistent kernel (both tiles) on ragged M and N: int32 sums and fp16 outputs of sampled rows."""
+    from tests.gpu_util import act_to_canonical, wgt_to_canonical
+    rng = np.random.default_rng(2027)
+    olay = [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("olay")]
+    for _ in range(10):
+        M = int(rng.integers(1, 2500))
+        N = 8 * int(rng.integers(1, 160))
+        K = 128 * int(rng.integers(2, 17))
+        X = rng.standard_normal((M, K)).astype(np.float32).astype(np.float16)
+        W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+        b = (rng.standard_normal(N) * 0.01).astype(np.float16)
+        A = B.quantize_act(dev(X), 0, layout=1)
+        Q = B.quantize_weight(dev(W), 0, layout=1)
+        rows = np.sort(rng.choice(M, min(M, 40), replace=False))
+        oa, ow = orc.quantize_act(X[rows], 0), orc.quantize_weight(W, 0)
+        assert np.array_equal(act_to_canonical(host(A.q))[rows], oa["q"]) and np.array_equal(wgt_to_canonical(host(Q.q)), ow["q"])
+        wantP = orc.gemm_i32(oa["q"], ow["q"], 0, 0)
+        want = orc.linear(oa, ow, 0, 0, b, 0)["out"]
+        for sch in olay:
+            assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch))[:, rows], wantP), (M, N, K, sch)
+            got = host(B.linear(A, Q, dev(b), 0, schedule=sch))[rows]
+            assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), (M, N, K, sch)
