@@ -210,7 +210,7 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
     const uint32_t lane_q = ((lane & 1) == 0 && n_ok)
                                 ? (uint32_t)(m0 + row_w + 4 * h) * row_b + (uint32_t)(n_lane >> 1) : kPoison;
     constexpr float kMagic = 12582912.0f + 8.0f;                  // 1.5 * 2^23 + 8
-    int osum[32];                                                 // odd-position code sums + 16 per row (MFMA)
+    int osum[32];                                                 // odd-position sums of (code + 8) per row (MFMA)
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -220,14 +220,17 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = q * 4 + rr;
-                uint32_t packed = 0;
+                uint32_t u[FN];
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    float t = __int_as_float(acc[i][j][r]) * ivv[rr];
-                    float u = t + kMagic;                         // low mantissa bits = rne(t) + 8
-                    packed |= (__float_as_uint(u) & 0xFu) << (4 * j);
+                    const float t = __int_as_float(acc[i][j][r]) * ivv[rr];
+                    u[j] = __float_as_uint(t + kMagic);           // low byte = rne(t) + 8, in 1 .. 15
                 }
-                if (MFMA) osum[i * 16 + r] = n_ok ? (int)(((packed >> 4) & 0xFu) + ((packed >> 12) & 0xFu)) - 16 : 0;
+                // the four low bytes side by side, then squeezed into four nibbles
+                const uint32_t d = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+                if (MFMA) osum[i * 16 + r] = n_ok ? (int)__builtin_amdgcn_sad_u8(d & 0xFF00FF00u, 0u, 0u) : 16;
+                const uint32_t sq = d | (d >> 4);                 // byte 0 = codes 0,1; byte 2 = codes 2,3
+                uint32_t packed = __builtin_amdgcn_perm(sq, sq, 0x0c0c0200u);
                 packed ^= MFMA ? 0x8080u : 0x8888u;               // offset binary -> two's complement where wanted
                 const uint32_t other = __shfl_down(packed, 1, kWave);   // the next lane holds the next four channels
                 __builtin_amdgcn_raw_buffer_store_b32(packed | (other << 16), q_rsrc,
@@ -246,7 +249,8 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
                 osum[k] = keep + __shfl_xor(send, o, kWave);
             }
         }
-        if (m_c < g.M) atomicAdd(g.out_osum + (long)m_c * g.osum_slices + slice, osum[0]);
+        // every lane added 16 (two offsets of 8, or the neutral 16 of a lane past N)
+        if (m_c < g.M) atomicAdd(g.out_osum + (long)m_c * g.osum_slices + slice, osum[0] - 32 * 16);
     }
 }
 
