@@ -23,6 +23,46 @@ __device__ __forceinline__ float wave_min(float v) {
     return v;
 }
 
+// ---- reduce-scatter of 32 values over the 32 lanes of a half wave ---------------------
+// On entry every lane of a 32-lane half holds v[0..31]; on return v[0] of lane c (c = lane & 31)
+// is op over the 32 lanes of v[c].  Five halving steps; in the step for index bit b a lane
+// keeps the entries whose bit b equals its own lane bit b and hands the others to a partner
+// whose lane bit b differs and whose higher bits agree.  Bit 4 swaps 16-lane rows between two
+// registers in place; bits 3..0 pair the lanes through the cross-lane operand modes
+// (row mirror, half-row mirror, two quad permutes), so no step goes through the LDS.
+template <int CTRL, typename T>
+__device__ __forceinline__ T dpp_fetch(T x) {
+    static_assert(sizeof(T) == 4, "one register");
+    const int r = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true);
+    return __builtin_bit_cast(T, r);
+}
+template <int O, int CTRL, typename T, typename Op>
+__device__ __forceinline__ void reduce_scatter_step(T (&v)[32], int lane, Op op) {
+    const bool up = (lane & O) != 0;
+#pragma unroll
+    for (int k = 0; k < O; ++k) {
+        const T keep = up ? v[k + O] : v[k];
+        const T send = up ? v[k] : v[k + O];
+        v[k] = op(keep, dpp_fetch<CTRL>(send));
+    }
+}
+template <typename T, typename Op>
+__device__ __forceinline__ void reduce_scatter32(T (&v)[32], int lane, Op op) {
+    static_assert(sizeof(T) == 4, "one register per value");
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        // rows 1 and 3 of v[k] change places with rows 0 and 2 of v[k+16]: afterwards both
+        // registers hold, in every lane, the two partial results of the entry that lane keeps
+        const auto sw = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v[k]),
+                                                         __builtin_bit_cast(unsigned, v[k + 16]), false, false);
+        v[k] = op(__builtin_bit_cast(T, (unsigned)sw[0]), __builtin_bit_cast(T, (unsigned)sw[1]));
+    }
+    reduce_scatter_step<8, 0x140>(v, lane, op);                   // row mirror: lane i <-> 15 - i
+    reduce_scatter_step<4, 0x141>(v, lane, op);                   // half-row mirror: i <-> 7 - i
+    reduce_scatter_step<2, 0x4E>(v, lane, op);                    // quad permute [2,3,0,1]
+    reduce_scatter_step<1, 0xB1>(v, lane, op);                    // quad permute [1,0,3,2]
+}
+
 // ---- the Sec. 3.1 mappings, b = 4 ----------------------------------------------------
 // A vector's range is summarised as (lo, inv, S): code = rne(clamp((x - lo) * inv)).
 // The reciprocal is one correctly rounded fp32 divide per vector; the per-element

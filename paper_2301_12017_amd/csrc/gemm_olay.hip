@@ -127,8 +127,9 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
     static_assert(FN == 4 && FM == 2, "32 rows per half wave; two lanes assemble one dword of eight codes");
     const bool gelu = g.act == W4A4_ACT_GELU;
     const int h = lane >> 5, c = lane & 31;
-    // 1. outputs in fp32, kept in place; vmax[i*16 + r] = max over this lane's channels
-    float vmax[32];
+    // 1. outputs in fp32, kept in place; vmax[i*16 + r] = bits of the max over this lane's channels
+    //    (a non-negative, non-NaN float: such bit patterns order like unsigned integers)
+    uint32_t vmax[32];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -160,23 +161,14 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
                     acc[i][j][q * 4 + rr] = __float_as_int(y[rr][j]);
                     v = fmaxf(v, fabsf(y[rr][j]));
                 }
-                vmax[i * 16 + q * 4 + rr] = n_ok ? v : 0.0f;      // channels past N do not count
+                vmax[i * 16 + q * 4 + rr] = n_ok ? __float_as_uint(v) : 0u;   // channels past N do not count
             }
         }
     // 2. butterfly: after the step with offset o a lane keeps the rows whose index bit o equals
     //    its own lane bit o; after five steps lane c holds the maximum of row c.
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) {
-        const bool up = (lane & o) != 0;
-#pragma unroll
-        for (int k = 0; k < o; ++k) {
-            const float keep = up ? vmax[k + o] : vmax[k];
-            const float send = up ? vmax[k] : vmax[k + o];
-            vmax[k] = fmaxf(keep, __shfl_xor(send, o, kWave));
-        }
-    }
+    reduce_scatter32(vmax, lane, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
     const int m_c = m0 + row_w + frag_row(c >> 4, c & 15, lane);  // the row this lane is responsible for
-    if (m_c < g.M) atomicMax(g.rowmax + m_c, __float_as_uint(vmax[0]));
+    if (m_c < g.M) atomicMax(g.rowmax + m_c, vmax[0]);
     // 3. wait for the siblings of the row panel.  Only relaxed device-scope atomics are used (they
     //    are performed at the coherence point and bypass the L1): a release / acquire FENCE at
     //    device scope would write back and invalidate the whole L2 on every poll.  Ordering comes
@@ -239,16 +231,7 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
         }
     if (MFMA) {
         // the same butterfly with sums: lane c ends with the sum over the wave's 128 channels of row c
-#pragma unroll
-        for (int o = 16; o > 0; o >>= 1) {
-            const bool up = (lane & o) != 0;
-#pragma unroll
-            for (int k = 0; k < o; ++k) {
-                const int keep = up ? osum[k + o] : osum[k];
-                const int send = up ? osum[k] : osum[k + o];
-                osum[k] = keep + __shfl_xor(send, o, kWave);
-            }
-        }
+        reduce_scatter32(osum, lane, [](int a, int b) { return a + b; });
         // every lane added 16 (two offsets of 8, or the neutral 16 of a lane past N)
         if (m_c < g.M) atomicAdd(g.out_osum + (long)m_c * g.osum_slices + slice, osum[0] - 32 * 16);
     }
