@@ -202,7 +202,9 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
     const uint32_t lane_q = ((lane & 1) == 0 && n_ok)
                                 ? (uint32_t)(m0 + row_w + 4 * h) * row_b + (uint32_t)(n_lane >> 1) : kPoison;
     constexpr float kMagic = 12582912.0f + 8.0f;                  // 1.5 * 2^23 + 8
-    int osum[32];                                                 // odd-position sums of (code + 8) per row (MFMA)
+    // even lanes fill the low half of a dword of eight codes, odd lanes the high half
+    const uint32_t half_sel = (lane & 1) ? 0x04000c0cu : 0x0c0c0400u;
+    int osum[32];                                                 // 16 * odd-position sums of (code + 8) per row (MFMA)
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -218,22 +220,21 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
                     const float t = __int_as_float(acc[i][j][r]) * ivv[rr];
                     u[j] = __float_as_uint(t + kMagic);           // low byte = rne(t) + 8, in 1 .. 15
                 }
-                // the four low bytes side by side, then squeezed into four nibbles
-                const uint32_t d = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
-                if (MFMA) osum[i * 16 + r] = n_ok ? (int)__builtin_amdgcn_sad_u8(d & 0xFF00FF00u, 0u, 0u) : 16;
-                const uint32_t sq = d | (d >> 4);                 // byte 0 = codes 0,1; byte 2 = codes 2,3
-                uint32_t packed = __builtin_amdgcn_perm(sq, sq, 0x0c0c0200u);
-                packed ^= MFMA ? 0x8080u : 0x8888u;               // offset binary -> two's complement where wanted
-                const uint32_t other = __shfl_down(packed, 1, kWave);   // the next lane holds the next four channels
-                __builtin_amdgcn_raw_buffer_store_b32(packed | (other << 16), q_rsrc,
-                                                      lane_q + (uint32_t)(i * 32 + 8 * q + rr) * row_b, 0, 0);
+                // two codes per byte (bits above the byte are junk), then the two bytes into this
+                // lane's half of the dword; the neighbour's half arrives through the quad permute
+                const uint32_t p01 = (u[1] << 4) | u[0], p23 = (u[3] << 4) | u[2];
+                const uint32_t half = __builtin_amdgcn_perm(p23, p01, half_sel);
+                if (MFMA) osum[i * 16 + r] = n_ok ? (int)__builtin_amdgcn_sad_u8(half & 0xF0F0F0F0u, 0u, 0u) : 256;
+                uint32_t packed = half | dpp_fetch<0xB1>(half);
+                packed ^= MFMA ? 0x80808080u : 0x88888888u;       // offset binary -> two's complement where wanted
+                __builtin_amdgcn_raw_buffer_store_b32(packed, q_rsrc, lane_q + (uint32_t)(i * 32 + 8 * q + rr) * row_b, 0, 0);
             }
         }
     if (MFMA) {
         // the same butterfly with sums: lane c ends with the sum over the wave's 128 channels of row c
         reduce_scatter32(osum, lane, [](int a, int b) { return a + b; });
-        // every lane added 16 (two offsets of 8, or the neutral 16 of a lane past N)
-        if (m_c < g.M) atomicAdd(g.out_osum + (long)m_c * g.osum_slices + slice, osum[0] - 32 * 16);
+        // in units of 1/16; every lane added 16 (two offsets of 8, or the neutral 16 of a lane past N)
+        if (m_c < g.M) atomicAdd(g.out_osum + (long)m_c * g.osum_slices + slice, (osum[0] >> 4) - 32 * 16);
     }
 }
 
