@@ -333,3 +333,66 @@ def truth64(A, W, mode=SYM, bias_f16=None, act=ACT_NONE):
         erf = np.vectorize(math.erf)
         y = 0.5 * y * (1.0 + erf(y / math.sqrt(2.0)))
     return y
+
+
+# ------------------------------------------------------------------ per-part strategy (Sec. 4.2 / 4.3)
+# The four linear parts are separate components whose INT4 quantization can be switched on or off;
+# a part that is off runs in the INT8 sibling.  A strategy is a bit set (bit p = part p in INT4),
+# plus FUSED_FFN when FFN1 hands requantized codes straight to FFN2 (Sec. 4.2: quantize fused
+# behind bias-add / GELU).
+PART_QKV, PART_ATTN_OUT, PART_FFN1, PART_FFN2 = range(4)
+FUSED_FFN = 16
+
+
+def strategy_valid(strategy: int) -> bool:
+    if strategy < 0 or strategy > 31:
+        return False
+    both = (1 << PART_FFN1) | (1 << PART_FFN2)
+    return not (strategy & FUSED_FFN) or (strategy & both) == both
+
+
+def strategy_cost(part_us, ffn_fused_us, strategy: int) -> float:
+    """Total cost of one strategy: part_us[p][0] = INT8, part_us[p][1] = INT4 for the part alone;
+    the fused FFN pair costs ffn_fused_us in place of its two parts."""
+    if not strategy_valid(strategy):
+        raise ValueError("invalid strategy")
+    bit = lambda p: (strategy >> p) & 1
+    total = float(part_us[PART_QKV][bit(PART_QKV)]) + float(part_us[PART_ATTN_OUT][bit(PART_ATTN_OUT)])
+    if strategy & FUSED_FFN:
+        total += float(ffn_fused_us)
+    else:
+        total += float(part_us[PART_FFN1][bit(PART_FFN1)]) + float(part_us[PART_FFN2][bit(PART_FFN2)])
+    return total
+
+
+def pick_strategy(part_us, ffn_fused_us) -> int:
+    """Every valid strategy priced; the cheapest wins, ties go to more INT4 parts, then to the fused pair."""
+    best = None
+    for s in range(32):
+        if not strategy_valid(s):
+            continue
+        key = (strategy_cost(part_us, ffn_fused_us, s), -bin(s & 15).count("1"), -(s >> 4))
+        if best is None or key < best[0]:
+            best = (key, s)
+    return best[1]
+
+
+def part_linear(X_f16, W_f16, int4: bool, bias_f16=None, act=ACT_NONE, mode=SYM, group=0):
+    """One part, fp16 in, fp16 out: token-wise quantize + linear in INT4 (Sec. 3.1 with b = 4) or in INT8."""
+    if int4:
+        return linear(quantize_act(X_f16, mode, group), quantize_weight(W_f16, mode, group), mode, group,
+                      bias_f16=bias_f16, act=act)["out"]
+    return linear8(quantize_rows8(X_f16), quantize_rows8(W_f16), bias_f16=bias_f16, act=act)["out"]
+
+
+def ffn(X_f16, W1_f16, b1_f16, act1, W2_f16, b2_f16, strategy: int):
+    """FFN1 (+ activation) then FFN2 under a strategy (symmetric per-channel weights).  Fused: FFN1's fp32
+    outputs are quantized per token without the fp16 rounding in between."""
+    if not strategy_valid(strategy):
+        raise ValueError("invalid strategy")
+    i1, i2 = bool(strategy >> PART_FFN1 & 1), bool(strategy >> PART_FFN2 & 1)
+    if strategy & FUSED_FFN:
+        H = linear(quantize_act(X_f16), quantize_weight(W1_f16), bias_f16=b1_f16, act=act1, requant=True)
+        return linear(H, quantize_weight(W2_f16), bias_f16=b2_f16)["out"]
+    H16 = part_linear(X_f16, W1_f16, i1, b1_f16, act1)
+    return part_linear(H16, W2_f16, i2, b2_f16)
