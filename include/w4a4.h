@@ -151,6 +151,75 @@ int w8a8_linear(const int8_t *Aq, int lda, const float *sa, int M, const int8_t 
 int w8a8_gemm_i32(const int8_t *Aq, int lda, const float *sa, int M, const int8_t *Wq, const float *sw,
                   int N, int K, int32_t *acc, void *stream);
 
+/* ---- per-part quantization strategy ---------------------------------------------------------
+ * Sec. 4.2 (last paragraphs) builds the four linear parts of an encoder layer (QKV projection,
+ * attention output, MLP intermediate, MLP output) as separate components whose INT4 quantization
+ * can be switched on or off one by one, because gain and quantize overhead depend on model size,
+ * input shape and hardware; Sec. 4.3 reports that on the paper's GPU the smallest inputs are
+ * served best with only the MLP intermediate GEMM in INT4.  A part that is switched off runs in
+ * a higher-bit type, which costs no accuracy; here that is the INT8 sibling above.  Which
+ * combination is fastest is measured in the deployment environment, as the paper tunes its
+ * GEMM schedules there. */
+enum { W4A4_PART_QKV = 0, W4A4_PART_ATTN_OUT = 1, W4A4_PART_FFN1 = 2, W4A4_PART_FFN2 = 3, W4A4_PARTS = 4 };
+
+/* A strategy is a bit set: bit p (1 << W4A4_PART_*) = part p runs in INT4, else in INT8.
+ * W4A4_STRATEGY_FUSED_FFN (needs the FFN1 and FFN2 bits): FFN1's epilogue requantizes its fp32
+ * outputs per token and hands packed codes to FFN2 (Sec. 4.2: quantize fused behind bias-add /
+ * GELU); without it FFN1 stores fp16 and FFN2 quantizes that. */
+#define W4A4_STRATEGY_FUSED_FFN 16
+#define W4A4_STRATEGY_ALL_INT4 31
+
+/* One linear part, its weights prepared in both precisions (device pointers, caller-owned). */
+typedef struct {
+    w4a4_weight   w4;        /* INT4 form, any mode / group / layout w4a4_linear accepts        */
+    const int8_t *w8q;       /* INT8 form [N, K] (w8a8_quantize_rows of the same fp16 weights) */
+    const float  *w8s;       /* [N]                                                            */
+    const void   *bias_f16;  /* [N] or NULL                                                    */
+    int           act;       /* w4a4_act_fn                                                    */
+} w4a4_part;
+
+/* Bytes of device workspace w4a4_part_linear needs for M tokens (either precision). */
+size_t w4a4_part_workspace_bytes(int M, const w4a4_part *P);
+
+/* out_f16 [M, N] = part P applied to X_f16 [M, ldx] (first K columns), in INT4 (int4 != 0:
+ * steps a1..a3, in one kernel when the shape allows, else token-wise quantize + w4a4_linear) or in
+ * INT8 (w8a8_quantize_rows + w8a8_linear).  The result is bit for bit what those calls give.
+ * Asynchronous on `stream`; the workspace (256-byte aligned) is free again when the call's work
+ * has finished.  INT8 needs K % 64 == 0, K >= 128. */
+int w4a4_part_linear(const void *X_f16, int M, int ldx, const w4a4_part *P, int int4, void *out_f16,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+/* FFN1 (+ its activation) followed by FFN2 under `strategy` (only the FFN1 / FFN2 / FUSED_FFN
+ * bits are read).  out_f16 [M, N2].  FUSED_FFN needs symmetric FFN2 weights.  The workspace
+ * holds the intermediate [M, N1] as well. */
+size_t w4a4_ffn_workspace_bytes(int M, const w4a4_part *ffn1, const w4a4_part *ffn2);
+int w4a4_ffn(const void *X_f16, int M, int ldx, const w4a4_part *ffn1, const w4a4_part *ffn2, int strategy,
+             void *out_f16, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Measured cost of the options, in microseconds. */
+typedef struct {
+    float part_us[4][2];     /* [part][0] = INT8, [part][1] = INT4: the part alone, fp16 in, fp16 out */
+    float ffn_fused_us;      /* FFN1 + FFN2 in INT4 with the codes handed over in the epilogue        */
+} w4a4_strategy_costs;
+
+/* The strategy of least total cost: QKV and attention output are independent choices; the FFN
+ * pair costs part_us[FFN1][.] + part_us[FFN2][.], or ffn_fused_us with FUSED_FFN.  Ties go to the
+ * strategy with more INT4 parts, then to the fused one.  Pure host arithmetic.  Returns the bit
+ * set, or W4A4_ERR_INVALID_ARG for NULL / negative / non-finite costs. */
+int w4a4_strategy_pick(const w4a4_strategy_costs *costs);
+
+/* Measures all options for an encoder layer of this shape (hidden size h: QKV h -> 3h, attention
+ * output h -> h, FFN1 h -> ffn with GELU, FFN2 ffn -> h; symmetric per-channel weights, biases)
+ * on the current device with synthetic operands: `iters` timed runs per option after two warm-up
+ * runs, HIP events on `stream`.  Allocates and frees its own device buffers and synchronizes the
+ * stream.  Fills *costs (may be NULL), remembers the picked strategy for this (device, M, h, ffn)
+ * and returns it (>= 0) or a w4a4_status (< 0).  h % 64 == 0, ffn % 64 == 0, h <= 4096, ffn <= 16384. */
+int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_strategy_costs *costs, void *stream);
+
+/* The strategy remembered by w4a4_strategy_tune for this shape on the current device, else the
+ * built-in table measured on MI355X (every part in INT4; FFN pair fused from 1024 tokens up). */
+int w4a4_strategy_lookup(int M, int hidden, int ffn);
+
 /* Measurement hook (no passage of the paper: it serves the roofline figure).  Arms the calling
  * thread: the GEMM kernel of its NEXT w4a4_linear / w4a4_gemm_i32 call records the two HIP events
  * (hipEvent_t, created by the caller with timing enabled) at the kernel's own start and end, the

@@ -46,6 +46,15 @@ class _Epilogue(ctypes.Structure):
                 ("requant_layout", ctypes.c_int), ("schedule", ctypes.c_int)]
 
 
+class _Part(ctypes.Structure):
+    _fields_ = [("w4", _Weight), ("w8q", ctypes.c_void_p), ("w8s", ctypes.c_void_p),
+                ("bias_f16", ctypes.c_void_p), ("act", ctypes.c_int)]
+
+
+class _StrategyCosts(ctypes.Structure):
+    _fields_ = [("part_us", (ctypes.c_float * 2) * 4), ("ffn_fused_us", ctypes.c_float)]
+
+
 _lib = None
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
@@ -68,6 +77,13 @@ _SIGNATURES = {
     "w4a4_layernorm_quantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, ctypes.c_float, _vp, _i, _i, _vp, _vp, _vp, _vp,
                                      _i, _vp, _vp]),
     "w4a4_linear_f16act": (_i, [_vp, _i, _i, _i, ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue), _vp, _vp]),
+    "w4a4_part_workspace_bytes": (_sz, [_i, ctypes.POINTER(_Part)]),
+    "w4a4_part_linear": (_i, [_vp, _i, _i, ctypes.POINTER(_Part), _i, _vp, _vp, _sz, _vp]),
+    "w4a4_ffn_workspace_bytes": (_sz, [_i, ctypes.POINTER(_Part), ctypes.POINTER(_Part)]),
+    "w4a4_ffn": (_i, [_vp, _i, _i, ctypes.POINTER(_Part), ctypes.POINTER(_Part), _i, _vp, _vp, _sz, _vp]),
+    "w4a4_strategy_pick": (_i, [ctypes.POINTER(_StrategyCosts)]),
+    "w4a4_strategy_tune": (_i, [_i, _i, _i, _i, ctypes.POINTER(_StrategyCosts), _vp]),
+    "w4a4_strategy_lookup": (_i, [_i, _i, _i]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
     "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
                                    ctypes.POINTER(_Epilogue), _vp, _vp, _vp, _vp, _vp]),
@@ -462,6 +478,88 @@ class PreparedQuantizeRows8:
         rc = self.fn(*self.args, _stream() if stream is None else stream)
         if rc:
             raise W4A4Error(rc, "w8a8_quantize_rows")
+
+
+# ---- per-part strategy -------------------------------------------------------------------------------
+PART_QKV, PART_ATTN_OUT, PART_FFN1, PART_FFN2 = range(4)
+STRATEGY_FUSED_FFN, STRATEGY_ALL_INT4 = 16, 31
+
+
+class Part:
+    """One linear part with its weights prepared in both precisions (w4a4_part in include/w4a4.h).
+    The INT4 weights take the layout the library prefers for M tokens."""
+
+    def __init__(self, W: torch.Tensor, M: int, bias: Optional[torch.Tensor] = None, act=ACT_NONE, mode=SYM, group=0):
+        N, K = W.shape
+        self.w4 = quantize_weight(W, mode, group, preferred_layout(M, N, K, mode, group))
+        self.w8q, self.w8s = quantize_rows8(W)
+        self.bias, self.act, self.N, self.K = bias, act, N, K
+
+    def c(self) -> _Part:
+        return _Part(self.w4.c(), _ptr(self.w8q), _ptr(self.w8s), _ptr(self.bias), self.act)
+
+
+def _workspace(nbytes: int, dev) -> torch.Tensor:
+    return torch.empty((max(nbytes, 256),), dtype=torch.uint8, device=dev)
+
+
+def part_linear(X: torch.Tensor, P: Part, int4: bool, out=None, workspace=None) -> torch.Tensor:
+    """w4a4_part_linear: fp16 [M, N] of part P in INT4 or in INT8."""
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    M = X.shape[0]
+    c = P.c()
+    need = lib().w4a4_part_workspace_bytes(M, ctypes.byref(c))
+    workspace = _workspace(need, X.device) if workspace is None else workspace
+    out = torch.empty((M, P.N), dtype=torch.float16, device=X.device) if out is None else out
+    rc = lib().w4a4_part_linear(_ptr(X), M, X.stride(0), ctypes.byref(c), int(bool(int4)), _ptr(out), _ptr(workspace),
+                                workspace.numel(), _stream())
+    _check(rc, "w4a4_part_linear")
+    return out
+
+
+def ffn(X: torch.Tensor, P1: Part, P2: Part, strategy: int, out=None, workspace=None) -> torch.Tensor:
+    """w4a4_ffn: FFN1 then FFN2 under `strategy` (bits PART_FFN1, PART_FFN2, STRATEGY_FUSED_FFN)."""
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    M = X.shape[0]
+    c1, c2 = P1.c(), P2.c()
+    need = lib().w4a4_ffn_workspace_bytes(M, ctypes.byref(c1), ctypes.byref(c2))
+    workspace = _workspace(need, X.device) if workspace is None else workspace
+    out = torch.empty((M, P2.N), dtype=torch.float16, device=X.device) if out is None else out
+    rc = lib().w4a4_ffn(_ptr(X), M, X.stride(0), ctypes.byref(c1), ctypes.byref(c2), strategy, _ptr(out),
+                        _ptr(workspace), workspace.numel(), _stream())
+    _check(rc, "w4a4_ffn")
+    return out
+
+
+def _costs_struct(part_us, ffn_fused_us) -> _StrategyCosts:
+    c = _StrategyCosts()
+    for p in range(4):
+        for k in range(2):
+            c.part_us[p][k] = part_us[p][k]
+    c.ffn_fused_us = ffn_fused_us
+    return c
+
+
+def strategy_pick(part_us, ffn_fused_us) -> int:
+    """w4a4_strategy_pick on a 4 x 2 table of microseconds ([part][0] INT8, [part][1] INT4)."""
+    c = _costs_struct(part_us, ffn_fused_us)
+    rc = lib().w4a4_strategy_pick(ctypes.byref(c))
+    _check(min(rc, 0), "w4a4_strategy_pick")
+    return rc
+
+
+def strategy_tune(M: int, hidden: int, ffn_size: int, iters: int = 20):
+    """w4a4_strategy_tune: (strategy, part_us [4][2], ffn_fused_us) measured on the current device."""
+    c = _StrategyCosts()
+    rc = lib().w4a4_strategy_tune(M, hidden, ffn_size, iters, ctypes.byref(c), _stream())
+    _check(min(rc, 0), "w4a4_strategy_tune")
+    return rc, [[c.part_us[p][k] for k in range(2)] for p in range(4)], c.ffn_fused_us
+
+
+def strategy_lookup(M: int, hidden: int, ffn_size: int) -> int:
+    rc = lib().w4a4_strategy_lookup(M, hidden, ffn_size)
+    _check(min(rc, 0), "w4a4_strategy_lookup")
+    return rc
 
 
 class PreparedLinearF16Act:

@@ -1,0 +1,375 @@
+// Per-part quantization strategy (Sec. 4.2, last paragraphs; Sec. 4.3): the four linear parts of
+// an encoder layer as components that run in INT4 or in the INT8 sibling, the FFN pair with or
+// without the codes handed over in FFN1's epilogue, and the tuner that measures every option on
+// the device it runs on and picks the cheapest combination.  Host code over the library's own
+// entry points; the only kernels here fill the tuner's synthetic operands.
+#include <math.h>
+
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
+
+#include "common.hpp"
+
+namespace w4a4 {
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t up(size_t b) { return (b + kAlign - 1) / kAlign * kAlign; }
+
+// Carves 256-byte aligned pieces off a workspace; `need` only adds up when base is null.
+struct Carver {
+    uint8_t *base;
+    size_t used = 0;
+    explicit Carver(void *b) : base(static_cast<uint8_t *>(b)) {}
+    template <typename T>
+    T *take(size_t count) {
+        T *p = base ? reinterpret_cast<T *>(base + used) : nullptr;
+        used += up(count * sizeof(T));
+        return p;
+    }
+};
+
+int groups_of(const w4a4_weight &w) { return (w.group == 0 || w.group >= w.K) ? 1 : w.K / w.group; }
+
+// Buffers of a token-wise quantized activation matrix [M, K] that matches weights `w`.
+struct ActBuffers {
+    uint8_t *q; float *scale, *zero; int32_t *gsum, *osum;
+};
+ActBuffers carve_act4(Carver &c, int M, int K, const w4a4_weight &w) {
+    ActBuffers b;
+    b.q = c.take<uint8_t>((size_t)M * (K / 2));
+    b.scale = c.take<float>(M);
+    b.zero = c.take<float>(M);
+    b.gsum = c.take<int32_t>((size_t)M * groups_of(w));
+    b.osum = c.take<int32_t>(M);
+    return b;
+}
+w4a4_act view_act4(const ActBuffers &b, int M, int K, const w4a4_weight &w) {
+    w4a4_act a;
+    a.q = b.q; a.scale = b.scale;
+    a.zero = w.mode == W4A4_ASYM ? b.zero : nullptr;
+    a.gsum = w.mode == W4A4_ASYM ? b.gsum : nullptr;
+    a.M = M; a.K = K; a.lda = K / 2; a.group = w.group; a.mode = w.mode; a.layout = w.layout;
+    a.osum = w.layout == W4A4_LAYOUT_MFMA ? b.osum : nullptr;
+    a.ldo = 1;
+    return a;
+}
+
+size_t part_bytes(int M, const w4a4_part &p) {
+    const int K = p.w4.K;
+    Carver c4(nullptr);
+    carve_act4(c4, M, K, p.w4);
+    Carver c8(nullptr);
+    c8.take<int8_t>((size_t)M * K);
+    c8.take<float>(M);
+    return c4.used > c8.used ? c4.used : c8.used;
+}
+
+bool part_ok(const w4a4_part *p) {
+    return p && p->w4.N > 0 && p->w4.K > 0 && p->w4.K % 32 == 0 &&
+           (p->act == W4A4_ACT_NONE || p->act == W4A4_ACT_GELU);
+}
+
+// one launch for small token counts: symmetric per-channel weights in the canonical layout
+bool one_kernel_shape(int M, const w4a4_weight &w) {
+    return w.layout == W4A4_LAYOUT_CANONICAL && w.mode == W4A4_SYM && groups_of(w) == 1 && w.K % 64 == 0 &&
+           w.K <= 4096 && (long)((M + 31) / 32) * ((w.N + 31) / 32) <= 512;
+}
+
+int run_part(const void *X, int M, int ldx, const w4a4_part &p, bool int4, void *out, void *ws, void *stream) {
+    const int K = p.w4.K, N = p.w4.N;
+    w4a4_epilogue ep = {};
+    ep.bias_f16 = p.bias_f16;
+    ep.act = p.act;
+    if (int4) {
+        if (one_kernel_shape(M, p.w4)) {
+            const int rc = w4a4_linear_f16act(X, M, K, ldx, &p.w4, &ep, out, stream);
+            if (rc != W4A4_ERR_UNSUPPORTED_SHAPE) return rc;
+        }
+        Carver c(ws);
+        const ActBuffers b = carve_act4(c, M, K, p.w4);
+        const w4a4_act a = view_act4(b, M, K, p.w4);
+        int rc = w4a4_quantize_act(X, M, K, ldx, p.w4.mode, p.w4.group, b.q, b.scale, a.zero ? b.zero : nullptr,
+                                   a.gsum ? b.gsum : nullptr, p.w4.layout, b.osum, stream);
+        if (rc) return rc;
+        return w4a4_linear(&a, &p.w4, &ep, out, nullptr, nullptr, nullptr, nullptr, 0, stream);
+    }
+    if (!p.w8q || !p.w8s) return W4A4_ERR_INVALID_ARG;
+    Carver c(ws);
+    int8_t *q = c.take<int8_t>((size_t)M * K);
+    float *s = c.take<float>(M);
+    int rc = w8a8_quantize_rows(X, M, K, ldx, q, s, stream);
+    if (rc) return rc;
+    return w8a8_linear(q, K, s, M, p.w8q, p.w8s, N, K, &ep, out, stream);
+}
+
+// ---- FFN pair -----------------------------------------------------------------------------------
+struct FusedPlan {
+    ActBuffers a1, h;
+    void *lin_ws;
+    size_t lin_bytes;
+    size_t total;
+};
+w4a4_epilogue fused_epilogue(const w4a4_part &f1, const w4a4_part &f2) {
+    w4a4_epilogue ep = {};
+    ep.bias_f16 = f1.bias_f16;
+    ep.act = f1.act;
+    ep.requant = 1;
+    ep.requant_mode = W4A4_SYM;
+    ep.requant_group = 0;
+    ep.requant_layout = f2.w4.layout;
+    return ep;
+}
+FusedPlan plan_fused(void *ws, int M, const w4a4_part &f1, const w4a4_part &f2) {
+    Carver c(ws);
+    FusedPlan p;
+    p.a1 = carve_act4(c, M, f1.w4.K, f1.w4);
+    p.h = carve_act4(c, M, f2.w4.K, f2.w4);
+    const w4a4_act a1 = view_act4(p.a1, M, f1.w4.K, f1.w4);
+    const w4a4_epilogue ep = fused_epilogue(f1, f2);
+    p.lin_bytes = w4a4_linear_workspace_bytes(&a1, &f1.w4, &ep, f2.w4.layout == W4A4_LAYOUT_MFMA);
+    p.lin_ws = c.take<uint8_t>(p.lin_bytes);
+    p.total = c.used;
+    return p;
+}
+size_t unfused_bytes(int M, const w4a4_part &f1, const w4a4_part &f2) {
+    const size_t a = part_bytes(M, f1), b = part_bytes(M, f2);
+    return up((size_t)M * f1.w4.N * 2) + (a > b ? a : b);
+}
+
+// ---- tuner --------------------------------------------------------------------------------------
+__global__ void fill_bytes_kernel(uint32_t *p, size_t words, uint32_t seed) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x) {
+        uint32_t x = (uint32_t)i * 0x9E3779B9u + seed;          // an integer hash: every byte looks random
+        x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+        p[i] = x;
+    }
+}
+__global__ void fill_halves_kernel(__half *p, size_t n, uint32_t seed, float amp) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        uint32_t x = (uint32_t)i * 0x9E3779B9u + seed;
+        x ^= x >> 16; x *= 0x7FEB352Du; x ^= x >> 15; x *= 0x846CA68Bu; x ^= x >> 16;
+        // the sum of two uniforms: a bell-ish spread, so that a token uses most of the sixteen levels
+        const float u = ((float)(x & 0xFFFF) + (float)(x >> 16)) * (1.0f / 65536.0f) - 1.0f;
+        p[i] = __float2half(u * amp);
+    }
+}
+__global__ void fill_floats_kernel(float *p, size_t n, float v) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// Device buffers of one tuning run; everything is released when it goes out of scope.
+struct Arena {
+    std::vector<void *> ptrs;
+    bool ok = true;
+    template <typename T>
+    T *get(size_t count) {
+        void *p = nullptr;
+        if (!ok || hipMalloc(&p, up(count * sizeof(T))) != hipSuccess) { ok = false; return nullptr; }
+        ptrs.push_back(p);
+        return static_cast<T *>(p);
+    }
+    ~Arena() { for (void *p : ptrs) (void)hipFree(p); }
+};
+
+unsigned fill_grid(size_t n) { const size_t b = (n + 255) / 256; return (unsigned)(b > 4096 ? 4096 : (b ? b : 1)); }
+
+// A synthetic part: random codes in both precisions, scales of the size trained layers have.
+bool make_part(Arena &ar, int M, int N, int K, int act, uint32_t seed, hipStream_t st, w4a4_part *out) {
+    w4a4_part p = {};
+    const int layout = w4a4_preferred_layout(M, N, K, W4A4_SYM, 0);
+    uint8_t *q4 = ar.get<uint8_t>((size_t)N * (K / 2));
+    float *s4 = ar.get<float>(N);
+    int32_t *es = ar.get<int32_t>(N);
+    int8_t *q8 = ar.get<int8_t>((size_t)N * K);
+    float *s8 = ar.get<float>(N);
+    __half *bias = ar.get<__half>(N);
+    if (!ar.ok) return false;
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3(fill_grid((size_t)N * K / 8)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t *>(q4), (size_t)N * K / 8, seed);
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3(fill_grid((size_t)N * K / 4)), dim3(256), 0, st,
+                       reinterpret_cast<uint32_t *>(q8), (size_t)N * K / 4, seed + 1);
+    hipLaunchKernelGGL(fill_floats_kernel, dim3(fill_grid(N)), dim3(256), 0, st, s4, (size_t)N, 0.02f);
+    hipLaunchKernelGGL(fill_floats_kernel, dim3(fill_grid(N)), dim3(256), 0, st, s8, (size_t)N, 0.001f);
+    hipLaunchKernelGGL(fill_floats_kernel, dim3(fill_grid(N)), dim3(256), 0, st, reinterpret_cast<float *>(es), (size_t)N, 0.0f);
+    hipLaunchKernelGGL(fill_halves_kernel, dim3(fill_grid(N)), dim3(256), 0, st, bias, (size_t)N, seed + 2, 0.1f);
+    p.w4.q = q4; p.w4.scale = s4; p.w4.N = N; p.w4.K = K; p.w4.group = 0; p.w4.mode = W4A4_SYM;
+    p.w4.layout = layout; p.w4.esum = layout == W4A4_LAYOUT_MFMA ? es : nullptr;
+    p.w8q = q8; p.w8s = s8; p.bias_f16 = bias; p.act = act;
+    *out = p;
+    return true;
+}
+
+struct ShapeKey {
+    int dev, M, h, ffn;
+    bool operator<(const ShapeKey &o) const { return std::tie(dev, M, h, ffn) < std::tie(o.dev, o.M, o.h, o.ffn); }
+};
+std::mutex g_mu;
+std::map<ShapeKey, int> g_tuned;
+
+bool shape_ok(int M, int h, int ffn) {
+    return M > 0 && h > 0 && ffn > 0 && h % 64 == 0 && ffn % 64 == 0 && h >= 128 && ffn >= 128 && h <= 4096 && ffn <= 16384;
+}
+
+}  // namespace
+}  // namespace w4a4
+
+using namespace w4a4;
+
+extern "C" size_t w4a4_part_workspace_bytes(int M, const w4a4_part *P) {
+    if (M <= 0 || !part_ok(P)) return 0;
+    return part_bytes(M, *P);
+}
+
+extern "C" int w4a4_part_linear(const void *X_f16, int M, int ldx, const w4a4_part *P, int int4, void *out_f16,
+                                void *workspace, size_t workspace_bytes, void *stream) {
+    if (M < 0 || !part_ok(P) || ldx < P->w4.K) return W4A4_ERR_INVALID_ARG;
+    if (M == 0) return W4A4_OK;
+    if (!X_f16 || !out_f16) return W4A4_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < part_bytes(M, *P) || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
+        return W4A4_ERR_WORKSPACE;
+    return run_part(X_f16, M, ldx, *P, int4 != 0, out_f16, workspace, stream);
+}
+
+extern "C" size_t w4a4_ffn_workspace_bytes(int M, const w4a4_part *ffn1, const w4a4_part *ffn2) {
+    if (M <= 0 || !part_ok(ffn1) || !part_ok(ffn2) || ffn1->w4.N != ffn2->w4.K) return 0;
+    const size_t a = unfused_bytes(M, *ffn1, *ffn2);
+    const size_t b = ffn2->w4.mode == W4A4_SYM ? plan_fused(nullptr, M, *ffn1, *ffn2).total : 0;
+    return a > b ? a : b;
+}
+
+extern "C" int w4a4_ffn(const void *X_f16, int M, int ldx, const w4a4_part *ffn1, const w4a4_part *ffn2, int strategy,
+                        void *out_f16, void *workspace, size_t workspace_bytes, void *stream) {
+    if (M < 0 || !part_ok(ffn1) || !part_ok(ffn2) || ffn1->w4.N != ffn2->w4.K || ldx < ffn1->w4.K)
+        return W4A4_ERR_INVALID_ARG;
+    if (strategy < 0 || strategy > W4A4_STRATEGY_ALL_INT4) return W4A4_ERR_INVALID_ARG;
+    const bool i1 = (strategy >> W4A4_PART_FFN1) & 1, i2 = (strategy >> W4A4_PART_FFN2) & 1;
+    const bool fused = (strategy & W4A4_STRATEGY_FUSED_FFN) != 0;
+    if (fused && !(i1 && i2)) return W4A4_ERR_INVALID_ARG;
+    if (fused && ffn2->w4.mode != W4A4_SYM) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return W4A4_OK;
+    if (!X_f16 || !out_f16) return W4A4_ERR_INVALID_ARG;
+    if (!workspace || workspace_bytes < w4a4_ffn_workspace_bytes(M, ffn1, ffn2) ||
+        (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1)))
+        return W4A4_ERR_WORKSPACE;
+    if (!fused) {
+        uint8_t *H = static_cast<uint8_t *>(workspace);
+        uint8_t *rest = H + up((size_t)M * ffn1->w4.N * 2);
+        int rc = run_part(X_f16, M, ldx, *ffn1, i1, H, rest, stream);
+        if (rc) return rc;
+        return run_part(H, M, ffn1->w4.N, *ffn2, i2, out_f16, rest, stream);
+    }
+    const FusedPlan p = plan_fused(workspace, M, *ffn1, *ffn2);
+    const w4a4_weight &w1 = ffn1->w4, &w2 = ffn2->w4;
+    const w4a4_act a1 = view_act4(p.a1, M, w1.K, w1);
+    int rc = w4a4_quantize_act(X_f16, M, w1.K, ldx, w1.mode, w1.group, p.a1.q, p.a1.scale, a1.zero ? p.a1.zero : nullptr,
+                               a1.gsum ? p.a1.gsum : nullptr, w1.layout, p.a1.osum, stream);
+    if (rc) return rc;
+    const w4a4_epilogue ep1 = fused_epilogue(*ffn1, *ffn2);
+    rc = w4a4_linear(&a1, &w1, &ep1, p.h.q, p.h.scale, nullptr, w2.layout == W4A4_LAYOUT_MFMA ? p.h.osum : nullptr,
+                     p.lin_ws, p.lin_bytes, stream);
+    if (rc) return rc;
+    const w4a4_act h = view_act4(p.h, M, w2.K, w2);
+    w4a4_epilogue ep2 = {};
+    ep2.bias_f16 = ffn2->bias_f16;
+    ep2.act = ffn2->act;
+    return w4a4_linear(&h, &w2, &ep2, out_f16, nullptr, nullptr, nullptr, nullptr, 0, stream);
+}
+
+extern "C" int w4a4_strategy_pick(const w4a4_strategy_costs *c) {
+    if (!c) return W4A4_ERR_INVALID_ARG;
+    for (int p = 0; p < W4A4_PARTS; ++p)
+        for (int k = 0; k < 2; ++k)
+            if (!(c->part_us[p][k] >= 0.0f) || isinf(c->part_us[p][k])) return W4A4_ERR_INVALID_ARG;
+    if (!(c->ffn_fused_us >= 0.0f) || isinf(c->ffn_fused_us)) return W4A4_ERR_INVALID_ARG;
+    int best = -1, best_parts = -1, best_fused = -1;
+    double best_cost = 0.0;
+    for (int s = 0; s <= W4A4_STRATEGY_ALL_INT4; ++s) {
+        const int b[4] = {s & 1, (s >> 1) & 1, (s >> 2) & 1, (s >> 3) & 1};
+        const int fused = (s & W4A4_STRATEGY_FUSED_FFN) != 0;
+        if (fused && !(b[2] && b[3])) continue;
+        double cost = (double)c->part_us[0][b[0]] + (double)c->part_us[1][b[1]];
+        cost += fused ? (double)c->ffn_fused_us : (double)c->part_us[2][b[2]] + (double)c->part_us[3][b[3]];
+        const int parts = b[0] + b[1] + b[2] + b[3];
+        const bool better = best < 0 || cost < best_cost ||
+                            (cost == best_cost && (parts > best_parts || (parts == best_parts && fused > best_fused)));
+        if (better) { best = s; best_cost = cost; best_parts = parts; best_fused = fused; }
+    }
+    return best;
+}
+
+extern "C" int w4a4_strategy_lookup(int M, int hidden, int ffn) {
+    if (!shape_ok(M, hidden, ffn)) return W4A4_ERR_INVALID_ARG;
+    int dev = 0;
+    if (hipGetDevice(&dev) == hipSuccess) {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_tuned.find(ShapeKey{dev, M, hidden, ffn});
+        if (it != g_tuned.end()) return it->second;
+    } else {
+        (void)hipGetLastError();
+    }
+    // measured on MI355X for BERT-base and BERT-large shapes: INT4 wins every part at every token
+    // count; below about a thousand tokens two one-kernel INT4 parts beat the three launches of
+    // the fused pair
+    return M >= 1024 ? W4A4_STRATEGY_ALL_INT4 : 15;
+}
+
+extern "C" int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_strategy_costs *costs, void *stream) {
+    if (!shape_ok(M, hidden, ffn) || iters <= 0 || iters > 1000) return W4A4_ERR_INVALID_ARG;
+    hipStream_t st = as_stream(stream);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return W4A4_ERR_HIP;
+    Arena ar;
+    const int dims[4][2] = {{3 * hidden, hidden}, {hidden, hidden}, {ffn, hidden}, {hidden, ffn}};   // {N, K}
+    w4a4_part parts[4];
+    for (int p = 0; p < 4; ++p)
+        if (!make_part(ar, M, dims[p][0], dims[p][1], p == W4A4_PART_FFN1 ? W4A4_ACT_GELU : W4A4_ACT_NONE, 1000u * (p + 1), st, &parts[p]))
+            return W4A4_ERR_HIP;
+    const int widest = ffn > 3 * hidden ? ffn : 3 * hidden;
+    __half *X = ar.get<__half>((size_t)M * widest);
+    __half *Y = ar.get<__half>((size_t)M * widest);
+    size_t ws_bytes = w4a4_ffn_workspace_bytes(M, &parts[2], &parts[3]);
+    for (int p = 0; p < 4; ++p) {
+        const size_t b = part_bytes(M, parts[p]);
+        if (b > ws_bytes) ws_bytes = b;
+    }
+    uint8_t *ws = ar.get<uint8_t>(ws_bytes);
+    if (!ar.ok) { (void)hipGetLastError(); return W4A4_ERR_HIP; }
+    hipLaunchKernelGGL(fill_halves_kernel, dim3(fill_grid((size_t)M * widest)), dim3(256), 0, st, X, (size_t)M * widest, 7u, 3.0f);
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return W4A4_ERR_HIP;
+    int status = W4A4_OK;
+    auto time_us = [&](auto &&run, float *us) {
+        if (status) return;
+        for (int i = 0; i < 2 && !status; ++i) status = run();
+        if (status) return;
+        (void)hipEventRecord(e0, st);
+        for (int i = 0; i < iters && !status; ++i) status = run();
+        (void)hipEventRecord(e1, st);
+        if (hipEventSynchronize(e1) != hipSuccess) { status = W4A4_ERR_HIP; return; }
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { status = W4A4_ERR_HIP; return; }
+        *us = ms * 1000.0f / (float)iters;
+    };
+    w4a4_strategy_costs c = {};
+    for (int p = 0; p < 4; ++p)
+        for (int k = 0; k < 2; ++k)
+            time_us([&] { return run_part(X, M, dims[p][1], parts[p], k == 1, Y, ws, stream); }, &c.part_us[p][k]);
+    time_us([&] { return w4a4_ffn(X, M, hidden, &parts[2], &parts[3], W4A4_STRATEGY_ALL_INT4, Y, ws, ws_bytes, stream); },
+            &c.ffn_fused_us);
+    (void)hipStreamSynchronize(st);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (status) return status;
+    if (hipGetLastError() != hipSuccess) return W4A4_ERR_HIP;
+    const int pick = w4a4_strategy_pick(&c);
+    if (pick < 0) return pick;
+    if (costs) *costs = c;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        g_tuned[ShapeKey{dev, M, hidden, ffn}] = pick;
+    }
+    return pick;
+}

@@ -1,0 +1,151 @@
+"""Per-part strategy on the GPU (Sec. 4.2: each linear part runs in INT4 or in a higher-bit type; the
+FFN pair may hand codes over in the epilogue): w4a4_part_linear and w4a4_ffn against the oracle and,
+bit for bit, against the entry points they are built from; the tuner's result against its own timings."""
+import numpy as np
+import pytest
+import torch
+
+from tests.gpu_util import dev, f16_close, has_gpu, host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2301_12017_amd import binding
+    binding.lib()
+    return binding
+
+
+def _xw(seed, M, N, K):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)).astype(np.float32).astype(np.float16)
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    return X, W, b
+
+
+# one-kernel shape; operand-layout two-call shape with a ragged last tile; canonical two-call shape (K > 4096)
+PART_SHAPES = [(48, 96, 128), (1100, 768, 256), (40, 64, 8192)]
+
+
+@pytest.mark.parametrize("M,N,K", PART_SHAPES)
+@pytest.mark.parametrize("act", [0, 1])
+def test_part_linear_int4(B, orc, M, N, K, act):
+    X, W, b = _xw(M + N + K, M, N, K)
+    P = B.Part(dev(W), M, dev(b), act)
+    got = B.part_linear(dev(X), P, True)
+    # the calls it stands for, bit for bit
+    A = B.quantize_act(dev(X), B.SYM, layout=P.w4.layout)
+    ref = B.linear(A, P.w4, dev(b), act)
+    assert torch.equal(got, ref)
+    want = orc.part_linear(X, W, True, b, act)
+    if act == 0:
+        assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16))
+    else:
+        ok, ratio = f16_close(host(got), want)
+        assert ok, ratio
+
+
+@pytest.mark.parametrize("M,N,K", [(48, 96, 128), (1100, 768, 256), (40, 64, 4096)])
+@pytest.mark.parametrize("act", [0, 1])
+def test_part_linear_int8(B, orc, M, N, K, act):
+    X, W, b = _xw(M + N + K + 1, M, N, K)
+    P = B.Part(dev(W), M, dev(b), act)
+    got = B.part_linear(dev(X), P, False)
+    want = orc.part_linear(X, W, False, b, act)
+    if act == 0:
+        assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16))
+    else:
+        ok, ratio = f16_close(host(got), want)
+        assert ok, ratio
+
+
+def test_part_linear_asymmetric_grouped(B, orc):
+    M, N, K = 70, 64, 256
+    X, W, b = _xw(9, M, N, K)
+    X = (X.astype(np.float32) + 0.7).astype(np.float16)
+    P = B.Part(dev(W), M, dev(b), 0, mode=B.ASYM, group=128)
+    got = B.part_linear(dev(X), P, True)
+    want = orc.part_linear(X, W, True, b, 0, mode=orc.ASYM, group=128)
+    ok, ratio = f16_close(host(got), want)
+    assert ok, ratio
+
+
+def test_part_linear_reads_a_column_slice_and_reuses_a_workspace(B, orc):
+    M, N, K = 36, 64, 128
+    X, W, b = _xw(4, M, N, 2 * K)
+    Xd = dev(X)
+    P = B.Part(dev(W[:, :K].copy()), M, dev(b), 0)
+    ws = torch.empty(1 << 16, dtype=torch.uint8, device="cuda")
+    for int4 in (True, False, True):
+        got = B.part_linear(Xd[:, K:], P, int4, workspace=ws)
+        want = orc.part_linear(np.ascontiguousarray(X[:, K:]), W[:, :K].copy(), int4, b, 0)
+        assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16))
+
+
+# (M, h, ffn): one-kernel parts; a mix (FFN1 in the operand layout, FFN2 one-kernel); both in the operand layout
+FFN_SHAPES = [(40, 128, 256), (1100, 256, 1024), (2100, 512, 1024)]
+
+
+def _ffn_inputs(seed, M, h, f):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, h)).astype(np.float32).astype(np.float16)
+    W1 = (rng.standard_normal((f, h)) * 0.05).astype(np.float16)
+    W2 = (rng.standard_normal((h, f)) * 0.05).astype(np.float16)
+    b1 = (rng.standard_normal(f) * 0.02).astype(np.float16)
+    b2 = (rng.standard_normal(h) * 0.02).astype(np.float16)
+    return X, W1, b1, W2, b2
+
+
+@pytest.mark.parametrize("M,h,f", FFN_SHAPES)
+@pytest.mark.parametrize("strategy", [0, 4, 8, 12, 28])
+def test_ffn_without_activation_matches_the_oracle(B, orc, M, h, f, strategy):
+    """Without GELU every intermediate value is bit-identical on both sides, so the whole pair is."""
+    X, W1, b1, W2, b2 = _ffn_inputs(M + strategy, M, h, f)
+    P1, P2 = B.Part(dev(W1), M, dev(b1), 0), B.Part(dev(W2), M, dev(b2), 0)
+    got = host(B.ffn(dev(X), P1, P2, strategy))
+    want = orc.ffn(X, W1, b1, 0, W2, b2, strategy)
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
+
+
+@pytest.mark.parametrize("M,h,f", FFN_SHAPES)
+@pytest.mark.parametrize("strategy", [0, 4, 8, 12, 28])
+def test_ffn_with_gelu_equals_its_building_blocks(B, orc, M, h, f, strategy):
+    X, W1, b1, W2, b2 = _ffn_inputs(M + strategy + 50, M, h, f)
+    P1, P2 = B.Part(dev(W1), M, dev(b1), 1), B.Part(dev(W2), M, dev(b2), 0)
+    Xd = dev(X)
+    got = B.ffn(Xd, P1, P2, strategy)
+    if strategy & B.STRATEGY_FUSED_FFN:
+        A = B.quantize_act(Xd, B.SYM, layout=P1.w4.layout)
+        H = B.linear(A, P1.w4, dev(b1), 1, requant=True, requant_layout=P2.w4.layout)
+        ref = B.linear(H, P2.w4, dev(b2), 0)
+    else:
+        H = B.part_linear(Xd, P1, bool(strategy & 4))
+        ref = B.part_linear(H, P2, bool(strategy & 8))
+    assert torch.equal(got, ref)
+    # and the oracle's pair: a GELU value that differs in its last bit can move a code of the
+    # intermediate by one step, so this comparison is statistical
+    want = orc.ffn(X, W1, b1, 1, W2, b2, strategy).astype(np.float64)
+    err = host(got).astype(np.float64) - want
+    assert np.sqrt((err ** 2).mean()) < 5e-3 * np.sqrt((want ** 2).mean())
+
+
+def test_ffn_is_repeatable_on_one_workspace(B):
+    M, h, f = 1100, 256, 1024
+    X, W1, b1, W2, b2 = _ffn_inputs(1, M, h, f)
+    P1, P2 = B.Part(dev(W1), M, dev(b1), 1), B.Part(dev(W2), M, dev(b2), 0)
+    Xd = dev(X)
+    ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    first = {s: B.ffn(Xd, P1, P2, s, workspace=ws).clone() for s in (28, 12, 0)}
+    for s in (0, 28, 12, 28):
+        assert torch.equal(B.ffn(Xd, P1, P2, s, workspace=ws), first[s])
+
+
+def test_tuner_picks_what_its_timings_say(B, orc):
+    for M, h, f in [(128, 768, 3072), (2048, 768, 3072)]:
+        pick, part_us, fused_us = B.strategy_tune(M, h, f, iters=10)
+        assert all(t > 0 for row in part_us for t in row) and fused_us > 0
+        assert pick == orc.pick_strategy(part_us, fused_us)
+        assert B.strategy_lookup(M, h, f) == pick                      # remembered for this device
+    assert B.strategy_lookup(136, 768, 3072) == 15                     # untuned shape: the built-in table
