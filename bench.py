@@ -428,6 +428,28 @@ def main():
         except Exception as ex:
             fp16["int8_library_gemm_error"] = str(ex)[:200]
 
+    # ---- per-part strategy (Sec. 4.2 / 4.3): every part timed in INT4 and in the INT8 sibling, the FFN pair also with
+    # the codes handed over in the epilogue, at the paper's annotated (batch-sequence) points for BERT-base and at
+    # this bench's own token count; the library's tuner does the timing and the picking
+    strat = {}
+    if cfg == 3:
+        names = ["qkv", "attn_out", "ffn1", "ffn2"]
+        points = [("1-32", 32, 768, 3072), ("1-128", 128, 768, 3072), ("8-32", 256, 768, 3072),
+                  ("16-128", 2048, 768, 3072), ("128-128", 16384, 768, 3072),
+                  ("bench", specs[0].M, specs[0].K, specs[2].N)]
+        rows = []
+        for tag, M_, h_, f_ in points:
+            pick, part_us, fused_us = B.strategy_tune(M_, h_, f_, iters=20)
+            rows.append({"bs_seq": tag, "M": M_, "hidden": h_, "ffn": f_,
+                         "int8_us": {n: part_us[i][0] for i, n in enumerate(names)},
+                         "int4_us": {n: part_us[i][1] for i, n in enumerate(names)},
+                         "ffn_fused_int4_us": fused_us, "strategy": pick,
+                         "int4_parts": [n for i, n in enumerate(names) if pick >> i & 1],
+                         "ffn_fused": bool(pick & B.STRATEGY_FUSED_FFN)})
+        strat = {"points": rows,
+                 "note": "w4a4_strategy_tune: each option = quantize + linear from fp16 to fp16 on synthetic operands, "
+                         "20 timed runs back to back; the paper's GPU wanted only ffn1 in INT4 at the three smallest points"}
+
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -444,6 +466,7 @@ def main():
         "latency": lat,
         "producer_fusion": ln,
         "int8_sibling": i8,
+        "per_part_strategy": strat,
         "fp16_library_gemm": fp16,
         "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": achieved / INT8_MFMA_PEAK_TOPS,

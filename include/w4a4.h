@@ -217,7 +217,8 @@ int w4a4_strategy_pick(const w4a4_strategy_costs *costs);
 int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_strategy_costs *costs, void *stream);
 
 /* The strategy remembered by w4a4_strategy_tune for this shape on the current device, else the
- * built-in table measured on MI355X (every part in INT4; FFN pair fused from 1024 tokens up). */
+ * built-in table measured on MI355X (every part in INT4; FFN pair fused from 6144 tokens up at
+ * hidden sizes >= 1024, from 16384 tokens up below that). */
 int w4a4_strategy_lookup(int M, int hidden, int ffn);
 
 /* Measurement hook (no passage of the paper: it serves the roofline figure).  Arms the calling

@@ -311,9 +311,11 @@ extern "C" int w4a4_strategy_lookup(int M, int hidden, int ffn) {
         (void)hipGetLastError();
     }
     // measured on MI355X for BERT-base and BERT-large shapes: INT4 wins every part at every token
-    // count; below about a thousand tokens two one-kernel INT4 parts beat the three launches of
-    // the fused pair
-    return M >= 1024 ? W4A4_STRATEGY_ALL_INT4 : 15;
+    // count (by 2x and more below a few hundred tokens, where the INT4 part is one kernel); handing
+    // the codes over in FFN1's epilogue beats a separate quantize of the fp16 intermediate only
+    // for many tokens: from about 6144 at hidden size 1024, from about 16384 at 768
+    const bool fused = hidden >= 1024 ? M >= 6144 : M >= 16384;
+    return fused ? W4A4_STRATEGY_ALL_INT4 : 15;
 }
 
 extern "C" int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_strategy_costs *costs, void *stream) {
