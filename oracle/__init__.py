@@ -396,3 +396,59 @@ def ffn(X_f16, W1_f16, b1_f16, act1, W2_f16, b2_f16, strategy: int):
         return linear(H, quantize_weight(W2_f16), bias_f16=b2_f16)["out"]
     H16 = part_linear(X_f16, W1_f16, i1, b1_f16, act1)
     return part_linear(H16, W2_f16, i2, b2_f16)
+
+
+# ------------------------------------------------------------------ whole encoder layer (Sec. 4.2: the pipeline
+# around the four linears: FP16 attention between QKV and the output projection, LayerNorm (+ residual) after
+# the attention output and after the MLP)
+FUSED_LN = 32
+
+
+def attention(QKV_f16, batch: int, seq: int, heads: int):
+    """softmax(Q K^T / sqrt(d)) V per sequence and head, in float64.  QKV_f16 [batch*seq, 3h]: columns [0,h) are
+    the queries, [h,2h) the keys, [2h,3h) the values; head j owns columns j*d .. (j+1)*d of each.  No mask.
+    Returns float64 [batch*seq, h]."""
+    QKV = np.asarray(QKV_f16, np.float16).astype(np.float64)
+    M, h3 = QKV.shape
+    h = h3 // 3
+    d = h // heads
+    assert M == batch * seq and h * 3 == h3 and d * heads == h
+    out = np.empty((M, h), np.float64)
+    for b in range(batch):
+        rows = slice(b * seq, (b + 1) * seq)
+        for j in range(heads):
+            q = QKV[rows, j * d:(j + 1) * d]
+            k = QKV[rows, h + j * d:h + (j + 1) * d]
+            v = QKV[rows, 2 * h + j * d:2 * h + (j + 1) * d]
+            s = (q @ k.T) / math.sqrt(d)
+            s = s - s.max(axis=1, keepdims=True)
+            p = np.exp(s)
+            p = p / p.sum(axis=1, keepdims=True)
+            out[rows, j * d:(j + 1) * d] = p @ v
+    return out
+
+
+def encoder_layer(X_f16, batch, seq, heads, Wqkv, bqkv, Wao, bao, W1, b1, W2, b2, g1, be1, g2, be2, eps, strategy):
+    """One post-LayerNorm encoder layer, fp16 in, fp16 out (symmetric per-channel weights):
+        x1  = LN1(x + attn_out(attention(qkv(x))));   out = LN2(x1 + ffn2(gelu(ffn1(x1))))
+    Strategy bits as for pick_strategy; FUSED_LN: FFN1 consumes the codes LN1 produced from its fp32 result
+    (Sec. 4.2: quantize fused with the LayerNorm) instead of quantizing the fp16 copy of x1."""
+    X = np.asarray(X_f16, np.float16)
+    bit = lambda p: bool(strategy >> p & 1)
+    if strategy & FUSED_LN and not bit(PART_FFN1):
+        raise ValueError("FUSED_LN needs FFN1 in INT4")
+    qkv = part_linear(X, Wqkv, bit(PART_QKV), bqkv)
+    ctx = store_f16(attention(qkv, batch, seq, heads).astype(np.float32))
+    ao = part_linear(ctx, Wao, bit(PART_ATTN_OUT), bao)
+    ln1 = layernorm_quantize(ao, X, g1, be1, eps)
+    x1 = ln1["y16"]
+    if strategy & FUSED_LN:
+        if strategy & FUSED_FFN:
+            H = linear(ln1, quantize_weight(W1), bias_f16=b1, act=ACT_GELU, requant=True)
+            h2 = linear(H, quantize_weight(W2), bias_f16=b2)["out"]
+        else:
+            H16 = linear(ln1, quantize_weight(W1), bias_f16=b1, act=ACT_GELU)["out"]
+            h2 = part_linear(H16, W2, bit(PART_FFN2), b2)
+    else:
+        h2 = ffn(x1, W1, b1, ACT_GELU, W2, b2, strategy & 31)
+    return layernorm_quantize(h2, x1, g2, be2, eps)["y16"]
