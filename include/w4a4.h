@@ -205,7 +205,8 @@ typedef struct {
 /* The strategy of least total cost: QKV and attention output are independent choices; the FFN
  * pair costs part_us[FFN1][.] + part_us[FFN2][.], or ffn_fused_us with FUSED_FFN.  Ties go to the
  * strategy with more INT4 parts, then to the fused one.  Pure host arithmetic.  Returns the bit
- * set, or W4A4_ERR_INVALID_ARG for NULL / negative / non-finite costs. */
+ * set (never with W4A4_STRATEGY_FUSED_LN, which is not a choice between GEMM precisions), or
+ * W4A4_ERR_INVALID_ARG for NULL / negative / non-finite costs. */
 int w4a4_strategy_pick(const w4a4_strategy_costs *costs);
 
 /* Measures all options for an encoder layer of this shape (hidden size h: QKV h -> 3h, attention
@@ -220,6 +221,42 @@ int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_strategy_cost
  * built-in table measured on MI355X (every part in INT4; FFN pair fused from 6144 tokens up at
  * hidden sizes >= 1024, from 16384 tokens up below that). */
 int w4a4_strategy_lookup(int M, int hidden, int ffn);
+
+/* ---- a whole encoder layer -----------------------------------------------------------------
+ * Sec. 4.2 describes the pipeline around the four linears: attention stays in FP16 between the QKV
+ * projection and the attention output, LayerNorm (with the residual) follows the attention output
+ * and the MLP, and for small batch x sequence the whole sequence of launches is replayed from a
+ * graph.  These calls enqueue that sequence for one post-LayerNorm (BERT) encoder layer; capturing
+ * it in a HIP graph is the caller's business (every launch is capturable: counters are cleared by
+ * fill kernels, nothing is allocated, no host synchronization). */
+
+/* FP16 attention without a mask, a plain stand-in for the attention kernel the paper takes from
+ * elsewhere: ctx[b*seq + i, j*64 .. j*64+63] = softmax_k(q_i . k_k / 8) V for every sequence b and
+ * head j.  QKV_f16 [batch*seq, 3h], h = heads*64: queries in columns [0,h), keys in [h,2h), values
+ * in [2h,3h); ctx_f16 [batch*seq, h].  fp32 arithmetic.  Head size 64 only, 1 <= seq <= 512,
+ * pointers 16-byte aligned. */
+int w4a4_attention_f16(const void *QKV_f16, int batch, int seq, int heads, void *ctx_f16, void *stream);
+
+/* Strategy bit (needs the FFN1 bit): FFN1 reads the codes LayerNorm 1 produced from its fp32
+ * result (Sec. 4.2: quantize fused with the LayerNorm that produces the activation) instead of
+ * quantizing the fp16 copy of the residual stream. */
+#define W4A4_STRATEGY_FUSED_LN 32
+
+typedef struct {
+    int hidden, heads, ffn;                 /* hidden = heads * 64                                  */
+    w4a4_part qkv, attn_out, ffn1, ffn2;    /* [3h,h], [h,h], [ffn,h] (its act applies), [h,ffn];
+                                               symmetric weights for ffn1 / ffn2                    */
+    const void *ln1_gamma_f16, *ln1_beta_f16, *ln2_gamma_f16, *ln2_beta_f16;   /* [h] each         */
+    float ln_eps;
+} w4a4_encoder_layer_weights;
+
+/* out_f16 [batch*seq, h] = LN2(x1 + ffn2(ffn1(x1))),  x1 = LN1(x + attn_out(attention(qkv(x)))),
+ * every part run as `strategy` says (bits of w4a4_strategy_pick plus W4A4_STRATEGY_FUSED_LN).
+ * X_f16 [batch*seq, h] dense.  Workspace 256-byte aligned, w4a4_encoder_layer_workspace_bytes
+ * large; it holds every intermediate, so one call per workspace at a time. */
+size_t w4a4_encoder_layer_workspace_bytes(int batch, int seq, const w4a4_encoder_layer_weights *L);
+int w4a4_encoder_layer(const void *X_f16, int batch, int seq, const w4a4_encoder_layer_weights *L, int strategy,
+                       void *out_f16, void *workspace, size_t workspace_bytes, void *stream);
 
 /* Measurement hook (no passage of the paper: it serves the roofline figure).  Arms the calling
  * thread: the GEMM kernel of its NEXT w4a4_linear / w4a4_gemm_i32 call records the two HIP events

@@ -55,6 +55,13 @@ class _StrategyCosts(ctypes.Structure):
     _fields_ = [("part_us", (ctypes.c_float * 2) * 4), ("ffn_fused_us", ctypes.c_float)]
 
 
+class _LayerWeights(ctypes.Structure):
+    _fields_ = [("hidden", ctypes.c_int), ("heads", ctypes.c_int), ("ffn", ctypes.c_int),
+                ("qkv", _Part), ("attn_out", _Part), ("ffn1", _Part), ("ffn2", _Part),
+                ("ln1_gamma_f16", ctypes.c_void_p), ("ln1_beta_f16", ctypes.c_void_p),
+                ("ln2_gamma_f16", ctypes.c_void_p), ("ln2_beta_f16", ctypes.c_void_p), ("ln_eps", ctypes.c_float)]
+
+
 _lib = None
 
 _vp, _i, _sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
@@ -84,6 +91,9 @@ _SIGNATURES = {
     "w4a4_strategy_pick": (_i, [ctypes.POINTER(_StrategyCosts)]),
     "w4a4_strategy_tune": (_i, [_i, _i, _i, _i, ctypes.POINTER(_StrategyCosts), _vp]),
     "w4a4_strategy_lookup": (_i, [_i, _i, _i]),
+    "w4a4_attention_f16": (_i, [_vp, _i, _i, _i, _vp, _vp]),
+    "w4a4_encoder_layer_workspace_bytes": (_sz, [_i, _i, ctypes.POINTER(_LayerWeights)]),
+    "w4a4_encoder_layer": (_i, [_vp, _i, _i, ctypes.POINTER(_LayerWeights), _i, _vp, _vp, _sz, _vp]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
     "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
                                    ctypes.POINTER(_Epilogue), _vp, _vp, _vp, _vp, _vp]),
@@ -560,6 +570,43 @@ def strategy_lookup(M: int, hidden: int, ffn_size: int) -> int:
     rc = lib().w4a4_strategy_lookup(M, hidden, ffn_size)
     _check(min(rc, 0), "w4a4_strategy_lookup")
     return rc
+
+
+# ---- whole encoder layer -----------------------------------------------------------------------------
+STRATEGY_FUSED_LN = 32
+
+
+def attention(QKV: torch.Tensor, batch: int, seq: int, heads: int, out=None) -> torch.Tensor:
+    """w4a4_attention_f16: fp16 [batch*seq, heads*64] from fp16 [batch*seq, 3*heads*64]."""
+    assert QKV.is_cuda and QKV.dtype == torch.float16 and QKV.is_contiguous() and QKV.shape == (batch * seq, 3 * heads * 64)
+    out = torch.empty((batch * seq, heads * 64), dtype=torch.float16, device=QKV.device) if out is None else out
+    _check(lib().w4a4_attention_f16(_ptr(QKV), batch, seq, heads, _ptr(out), _stream()), "w4a4_attention_f16")
+    return out
+
+
+class EncoderLayer:
+    """The weights of one encoder layer (w4a4_encoder_layer_weights) and a workspace for `batch` x `seq` tokens."""
+
+    def __init__(self, batch, seq, heads, Wqkv, bqkv, Wao, bao, W1, b1, W2, b2, g1, be1, g2, be2, eps=1e-12):
+        M = batch * seq
+        self.batch, self.seq, self.heads, self.hidden, self.ffn = batch, seq, heads, Wao.shape[0], W1.shape[0]
+        self.qkv, self.attn_out = Part(Wqkv, M, bqkv), Part(Wao, M, bao)
+        self.ffn1, self.ffn2 = Part(W1, M, b1, ACT_GELU), Part(W2, M, b2)
+        self.ln = (g1, be1, g2, be2)
+        self.c = _LayerWeights(self.hidden, heads, self.ffn, self.qkv.c(), self.attn_out.c(), self.ffn1.c(), self.ffn2.c(),
+                               _ptr(g1), _ptr(be1), _ptr(g2), _ptr(be2), eps)
+        need = lib().w4a4_encoder_layer_workspace_bytes(batch, seq, ctypes.byref(self.c))
+        if need == 0:
+            raise W4A4Error(-1, "w4a4_encoder_layer_workspace_bytes")
+        self.workspace = _workspace(need, Wqkv.device)
+
+    def __call__(self, X: torch.Tensor, strategy: int, out=None, stream=None) -> torch.Tensor:
+        assert X.is_cuda and X.dtype == torch.float16 and X.is_contiguous() and X.shape == (self.batch * self.seq, self.hidden)
+        out = torch.empty_like(X) if out is None else out
+        rc = lib().w4a4_encoder_layer(_ptr(X), self.batch, self.seq, ctypes.byref(self.c), strategy, _ptr(out),
+                                      _ptr(self.workspace), self.workspace.numel(), _stream() if stream is None else stream)
+        _check(rc, "w4a4_encoder_layer")
+        return out
 
 
 class PreparedLinearF16Act:

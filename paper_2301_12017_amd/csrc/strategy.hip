@@ -139,6 +139,42 @@ size_t unfused_bytes(int M, const w4a4_part &f1, const w4a4_part &f2) {
     return up((size_t)M * f1.w4.N * 2) + (a > b ? a : b);
 }
 
+// ---- whole encoder layer ------------------------------------------------------------------------
+struct LayerPlan {
+    __half *qkv, *ctx, *ao, *x1, *h2;
+    ActBuffers ln;                  // codes of LayerNorm 1 for FFN1 (LayerNorm 2 reuses them as a dump)
+    uint8_t *rest;                  // whatever the part that is running needs
+    size_t rest_bytes, total;
+};
+bool layer_ok(const w4a4_encoder_layer_weights *L) {
+    if (!L || L->hidden <= 0 || L->heads <= 0 || L->ffn <= 0 || L->hidden != L->heads * 64) return false;
+    if (!part_ok(&L->qkv) || !part_ok(&L->attn_out) || !part_ok(&L->ffn1) || !part_ok(&L->ffn2)) return false;
+    const int h = L->hidden, f = L->ffn;
+    return L->qkv.w4.N == 3 * h && L->qkv.w4.K == h && L->attn_out.w4.N == h && L->attn_out.w4.K == h &&
+           L->ffn1.w4.N == f && L->ffn1.w4.K == h && L->ffn2.w4.N == h && L->ffn2.w4.K == f &&
+           L->ffn1.w4.mode == W4A4_SYM && L->ffn2.w4.mode == W4A4_SYM && groups_of(L->ffn1.w4) == 1 &&
+           L->ln1_gamma_f16 && L->ln1_beta_f16 && L->ln2_gamma_f16 && L->ln2_beta_f16 && L->ln_eps >= 0.0f;
+}
+LayerPlan plan_layer(void *ws, int M, const w4a4_encoder_layer_weights &L) {
+    Carver c(ws);
+    LayerPlan p;
+    const size_t h = L.hidden;
+    p.qkv = c.take<__half>((size_t)M * 3 * h);
+    p.ctx = c.take<__half>((size_t)M * h);
+    p.ao = c.take<__half>((size_t)M * h);
+    p.x1 = c.take<__half>((size_t)M * h);
+    p.h2 = c.take<__half>((size_t)M * h);
+    p.ln = carve_act4(c, M, L.hidden, L.ffn1.w4);
+    size_t r = w4a4_ffn_workspace_bytes(M, &L.ffn1, &L.ffn2);   // covers both ways FFN1 can take LayerNorm's codes, too
+    const size_t a = part_bytes(M, L.qkv), b = part_bytes(M, L.attn_out);
+    r = r > a ? r : a;
+    r = r > b ? r : b;
+    p.rest_bytes = r;
+    p.rest = c.take<uint8_t>(r);
+    p.total = c.used;
+    return p;
+}
+
 // ---- tuner --------------------------------------------------------------------------------------
 __global__ void fill_bytes_kernel(uint32_t *p, size_t words, uint32_t seed) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < words; i += (size_t)gridDim.x * blockDim.x) {
@@ -374,4 +410,72 @@ extern "C" int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_st
         g_tuned[ShapeKey{dev, M, hidden, ffn}] = pick;
     }
     return pick;
+}
+
+extern "C" size_t w4a4_encoder_layer_workspace_bytes(int batch, int seq, const w4a4_encoder_layer_weights *L) {
+    if (batch <= 0 || seq <= 0 || (long)batch * seq > 0x7fffffffL / 4 || !layer_ok(L)) return 0;
+    return plan_layer(nullptr, batch * seq, *L).total;
+}
+
+extern "C" int w4a4_encoder_layer(const void *X_f16, int batch, int seq, const w4a4_encoder_layer_weights *L, int strategy,
+                                  void *out_f16, void *workspace, size_t workspace_bytes, void *stream) {
+    if (batch < 0 || seq < 0 || (long)batch * seq > 0x7fffffffL / 4 || !layer_ok(L)) return W4A4_ERR_INVALID_ARG;
+    if (strategy < 0 || strategy > (W4A4_STRATEGY_ALL_INT4 | W4A4_STRATEGY_FUSED_LN)) return W4A4_ERR_INVALID_ARG;
+    const bool i0 = strategy & 1, i1 = (strategy >> 1) & 1, i2 = (strategy >> 2) & 1, i3 = (strategy >> 3) & 1;
+    const bool fused_ffn = (strategy & W4A4_STRATEGY_FUSED_FFN) != 0, fused_ln = (strategy & W4A4_STRATEGY_FUSED_LN) != 0;
+    if ((fused_ffn && !(i2 && i3)) || (fused_ln && !i2)) return W4A4_ERR_INVALID_ARG;
+    const int M = batch * seq;
+    if (M == 0) return W4A4_OK;
+    if (!X_f16 || !out_f16) return W4A4_ERR_INVALID_ARG;
+    if (seq > 512) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & (kAlign - 1))) return W4A4_ERR_WORKSPACE;
+    const LayerPlan p = plan_layer(workspace, M, *L);
+    if (workspace_bytes < p.total) return W4A4_ERR_WORKSPACE;
+    const int h = L->hidden;
+    const w4a4_weight &w1 = L->ffn1.w4, &w2 = L->ffn2.w4;
+
+    int rc = run_part(X_f16, M, h, L->qkv, i0, p.qkv, p.rest, stream);
+    if (rc) return rc;
+    rc = w4a4_attention_f16(p.qkv, batch, seq, L->heads, p.ctx, stream);
+    if (rc) return rc;
+    rc = run_part(p.ctx, M, h, L->attn_out, i1, p.ao, p.rest, stream);
+    if (rc) return rc;
+    // x1 = LN1(attn_out + x); its codes are in FFN1's layout whether or not FFN1 reads them
+    rc = w4a4_layernorm_quantize(p.ao, X_f16, M, h, h, L->ln1_gamma_f16, L->ln1_beta_f16, L->ln_eps, p.x1, W4A4_SYM, 0,
+                                 p.ln.q, p.ln.scale, nullptr, nullptr, w1.layout, p.ln.osum, stream);
+    if (rc) return rc;
+    if (!fused_ln) {
+        rc = w4a4_ffn(p.x1, M, h, &L->ffn1, &L->ffn2, strategy & W4A4_STRATEGY_ALL_INT4, p.h2, p.rest, p.rest_bytes, stream);
+        if (rc) return rc;
+    } else {
+        const w4a4_act a1 = view_act4(p.ln, M, h, w1);
+        Carver c(p.rest);
+        if (fused_ffn) {
+            const ActBuffers hb = carve_act4(c, M, w2.K, w2);
+            const w4a4_epilogue ep1 = fused_epilogue(L->ffn1, L->ffn2);
+            const size_t lin_bytes = w4a4_linear_workspace_bytes(&a1, &w1, &ep1, w2.layout == W4A4_LAYOUT_MFMA);
+            void *lin_ws = c.take<uint8_t>(lin_bytes);
+            rc = w4a4_linear(&a1, &w1, &ep1, hb.q, hb.scale, nullptr, w2.layout == W4A4_LAYOUT_MFMA ? hb.osum : nullptr,
+                             lin_ws, lin_bytes, stream);
+            if (rc) return rc;
+            const w4a4_act hv = view_act4(hb, M, w2.K, w2);
+            w4a4_epilogue ep2 = {};
+            ep2.bias_f16 = L->ffn2.bias_f16;
+            ep2.act = L->ffn2.act;
+            rc = w4a4_linear(&hv, &w2, &ep2, p.h2, nullptr, nullptr, nullptr, nullptr, 0, stream);
+            if (rc) return rc;
+        } else {
+            __half *H = c.take<__half>((size_t)M * w1.N);
+            w4a4_epilogue ep1 = {};
+            ep1.bias_f16 = L->ffn1.bias_f16;
+            ep1.act = L->ffn1.act;
+            rc = w4a4_linear(&a1, &w1, &ep1, H, nullptr, nullptr, nullptr, nullptr, 0, stream);
+            if (rc) return rc;
+            rc = run_part(H, M, w1.N, L->ffn2, i3, p.h2, p.rest + c.used, stream);
+            if (rc) return rc;
+        }
+    }
+    // out = LN2(ffn2 + x1); the codes go to the buffers FFN1 has finished with (canonical layout, unused)
+    return w4a4_layernorm_quantize(p.h2, p.x1, M, h, h, L->ln2_gamma_f16, L->ln2_beta_f16, L->ln_eps, out_f16, W4A4_SYM, 0,
+                                   p.ln.q, p.ln.scale, nullptr, nullptr, W4A4_LAYOUT_CANONICAL, nullptr, stream);
 }

@@ -103,3 +103,46 @@ def test_part_and_ffn_argument_errors(b):
     assert ffn(12, ws=None) == -3 and ffn(12, nbytes=64) == -3
     assert ffn(12, x=None) == -1 and ffn(12, o=None) == -1
     assert ffn(12, M=0) == 0
+
+
+def test_attention_argument_errors(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x4000)
+    assert L.w4a4_attention_f16(p, -1, 8, 2, p, None) == -1 and L.w4a4_attention_f16(p, 1, 8, 0, p, None) == -1
+    assert L.w4a4_attention_f16(None, 1, 8, 2, p, None) == -1 and L.w4a4_attention_f16(p, 1, 8, 2, None, None) == -1
+    assert L.w4a4_attention_f16(p, 1, 513, 2, p, None) == -2                # keys and values must fit the LDS
+    assert L.w4a4_attention_f16(ctypes.c_void_p(0x4008), 1, 8, 2, p, None) == -2
+    assert L.w4a4_attention_f16(p, 0, 8, 2, p, None) == 0 and L.w4a4_attention_f16(p, 3, 0, 2, p, None) == 0
+
+
+def test_encoder_layer_argument_errors(b):
+    L = b.lib()
+    p = ctypes.c_void_p(0x4000)
+    h, heads, f = 128, 2, 256
+
+    def weights(**kw):
+        parts = dict(qkv=_part(b, 3 * h, h), attn_out=_part(b, h, h), ffn1=_part(b, f, h, act=1), ffn2=_part(b, h, f))
+        parts.update({k: v for k, v in kw.items() if k in parts})
+        return b._LayerWeights(kw.get("hidden", h), kw.get("heads", heads), kw.get("ffn", f), parts["qkv"], parts["attn_out"],
+                               parts["ffn1"], parts["ffn2"], kw.get("g1", 0x5000), 0x5000, 0x5000, 0x5000, kw.get("eps", 1e-12))
+
+    W = weights()
+    need = L.w4a4_encoder_layer_workspace_bytes(2, 8, ctypes.byref(W))
+    assert need >= 16 * (3 * h + 4 * h) * 2 and need % 256 == 0
+    assert L.w4a4_encoder_layer_workspace_bytes(0, 8, ctypes.byref(W)) == 0
+    assert L.w4a4_encoder_layer_workspace_bytes(2, 8, None) == 0
+
+    def run(strategy=15, w=W, batch=2, seq=8, x=p, o=p, ws=p, nbytes=1 << 24):
+        return L.w4a4_encoder_layer(x, batch, seq, ctypes.byref(w), strategy, o, ws, nbytes, None)
+
+    assert run(w=weights(heads=3)) == -1                                     # hidden != heads * 64
+    assert run(w=weights(qkv=_part(b, 2 * h, h))) == -1                      # part shapes must chain
+    assert run(w=weights(ffn2=_part(b, h, f, mode=1))) == -1                 # symmetric FFN weights
+    assert run(w=weights(g1=None)) == -1 and run(w=weights(eps=-1.0)) == -1
+    assert L.w4a4_encoder_layer_workspace_bytes(2, 8, ctypes.byref(weights(heads=3))) == 0
+    assert run(strategy=64) == -1 and run(strategy=-1) == -1
+    assert run(strategy=16 | 4) == -1 and run(strategy=32 | 3) == -1         # flags without their parts
+    assert run(x=None) == -1 and run(o=None) == -1
+    assert run(seq=600) == -2
+    assert run(ws=None) == -3 and run(nbytes=1024) == -3 and run(ws=ctypes.c_void_p(0x4040)) == -3
+    assert run(batch=0) == 0
