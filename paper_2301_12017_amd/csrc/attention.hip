@@ -1,7 +1,7 @@
 // FP16 attention between the QKV projection and the attention output (Sec. 4.2 keeps the attention
 // in FP16 and takes its kernel from elsewhere; this is a plain stand-in so that a whole encoder
 // layer can be timed): softmax(q.k / sqrt(64)) V per sequence and head, no mask, fp32 arithmetic.
-// One workgroup per (sequence, head, block of 16 queries): the keys and values of the head go to
+// One workgroup per (sequence, head, block of 4 or 16 queries): the keys and values of the head go to
 // LDS once, then each of the four waves takes one query at a time: a lane scores keys lane,
 // lane + 64, ..., the wave reduces maximum and sum, and lane d accumulates output feature d.
 #include "common.hpp"
@@ -10,7 +10,6 @@ namespace w4a4 {
 namespace {
 
 constexpr int kHead = 64;             // features per head
-constexpr int kQBlock = 16;           // queries per workgroup
 constexpr int kAttnWaves = 4;
 constexpr int kKeyPitch = kHead / 2 + 1;   // key rows in 32-bit words, padded: lanes read different rows
 
@@ -21,7 +20,7 @@ __device__ __forceinline__ float wave_sum_f(float v) {
 }
 
 __global__ __launch_bounds__(kAttnWaves *kWave) void attention_f16_kernel(const __half *qkv, __half *ctx, int seq,
-                                                                            int heads) {
+                                                                            int heads, int qblock) {
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     uint32_t *k_lds = reinterpret_cast<uint32_t *>(smem);                       // [seq][kKeyPitch] half2
     const int k_words = (seq * kKeyPitch + 3) & ~3;                              // keeps the value rows 16-byte aligned
@@ -29,7 +28,7 @@ __global__ __launch_bounds__(kAttnWaves *kWave) void attention_f16_kernel(const 
     float *p_lds = reinterpret_cast<float *>(v_lds + (size_t)seq * kHead);       // [waves][seq]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int qblocks = (seq + kQBlock - 1) / kQBlock;
+    const int qblocks = (seq + qblock - 1) / qblock;
     const int qb = blockIdx.x % qblocks, head = (blockIdx.x / qblocks) % heads, b = blockIdx.x / (qblocks * heads);
     const int h = heads * kHead;
     const long ld = 3L * h;
@@ -47,8 +46,8 @@ __global__ __launch_bounds__(kAttnWaves *kWave) void attention_f16_kernel(const 
     __syncthreads();
 
     float *p = p_lds + wave * seq;
-    for (int qi = wave; qi < kQBlock; qi += kAttnWaves) {
-        const int i = qb * kQBlock + qi;
+    for (int qi = wave; qi < qblock; qi += kAttnWaves) {
+        const int i = qb * qblock + qi;
         if (i >= seq) break;                                    // uniform per wave; no barrier below
         // the query, the same 64 values in every lane
         uint32_t q2[kHead / 2];
@@ -65,11 +64,9 @@ __global__ __launch_bounds__(kAttnWaves *kWave) void attention_f16_kernel(const 
             float s = 0.0f;
 #pragma unroll
             for (int w = 0; w < kHead / 2; ++w) {
-                const float2 a = __half22float2(*reinterpret_cast<const __half2 *>(&q2[w]));
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
                 const uint32_t kw = kr[w];
-                const float2 c = __half22float2(*reinterpret_cast<const __half2 *>(&kw));
-                s = fmaf(a.x, c.x, s);
-                s = fmaf(a.y, c.y, s);
+                s = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, q2[w]), __builtin_bit_cast(h2, kw), s, false);   // fp32 sum of exact products
             }
             s *= 0.125f;                                        // 1 / sqrt(64)
             p[k] = s;
@@ -86,6 +83,7 @@ __global__ __launch_bounds__(kAttnWaves *kWave) void attention_f16_kernel(const 
         __builtin_amdgcn_wave_barrier();                        // the wave's LDS writes are in order; keep the compiler from moving the reads up
         // output feature `lane`
         float acc = 0.0f;
+#pragma unroll 8
         for (int k = 0; k < seq; ++k) acc = fmaf(p[k], __half2float(v_lds[k * kHead + lane]), acc);
         ctx[((long)b * seq + i) * h + head * kHead + lane] = __float2half(acc / sum);
         __builtin_amdgcn_wave_barrier();                        // p is reused by the wave's next query
@@ -103,12 +101,15 @@ extern "C" int w4a4_attention_f16(const void *QKV_f16, int batch, int seq, int h
     if (!QKV_f16 || !ctx_f16) return W4A4_ERR_INVALID_ARG;
     if (seq > 512 || heads > 1024) return W4A4_ERR_UNSUPPORTED_SHAPE;
     if (!aligned16(QKV_f16) || !aligned16(ctx_f16)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const long blocks = (long)batch * heads * ((seq + kQBlock - 1) / kQBlock);
+    // sixteen queries share one copy of the head's keys and values; with few sequences and heads four do, so that
+    // the launch still covers the chip
+    const int qblock = (long)batch * heads * ((seq + 15) / 16) >= 512 ? 16 : 4;
+    const long blocks = (long)batch * heads * ((seq + qblock - 1) / qblock);
     if (blocks > 0x7fffffffL || (long)batch * seq * 3 * heads * kHead >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const size_t lds = (size_t)((seq * kKeyPitch + 3) & ~3) * 4 + (size_t)seq * kHead * 2 + (size_t)kAttnWaves * seq * 4;
     static KernelState ks;
     if (prepare_kernel(reinterpret_cast<const void *>(attention_f16_kernel), lds, ks) < 0) return W4A4_ERR_HIP;
     hipLaunchKernelGGL(attention_f16_kernel, dim3((unsigned)blocks), dim3(kAttnWaves * kWave), lds, as_stream(stream),
-                       static_cast<const __half *>(QKV_f16), static_cast<__half *>(ctx_f16), seq, heads);
+                       static_cast<const __half *>(QKV_f16), static_cast<__half *>(ctx_f16), seq, heads, qblock);
     return hipGetLastError() == hipSuccess ? W4A4_OK : W4A4_ERR_HIP;
 }
