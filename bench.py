@@ -37,6 +37,9 @@ def parse():
     p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped, 5 = one layer of the chained stack)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--step-only", action="store_true",
+                   help="only the timed step and its roofline: skip the latency, fusion, sibling, strategy and library legs "
+                        "(for profiler runs, so that a kernel trace holds the step's launches alone)")
     p.add_argument("--copy-probe-mb", type=int, default=0,
                    help="also run one plain device copy of this many MiB (a kernel of known traffic, used to "
                         "calibrate the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -157,6 +160,7 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     cfg = args.config
+    side_legs = cfg == 3 and not args.step_only
     specs = synth.config_linears(cfg)
     layers = [WL.make_layer(s, cfg, i, keep_host=False) for i, s in enumerate(specs)]
     Xs = [WL.dev(WL.make_input(s, cfg, i)) for i, s in enumerate(specs)]
@@ -227,7 +231,7 @@ def main():
 
     # ---- latency leg: BERT-base layer linears at batch 1 x seq 128 (launch/latency-bound)
     lat = {}
-    if cfg == 3:
+    if side_legs:
         s2 = synth.config_linears(2)
         l2 = [WL.make_layer(s, 2, i, keep_host=False) for i, s in enumerate(s2)]
         x2 = [WL.dev(WL.make_input(s, 2, i)) for i, s in enumerate(s2)]
@@ -325,7 +329,7 @@ def main():
     # the launch sequence replayed from a graph): w4a4_encoder_layer, eager and from a HIP graph, under the strategy
     # the library's table names for this shape and, for comparison, with every part in the INT8 sibling
     whole = {}
-    if cfg == 3:
+    if side_legs:
         bsz, sq, hd, hh, ff = 1, 128, 12, 768, 3072
         gen = torch.Generator(device="cuda").manual_seed(1)
         rn = lambda *shape, std=1.0: (torch.randn(shape, device="cuda", generator=gen) * std).half()
@@ -377,7 +381,7 @@ def main():
     # hidden size of this workload; HBM-bound, so it is reported against the HBM peak.  Four rotating
     # buffer sets (> the 256 MB on-package cache) so that nothing is served from cache.
     ln = {}
-    if cfg == 3:
+    if side_legs:
         Mh, Kh, nset = specs[0].M, specs[0].K, 4
         rng_t = torch.Generator(device="cuda").manual_seed(0)
         sets = []
@@ -407,7 +411,7 @@ def main():
     # ---- the INT8 sibling on the same workload (the paper's Sec. 4.1 comparison, on this hardware): the same
     # step with w8a8_quantize_rows + w8a8_linear, timed the same way
     i8 = {}
-    if cfg == 3:
+    if side_legs:
         w8 = [B.quantize_rows8(WL.dev(WL.make_layer(s_, cfg, i, keep_host=True).host_W)) for i, s_ in enumerate(specs)]
         a8 = [B.quantize_rows8(X) for X in Xs]
         q8_calls = [B.PreparedQuantizeRows8(X, a[0], a[1]) for X, a in zip(Xs, a8)]
@@ -443,7 +447,7 @@ def main():
     # ---- context only: the vendor library's FP16 GEMM (torch.matmul -> hipBLASLt) on the same four shapes, the
     # precision the paper's speedups are quoted against.  Plain matmul: no bias, no GELU, no quantize.
     fp16 = {}
-    if cfg == 3:
+    if side_legs:
         try:
             Wh = [torch.randn((s_.N, s_.K), device="cuda").half() * 0.02 for s_ in specs]
             Yh = [torch.empty((s_.M, s_.N), dtype=torch.float16, device="cuda") for s_ in specs]
@@ -484,7 +488,7 @@ def main():
     # the codes handed over in the epilogue, at the paper's annotated (batch-sequence) points for BERT-base and at
     # this bench's own token count; the library's tuner does the timing and the picking
     strat = {}
-    if cfg == 3:
+    if side_legs:
         names = ["qkv", "attn_out", "ffn1", "ffn2"]
         points = [("1-32", 32, 768, 3072), ("1-128", 128, 768, 3072), ("8-32", 256, 768, 3072),
                   ("16-128", 2048, 768, 3072), ("128-128", 16384, 768, 3072),

@@ -376,8 +376,13 @@ extern "C" int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_st
     uint8_t *ws = ar.get<uint8_t>(ws_bytes);
     if (!ar.ok) { (void)hipGetLastError(); return W4A4_ERR_HIP; }
     hipLaunchKernelGGL(fill_halves_kernel, dim3(fill_grid((size_t)M * widest)), dim3(256), 0, st, X, (size_t)M * widest, 7u, 3.0f);
-    hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return W4A4_ERR_HIP;
+    struct Events {
+        hipEvent_t e[2] = {nullptr, nullptr};
+        bool create() { return hipEventCreate(&e[0]) == hipSuccess && hipEventCreate(&e[1]) == hipSuccess; }
+        ~Events() { for (hipEvent_t x : e) if (x) (void)hipEventDestroy(x); }
+    } ev;
+    if (!ev.create()) { (void)hipStreamSynchronize(st); return W4A4_ERR_HIP; }   // (the fills must finish before the arena goes)
+    const hipEvent_t e0 = ev.e[0], e1 = ev.e[1];
     int status = W4A4_OK;
     auto time_us = [&](auto &&run, float *us) {
         if (status) return;
@@ -398,8 +403,6 @@ extern "C" int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_st
     time_us([&] { return w4a4_ffn(X, M, hidden, &parts[2], &parts[3], W4A4_STRATEGY_ALL_INT4, Y, ws, ws_bytes, stream); },
             &c.ffn_fused_us);
     (void)hipStreamSynchronize(st);
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
     if (status) return status;
     if (hipGetLastError() != hipSuccess) return W4A4_ERR_HIP;
     const int pick = w4a4_strategy_pick(&c);
