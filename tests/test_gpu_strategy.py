@@ -149,3 +149,39 @@ def test_tuner_picks_what_its_timings_say(B, orc):
         assert pick == orc.pick_strategy(part_us, fused_us)
         assert B.strategy_lookup(M, h, f) == pick                      # remembered for this device
     assert B.strategy_lookup(136, 768, 3072) == 15                     # untuned shape: the built-in table
+
+
+def _big(seed, M, h, f):
+    """Full-size operands made on the device (the host copy of the weights and of the sampled rows goes to the oracle)."""
+    g = torch.Generator(device="cuda").manual_seed(seed)
+    rn = lambda *s, std=1.0: (torch.randn(s, device="cuda", generator=g) * std).half()
+    return rn(M, h), rn(f, h, std=0.03), rn(f, std=0.02), rn(h, f, std=0.03), rn(h, std=0.02)
+
+
+@pytest.mark.parametrize("int4", [True, False])
+def test_part_linear_at_full_size_on_sampled_rows(B, orc, int4):
+    """BERT-large MLP output at the bench's token count (12288 x 1024 x 4096): the GPU runs the whole part, the
+    oracle the sampled token rows (rows are independent end to end)."""
+    M, h, f = 12288, 1024, 4096
+    X, W1, b1, W2, b2 = _big(3, M, f, h)                    # here: X [M, 4096], W1 [1024, 4096]
+    P = B.Part(W1, M, b1, 0)
+    got = B.part_linear(X, P, int4)
+    rows = np.sort(np.concatenate([[0, M - 1], np.random.default_rng(1).choice(M, 6, replace=False)]))
+    rt = torch.from_numpy(rows).cuda()
+    want = orc.part_linear(host(X[rt]), host(W1), int4, host(b1), 0)
+    assert np.array_equal(host(got[rt]).view(np.uint16), want.view(np.uint16))
+
+
+@pytest.mark.parametrize("strategy", [12, 28])
+def test_ffn_at_full_size_on_sampled_rows(B, orc, strategy):
+    """The BERT-large FFN pair at 12288 tokens without an activation in between (so that both sides are
+    bit-identical): separate quantize of the fp16 intermediate, and codes handed over in the epilogue."""
+    M, h, f = 12288, 1024, 4096
+    X, W1, b1, W2, b2 = _big(4, M, h, f)
+    P1, P2 = B.Part(W1, M, b1, 0), B.Part(W2, M, b2, 0)
+    assert P1.w4.layout == 1 and P2.w4.layout == 1           # the operand layout at this size
+    got = B.ffn(X, P1, P2, strategy)
+    rows = np.sort(np.concatenate([[0, M - 1], np.random.default_rng(2).choice(M, 4, replace=False)]))
+    rt = torch.from_numpy(rows).cuda()
+    want = orc.ffn(host(X[rt]), host(W1), host(b1), 0, host(W2), host(b2), strategy)
+    assert np.array_equal(host(got[rt]).view(np.uint16), want.view(np.uint16))
