@@ -37,6 +37,9 @@ def parse():
     p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped, 5 = one layer of the chained stack)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--gemm-curve", action="store_true",
+                   help="instead of the step: INT4 and INT8 GEMM kernel time over the token count for the BERT-base and "
+                        "BERT-large shapes (the comparison of Sec. 4.1 on this hardware); prints its own JSON line")
     p.add_argument("--step-only", action="store_true",
                    help="only the timed step and its roofline: skip the latency, fusion, sibling, strategy and library legs "
                         "(for profiler runs, so that a kernel trace holds the step's launches alone)")
@@ -147,12 +150,60 @@ def bench_chain(args):
     print(json.dumps(line))
 
 
+def bench_curve(args):
+    """Sec. 4.1 compares the INT4 with the INT8 GEMM over the token count M for the four encoder shapes.  Here: the
+    fused linears (GEMM + dequantize + fp16 store, operands already quantized), kernel-boundary times."""
+    import torch
+    from paper_2301_12017_amd import binding as B, synth
+    B.lib()
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    reps = max(args.steps, 5)
+    rows = []
+    for model, h, ffn in (("bert-base", 768, 3072), ("bert-large", 1024, 4096)):
+        for M in (128, 512, 1024, 2048, 4096, 8192, 12288, 16384):
+            for spec in synth._encoder_linears(M, h, ffn):
+                X = torch.randn((M, spec.K), device="cuda", generator=gen).half()
+                W = (torch.randn((spec.N, spec.K), device="cuda", generator=gen) * 0.03).half()
+                layout = B.preferred_layout(M, spec.N, spec.K)
+                W4 = B.quantize_weight(W, B.SYM, 0, layout)
+                A4 = B.quantize_act(X, B.SYM, layout=layout)
+                c4 = B.PreparedLinear(A4, W4, schedule=args.schedule if layout == 1 else 0)
+                w8 = B.quantize_rows8(W)
+                a8 = B.quantize_rows8(X)
+                c8 = B.PreparedLinear8(a8[0], a8[1], w8[0], w8[1])
+                st = B._stream()
+                us = {}
+                for name, call in (("int4", c4), ("int8", c8)):
+                    tms = [B.KernelTimer() for _ in range(reps)]
+                    for _ in range(3):
+                        call(st)
+                    for t in tms:
+                        t.arm()
+                        call(st)
+                    torch.cuda.synchronize()
+                    us[name] = sum(t.elapsed_ms() for t in tms) / reps * 1e3
+                ops = 2.0 * M * spec.N * spec.K
+                rows.append({"model": model, "M": M, "gemm": spec.name, "N": spec.N, "K": spec.K,
+                             "int4_us": us["int4"], "int8_us": us["int8"],
+                             "int4_TOPS": ops / us["int4"] / 1e6, "int8_TOPS": ops / us["int8"] / 1e6,
+                             "int4_over_int8": us["int8"] / us["int4"]})
+                del X, W, W4, A4, c4, w8, a8, c8
+    print(json.dumps({"metric": "INT4 vs INT8 fused-linear kernel time over the token count (Sec. 4.1 shapes)", "unit": "us / TOPS",
+                      "n_gpus": 1, "data": "synthetic", "reps": reps,
+                      "note": "w4a4_linear against w8a8_linear on operands quantized beforehand, no bias, fp16 out; durations "
+                              "from HIP events at the kernel's own start and end, mean of `reps` launches",
+                      "curve": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the path is token-parallel with no "
               "exchange); --gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
+    if args.gemm_curve:
+        return bench_curve(args)
     if args.config == 5:
         return bench_chain(args)
     import torch

@@ -36,6 +36,7 @@ static const Schedule kSchedules[] = {
     {"olay_192x128", 4, 1, false},
     {"group_128x128", 5, 0, true},
     {"small_splitk", 6, 0, false},
+    {"olay_128x128", 4, 2, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 
@@ -47,6 +48,7 @@ static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
 constexpr int kOlaySchedule = 14;                             // olay_128x256; +1 = olay_192x128
 constexpr int kGroupSchedule = 16;                            // group_128x128
 constexpr int kSmallSchedule = 17;                            // small_splitk
+constexpr int kOlayMidSchedule = 18;                          // olay_128x128
 
 // The small-problem kernel: symmetric per-channel layers in the canonical layout, fp16 or int32 output.
 static bool small_ok(const GemmArgs &g, bool grouped, int out_kind) {
@@ -80,17 +82,28 @@ static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
     return 7;
 }
 
-// Tile choice of the persistent kernel: two workgroups share a CU's matrix pipe, so what counts is
-// the largest number of tiles any CU ends up with (workgroups b and b + 256 share a CU) times the
-// tile area; the 192 x 128 tile unpacks 11 % more operand registers per MFMA.
+// Tile choice of the persistent kernel.  What counts is the CU that ends up with the most tiles: n tiles
+// of area a, worked on by min(n, workgroups per CU) co-resident workgroups.  Fitted to kernel times over
+// M = 512 .. 16384 on the BERT-base and BERT-large shapes: one workgroup alone gets about half of what two
+// get out of a CU's matrix pipe, three get 0.85 of it (LDS and cache contention); per unit of area the
+// 192 x 128 tile is 8 % dearer than the 128 x 256 one (more operand registers unpacked per MFMA) and the
+// 128 x 128 tile 6 % cheaper in the mid range, where it also leaves fewer CUs idle.  Below about 1500
+// tokens a tile's K loop is latency-bound and the small tile gains nothing.
 static int pick_olay(const GemmArgs &g) {
     const long cus = 256;
-    auto cost = [&](int bm, int bn, double penalty) {
+    auto cost = [&](int bm, int bn, int occ, double eff) {
         const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
-        const long per_cu = (tiles + cus - 1) / cus;
-        return (double)per_cu * bm * bn * penalty;
+        const long n = (tiles + cus - 1) / cus;
+        const long together = n < occ ? n : occ;
+        const double rate = together == 1 ? 0.5 : together == 2 ? 1.0 : 0.85;
+        return (double)n * bm * bn / (rate * eff);
     };
-    return cost(128, 256, 1.0) <= cost(192, 128, 1.08) ? kOlaySchedule : kOlaySchedule + 1;
+    int best = kOlaySchedule;
+    double c = cost(128, 256, 2, 1.0);
+    const double c192 = cost(192, 128, 2, 0.92);
+    if (c192 < c) { best = kOlaySchedule + 1; c = c192; }
+    if (g.M >= 1536 && cost(128, 128, 3, 1.06) < c) best = kOlayMidSchedule;
+    return best;
 }
 
 static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int schedule, hipStream_t st) {

@@ -576,6 +576,7 @@ static int launch_variant(int variant, GemmArgs &g, hipStream_t st) {
     switch (variant) {
         case 0: return launch_one<2, 4, 2, 2, 2, OUT>(g, st);   // 128 x 256, two workgroups per CU
         case 1: return launch_one<3, 2, 2, 2, 2, OUT>(g, st);   // 192 x 128, two workgroups per CU
+        case 2: return launch_one<2, 2, 2, 2, 3, OUT>(g, st);   // 128 x 128, three workgroups per CU: mid-sized problems
         default: return W4A4_ERR_INVALID_ARG;
     }
 }
