@@ -58,3 +58,9 @@ def f16_close(got_f16, want_f16, want_f32=None):
     err = np.abs(g[fin] - w[fin])
     ratio = float(np.max(err / np.maximum(tol, 1e-300))) if err.size else 0.0
     return ratio <= 1.0, ratio
+
+
+def olay_schedules(B, K):
+    """Schedule numbers of the persistent operand-layout kernel (every tile shape takes any K % 128 == 0, K >= 256)."""
+    assert K % 128 == 0 and K >= 256
+    return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("olay")]

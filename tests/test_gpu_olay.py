@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import act_to_canonical, dev, f16_close, has_gpu, host, wgt_to_canonical
+from tests.gpu_util import act_to_canonical, dev, f16_close, has_gpu, host, olay_schedules, wgt_to_canonical
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -83,8 +83,8 @@ def test_layout_argument_errors(B):
         B.gemm_i32(A, Wm, schedule=1)                              # that kernel reads canonical codes
 
 
-def _olay_schedules(B):
-    return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("olay")]
+def _olay_schedules(B, K):
+    return olay_schedules(B, K)
 
 
 @pytest.mark.parametrize("M,N,K", [(301, 520, 384), (128, 256, 256), (1, 8, 256), (700, 1032, 1024), (257, 264, 4096)])
@@ -94,7 +94,7 @@ def test_gemm_i32_bit_exact(B, orc, M, N, K):
     A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
     Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
     want = orc.gemm_i32(act_to_canonical(host(A.q)), wgt_to_canonical(host(Q.q)), SYM, 0)
-    scheds = _olay_schedules(B)
+    scheds = _olay_schedules(B, K)
     assert len(scheds) >= 2
     for sch in [0] + scheds:
         got = host(B.gemm_i32(A, Q, schedule=sch))
@@ -120,7 +120,7 @@ def test_gemm_i32_extreme_codes(B):
         esum = torch.full((N,), cw * K // 2, dtype=torch.int32, device="cuda")
         A = B.QAct(Aq, one, None, None, M, K, K // 2, 0, SYM, 0, MFMA, osum)
         Q = B.QWeight(Wq, one.reshape(-1, 1), None, None, None, N, K, 0, SYM, MFMA, esum)
-        for sch in _olay_schedules(B):
+        for sch in _olay_schedules(B, K):
             P = host(B.gemm_i32(A, Q, schedule=sch))
             assert (P == ca * cw * K).all(), (ca, cw, sch)
 
@@ -134,7 +134,7 @@ def test_linear_fp16(B, orc, act, with_bias):
     bias = (rng.standard_normal(N) * 0.01).astype(np.float16) if with_bias else None
     a, w = _qhost(A, Q)
     want = orc.linear(a, w, SYM, 0, bias, act)
-    for sch in _olay_schedules(B):
+    for sch in _olay_schedules(B, K):
         got = host(B.linear(A, Q, None if bias is None else dev(bias), act, schedule=sch))
         ok, ratio = f16_close(got, want["out"])
         assert ok, f"schedule {sch}: tolerance ratio {ratio}"
@@ -144,11 +144,13 @@ def test_linear_fp16(B, orc, act, with_bias):
             assert np.mean(got.view(np.uint16) == want["out"].view(np.uint16)) > 0.98
 
 
-def test_many_tiles_per_workgroup(B, orc):
-    """More tiles than resident workgroups (2 x 256 CUs): every workgroup walks several tiles, so the
-    K stream crosses tile boundaries; sampled rows are checked against the oracle."""
-    rng = np.random.default_rng(930)
-    M, N, K = 128 * 40, 256 * 30, 256                               # 1200 tiles
+@pytest.mark.parametrize("K", [256, 768])
+def test_many_tiles_per_workgroup(B, orc, K):
+    """More tiles than resident workgroups (at most 3 x 256 CUs): every workgroup walks several tiles, so
+    the K stream crosses tile boundaries (two K steps of the next tile are requested before the current
+    one ends); sampled rows are checked against the oracle."""
+    rng = np.random.default_rng(930 + K)
+    M, N = 128 * 40, 256 * 30                                       # 1200 tiles of 128 x 256
     X = _rand_x(rng, M, K)
     A = B.quantize_act(dev(X), SYM, layout=MFMA)
     Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
@@ -157,7 +159,7 @@ def test_many_tiles_per_workgroup(B, orc):
     a, w = _qhost(A, Q)
     a = dict(q=a["q"][rows], s=a["s"][rows], z=a["z"][rows], gsum=None)
     want = orc.linear(a, w, SYM, 0, bias, 0)
-    for sch in _olay_schedules(B):
+    for sch in _olay_schedules(B, K):
         got = host(B.linear(A, Q, dev(bias), 0, schedule=sch))
         assert np.array_equal(got[rows].view(np.uint16), want["out"].view(np.uint16)), sch
     # untouched rows would show up as the fill pattern: every output row was written

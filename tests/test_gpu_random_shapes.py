@@ -75,9 +75,8 @@ def test_layernorm_random_shapes(B, orc):
 
 def test_operand_layout_gemm_random_shapes(B, orc):
     """The persistent kernel (both tiles) on ragged M and N: int32 sums and fp16 outputs of sampled rows."""
-    from tests.gpu_util import act_to_canonical, wgt_to_canonical
+    from tests.gpu_util import act_to_canonical, olay_schedules, wgt_to_canonical
     rng = np.random.default_rng(2027)
-    olay = [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("olay")]
     for _ in range(10):
         M = int(rng.integers(1, 2500))
         N = 8 * int(rng.integers(1, 160))
@@ -92,7 +91,7 @@ def test_operand_layout_gemm_random_shapes(B, orc):
         assert np.array_equal(act_to_canonical(host(A.q))[rows], oa["q"]) and np.array_equal(wgt_to_canonical(host(Q.q)), ow["q"])
         wantP = orc.gemm_i32(oa["q"], ow["q"], 0, 0)
         want = orc.linear(oa, ow, 0, 0, b, 0)["out"]
-        for sch in olay:
+        for sch in olay_schedules(B, K):
             assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch))[:, rows], wantP), (M, N, K, sch)
             got = host(B.linear(A, Q, dev(b), 0, schedule=sch))[rows]
             assert np.array_equal(got.view(np.uint16), want.view(np.uint16)), (M, N, K, sch)
