@@ -77,8 +77,9 @@ static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
     }
     const long mid = (long)((g.M + 63) / 64) * ((g.N + 127) / 128);
     if (mid >= 256) return 5;
+    // 64 x 64 tiles beat 32 x 32 ones wherever there are a few dozen of them (measured at 384 .. 1536 tokens)
     const long small = (long)((g.M + 63) / 64) * ((g.N + 63) / 64);
-    if (small >= 256) return 6;
+    if (small >= 64) return 6;
     return 7;
 }
 
@@ -231,7 +232,7 @@ extern "C" int w4a4_preferred_layout(int M, int N, int K, int mode, int group) {
     // the operand layout exists for symmetric per-channel layers whose K the persistent kernel accepts;
     // small token counts (latency-bound, a handful of 128-row tiles) stay on the canonical kernels
     if (mode != W4A4_SYM || (group != 0 && group != K) || K % kBK || K < 2 * kBK) return W4A4_LAYOUT_CANONICAL;
-    return M >= 2048 ? W4A4_LAYOUT_MFMA : W4A4_LAYOUT_CANONICAL;
+    return M >= 1536 ? W4A4_LAYOUT_MFMA : W4A4_LAYOUT_CANONICAL;   // (measured crossover between 1024 and 1536 tokens)
 }
 
 extern "C" const char *w4a4_schedule_name(int schedule) {
