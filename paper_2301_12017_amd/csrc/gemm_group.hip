@@ -183,9 +183,17 @@ void gemm_group_kernel(GemmArgs g) {
     acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
                                                                    acc[(k) / FN][(k) % FN], 0, 0, 0);    \
     __builtin_amdgcn_sched_barrier(0);
+        // The first MFMA of a group starts from a constant C operand.  For unsigned codes whose sums go to
+        // the fp32 fold that constant is the bit pattern of 1.0f: the group's sum P (0 <= P < 2^23) then sits in
+        // the mantissa field, the accumulator read as a float is 1 + P * 2^-23 exactly, and
+        // fma(sw * 2^23, that, -sw * 2^23) is sw * P rounded once: the int-to-float conversion and the multiply of
+        // the definition in one instruction, with the same bits.
+        constexpr bool BIASED = !SGN && OUT != OUT_I32;
+        constexpr int kC0 = BIASED ? 0x3F800000 : 0;
 #define W4A4_SLOT_BEGIN_ZERO(Ucur, k)                                                                     \
-    acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(Ucur[(k) / FN], Ucur[FM + (k) % FN],   \
-                                                                   v16i{0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, 0, 0, 0); \
+    acc[(k) / FN][(k) % FN] = __builtin_amdgcn_mfma_i32_32x32x32_i8(                                       \
+        Ucur[(k) / FN], Ucur[FM + (k) % FN],                                                              \
+        v16i{kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0, kC0}, 0, 0, 0);    \
     __builtin_amdgcn_sched_barrier(0);
         constexpr int kBarSlot = NM - NF;
         float swg[FN];                                          // weight scales of the current group (this lane's channels)
@@ -268,14 +276,15 @@ void gemm_group_kernel(GemmArgs g) {
                 } else {
                     float sc[FN];
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) sc[j] = SGN ? swg[j] * 0.00390625f : swg[j];
+                    for (int j = 0; j < FN; ++j) sc[j] = SGN ? swg[j] * 0.00390625f : BIASED ? swg[j] * 8388608.0f : swg[j];
 #pragma unroll
                     for (int i = 0; i < FM; ++i)
 #pragma unroll
                         for (int j = 0; j < FN; ++j)
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
-                                const float u = sc[j] * (float)acc[i][j][r];
+                                const float u = BIASED ? __fmaf_rn(sc[j], __int_as_float(acc[i][j][r]), -sc[j])
+                                                       : sc[j] * (float)acc[i][j][r];
                                 facc[i][j][r] = facc[i][j][r] + u;
                             }
                 }
