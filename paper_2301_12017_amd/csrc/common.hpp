@@ -5,6 +5,9 @@
 #include <hip/hip_ext.h>
 #include <stdint.h>
 
+#include <atomic>
+#include <mutex>
+
 #include "../../include/w4a4.h"
 
 namespace w4a4 {
@@ -173,21 +176,30 @@ inline void launch_gemm(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t ld
 // count.  Function attributes and CU counts belong to a device and a process may use several, so both are
 // kept per device (races between threads are benign: the calls are idempotent).
 constexpr int kMaxDevices = 16;
-struct KernelState { size_t lds[kMaxDevices] = {}; int cus[kMaxDevices] = {}; };
+// Per-kernel, per-device launch state.  The LDS limit of a kernel only ever grows: raising it happens under
+// the mutex, reading it does not need one.
+struct KernelState {
+    std::atomic<size_t> lds[kMaxDevices] = {};
+    std::atomic<int> cus[kMaxDevices] = {};
+    std::mutex grow;
+};
 // Lets `kern` use `lds` bytes of dynamic LDS on the current device.  Returns that device's CU count, or -1.
 inline int prepare_kernel(const void *kern, size_t lds, KernelState &ks) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
-    if (lds > ks.lds[dev]) {
-        if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -1;
-        ks.lds[dev] = lds;
+    if (lds > ks.lds[dev].load(std::memory_order_acquire)) {
+        std::lock_guard<std::mutex> lock(ks.grow);
+        if (lds > ks.lds[dev].load(std::memory_order_relaxed)) {
+            if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return -1;
+            ks.lds[dev].store(lds, std::memory_order_release);
+        }
     }
-    if (!ks.cus[dev]) {
-        int cus = 0;
+    int cus = ks.cus[dev].load(std::memory_order_relaxed);
+    if (!cus) {
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return -1;
-        ks.cus[dev] = cus;
+        ks.cus[dev].store(cus, std::memory_order_relaxed);
     }
-    return ks.cus[dev];
+    return cus;
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
