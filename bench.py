@@ -37,6 +37,10 @@ def parse():
     p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped, 5 = one layer of the chained stack)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
     p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--settle-ms", type=float, default=300.0,
+                   help="untimed steps run for this long before the warm-up steps: after an idle phase the chip's "
+                        "clocks dip for some milliseconds a few milliseconds into a burst of work, and a short timed "
+                        "region that starts right after set-up would measure that transient instead of the sustained rate")
     p.add_argument("--gemm-curve", action="store_true",
                    help="instead of the step: INT4 and INT8 GEMM kernel time over the token count for the BERT-base and "
                         "BERT-large shapes (the comparison of Sec. 4.1 on this hardware); prints its own JSON line")
@@ -48,6 +52,17 @@ def parse():
                         "calibrate the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     p.add_argument("--cpu-rows", type=int, default=1024, help="token rows per GEMM the oracle is timed on")
     return p.parse_args()
+
+
+def settle(fn, ms):
+    """Keeps the GPU busy with untimed calls of fn for `ms` milliseconds (checked every ten calls, so that the
+    launch queue stays short)."""
+    import torch
+    t_end = time.perf_counter() + ms * 1e-3
+    while time.perf_counter() < t_end:
+        for _ in range(10):
+            fn()
+        torch.cuda.synchronize()
 
 
 def cpu_baseline(specs, cfg, rows):
@@ -113,6 +128,7 @@ def bench_chain(args):
                 tm[j].arm()                                     # stamps the GEMM kernel's own start and end
             calls[(k % nl) * 4 + j](stream)
 
+    settle(lambda: step(0), args.settle_ms)
     for k in range(args.warmup):
         step(k)
     torch.cuda.synchronize()
@@ -133,7 +149,7 @@ def bench_chain(args):
     achieved = ops / (sum(gemm_ms) * 1e-3) / 1e12
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
-        "value": ops / (ms * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup,
+        "value": ops / (ms * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "settle_ms": args.settle_ms,
         "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, int4 out)", "data": "synthetic",
         "config": {"workload": f"configs[4]: one layer of the chained BERT-large stack, M={M}: qkv, attn_out (V third in "
@@ -234,6 +250,7 @@ def main():
                 tm[i].arm()                                     # stamps the GEMM kernel's own start and end
             l_calls[i](st)
 
+    settle(step, args.settle_ms)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -269,9 +286,7 @@ def main():
         gr = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gr):
             step(st=B._stream())
-        for _ in range(3):
-            gr.replay()
-        torch.cuda.synchronize()
+        settle(gr.replay, args.settle_ms)
         tg = time.perf_counter()
         for _ in range(args.steps):
             gr.replay()
@@ -297,9 +312,8 @@ def main():
             for qc, lc in zip(qc2, lc2):
                 qc(st)
                 lc(st)
-        for _ in range(20):
-            layer2()
-        torch.cuda.synchronize()
+        lat_settle = min(args.settle_ms, 50.0)
+        settle(layer2, lat_settle)
         reps = 200
         t1 = time.perf_counter()
         for _ in range(reps):
@@ -337,9 +351,7 @@ def main():
             st = B._stream()
             for fc in fc2:
                 fc(st)
-        for _ in range(20):
-            layer2_fused()
-        torch.cuda.synchronize()
+        settle(layer2_fused, lat_settle)
         for fc, lc in zip(fc2, lc2):                                 # same bits as the two-call path
             assert torch.equal(fc.out.view(torch.int16), lc.out[0].view(torch.int16))
         t4 = time.perf_counter()
@@ -356,9 +368,7 @@ def main():
             st = B._stream()
             for _ in range(8):
                 tiny(st)
-        for _ in range(20):
-            eight()
-        torch.cuda.synchronize()
+        settle(eight, lat_settle)
         t3 = time.perf_counter()
         for _ in range(reps):
             eight()
@@ -393,9 +403,7 @@ def main():
         pick = B.strategy_lookup(bsz * sq, hh, ff)
         reps = 200
         for name, strat_ in (("int4", pick), ("int8", 0)):
-            for _ in range(20):
-                enc(xin, strat_, out=yout)
-            torch.cuda.synchronize()
+            settle(lambda: enc(xin, strat_, out=yout), lat_settle)
             eager = yout.clone()
             tw = time.perf_counter()
             for _ in range(reps):
@@ -444,9 +452,7 @@ def main():
             out = B._new_qact(Mh, Kh, B.SYM, 0, layers[0].W.layout, x.device)
             y = torch.empty((Mh, Kh), dtype=torch.float16, device="cuda")
             sets.append(B.PreparedLayerNormQuantize(x, r, g, b, 1e-12, out, y))
-        for c in sets:
-            c(stream)
-        torch.cuda.synchronize()
+        settle(lambda: [c(stream) for c in sets], lat_settle)
         reps_ln = 200
         t5 = time.perf_counter()
         for i in range(reps_ln):
@@ -476,6 +482,7 @@ def main():
                 if tm:
                     tm[i].arm()
                 l8_calls[i](stream)
+        settle(step8, args.settle_ms)
         for _ in range(args.warmup):
             step8()
         torch.cuda.synchronize()
@@ -502,9 +509,7 @@ def main():
         try:
             Wh = [torch.randn((s_.N, s_.K), device="cuda").half() * 0.02 for s_ in specs]
             Yh = [torch.empty((s_.M, s_.N), dtype=torch.float16, device="cuda") for s_ in specs]
-            for X, W_, Y_ in zip(Xs, Wh, Yh):
-                torch.matmul(X, W_.t(), out=Y_)
-            torch.cuda.synchronize()
+            settle(lambda: [torch.matmul(X, W_.t(), out=Y_) for X, W_, Y_ in zip(Xs, Wh, Yh)], args.settle_ms)   # same treatment
             t7 = time.perf_counter()
             for _ in range(args.steps):
                 for X, W_, Y_ in zip(Xs, Wh, Yh):
@@ -521,9 +526,7 @@ def main():
         try:                                                          # and its INT8 GEMM (int32 out, no epilogue)
             a8l = [a[0] for a in a8]
             w8l = [w[0].t() for w in w8]
-            for a_, w_ in zip(a8l, w8l):
-                torch._int_mm(a_, w_)
-            torch.cuda.synchronize()
+            settle(lambda: [torch._int_mm(a_, w_) for a_, w_ in zip(a8l, w8l)], args.settle_ms)
             t8l = time.perf_counter()
             for _ in range(args.steps):
                 for a_, w_ in zip(a8l, w8l):
@@ -559,7 +562,7 @@ def main():
 
     line = {
         "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
-        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "settle_ms": args.settle_ms,
         "ms_per_step": ms_per_step, "ms_per_step_graph_replay": graph_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, fp16 out)",
         "data": "synthetic",
