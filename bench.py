@@ -192,8 +192,7 @@ def bench_curve(args):
                 us = {}
                 for name, call in (("int4", c4), ("int8", c8)):
                     tms = [B.KernelTimer() for _ in range(reps)]
-                    for _ in range(3):
-                        call(st)
+                    settle(lambda: call(st), min(args.settle_ms, 100.0))
                     for t in tms:
                         t.arm()
                         call(st)
@@ -208,7 +207,8 @@ def bench_curve(args):
     print(json.dumps({"metric": "INT4 vs INT8 fused-linear kernel time over the token count (Sec. 4.1 shapes)", "unit": "us / TOPS",
                       "n_gpus": 1, "data": "synthetic", "reps": reps,
                       "note": "w4a4_linear against w8a8_linear on operands quantized beforehand, no bias, fp16 out; durations "
-                              "from HIP events at the kernel's own start and end, mean of `reps` launches",
+                              "from HIP events at the kernel's own start and end, mean of `reps` launches after up to 100 ms "
+                              "of untimed launches of the same call",
                       "curve": rows}))
 
 
