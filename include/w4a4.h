@@ -147,6 +147,13 @@ int w8a8_quantize_rows(const void *X_f16, int M, int K, int ldx, int8_t *q, floa
 int w8a8_linear(const int8_t *Aq, int lda, const float *sa, int M, const int8_t *Wq, const float *sw,
                 int N, int K, const w4a4_epilogue *ep, void *out, void *stream);
 
+/* w8a8_quantize_rows + w8a8_linear in ONE kernel for small token counts, as w4a4_linear_f16act does it
+ * for INT4 (Sec. 4.2: at small batch x sequence launch overhead and the quantize kernels decide): the
+ * result equals those two calls bit for bit.  X_f16 [M, ldx] fp16, Wq [N, K] int8, sw [N]; K % 64 == 0,
+ * K <= 4096, N % 8 == 0; ep->requant must be 0.  Meant for M up to a few hundred tokens. */
+int w8a8_linear_f16act(const void *X_f16, int M, int K, int ldx, const int8_t *Wq, const float *sw, int N,
+                       const w4a4_epilogue *ep, void *out, void *stream);
+
 /* The int32 accumulators alone (parity export): acc [M, N]. */
 int w8a8_gemm_i32(const int8_t *Aq, int lda, const float *sa, int M, const int8_t *Wq, const float *sw,
                   int N, int K, int32_t *acc, void *stream);
@@ -183,7 +190,8 @@ size_t w4a4_part_workspace_bytes(int M, const w4a4_part *P);
 
 /* out_f16 [M, N] = part P applied to X_f16 [M, ldx] (first K columns), in INT4 (int4 != 0:
  * steps a1..a3, in one kernel when the shape allows, else token-wise quantize + w4a4_linear) or in
- * INT8 (w8a8_quantize_rows + w8a8_linear).  The result is bit for bit what those calls give.
+ * INT8 (one kernel when the shape allows, else w8a8_quantize_rows + w8a8_linear).  The result is bit for
+ * bit what those calls give.
  * Asynchronous on `stream`; the workspace (256-byte aligned) is free again when the call's work
  * has finished.  INT8 needs K % 64 == 0, K >= 128. */
 int w4a4_part_linear(const void *X_f16, int M, int ldx, const w4a4_part *P, int int4, void *out_f16,

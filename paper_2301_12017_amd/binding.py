@@ -80,6 +80,7 @@ _SIGNATURES = {
                          _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
     "w8a8_quantize_rows": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "w8a8_linear": (_i, [_vp, _i, _vp, _i, _vp, _vp, _i, _i, ctypes.POINTER(_Epilogue), _vp, _vp]),
+    "w8a8_linear_f16act": (_i, [_vp, _i, _i, _i, _vp, _vp, _i, ctypes.POINTER(_Epilogue), _vp, _vp]),
     "w8a8_gemm_i32": (_i, [_vp, _i, _vp, _i, _vp, _vp, _i, _i, _vp, _vp]),
     "w4a4_layernorm_quantize": (_i, [_vp, _vp, _i, _i, _i, _vp, _vp, ctypes.c_float, _vp, _i, _i, _vp, _vp, _vp, _vp,
                                      _i, _vp, _vp]),
@@ -447,6 +448,18 @@ def linear8(Aq, sa, Wq, sw, bias=None, act=ACT_NONE, out=None):
     rc = lib().w8a8_linear(_ptr(Aq), Aq.stride(0), _ptr(sa), M, _ptr(Wq), _ptr(sw), N, K, ctypes.byref(ep), _ptr(out),
                            _stream())
     _check(rc, "w8a8_linear")
+    return out
+
+
+def linear8_f16act(X, Wq, sw, bias=None, act=ACT_NONE, out=None):
+    """w8a8_linear_f16act: fp16 [M,N] from fp16 activations in one kernel (small token counts)."""
+    assert X.is_cuda and X.dtype == torch.float16 and X.dim() == 2 and X.stride(1) == 1
+    M, K = X.shape
+    N = Wq.shape[0]
+    out = torch.empty((M, N), dtype=torch.float16, device=X.device) if out is None else out
+    ep = _epilogue(bias, act, False, SYM, 0, 0, LAYOUT_CANONICAL)
+    rc = lib().w8a8_linear_f16act(_ptr(X), M, K, X.stride(0), _ptr(Wq), _ptr(sw), N, ctypes.byref(ep), _ptr(out), _stream())
+    _check(rc, "w8a8_linear_f16act")
     return out
 
 

@@ -34,7 +34,7 @@ struct SmallArgs {
     const uint8_t *Aq; long lda;     // [M, K/2] canonical packed codes, row stride in bytes (packed form)
     const float *sa;                 // [M] token scales (packed form)
     int32_t *acc_out;                // packed form only: store the int32 sums P [M, N] instead of fp16 outputs
-    const uint8_t *Wq; long ldw;     // canonical packed codes [N, K/2]
+    const uint8_t *Wq; long ldw;     // canonical packed codes [N, K/2]; INT8 sibling: int8 codes [N, K]
     const float *sw;                 // [N]
     const __half *bias; int act;
     __half *out;                     // [M, N]
@@ -47,6 +47,8 @@ constexpr int small_xchunks(int tm) { return tm == 16 ? 8 : 16; }
 constexpr int small_wchunks(int nw) { return nw == 16 ? 4 : 6; }
 
 // eight fp16 values -> their codes, as two operand registers: bytes (c0,c2,c4,c6) and (c1,c3,c5,c7)
+// (NATURAL: bytes (c0,c1,c2,c3) and (c4,c5,c6,c7) instead: the order of one-byte weight codes)
+template <bool NATURAL = false>
 __device__ __forceinline__ void codes8(const u32x4 &x, float inv, uint32_t &even, uint32_t &odd) {
     uint32_t u[8];
     const float nzero = -0.0f;
@@ -60,8 +62,13 @@ __device__ __forceinline__ void codes8(const u32x4 &x, float inv, uint32_t &even
         u[2 * i] = __float_as_uint(t0 + 12582912.0f);
         u[2 * i + 1] = __float_as_uint(t1 + 12582912.0f);
     }
-    even = __builtin_amdgcn_perm(u[2], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[6], u[4], 0x04000c0cu);
-    odd = __builtin_amdgcn_perm(u[3], u[1], 0x0c0c0400u) | __builtin_amdgcn_perm(u[7], u[5], 0x04000c0cu);
+    if (NATURAL) {
+        even = __builtin_amdgcn_perm(u[1], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[3], u[2], 0x04000c0cu);
+        odd = __builtin_amdgcn_perm(u[5], u[4], 0x0c0c0400u) | __builtin_amdgcn_perm(u[7], u[6], 0x04000c0cu);
+    } else {
+        even = __builtin_amdgcn_perm(u[2], u[0], 0x0c0c0400u) | __builtin_amdgcn_perm(u[6], u[4], 0x04000c0cu);
+        odd = __builtin_amdgcn_perm(u[3], u[1], 0x0c0c0400u) | __builtin_amdgcn_perm(u[7], u[5], 0x04000c0cu);
+    }
 }
 
 // NW waves, FN column fragments of 32 channels, TM = 32 or 16 tokens per workgroup (with 16 the upper
@@ -69,8 +76,11 @@ __device__ __forceinline__ void codes8(const u32x4 &x, float inv, uint32_t &even
 // PACKED: the activations arrive already quantized (packed codes + token scales, the output of
 // w4a4_quantize_act or of a producer kernel): pass 1 only parks their tile in LDS, and both operands are
 // widened to 16 * code on their way into the MFMA (the sums hold 256 * P).
-template <int NW, int FN, int TM, bool WLDS, bool PACKED>
+// W8 (fp16-activation form only): the INT8 sibling.  Tokens are quantized with 127 levels per side, the
+// weights are one int8 code per byte and go into the MFMA as they are (the sums hold P).
+template <int NW, int FN, int TM, bool WLDS, bool PACKED, bool W8 = false>
 __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
+    static_assert(!(W8 && PACKED), "the INT8 sibling takes fp16 activations");
     constexpr int NT = NW * 64, LPR = NT / TM;                  // LPR consecutive lanes share a token in pass 1
     constexpr int RV = TM / 2;                                  // accumulator registers per fragment that hold real rows
     constexpr int R = RV * FN;                                  // ... of the tile
@@ -80,7 +90,7 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     constexpr int ACH = PACKED ? 4 : 1;                         // 16-byte chunks of the packed activation tile per lane
     static_assert(LPR <= 64 && (LPR & (LPR - 1)) == 0, "a token's lanes sit in one wave");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const int wpitch = a.K / 2 + 16, pitch = PACKED ? wpitch : a.K + 16;
+    const int wpitch = (W8 ? a.K : a.K / 2) + 16, pitch = PACKED ? a.K / 2 + 16 : a.K + 16;
     uint8_t *codes = smem;                                      // [TM][pitch] int8 activation codes (packed codes if PACKED)
     uint8_t *wt = codes + TM * pitch;                           // [32 FN][wpitch] packed weight codes (WLDS)
     int *s_sum = reinterpret_cast<int *>(wt + (WLDS ? 32 * FN * wpitch : 0));   // [R][64]
@@ -97,7 +107,7 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     // ---- requests, in the order they are needed: activation rows, weights, channel constants ----------------
     const int row = tid / LPR, c0 = tid % LPR;
     const int nchunks = a.K / 8;                                // 16-byte chunks of an activation row
-    const int wcpr = a.K / 32;                                  // 16-byte chunks of a row of packed codes
+    const int wcpr = W8 ? a.K / 16 : a.K / 32;                  // 16-byte chunks of a row of weight codes
     u32x4 x[XCH];
     u32x4 ast[ACH];
     int arow_i[ACH];
@@ -179,7 +189,11 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
         float amax = fmaxf((float)mx[0], (float)mx[1]);
 #pragma unroll
         for (int o = LPR / 2; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, kWave));
-        const Range rg = range_sym(amax);
+        Range rg = range_sym(amax);
+        if (W8) {                                                // Sec. 3.1 with b = 8: 127 levels per side
+            if (amax == 0.0f) { rg.inv = 0.0f; rg.S = 1.0f; }
+            else { rg.inv = 127.0f / amax; rg.S = amax / 127.0f; }
+        }
         if (c0 == 0) s_S[row] = rg.S;
         uint8_t *dst = codes + row * pitch;
 #pragma unroll
@@ -187,7 +201,7 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
             const int c = c0 + i * LPR;
             if (i * LPR < nchunks && c < nchunks) {
                 uint32_t ev, od;
-                codes8(x[i], rg.inv, ev, od);
+                codes8<W8>(x[i], rg.inv, ev, od);
                 *reinterpret_cast<uint2 *>(dst + c * 8) = make_uint2(ev, od);
             }
         }
@@ -207,7 +221,7 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[j][q] = 0;
     const uint8_t *arow = codes + (r % TM) * pitch + h * (PACKED ? 16 : 32);
-    const uint8_t *wrow = wt + r * wpitch + h * 16;
+    const uint8_t *wrow = wt + r * wpitch + h * (W8 ? 32 : 16);
 #pragma unroll 1
     for (int b = wave; b < nb; b += NW) {
         v4i alo, ahi;
@@ -219,6 +233,27 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
             alo = *reinterpret_cast<const v4i *>(arow + b * 64);
             ahi = *reinterpret_cast<const v4i *>(arow + b * 64 + 16);
         }
+        if constexpr (W8) {
+            // one-byte codes: lane (r, h) takes 32 bytes of channel r, two MFMA operands as they are
+            v4i w0[FN], w1[FN];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                if constexpr (WLDS) {
+                    w0[j] = *reinterpret_cast<const v4i *>(wrow + 32 * j * wpitch + b * 64);
+                    w1[j] = *reinterpret_cast<const v4i *>(wrow + 32 * j * wpitch + b * 64 + 16);
+                } else {
+                    const uint32_t off = (uint32_t)(n0 + 32 * j + r) * (uint32_t)a.ldw + (uint32_t)(b * 64 + h * 32);
+                    const u32x4 t0 = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off, 0, 0);
+                    const u32x4 t1 = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, off + 16, 0, 0);
+                    w0[j] = v4i{(int)t0[0], (int)t0[1], (int)t0[2], (int)t0[3]};
+                    w1[j] = v4i{(int)t1[0], (int)t1[1], (int)t1[2], (int)t1[3]};
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo, w0[j], acc[j], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, w1[j], acc[j], 0, 0, 0);
+        } else {
         u32x4 wv[FN];
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
@@ -232,6 +267,7 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
 #pragma unroll
         for (int j = 0; j < FN; ++j)
             acc[j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi, widen2<true>(wv[j][2], wv[j][3]), acc[j], 0, 0, 0);
+        }
     }
 
     // ---- add the partial sums of the waves in LDS (exact, so the order is free).  Accumulator register q of
@@ -259,8 +295,9 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
             __builtin_amdgcn_raw_buffer_store_b32((uint32_t)(s_sum[qq * 64 + lane] >> 8), o_rsrc, ioff, 0, 0);
             continue;
         }
-        // the sums hold 16 * P (256 * P if PACKED); a power of two, so the rescaled weight scale is exact
-        const float swn = __uint_as_float(sw_raw[k]) * (PACKED ? 0.00390625f : 0.0625f);
+        // the sums hold 16 * P (256 * P if PACKED, P itself for the INT8 sibling); a power of two, so the rescaled
+        // weight scale is exact
+        const float swn = __uint_as_float(sw_raw[k]) * (PACKED ? 0.00390625f : W8 ? 1.0f : 0.0625f);
         float y = ((float)s_sum[qq * 64 + lane] * s_S[trow]) * swn;
         if (a.bias) y = y + __half2float(__ushort_as_half(b_raw[k]));
         const uint32_t off = n_ok ? ((uint32_t)(m0 + trow) * (uint32_t)a.N + (uint32_t)n) * 2u : kPoison;   // rows >= M fall off the end
@@ -269,14 +306,14 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     }
 }
 
-template <int NW, int FN, int TM, bool WLDS, bool PACKED>
+template <int NW, int FN, int TM, bool WLDS, bool PACKED, bool W8 = false>
 static int launch_small(SmallArgs &a, hipStream_t st) {
     a.tiles_n = (a.N + 32 * FN - 1) / (32 * FN);
     const long tiles = (long)((a.M + TM - 1) / TM) * a.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const size_t lds = TM * (size_t)((PACKED ? a.K / 2 : a.K) + 16) + (WLDS ? 32 * FN * (size_t)(a.K / 2 + 16) : 0) +
+    const size_t lds = TM * (size_t)((PACKED ? a.K / 2 : a.K) + 16) + (WLDS ? 32 * FN * (size_t)((W8 ? a.K : a.K / 2) + 16) : 0) +
                        (size_t)(TM / 2) * FN * 64 * 4 + TM * 4;
-    auto kern = linear_f16act_kernel<NW, FN, TM, WLDS, PACKED>;
+    auto kern = linear_f16act_kernel<NW, FN, TM, WLDS, PACKED, W8>;
     static KernelState ks;
     if (prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks) < 0) return W4A4_ERR_HIP;
     launch_gemm(kern, dim3((unsigned)tiles), dim3(NW * 64), lds, st, a);
@@ -288,20 +325,20 @@ static int launch_small(SmallArgs &a, hipStream_t st) {
 // redundant work, but a tile is one CU's job: 32 x 32 while that gives at most one workgroup per CU, 32 x 64
 // beyond, and 16-token tiles when 32-token tiles would leave more than half of the CUs idle.  The weight
 // tile is staged in LDS (coalesced loads) whenever it fits beside the activation codes.
-template <bool PACKED>
+template <bool PACKED, bool W8 = false>
 static int small_dispatch(SmallArgs &a, hipStream_t st) {
     const int M = a.M, N = a.N, K = a.K;
     const long t32 = (long)((M + 31) / 32) * ((N + 31) / 32);
     const bool wide = t32 > 256, low = t32 <= 128;
-    const size_t code_b = (size_t)(low ? 16 : 32) * ((PACKED ? K / 2 : K) + 16), wt_b = (size_t)(wide ? 64 : 32) * (K / 2 + 16);
+    const size_t code_b = (size_t)(low ? 16 : 32) * ((PACKED ? K / 2 : K) + 16), wt_b = (size_t)(wide ? 64 : 32) * ((W8 ? K : K / 2) + 16);
     const int nw = K > 1536 ? 16 : K > 384 ? 8 : 4;
-    const long wchunks = ((long)(wide ? 64 : 32) * (K / 32) + nw * 64 - 1) / (nw * 64);   // per lane
+    const long wchunks = ((long)(wide ? 64 : 32) * (K / (W8 ? 16 : 32)) + nw * 64 - 1) / (nw * 64);   // per lane
     const bool wlds = code_b + wt_b <= 144 * 1024 && wchunks <= small_wchunks(nw);   // beside the sums, within a CU's 160 KB
 #define W4A4_SMALL(NW)                                                                                  \
     do {                                                                                                \
-        if (wide) return wlds ? launch_small<NW, 2, 32, true, PACKED>(a, st) : launch_small<NW, 2, 32, false, PACKED>(a, st); \
-        if (low) return wlds ? launch_small<NW, 1, 16, true, PACKED>(a, st) : launch_small<NW, 1, 16, false, PACKED>(a, st);  \
-        return wlds ? launch_small<NW, 1, 32, true, PACKED>(a, st) : launch_small<NW, 1, 32, false, PACKED>(a, st);     \
+        if (wide) return wlds ? launch_small<NW, 2, 32, true, PACKED, W8>(a, st) : launch_small<NW, 2, 32, false, PACKED, W8>(a, st); \
+        if (low) return wlds ? launch_small<NW, 1, 16, true, PACKED, W8>(a, st) : launch_small<NW, 1, 16, false, PACKED, W8>(a, st);  \
+        return wlds ? launch_small<NW, 1, 32, true, PACKED, W8>(a, st) : launch_small<NW, 1, 32, false, PACKED, W8>(a, st);     \
     } while (0)
     if (K > 1536) W4A4_SMALL(16);
     if (K > 384) W4A4_SMALL(8);
@@ -351,4 +388,25 @@ extern "C" int w4a4_linear_f16act(const void *X_f16, int M, int K, int ldx, cons
     a.out = static_cast<__half *>(out);
     a.M = M; a.N = W->N; a.K = K; a.tiles_n = 0;
     return small_dispatch<false>(a, as_stream(stream));
+}
+
+extern "C" int w8a8_linear_f16act(const void *X_f16, int M, int K, int ldx, const int8_t *Wq, const float *sw, int N,
+                                  const w4a4_epilogue *ep, void *out, void *stream) {
+    if (!ep || M < 0 || K <= 0 || ldx < K || N <= 0) return W4A4_ERR_INVALID_ARG;
+    if (ep->act != W4A4_ACT_NONE && ep->act != W4A4_ACT_GELU) return W4A4_ERR_INVALID_ARG;
+    if (ep->requant) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (K % 64 || K > 4096 || N % 8 || (ldx * 2) % 16) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (M == 0) return W4A4_OK;
+    if (!X_f16 || !Wq || !sw || !out) return W4A4_ERR_INVALID_ARG;
+    if (!aligned16(X_f16) || !aligned16(Wq) || !aligned16(out) || (ep->bias_f16 && !aligned16(ep->bias_f16)))
+        return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if ((long)M * ldx * 2 >= 0x7fffffffL || (long)N * K >= 0x7fffffffL || ((long)M + 32) * N * 2 >= 0x7fffffffL)
+        return W4A4_ERR_UNSUPPORTED_SHAPE;
+    SmallArgs a{};
+    a.X = static_cast<const __half *>(X_f16); a.ldx = ldx;
+    a.Wq = reinterpret_cast<const uint8_t *>(Wq); a.ldw = K; a.sw = sw;
+    a.bias = static_cast<const __half *>(ep->bias_f16); a.act = ep->act;
+    a.out = static_cast<__half *>(out);
+    a.M = M; a.N = N; a.K = K; a.tiles_n = 0;
+    return small_dispatch<false, true>(a, as_stream(stream));
 }

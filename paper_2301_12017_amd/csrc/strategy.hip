@@ -97,6 +97,10 @@ int run_part(const void *X, int M, int ldx, const w4a4_part &p, bool int4, void 
         return w4a4_linear(&a, &p.w4, &ep, out, nullptr, nullptr, nullptr, nullptr, 0, stream);
     }
     if (!p.w8q || !p.w8s) return W4A4_ERR_INVALID_ARG;
+    if (K % 64 == 0 && K <= 4096 && (long)((M + 31) / 32) * ((N + 31) / 32) <= 512) {   // one launch for small token counts
+        const int rc = w8a8_linear_f16act(X, M, K, ldx, p.w8q, p.w8s, N, &ep, out, stream);
+        if (rc != W4A4_ERR_UNSUPPORTED_SHAPE) return rc;
+    }
     Carver c(ws);
     int8_t *q = c.take<int8_t>((size_t)M * K);
     float *s = c.take<float>(M);

@@ -191,6 +191,17 @@ def test_int8_sibling_argument_errors(b):
     assert L.w8a8_quantize_rows(p, 4, 48, 48, p, p, None) == -2       # K % 32
     assert L.w8a8_quantize_rows(p, 4, 32768, 32768, p, p, None) == -2
     assert L.w8a8_quantize_rows(p, 0, 64, 64, p, p, None) == 0
+    ep0 = b._Epilogue(None, 0, 0, 0, 0, 0, 0)
+
+    def f8(M=4, K=64, ldx=None, N=8, e=ep0, x=p, w=p, s_=p, o=p):
+        return L.w8a8_linear_f16act(x, M, K, K if ldx is None else ldx, w, s_, N, ctypes.byref(e), o, None)
+
+    assert f8(ldx=32) == -1 and f8(x=None) == -1 and f8(w=None) == -1 and f8(s_=None) == -1 and f8(o=None) == -1
+    assert f8(e=b._Epilogue(None, 9, 0, 0, 0, 0, 0)) == -1
+    assert f8(e=b._Epilogue(None, 0, 1, 0, 0, 0, 0)) == -2              # requant belongs to the INT4 path
+    assert f8(K=96) == -2 and f8(K=8192) == -2 and f8(N=12) == -2 and f8(ldx=68) == -2
+    assert f8(x=ctypes.c_void_p(0x1004)) == -2
+    assert f8(M=0) == 0
 
 
 def test_workspace_bytes(b):

@@ -83,3 +83,36 @@ def test_extreme_codes_and_untouched_neighbours(B, orc):
     buf = torch.full((M + 16, N), 3.0, dtype=torch.float16, device="cuda")
     B.linear8(dev(A), dev(sa * 1e-6), dev(W), dev(sw), None, 0, out=buf[:M])
     assert bool((buf[M:] == 3.0).all())
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 768, 768), (128, 3072, 768), (128, 768, 3072), (1, 8, 128), (37, 200, 4096),
+                                   (300, 96, 256), (32, 2304, 768), (130, 1024, 1024), (512, 512, 1536)])
+@pytest.mark.parametrize("act", [0, 1])
+def test_one_kernel_linear_equals_the_two_calls_and_the_oracle(B, orc, M, N, K, act):
+    """w8a8_linear_f16act (token quantize inside the GEMM kernel): bit for bit the two-call path, whichever
+    tile, wave count and weight staging the shape selects; against the oracle as w8a8_linear."""
+    rng = np.random.default_rng(M + N + K + act)
+    X, W, b = _xw(rng, M, N, K)
+    X[0, :] = 0                                                      # an all-zero token: scale 1, codes 0
+    Wq, sw = B.quantize_rows8(dev(W))
+    got = B.linear8_f16act(dev(X), Wq, sw, dev(b), act)
+    Aq, sa = B.quantize_rows8(dev(X))
+    ref = B.linear8(Aq, sa, Wq, sw, dev(b), act)
+    assert torch.equal(got, ref)
+    want = orc.linear8(orc.quantize_rows8(X), orc.quantize_rows8(W), b, act)["out"]
+    if act == 0:
+        assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16))
+    else:
+        ok, ratio = f16_close(host(got), want)
+        assert ok, ratio
+
+
+def test_one_kernel_linear_reads_strided_rows(B, orc):
+    rng = np.random.default_rng(77)
+    M, N, K = 70, 64, 128
+    X, W, b = _xw(rng, M, N, 3 * K)
+    Wq, sw = B.quantize_rows8(dev(np.ascontiguousarray(W[:, :K])))
+    Xd = dev(X)
+    got = B.linear8_f16act(Xd[:, K:2 * K], Wq, sw)
+    want = orc.linear8(orc.quantize_rows8(np.ascontiguousarray(X[:, K:2 * K])), orc.quantize_rows8(np.ascontiguousarray(W[:, :K])))["out"]
+    assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16))
