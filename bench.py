@@ -434,7 +434,7 @@ def main():
         whole["strategy"] = pick
         whole["note"] = ("one post-LN BERT-base encoder layer, batch 1 x seq 128, fp16 in / fp16 out: qkv, FP16 attention "
                          "stand-in (no mask), attention output, residual + LayerNorm, ffn1 + GELU, ffn2, residual + LayerNorm "
-                         "= 7 launches in INT4 (quantize inside the GEMM kernels), 11 in INT8; back-to-back calls, weights warm")
+                         "= 7 launches in either precision (quantize inside the GEMM kernels); back-to-back calls, weights warm")
 
     # ---- producer fusion (Sec. 4.2): LayerNorm(x + residual) fused with the token-wise quantize, at the
     # hidden size of this workload; HBM-bound, so it is reported against the HBM peak.  Four rotating

@@ -221,8 +221,10 @@ int w4a4_strategy_pick(const w4a4_strategy_costs *costs);
  * output h -> h, FFN1 h -> ffn with GELU, FFN2 ffn -> h; symmetric per-channel weights, biases)
  * on the current device with synthetic operands: `iters` timed runs per option after two warm-up
  * runs, HIP events on `stream`.  Allocates and frees its own device buffers and synchronizes the
- * stream.  Fills *costs (may be NULL), remembers the picked strategy for this (device, M, h, ffn)
- * and returns it (>= 0) or a w4a4_status (< 0).  h % 64 == 0, ffn % 64 == 0, h <= 4096, ffn <= 16384. */
+ * stream.  Timings that differ by at most 3 % count as equal (a part's two precisions; the fused
+ * pair against its two INT4 parts), so that the tie rules of w4a4_strategy_pick decide and not the
+ * timing noise.  Fills *costs with the raw timings (may be NULL), remembers the picked strategy for this
+ * (device, M, h, ffn) and returns it (>= 0) or a w4a4_status (< 0).  h % 64 == 0, ffn % 64 == 0, h <= 4096, ffn <= 16384. */
 int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_strategy_costs *costs, void *stream);
 
 /* The strategy remembered by w4a4_strategy_tune for this shape on the current device, else the

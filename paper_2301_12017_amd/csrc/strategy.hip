@@ -409,7 +409,19 @@ extern "C" int w4a4_strategy_tune(int M, int hidden, int ffn, int iters, w4a4_st
     (void)hipStreamSynchronize(st);
     if (status) return status;
     if (hipGetLastError() != hipSuccess) return W4A4_ERR_HIP;
-    const int pick = w4a4_strategy_pick(&c);
+    // Differences below 3 % are timing noise: price such options equally, so that the tie rules of the pick
+    // (more INT4 parts, then the fused pair) decide and not the noise.  The caller gets the raw timings.
+    w4a4_strategy_costs snapped = c;
+    auto tie = [](float &a, float &b) {
+        const float lo = a < b ? a : b, hi = a < b ? b : a;
+        if (hi - lo <= 0.03f * lo) a = b = lo;
+    };
+    for (int p = 0; p < 4; ++p) tie(snapped.part_us[p][0], snapped.part_us[p][1]);
+    {
+        const float unfused = snapped.part_us[W4A4_PART_FFN1][1] + snapped.part_us[W4A4_PART_FFN2][1];
+        if (snapped.ffn_fused_us > unfused && snapped.ffn_fused_us - unfused <= 0.03f * unfused) snapped.ffn_fused_us = unfused;
+    }
+    const int pick = w4a4_strategy_pick(&snapped);
     if (pick < 0) return pick;
     if (costs) *costs = c;
     {
