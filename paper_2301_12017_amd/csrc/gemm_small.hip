@@ -76,21 +76,22 @@ __device__ __forceinline__ void codes8(const u32x4 &x, float inv, uint32_t &even
 // PACKED: the activations arrive already quantized (packed codes + token scales, the output of
 // w4a4_quantize_act or of a producer kernel): pass 1 only parks their tile in LDS, and both operands are
 // widened to 16 * code on their way into the MFMA (the sums hold 256 * P).
-// W8 (fp16-activation form only): the INT8 sibling.  Tokens are quantized with 127 levels per side, the
-// weights are one int8 code per byte and go into the MFMA as they are (the sums hold P).
+// W8: the INT8 sibling.  Tokens are quantized with 127 levels per side (or arrive as one int8 code per
+// byte when PACKED), the weights are one int8 code per byte, and both go into the MFMA as they are (the
+// sums hold P).
 template <int NW, int FN, int TM, bool WLDS, bool PACKED, bool W8 = false>
 __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
-    static_assert(!(W8 && PACKED), "the INT8 sibling takes fp16 activations");
     constexpr int NT = NW * 64, LPR = NT / TM;                  // LPR consecutive lanes share a token in pass 1
     constexpr int RV = TM / 2;                                  // accumulator registers per fragment that hold real rows
     constexpr int R = RV * FN;                                  // ... of the tile
     constexpr int RPW = (R + NW - 1) / NW;                      // ... finished by one wave
     constexpr int WCH = WLDS ? small_wchunks(NW) : 1;
     constexpr int XCH = PACKED ? 1 : small_xchunks(TM);
-    constexpr int ACH = PACKED ? 4 : 1;                         // 16-byte chunks of the packed activation tile per lane
+    constexpr int ACH = PACKED ? (W8 ? 8 : 4) : 1;              // 16-byte chunks of the packed activation tile per lane
+    constexpr bool NIBBLES = PACKED && !W8;                     // activation codes arrive two per byte
     static_assert(LPR <= 64 && (LPR & (LPR - 1)) == 0, "a token's lanes sit in one wave");
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
-    const int wpitch = (W8 ? a.K : a.K / 2) + 16, pitch = PACKED ? a.K / 2 + 16 : a.K + 16;
+    const int wpitch = (W8 ? a.K : a.K / 2) + 16, pitch = NIBBLES ? a.K / 2 + 16 : a.K + 16;
     uint8_t *codes = smem;                                      // [TM][pitch] int8 activation codes (packed codes if PACKED)
     uint8_t *wt = codes + TM * pitch;                           // [32 FN][wpitch] packed weight codes (WLDS)
     int *s_sum = reinterpret_cast<int *>(wt + (WLDS ? 32 * FN * wpitch : 0));   // [R][64]
@@ -98,7 +99,7 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m0 = (blockIdx.x / a.tiles_n) * TM, n0 = (blockIdx.x % a.tiles_n) * (32 * FN);
-    const __amdgpu_buffer_rsrc_t x_rsrc = PACKED ? make_rsrc(a.Aq, (uint32_t)((long)(a.M - 1) * a.lda + a.K / 2))
+    const __amdgpu_buffer_rsrc_t x_rsrc = PACKED ? make_rsrc(a.Aq, (uint32_t)((long)(a.M - 1) * a.lda + (W8 ? a.K : a.K / 2)))
                                                  : make_rsrc(a.X, (uint32_t)(((long)(a.M - 1) * a.ldx + a.K) * 2));
     const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(a.Wq, (uint32_t)((long)a.N * a.ldw));
     const int r = lane & 31, h = lane >> 5;                     // pass 2: token / channel r, K half h
@@ -220,12 +221,12 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
     for (int j = 0; j < FN; ++j)
 #pragma unroll
         for (int q = 0; q < 16; ++q) acc[j][q] = 0;
-    const uint8_t *arow = codes + (r % TM) * pitch + h * (PACKED ? 16 : 32);
+    const uint8_t *arow = codes + (r % TM) * pitch + h * (NIBBLES ? 16 : 32);
     const uint8_t *wrow = wt + r * wpitch + h * (W8 ? 32 : 16);
 #pragma unroll 1
     for (int b = wave; b < nb; b += NW) {
         v4i alo, ahi;
-        if constexpr (PACKED) {
+        if constexpr (NIBBLES) {
             const u32x4 ap = *reinterpret_cast<const u32x4 *>(arow + b * 32);
             alo = widen2<true>(ap[0], ap[1]);
             ahi = widen2<true>(ap[2], ap[3]);
@@ -292,12 +293,12 @@ __global__ __launch_bounds__(NW * 64) void linear_f16act_kernel(SmallArgs a) {
         const int trow = frag_row(0, q, lane);
         if (ints) {                                              // parity export: P itself
             const uint32_t ioff = n_ok ? ((uint32_t)(m0 + trow) * (uint32_t)a.N + (uint32_t)n) * 4u : kPoison;
-            __builtin_amdgcn_raw_buffer_store_b32((uint32_t)(s_sum[qq * 64 + lane] >> 8), o_rsrc, ioff, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b32((uint32_t)(W8 ? s_sum[qq * 64 + lane] : s_sum[qq * 64 + lane] >> 8), o_rsrc, ioff, 0, 0);
             continue;
         }
         // the sums hold 16 * P (256 * P if PACKED, P itself for the INT8 sibling); a power of two, so the rescaled
         // weight scale is exact
-        const float swn = __uint_as_float(sw_raw[k]) * (PACKED ? 0.00390625f : W8 ? 1.0f : 0.0625f);
+        const float swn = __uint_as_float(sw_raw[k]) * (W8 ? 1.0f : PACKED ? 0.00390625f : 0.0625f);
         float y = ((float)s_sum[qq * 64 + lane] * s_S[trow]) * swn;
         if (a.bias) y = y + __half2float(__ushort_as_half(b_raw[k]));
         const uint32_t off = n_ok ? ((uint32_t)(m0 + trow) * (uint32_t)a.N + (uint32_t)n) * 2u : kPoison;   // rows >= M fall off the end
@@ -311,7 +312,7 @@ static int launch_small(SmallArgs &a, hipStream_t st) {
     a.tiles_n = (a.N + 32 * FN - 1) / (32 * FN);
     const long tiles = (long)((a.M + TM - 1) / TM) * a.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const size_t lds = TM * (size_t)((PACKED ? a.K / 2 : a.K) + 16) + (WLDS ? 32 * FN * (size_t)((W8 ? a.K : a.K / 2) + 16) : 0) +
+    const size_t lds = TM * (size_t)((PACKED && !W8 ? a.K / 2 : a.K) + 16) + (WLDS ? 32 * FN * (size_t)((W8 ? a.K : a.K / 2) + 16) : 0) +
                        (size_t)(TM / 2) * FN * 64 * 4 + TM * 4;
     auto kern = linear_f16act_kernel<NW, FN, TM, WLDS, PACKED, W8>;
     static KernelState ks;
@@ -330,7 +331,7 @@ static int small_dispatch(SmallArgs &a, hipStream_t st) {
     const int M = a.M, N = a.N, K = a.K;
     const long t32 = (long)((M + 31) / 32) * ((N + 31) / 32);
     const bool wide = t32 > 256, low = t32 <= 128;
-    const size_t code_b = (size_t)(low ? 16 : 32) * ((PACKED ? K / 2 : K) + 16), wt_b = (size_t)(wide ? 64 : 32) * ((W8 ? K : K / 2) + 16);
+    const size_t code_b = (size_t)(low ? 16 : 32) * ((PACKED && !W8 ? K / 2 : K) + 16), wt_b = (size_t)(wide ? 64 : 32) * ((W8 ? K : K / 2) + 16);
     const int nw = K > 1536 ? 16 : K > 384 ? 8 : 4;
     const long wchunks = ((long)(wide ? 64 : 32) * (K / (W8 ? 16 : 32)) + nw * 64 - 1) / (nw * 64);   // per lane
     const bool wlds = code_b + wt_b <= 144 * 1024 && wchunks <= small_wchunks(nw);   // beside the sums, within a CU's 160 KB
@@ -362,6 +363,24 @@ int launch_small_packed(int out_kind, GemmArgs &g, hipStream_t st) {
     else a.out = static_cast<__half *>(g.out);
     a.M = g.M; a.N = g.N; a.K = g.K;
     return small_dispatch<true>(a, st);
+}
+
+// The INT8 sibling's small-problem path on int8 codes that are already in memory (w8a8_linear / w8a8_gemm_i32
+// for at most 512 tiles of 32 x 32).  g.lda / g.ldw are row strides in bytes = codes.
+bool small8_ok(const GemmArgs &g) {
+    return g.K % 64 == 0 && g.K <= 4096 && g.lda % 16 == 0 && (long)((g.M + 31) / 32) * ((g.N + 31) / 32) <= 512 &&
+           (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL && ((long)g.M + 32) * g.N * 4 < 0x7fffffffL;
+}
+int launch_small_packed8(int out_kind, GemmArgs &g, hipStream_t st) {
+    if ((out_kind != OUT_F16 && out_kind != OUT_I32) || !small8_ok(g)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    SmallArgs a{};
+    a.Aq = g.Aq; a.lda = g.lda; a.sa = g.sa;
+    a.Wq = g.Wq; a.ldw = g.ldw; a.sw = g.sw;
+    a.bias = g.bias; a.act = g.act;
+    if (out_kind == OUT_I32) a.acc_out = static_cast<int32_t *>(g.out);
+    else a.out = static_cast<__half *>(g.out);
+    a.M = g.M; a.N = g.N; a.K = g.K;
+    return small_dispatch<true, true>(a, st);
 }
 
 }  // namespace w4a4

@@ -317,8 +317,13 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     return launch_status();
 }
 
+bool small8_ok(const GemmArgs &g);                              // gemm_small.hip: the split-K kernel for small problems
+int launch_small_packed8(int out_kind, GemmArgs &g, hipStream_t st);
+
 // Tile choice as for the INT4 kernel: the largest number of tiles any CU ends up with times the tile area.
+// A few hundred 32 x 32 tiles at most go to the small-problem kernel instead (latency decides there).
 static int launch_w8(int out_kind, GemmArgs &g, hipStream_t st) {
+    if (small8_ok(g)) return launch_small_packed8(out_kind, g, st);
     const long cus = 256;
     auto cost = [&](int bm, int bn) {
         const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);

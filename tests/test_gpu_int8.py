@@ -116,3 +116,20 @@ def test_one_kernel_linear_reads_strided_rows(B, orc):
     got = B.linear8_f16act(Xd[:, K:2 * K], Wq, sw)
     want = orc.linear8(orc.quantize_rows8(np.ascontiguousarray(X[:, K:2 * K])), orc.quantize_rows8(np.ascontiguousarray(W[:, :K])))["out"]
     assert np.array_equal(host(got).view(np.uint16), want.view(np.uint16))
+
+
+def test_small_problem_path_reads_a_column_slice_of_codes(B, orc):
+    """w8a8_linear / w8a8_gemm_i32 on a few tiles go to the split-K kernel; the codes may sit in a wider matrix."""
+    rng = np.random.default_rng(78)
+    M, N, K = 100, 72, 256
+    A = rng.integers(-127, 128, size=(M, 3 * K), dtype=np.int8)
+    W = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
+    sa = (rng.random(M) * 0.01 + 0.001).astype(np.float32)
+    sw = (rng.random(N) * 0.01 + 0.001).astype(np.float32)
+    Ad = dev(A)
+    view = Ad[:, K:2 * K]
+    P = host(B.gemm8_i32(view, dev(sa), dev(W), dev(sw)))
+    assert np.array_equal(P, orc.gemm8_i32(np.ascontiguousarray(A[:, K:2 * K]), W))
+    got = host(B.linear8(view, dev(sa), dev(W), dev(sw)))
+    want = orc.linear8(dict(q=np.ascontiguousarray(A[:, K:2 * K]), s=sa), dict(q=W, s=sw))["out"]
+    assert np.array_equal(got.view(np.uint16), want.view(np.uint16))
