@@ -359,3 +359,24 @@ def test_grouped_kernel_many_tiles(B, orc, mode, group, K):
     # the shape table picks this kernel for large grouped layers: same result without naming it
     auto = host(B.linear(A, Q, dev(bias), 0))[rows]
     assert np.array_equal(auto, host(B.linear(A, Q, dev(bias), 0, schedule=sch))[rows])
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("M,K,ldx", [(8193, 32, 32), (8192, 160, 192), (9001, 1024, 1024), (8195, 2048, 2056), (8200, 992, 1000)])
+def test_quantize_act_many_short_rows(B, orc, layout, M, K, ldx):
+    """Thousands of short symmetric rows (more waves than the chip holds at once): odd row counts, ragged chunk
+    counts and strided rows, in both layouts; the whole matrix against the oracle."""
+    from tests.gpu_util import act_to_canonical
+    rng = np.random.default_rng(M + K)
+    Xw = (rng.standard_normal((M, ldx)) * rng.uniform(0.1, 4.0, size=(M, 1))).astype(np.float32).astype(np.float16)
+    Xw[5, :] = 0                                              # an all-zero token
+    Xw[M - 1, :K] = np.float16(65504.0)                       # the last row, at the top of the fp16 range
+    Xd = dev(Xw)
+    A = B.quantize_act(Xd[:, :K], SYM, layout=layout)
+    want = orc.quantize_act(np.ascontiguousarray(Xw[:, :K]), SYM)
+    q = host(A.q)
+    assert np.array_equal(act_to_canonical(q) if layout == 1 else q, want["q"])
+    assert np.array_equal(host(A.scale).view(np.uint32), want["s"].view(np.uint32))
+    if layout == 1:
+        odd = orc.unpack(want["q"], 0).astype(np.int64)[:, 1::2].sum(axis=1)
+        assert np.array_equal(host(A.osum).astype(np.int64), odd)
