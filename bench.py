@@ -141,7 +141,7 @@ def bench_chain(args):
     for k in range(steps):
         step(k, timers[k])
     torch.cuda.synchronize()
-    assert B.fused_fault(ws, (M + M // 128 + 4) * 4) == 0
+    assert B.fused_fault_check() is False                       # no workgroup of a fused requantize gave up waiting
     ms = dt * 1e3 / steps
     shapes = [(3 * h, h), (h, h), (ffn, h), (h, ffn)]
     ops = sum(2 * M * n * k for n, k in shapes)

@@ -285,17 +285,36 @@ int w4a4_preferred_layout(int M, int N, int K, int mode, int group);
  * epilogue (0 when none is needed; M*N*4 for a requantizing epilogue). */
 size_t w4a4_workspace_bytes(int M, int N, int K, const w4a4_epilogue *ep);
 
-/* Bytes of workspace w4a4_linear needs for exactly this layer.  A symmetric, per-channel
- * layer with K % 128 == 0 that requantizes to symmetric codes without code sums
- * (want_gsum == 0) runs fused in one kernel and needs only (M + M/128 + 4) words: the
+/* Bytes of workspace w4a4_linear needs for exactly this layer on the current device.  A symmetric,
+ * per-channel layer with K % 128 == 0 that requantizes to symmetric codes without code sums
+ * (want_gsum == 0) runs fused in one kernel and needs only (M + ceil(M/128) + 4) 32-bit words: the
  * column tiles of a row panel exchange per-token maxima through it (Sec. 4.2: quantize
- * fused behind bias-add / GELU).  Every other requantizing layer needs M*N*4 bytes: the
- * GEMM leaves fp32 rows there and a second kernel packs them.  After the stream has been
- * synchronized the LAST 32-bit word of a fused layer's workspace is non-zero if a workgroup
- * gave up waiting for its siblings (outputs are then invalid; this does not happen when a
- * row panel's tiles are co-resident, which the library's tile order ensures). */
+ * fused behind bias-add / GELU).  The fused kernel's workgroups wait for each other, so it is only
+ * taken when the runtime's occupancy figure for it on this device says that the tiles which wait
+ * for each other are resident together; every other requantizing layer needs M*N*4 bytes: the
+ * GEMM leaves fp32 rows there and a second kernel packs them.
+ * Failure mode of the fused kernel: a workgroup polls a bounded number of times for its siblings
+ * (about a second); if they do not arrive (for instance because kernels of OTHER streams occupy the
+ * device's workgroup slots, which the occupancy figure cannot know) it sets the LAST 32-bit word of
+ * this workspace and the device-wide flag behind w4a4_fused_fault_check to non-zero and finishes
+ * with invalid codes.  Read either one after the stream has been synchronized. */
 size_t w4a4_linear_workspace_bytes(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
                                    int want_gsum);
+
+/* Waits for `stream`, then returns 1 if any fused-requantize kernel on the current device has given
+ * up waiting for its sibling tiles since the last check (and clears the flag), 0 if none has, or a
+ * w4a4_status < 0.  This is how callers of w4a4_ffn and w4a4_encoder_layer, whose inner w4a4_linear
+ * workspaces are carved by the library, learn of that failure; the outputs of such a call are invalid.
+ * Synchronizes; not for capture in a graph. */
+int w4a4_fused_fault_check(void *stream);
+
+/* Test hook for that failure path (no passage of the paper).  Fused-requantize kernels launched by the
+ * calling thread from now on poll at most spin_limit times (0 = the default bound) and wait for
+ * extra_arrivals more sibling tiles than a row panel has (0 = none).  With extra_arrivals > 0 every
+ * workgroup gives up after spin_limit polls, raises the fault words and exits normally, so the failure
+ * path can be exercised without a hang.  (0, 0) restores the defaults.  Returns W4A4_OK, or
+ * W4A4_ERR_INVALID_ARG for a negative argument. */
+int w4a4_debug_fused_wait(int spin_limit, int extra_arrivals);
 
 /* Step a0 (offline): App. A weight quantization of W_f16[N,K] with the Sec. 3.1 mapping.
  * Outputs: q[N,K/2], scale[N,ng], zero[N,ng] (ASYM; may be NULL for SYM),
@@ -359,13 +378,21 @@ int w4a4_layernorm_quantize(const void *X_f16, const void *R_f16, int M, int K, 
 int w4a4_linear_f16act(const void *X_f16, int M, int K, int ldx, const w4a4_weight *W,
                        const w4a4_epilogue *ep, void *out, void *stream);
 
-/* Step a2 alone (parity / debugging export): acc[ng, M, N] int32, one plane per
- * weight K-group (ng == 1 for per-channel weights). */
+/* Step a2 alone, the INT4 x INT4 -> INT32 GEMM of Sec. 4.1 (activations [M,K] times weights [N,K]
+ * transposed, the four encoder shapes) before the dequantize of Sec. 4.2 is applied: the parity /
+ * debugging export.  acc[ng, M, N] int32 (device, 16-byte aligned), one plane per weight K-group
+ * (App. A groups; ng == 1 for per-channel weights): acc[g,m,n] = sum over the codes k of group g of
+ * qa[m,k] * qw[n,k], exact.  Operand rules as for w4a4_linear; schedule as in w4a4_epilogue.
+ * Argument errors return before anything is launched. */
 int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream);
 
-/* Step a3 alone: the same epilogue applied to int32 accumulators acc[ng, M, N] that
- * are already in memory.  Outputs as for w4a4_linear (requantized codes in the canonical
- * layout only).  Needs no workspace. */
+/* Step a3 alone, the dequantize of Sec. 4.2 (per-token and per-channel / per-group scales of
+ * Sec. 3.1 and App. A, the zero-point terms that Sec. 4.3 calls the extra bias-term work of the
+ * asymmetric mapping, bias, GELU, then the fp16 store or the next layer's token-wise quantize)
+ * applied to int32 accumulators acc[ng, M, N] that are already in device memory (the layout
+ * w4a4_gemm_i32 writes).  A and W supply scales, zero points and code sums; their code pointers
+ * are not read.  Outputs as for w4a4_linear (requantized codes in the canonical layout only).
+ * Needs no workspace.  Argument errors return before anything is launched. */
 int w4a4_dequant_epilogue(const int32_t *acc, const w4a4_act *A, const w4a4_weight *W,
                           const w4a4_epilogue *ep, void *out, float *out_scale, float *out_zero,
                           int32_t *out_gsum, void *stream);

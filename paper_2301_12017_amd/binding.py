@@ -95,6 +95,8 @@ _SIGNATURES = {
     "w4a4_attention_f16": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "w4a4_encoder_layer_workspace_bytes": (_sz, [_i, _i, ctypes.POINTER(_LayerWeights)]),
     "w4a4_encoder_layer": (_i, [_vp, _i, _i, ctypes.POINTER(_LayerWeights), _i, _vp, _vp, _sz, _vp]),
+    "w4a4_fused_fault_check": (_i, [_vp]),
+    "w4a4_debug_fused_wait": (_i, [_i, _i]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
     "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
                                    ctypes.POINTER(_Epilogue), _vp, _vp, _vp, _vp, _vp]),
@@ -174,6 +176,23 @@ def status_string(status: int) -> str:
 def schedule_names():
     L = lib()
     return [L.w4a4_schedule_name(i + 1).decode() for i in range(L.w4a4_schedule_count())]
+
+
+def schedule_number(name: str) -> int:
+    """1-based number of the schedule called `name` (what w4a4_epilogue.schedule takes)."""
+    return schedule_names().index(name) + 1
+
+
+def fused_fault_check() -> bool:
+    """w4a4_fused_fault_check on the current stream: True if a fused requantize gave up since the last check."""
+    rc = lib().w4a4_fused_fault_check(_stream())
+    if rc < 0:
+        raise W4A4Error(rc, "w4a4_fused_fault_check")
+    return bool(rc)
+
+
+def debug_fused_wait(spin_limit: int = 0, extra_arrivals: int = 0):
+    _check(lib().w4a4_debug_fused_wait(spin_limit, extra_arrivals), "w4a4_debug_fused_wait")
 
 
 def preferred_layout(M: int, N: int, K: int, mode=SYM, group=0) -> int:
@@ -343,7 +362,8 @@ def linear_workspace_bytes(A: "QAct", W: "QWeight", requant=True, requant_mode=S
 
 
 def fused_fault(workspace: torch.Tensor, nbytes: int) -> int:
-    """Last word of a fused requantize workspace (0 = the row-maximum exchange completed)."""
+    """Last word of a fused requantize workspace of `nbytes` bytes, the size w4a4_linear_workspace_bytes gave
+    for the layer (0 = the row-maximum exchange completed)."""
     return int(workspace[:nbytes].view(torch.int32)[-1].item())
 
 

@@ -181,6 +181,7 @@ constexpr int kMaxDevices = 16;
 struct KernelState {
     std::atomic<size_t> lds[kMaxDevices] = {};
     std::atomic<int> cus[kMaxDevices] = {};
+    std::atomic<int> occ[kMaxDevices] = {};                        // workgroups of this kernel a CU holds at once (0 = not asked yet)
     std::mutex grow;
 };
 // Lets `kern` use `lds` bytes of dynamic LDS on the current device.  Returns that device's CU count, or -1.
@@ -200,6 +201,21 @@ inline int prepare_kernel(const void *kern, size_t lds, KernelState &ks) {
         ks.cus[dev].store(cus, std::memory_order_relaxed);
     }
     return cus;
+}
+
+// Workgroups of `kern` (block size `threads`, `lds` bytes of dynamic LDS) that the runtime says one CU holds at
+// once on the current device; asked once per kernel and device.  Kernels whose workgroups wait for each other
+// size their grid from this figure, never from the attributes they were compiled with.  Returns -1 on error.
+inline int resident_per_cu(const void *kern, int threads, size_t lds, KernelState &ks) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+    int occ = ks.occ[dev].load(std::memory_order_relaxed);
+    if (!occ) {
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, kern, threads, lds) != hipSuccess || occ < 0) return -1;
+        if (occ == 0) return 0;                                    // does not fit at all: nothing to remember
+        ks.occ[dev].store(occ, std::memory_order_relaxed);
+    }
+    return occ;
 }
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }

@@ -5,50 +5,44 @@
 namespace w4a4 {
 
 // Schedules (Sec. 4.2: the GEMM schedule is chosen per shape ahead of time).  A schedule
-// names a kernel family and a tile variant of it.
+// names a kernel family and a tile variant of it.  Every schedule is picked by the built-in
+// shape tables below for some shape; forcing one (w4a4_epilogue.schedule) is for measurements
+// and parity tests.
+enum Family {
+    F_PIPE,      // pipelined kernel on canonical codes (symmetric, per-channel, K % 128 == 0): many tokens whose
+                 // operands were left in the canonical layout
+    F_GENERIC,   // any mode / grouping / K % 32: small and odd shapes
+    F_OLAY,      // persistent kernel on operands in the MFMA operand layout
+    F_GROUP,     // persistent kernel for K-grouped / asymmetric layers
+    F_SMALL      // small-problem kernel: the waves of a workgroup split K (symmetric per-channel, K % 64 == 0)
+};
 struct Schedule {
     const char *name;
-    int family;          // 0 = pipelined kernel, codes widened per wave (symmetric, per-channel, K % 128 == 0),
-                         // 1 = generic, 2 = pipelined kernel, codes widened once into LDS (K % 64 == 0),
-                         // 3 = pipelined kernel with direct global->LDS loads (K % 128 == 0),
-                         // 4 = persistent kernel on operands in the MFMA operand layout,
-                         // 5 = persistent kernel for K-grouped / asymmetric layers,
-                         // 6 = small-problem kernel: the waves of a workgroup split K (symmetric per-channel, K % 64 == 0)
+    int family;
     int variant;
     bool grouped_ok;     // usable for K-grouped / asymmetric layers
 };
 // index = schedule number - 1
 static const Schedule kSchedules[] = {
-    {"pipe_128x256", 0, 0, false},
-    {"pipe_256x256", 0, 1, false},
-    {"generic_128x256", 1, 1, true},
-    {"generic_256x256", 1, 0, false},
-    {"generic_64x128", 1, 2, true},
-    {"generic_64x64", 1, 3, true},
-    {"generic_32x32", 1, 4, true},
-    {"pipe_192x128", 0, 2, false},
-    {"pipe_192x256", 0, 3, false},
-    {"pipe8_128x256", 2, 0, false},
-    {"pipe8_256x256", 2, 1, false},
-    {"dma_128x256", 3, 0, false},
-    {"dma_256x256", 3, 1, false},
-    {"olay_128x256", 4, 0, false},
-    {"olay_192x128", 4, 1, false},
-    {"group_128x128", 5, 0, true},
-    {"small_splitk", 6, 0, false},
-    {"olay_128x128", 4, 2, false},
+    {"pipe_128x256", F_PIPE, 0, false},
+    {"pipe_192x128", F_PIPE, 1, false},
+    {"generic_64x128", F_GENERIC, 0, true},
+    {"generic_64x64", F_GENERIC, 1, true},
+    {"generic_32x32", F_GENERIC, 2, true},
+    {"olay_128x256", F_OLAY, 0, false},
+    {"olay_192x128", F_OLAY, 1, false},
+    {"olay_128x128", F_OLAY, 2, false},
+    {"group_128x128", F_GROUP, 0, true},
+    {"small_splitk", F_SMALL, 0, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
+enum { S_PIPE_128x256 = 1, S_PIPE_192x128, S_GEN_64x128, S_GEN_64x64, S_GEN_32x32, S_OLAY_128x256, S_OLAY_192x128,
+       S_OLAY_128x128, S_GROUP, S_SMALL };
 
 static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
     // 32-bit buffer offsets and whole K steps
     return !grouped && g.K % kstep == 0 && (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL;
 }
-
-constexpr int kOlaySchedule = 14;                             // olay_128x256; +1 = olay_192x128
-constexpr int kGroupSchedule = 16;                            // group_128x128
-constexpr int kSmallSchedule = 17;                            // small_splitk
-constexpr int kOlayMidSchedule = 18;                          // olay_128x128
 
 // The small-problem kernel: symmetric per-channel layers in the canonical layout, fp16 or int32 output.
 static bool small_ok(const GemmArgs &g, bool grouped, int out_kind) {
@@ -62,25 +56,38 @@ static bool group_ok(const GemmArgs &g, bool grouped) {
            (size_t)g.ng * 256 * 4 + 3 * 256 * 64 + 2048 <= 80 * 1024;
 }
 
-// Built-in shape table: large problems take the pipelined tiles (192 x 128 when the output is
-// narrow, so that a 12288-token problem splits into a whole number of rounds of two
+// Built-in shape table of the canonical layout: large problems take the pipelined tiles (192 x 128 when the
+// output is narrow, so that a 12288-token problem splits into a whole number of rounds of two
 // workgroups per CU; 128 x 256 otherwise), small ones the generic tiles that still give every
 // CU something to do.
 static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
     // a few hundred 32 x 32 tiles at most: latency decides, the waves of a workgroup split K
-    if ((long)((g.M + 31) / 32) * ((g.N + 31) / 32) <= 512 && small_ok(g, grouped, out_kind)) return kSmallSchedule;
+    if ((long)((g.M + 31) / 32) * ((g.N + 31) / 32) <= 512 && small_ok(g, grouped, out_kind)) return S_SMALL;
     const long big = (long)((g.M + 127) / 128) * ((g.N + 255) / 256);
     if (big >= 256) {
-        if (group_ok(g, grouped)) return kGroupSchedule;
-        if (!pipe_ok(g, grouped)) return 5;      // grouped layers: the 64 x 128 tile leaves LDS for the group tables
-        return g.N <= 1024 ? 8 : 1;
+        if (group_ok(g, grouped)) return S_GROUP;
+        if (!pipe_ok(g, grouped)) return S_GEN_64x128;   // grouped layers: the 64 x 128 tile leaves LDS for the group tables
+        return g.N <= 1024 ? S_PIPE_192x128 : S_PIPE_128x256;
     }
     const long mid = (long)((g.M + 63) / 64) * ((g.N + 127) / 128);
-    if (mid >= 256) return 5;
+    if (mid >= 256) return S_GEN_64x128;
     // 64 x 64 tiles beat 32 x 32 ones wherever there are a few dozen of them (measured at 384 .. 1536 tokens)
     const long small = (long)((g.M + 63) / 64) * ((g.N + 63) / 64);
-    if (small >= 64) return 6;
-    return 7;
+    if (small >= 64) return S_GEN_64x64;
+    return S_GEN_32x32;
+}
+
+// CU count of the current device (the tile choice of the persistent kernel depends on it); 256 if it cannot be read.
+static int device_cus() {
+    static std::atomic<int> cached[kMaxDevices] = {};
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 256;
+    cus = cached[dev].load(std::memory_order_relaxed);
+    if (!cus) {
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return 256;
+        cached[dev].store(cus, std::memory_order_relaxed);
+    }
+    return cus;
 }
 
 // Tile choice of the persistent kernel.  What counts is the CU that ends up with the most tiles: n tiles
@@ -91,7 +98,7 @@ static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
 // 128 x 128 tile 6 % cheaper in the mid range, where it also leaves fewer CUs idle.  Below about 1500
 // tokens a tile's K loop is latency-bound and the small tile gains nothing.
 static int pick_olay(const GemmArgs &g) {
-    const long cus = 256;
+    const long cus = device_cus();
     auto cost = [&](int bm, int bn, int occ, double eff) {
         const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
         const long n = (tiles + cus - 1) / cus;
@@ -99,48 +106,71 @@ static int pick_olay(const GemmArgs &g) {
         const double rate = together == 1 ? 0.5 : together == 2 ? 1.0 : 0.85;
         return (double)n * bm * bn / (rate * eff);
     };
-    int best = kOlaySchedule;
+    int best = S_OLAY_128x256;
     double c = cost(128, 256, 2, 1.0);
     const double c192 = cost(192, 128, 2, 0.92);
-    if (c192 < c) { best = kOlaySchedule + 1; c = c192; }
-    if (g.M >= 1536 && cost(128, 128, 3, 1.06) < c) best = kOlayMidSchedule;
+    if (c192 < c) { best = S_OLAY_192x128; c = c192; }
+    if (g.M >= 1536 && cost(128, 128, 3, 1.06) < c) best = S_OLAY_128x128;
     return best;
 }
 
-static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int schedule, hipStream_t st) {
+// Resolves schedule 0 to the table's choice and checks everything a launcher of that family requires, so that
+// a caller can still refuse the call with its outputs untouched.  Nothing is launched here.
+static int resolve_schedule(const GemmArgs &g, bool grouped, int out_kind, int *schedule) {
     // the epilogue addresses the output with 32-bit byte offsets below 2^31
     if (((long)g.M + 512) * g.N * 4 >= 0x80000000L) return W4A4_ERR_UNSUPPORTED_SHAPE;   // (tile overhang included)
     const bool olay = g.osum != nullptr;                        // operands in the MFMA operand layout
-    if (schedule == 0) schedule = olay ? pick_olay(g) : pick_schedule(g, grouped, out_kind);
-    if (schedule < 1 || schedule > kNumSchedules) return W4A4_ERR_INVALID_ARG;
-    const Schedule &s = kSchedules[schedule - 1];
+    int sch = *schedule;
+    if (sch == 0) sch = olay ? pick_olay(g) : pick_schedule(g, grouped, out_kind);
+    if (sch < 1 || sch > kNumSchedules) return W4A4_ERR_INVALID_ARG;
+    const Schedule &s = kSchedules[sch - 1];
     if (grouped && !s.grouped_ok) return W4A4_ERR_INVALID_ARG;
-    if (olay != (s.family == 4)) return W4A4_ERR_INVALID_ARG;   // a kernel family understands one layout
-    if (s.family == 4) {
-        if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        return launch_olay(s.variant, out_kind, g, st);
+    if (olay != (s.family == F_OLAY)) return W4A4_ERR_INVALID_ARG;   // a kernel family understands one layout
+    const bool q4 = out_kind == OUT_Q4 || out_kind == OUT_Q4M;
+    switch (s.family) {
+        case F_OLAY:
+            if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            if (q4) {
+                if (s.variant != 0) return W4A4_ERR_INVALID_ARG;
+                const int lim = olay_requant_max_tiles_n(out_kind == OUT_Q4M);
+                if (lim < 0) return W4A4_ERR_HIP;
+                if ((g.N + 255) / 256 > lim) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            }
+            break;
+        case F_SMALL:
+            if (!small_ok(g, grouped, out_kind)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            break;
+        case F_GROUP:
+            if (!group_ok(g, grouped) || q4) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            break;
+        case F_PIPE:
+            if (!pipe_ok(g, grouped) || out_kind == OUT_Q4M) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            if (out_kind == OUT_Q4) {
+                if (s.variant != 0) return W4A4_ERR_INVALID_ARG;
+                const int lim = pipe_requant_max_tiles();
+                if (lim < 0) return W4A4_ERR_HIP;
+                if ((long)((g.M + 127) / 128) * ((g.N + 255) / 256) > lim) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            }
+            break;
+        default:
+            if (q4) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            break;
     }
-    if (s.family == 6) {
-        if (!small_ok(g, grouped, out_kind)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        return launch_small_packed(out_kind, g, st);
+    *schedule = sch;
+    return W4A4_OK;
+}
+
+static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int schedule, hipStream_t st) {
+    const int rc = resolve_schedule(g, grouped, out_kind, &schedule);
+    if (rc) return rc;
+    const Schedule &s = kSchedules[schedule - 1];
+    switch (s.family) {
+        case F_OLAY: return launch_olay(s.variant, out_kind, g, st);
+        case F_SMALL: return launch_small_packed(out_kind, g, st);
+        case F_GROUP: return launch_group(mode, out_kind, g, st);
+        case F_PIPE: return launch_pipe(s.variant, out_kind, g, st);
+        default: return launch_generic(s.variant, mode, grouped, out_kind, g, st);
     }
-    if (s.family == 5) {
-        if (!group_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        return launch_group(mode, out_kind, g, st);
-    }
-    if (s.family == 0) {
-        if (!pipe_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        return launch_pipe(s.variant, out_kind, g, st);
-    }
-    if (s.family == 3) {
-        if (!pipe_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        return launch_dma(s.variant, out_kind, g, st);
-    }
-    if (s.family == 2) {
-        if (!pipe_ok(g, grouped, 64)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        return launch_pipe8(s.variant, out_kind, g, st);
-    }
-    return launch_generic(s.variant, mode, grouped, out_kind, g, st);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -215,7 +245,8 @@ static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int 
     g.sw = W->scale; g.zw = W->zero; g.c = W->rowsum_deq;
     g.bias = nullptr; g.act = W4A4_ACT_NONE; g.out = nullptr;
     g.tiles_m = g.tiles_n = 0;
-    g.rowmax = nullptr; g.arrived = nullptr; g.fault = nullptr; g.out_scale = nullptr;
+    g.rowmax = nullptr; g.arrived = nullptr; g.fault = nullptr; g.fault_sticky = nullptr; g.out_scale = nullptr;
+    g.spin_limit = 0; g.wait_for = 0;
     const bool olay = A->layout == W4A4_LAYOUT_MFMA;
     g.osum = olay ? A->osum : nullptr; g.ldo = olay ? A->ldo : 0; g.esum = olay ? W->esum : nullptr;
     g.out_osum = nullptr; g.osum_slices = 1; g.slice_tiles = 0;
@@ -241,28 +272,33 @@ extern "C" const char *w4a4_schedule_name(int schedule) {
 
 // Fused requantize (one kernel: the column tiles of a row panel exchange per-token maxima and pack
 // the codes from registers).  Two kernels can do it:
-//   1 = the pipelined kernel on canonical operands, canonical symmetric codes out, no code sums;
+//   1 = the pipelined kernel on canonical operands, canonical symmetric codes out, no code sums; its whole
+//       grid must be resident, which limits it to a few hundred tiles;
 //   2 = the persistent kernel on operands in the MFMA operand layout; symmetric codes out in either
 //       layout (the operand layout with odd-position sums per column slice of requant_group, which
-//       must be whole 256-column tiles).
+//       must be whole 256-column tiles); the column tiles of a panel must fit one XCD's resident share.
 // 0 = not fusable: the GEMM stores fp32 rows and the row quantizer packs them.
+// The residency limits come from the runtime's occupancy figure for the kernel on the current device.
 static int fused_requant_kind(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
     if (!ep->requant || ep->requant_mode != W4A4_SYM) return 0;
     if (A->mode != W4A4_SYM || (W->group != 0 && W->group != W->K)) return 0;
     if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return 0;
+    if (((long)A->M + 512) * W->N * 4 >= 0x80000000L) return 0;
     const int tn = (W->N + 255) / 256;
     if (A->layout == W4A4_LAYOUT_MFMA) {
-        if (ep->schedule != 0 && ep->schedule != kOlaySchedule) return 0;
-        if (tn > 32 || A->K < 2 * kBK) return 0;
-        if (ep->requant_layout == W4A4_LAYOUT_MFMA) {
+        if (ep->schedule != 0 && ep->schedule != S_OLAY_128x256) return 0;
+        if (A->K < 2 * kBK || (long)A->M * A->ldo * 4 >= 0x7fffffffL) return 0;
+        const bool mfma_out = ep->requant_layout == W4A4_LAYOUT_MFMA;
+        if (tn > olay_requant_max_tiles_n(mfma_out)) return 0;
+        if (mfma_out) {
             const int rg = ep->requant_group == 0 ? W->N : ep->requant_group;
             return (rg % 256 == 0 || rg == W->N) && W->N % rg == 0 && (rg == W->N || W->N % 256 == 0) ? 2 : 0;
         }
         return want_gsum ? 0 : 2;
     }
     if (ep->requant_layout != W4A4_LAYOUT_CANONICAL || want_gsum) return 0;
-    if (ep->schedule != 0 && ep->schedule != 1) return 0;
-    return tn <= 32 ? 1 : 0;
+    if (ep->schedule != 0 && ep->schedule != S_PIPE_128x256) return 0;
+    return (long)((A->M + 127) / 128) * tn <= pipe_requant_max_tiles() ? 1 : 0;
 }
 static size_t fused_workspace_bytes(int M) {
     return ((size_t)M + (size_t)(M + 127) / 128 + 4) * sizeof(uint32_t);
@@ -288,6 +324,51 @@ __global__ void zero_words_kernel(uint32_t *p, int n, uint32_t *p2, int n2) {
     else if (i - n < n2) p2[i - n] = 0;
 }
 
+// ---- the device-wide fault flag of the fused requantize ---------------------------------------------------
+// A workgroup that gives up waiting for its siblings sets the last word of that call's workspace AND this
+// flag, which callers that never see the workspace of an inner w4a4_linear (w4a4_ffn, w4a4_encoder_layer)
+// read through w4a4_fused_fault_check.  One copy per device; host code uses the address the runtime reports
+// for the current device, never the symbol's name.
+static __device__ int fused_fault_flag;
+static int *fault_flag_address() {
+    static std::atomic<int *> addr[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    int *p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(fused_fault_flag)) != hipSuccess || !p) return nullptr;
+        addr[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
+extern "C" int w4a4_fused_fault_check(void *stream) {
+    int *flag = fault_flag_address();
+    if (!flag) return W4A4_ERR_HIP;
+    hipStream_t st = as_stream(stream);
+    int host = 0;
+    if (hipMemcpyAsync(&host, flag, sizeof(int), hipMemcpyDeviceToHost, st) != hipSuccess) return W4A4_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return W4A4_ERR_HIP;
+    if (host) {
+        hipLaunchKernelGGL(zero_words_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<uint32_t *>(flag), 1, nullptr, 0);
+        if (hipStreamSynchronize(st) != hipSuccess) return W4A4_ERR_HIP;
+    }
+    return host ? 1 : 0;
+}
+
+// Test hook: the fused requantize kernels launched by this thread from now on poll at most `spin_limit` times
+// and wait for `extra_arrivals` more column tiles than a row panel has.  (0, 0) restores the defaults.  With
+// extra_arrivals > 0 no panel ever completes, so every workgroup gives up after spin_limit polls, raises the
+// fault words and exits normally: the way to exercise the give-up path without a hang.
+static thread_local int tl_spin_limit = 0, tl_extra_arrivals = 0;
+extern "C" int w4a4_debug_fused_wait(int spin_limit, int extra_arrivals) {
+    if (spin_limit < 0 || extra_arrivals < 0) return W4A4_ERR_INVALID_ARG;
+    tl_spin_limit = spin_limit;
+    tl_extra_arrivals = extra_arrivals;
+    return W4A4_OK;
+}
+constexpr int kSpinLimit = 1 << 22;
+
 extern "C" int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream) {
     int ng = 0;
     int rc = check_operands(A, W, &ng);
@@ -302,16 +383,12 @@ extern "C" int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *a
     return run_gemm(g, A->mode, grouped, OUT_I32, schedule, as_stream(stream));
 }
 
-extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, void *out,
-                           float *out_scale, float *out_zero, int32_t *out_gsum, void *workspace,
-                           size_t workspace_bytes, void *stream) {
-    int ng = 0, rng = 0;
-    int rc = check_layer(A, W, ep, out, out_scale, out_zero, &ng, &rng);
-    if (rc) return rc;
-    if (A->M == 0) return W4A4_OK;
-    const size_t need = w4a4_linear_workspace_bytes(A, W, ep, out_gsum != nullptr);
-    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return W4A4_ERR_WORKSPACE;
-    hipStream_t st = as_stream(stream);
+// w4a4_linear behind its argument checks.  `exchange` is the area the fused requantize exchanges row maxima
+// through (fused_workspace_bytes(M) bytes, cleared here by a fill kernel); `rows_f32` receives the fp32 rows
+// of a requantize that cannot be fused.  Whichever the layer does not need may be NULL.
+static int linear_impl(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, void *out, float *out_scale,
+                       float *out_zero, int32_t *out_gsum, int ng, int fused, uint32_t *exchange, void *rows_f32,
+                       hipStream_t st) {
     GemmArgs g;
     fill_args(g, A, W, ng);
     g.bias = static_cast<const __half *>(ep->bias_f16);
@@ -321,39 +398,59 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
         g.out = out;
         return run_gemm(g, A->mode, grouped, OUT_F16, ep->schedule, st);
     }
-    const int fused = fused_requant_kind(A, W, ep, out_gsum != nullptr);
     if (ep->requant_layout == W4A4_LAYOUT_MFMA) {
         if (!out_gsum) return W4A4_ERR_INVALID_ARG;            // receives the odd-position code sums
         if (!fused && ep->requant_group != 0 && ep->requant_group != W->N) return W4A4_ERR_UNSUPPORTED_SHAPE;
     }
     if (fused) {
-        // One kernel: the column tiles of a row panel exchange their row maxima through the
-        // workspace (zeroed here) and pack the codes from registers.
+        // One kernel: the column tiles of a row panel exchange their row maxima through the exchange area and
+        // pack the codes from registers.
         const int words = (int)(fused_workspace_bytes(A->M) / sizeof(uint32_t));
-        uint32_t *wsp = static_cast<uint32_t *>(workspace);
         const bool sums = fused == 2 && ep->requant_layout == W4A4_LAYOUT_MFMA;
         const int rg = ep->requant_group == 0 ? W->N : ep->requant_group;
         const int slices = sums ? W->N / rg : 1;
         const long n2 = sums ? (long)A->M * slices : 0;
         if (n2 + words > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + n2 + 255) / 256)), dim3(256), 0, st, wsp, words,
-                           reinterpret_cast<uint32_t *>(out_gsum), (int)n2);
-        g.rowmax = wsp;
-        g.arrived = reinterpret_cast<int *>(wsp + A->M);
-        g.fault = reinterpret_cast<int *>(wsp + words - 1);
+        g.rowmax = exchange;
+        g.arrived = reinterpret_cast<int *>(exchange + A->M);
+        g.fault = reinterpret_cast<int *>(exchange + words - 1);
+        g.fault_sticky = fault_flag_address();
+        if (!g.fault_sticky) return W4A4_ERR_HIP;
+        g.spin_limit = tl_spin_limit > 0 ? tl_spin_limit : kSpinLimit;
+        g.wait_for = tl_extra_arrivals > 0 ? (W->N + 255) / 256 + tl_extra_arrivals : 0;   // 0: the launcher fills in tiles_n
         g.out_scale = out_scale;
         g.out = out;
         g.out_osum = out_gsum; g.osum_slices = slices; g.slice_tiles = sums && slices > 1 ? rg / 256 : 0x40000000;
-        if (fused == 1) return run_gemm(g, A->mode, false, OUT_Q4, 1, st);
-        return run_gemm(g, A->mode, false, sums ? OUT_Q4M : OUT_Q4, kOlaySchedule, st);
+        const int out_kind = fused == 1 ? OUT_Q4 : (sums ? OUT_Q4M : OUT_Q4);
+        int schedule = fused == 1 ? S_PIPE_128x256 : S_OLAY_128x256;
+        // everything that can refuse the launch is checked before the outputs are touched
+        const int rc = resolve_schedule(g, false, out_kind, &schedule);
+        if (rc) return rc;
+        hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + n2 + 255) / 256)), dim3(256), 0, st, exchange, words,
+                           reinterpret_cast<uint32_t *>(out_gsum), (int)n2);
+        return run_gemm(g, A->mode, false, out_kind, schedule, st);
     }
     // Requantize: the per-token range needs the whole output row, which no single tile
     // sees.  The GEMM leaves the fp32 rows in the workspace and the row quantizer turns
     // them into packed codes.
-    g.out = workspace;
-    rc = run_gemm(g, A->mode, grouped, OUT_F32, ep->schedule, st);
+    g.out = rows_f32;
+    const int rc = run_gemm(g, A->mode, grouped, OUT_F32, ep->schedule, st);
     if (rc) return rc;
-    return quantize_rows_f32(static_cast<const float *>(workspace), A->M, W->N, W->N, ep->requant_mode,
+    return quantize_rows_f32(static_cast<const float *>(rows_f32), A->M, W->N, W->N, ep->requant_mode,
                              ep->requant_group, static_cast<uint8_t *>(out), out_scale, out_zero, out_gsum, st,
                              ep->requant_layout);
+}
+
+extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, void *out,
+                           float *out_scale, float *out_zero, int32_t *out_gsum, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    int ng = 0, rng = 0;
+    int rc = check_layer(A, W, ep, out, out_scale, out_zero, &ng, &rng);
+    if (rc) return rc;
+    if (A->M == 0) return W4A4_OK;
+    const int fused = fused_requant_kind(A, W, ep, out_gsum != nullptr);
+    const size_t need = !ep->requant ? 0 : fused ? fused_workspace_bytes(A->M) : (size_t)A->M * (size_t)W->N * sizeof(float);
+    if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return W4A4_ERR_WORKSPACE;
+    return linear_impl(A, W, ep, out, out_scale, out_zero, out_gsum, ng, fused, static_cast<uint32_t *>(workspace),
+                       workspace, as_stream(stream));
 }

@@ -30,6 +30,9 @@ struct GemmArgs {
     uint32_t *rowmax;              // [M]       bit pattern of max |y| of the row, zeroed before the launch
     int *arrived;                  // [tiles_m] tiles of the row panel that have published their maxima
     int *fault;                    // [1]       set if a workgroup gave up waiting for its siblings
+    int *fault_sticky;             // [1]       the device-wide flag behind w4a4_fused_fault_check, set together with *fault
+    int spin_limit;                // polls of arrived[panel] before a workgroup gives up
+    int wait_for;                  // arrivals a workgroup waits for: tiles_n (a test hook may ask for more)
     float *out_scale;              // [M]
     // MFMA operand layout: code sums that the contraction picks up (see w4a4_layout)
     const int32_t *osum; long ldo; // [M * ldo]  odd-position code sums of the tokens
@@ -277,6 +280,32 @@ __device__ __forceinline__ void tile_epilogue(const GemmArgs &g, v16i (&acc)[FM]
 }
 
 
+// Bounded wait of the fused requantize: thread 0 of a workgroup announces the workgroup on arrived[panel] and
+// polls until g.wait_for column tiles of the row panel have done the same.  Only relaxed device-scope atomics
+// are used (they are performed at the coherence point and bypass the L1): a release / acquire FENCE at device
+// scope would write back and invalidate the whole L2 on every poll.  Ordering comes from waiting for this
+// wave's atomics to be acknowledged (vmcnt) before the workgroup barrier that precedes the counter increment.
+// The wait never hangs: after g.spin_limit polls the workgroup raises both fault words and carries on (its
+// codes are then invalid; the host learns of it from w4a4_fused_fault_check or the workspace word).
+__device__ __forceinline__ void panel_arrive_and_wait(const GemmArgs &g, int panel, int tid) {
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    if (tid == 0) {
+        __hip_atomic_fetch_add(g.arrived + panel, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0;
+        while (__hip_atomic_load(g.arrived + panel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.wait_for) {
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > g.spin_limit) {
+                *g.fault = 1;
+                *g.fault_sticky = 1;
+                break;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+
 // Fused per-token requantize of one wave's part of the tile (symmetric output codes, Sec. 4.2:
 // the next layer's quantize rides behind bias-add / GELU).  The range of a token needs the
 // whole output row, which is spread over the tiles_n workgroups of the row panel, so:
@@ -346,22 +375,8 @@ __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&
     reduce_scatter32(vmax, lane, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
     const int m_c = m0 + row_w + frag_row(c >> 4, c & 15, lane);  // the row this lane is responsible for
     if (m_c < g.M) atomicMax(g.rowmax + m_c, vmax[0]);
-    // 3. wait for the siblings of the row panel.  Only relaxed device-scope atomics are used
-    //    (they are performed at the coherence point and bypass the L1): a release / acquire
-    //    FENCE at device scope would write back and invalidate the whole L2 on every poll.
-    //    Ordering comes from waiting for this wave's atomics to be acknowledged (vmcnt) before
-    //    the workgroup barrier that precedes the counter increment.
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0) {
-        __hip_atomic_fetch_add(g.arrived + panel, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int spins = 0;
-        while (__hip_atomic_load(g.arrived + panel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.tiles_n) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins > (1 << 22)) { *g.fault = 1; break; }     // never hang: report and carry on
-        }
-    }
-    __syncthreads();
+    // 3. wait for the siblings of the row panel (bounded)
+    panel_arrive_and_wait(g, panel, tid);
     // 4. ranges
     {
         const __amdgpu_buffer_rsrc_t mx_rsrc = make_rsrc(g.rowmax, (uint32_t)g.M * 4u);
@@ -404,14 +419,15 @@ __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&
         }
 }
 
-// Launchers of the kernel families (defined in gemm_generic.hip / gemm_pipe.hip / gemm_pipe8.hip).
+// Launchers of the kernel families (each defined in the file of its kernel).
 // `variant` selects the tile shape; both return a w4a4_status.
 int launch_generic(int variant, int mode, bool grouped, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_pipe(int variant, int out_kind, GemmArgs &g, hipStream_t st);
-int launch_pipe8(int variant, int out_kind, GemmArgs &g, hipStream_t st);
-int launch_dma(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_olay(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_group(int mode, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_small_packed(int out_kind, GemmArgs &g, hipStream_t st);
+// Residency limits of the fused requantize on the current device (see the definitions)
+int olay_requant_max_tiles_n(bool mfma_out);
+int pipe_requant_max_tiles();
 
 }  // namespace w4a4

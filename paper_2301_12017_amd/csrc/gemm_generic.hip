@@ -217,20 +217,15 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
     return launch_status();
 }
 
-// variant: 0 = 256x256 (8 waves, ungrouped only), 1 = 128x256, 2 = 64x128, 3 = 64x64, 4 = 32x32
+// variant: 0 = 64x128, 1 = 64x64, 2 = 32x32
 template <int MODE, bool GROUPED, int OUT>
 static int launch_variant(int variant, GemmArgs &g, hipStream_t st) {
     switch (variant) {
-        case 1: return launch_one<2, 4, 2, 2, MODE, GROUPED, OUT>(g, st);
-        case 2: return launch_one<1, 2, 2, 2, MODE, GROUPED, OUT>(g, st);
-        case 3: return launch_one<1, 1, 2, 2, MODE, GROUPED, OUT>(g, st);
-        case 4: return launch_one<1, 1, 1, 1, MODE, GROUPED, OUT>(g, st);
-        default: break;
+        case 0: return launch_one<1, 2, 2, 2, MODE, GROUPED, OUT>(g, st);
+        case 1: return launch_one<1, 1, 2, 2, MODE, GROUPED, OUT>(g, st);
+        case 2: return launch_one<1, 1, 1, 1, MODE, GROUPED, OUT>(g, st);
+        default: return W4A4_ERR_INVALID_ARG;
     }
-    if constexpr (!GROUPED) {
-        if (variant == 0) return launch_one<2, 4, 4, 2, MODE, false, OUT>(g, st);
-    }
-    return W4A4_ERR_INVALID_ARG;
 }
 
 int launch_generic(int variant, int mode, bool grouped, int out_kind, GemmArgs &g, hipStream_t st) {

@@ -169,22 +169,8 @@ __device__ __forceinline__ void olay_epilogue_requant(const GemmArgs &g, v16i (&
     reduce_scatter32(vmax, lane, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
     const int m_c = m0 + row_w + frag_row(c >> 4, c & 15, lane);  // the row this lane is responsible for
     if (m_c < g.M) atomicMax(g.rowmax + m_c, vmax[0]);
-    // 3. wait for the siblings of the row panel.  Only relaxed device-scope atomics are used (they
-    //    are performed at the coherence point and bypass the L1): a release / acquire FENCE at
-    //    device scope would write back and invalidate the whole L2 on every poll.  Ordering comes
-    //    from waiting for this wave's atomics to be acknowledged (vmcnt) before the workgroup
-    //    barrier that precedes the counter increment.
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
-    if (tid == 0) {
-        __hip_atomic_fetch_add(g.arrived + panel, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int spins = 0;
-        while (__hip_atomic_load(g.arrived + panel, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < g.tiles_n) {
-            __builtin_amdgcn_s_sleep(1);
-            if (++spins > (1 << 22)) { *g.fault = 1; break; }     // never hang: report and carry on
-        }
-    }
-    __syncthreads();
+    // 3. wait for the siblings of the row panel (bounded)
+    panel_arrive_and_wait(g, panel, tid);
     // 4. ranges
     {
         const __amdgpu_buffer_rsrc_t mx_rsrc = make_rsrc(g.rowmax, (uint32_t)g.M * 4u);
@@ -546,17 +532,34 @@ void gemm_olay_kernel(GemmArgs g) {
     __builtin_amdgcn_s_waitcnt(vmcnt_only(0));                  // no DMA may outlive the workgroup's LDS
 }
 
+// Launch geometry of one instantiation on the current device.  The requantizing outputs make the column tiles
+// of a row panel wait for each other, so every workgroup of their grid must be resident: the grid is sized from
+// what the runtime reports for this kernel (hipOccupancyMaxActiveBlocksPerMultiprocessor), capped by the
+// occupancy the kernel was compiled for, and a panel's tiles_n tiles must fit into one XCD's share of it.
+template <int FM, int FN, int WM, int WN, int OCC, int OUT>
+struct OlayLaunch {
+    static constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+    static constexpr size_t lds = 3 * (size_t)(BM + BN) * (kBK / 2) + 2 * 2 * BM * 4 + (OUT == OUT_Q4 || OUT == OUT_Q4M ? 1024 : 0);
+    static KernelState &state() { static KernelState ks; return ks; }
+    static auto kernel() { return gemm_olay_kernel<FM, FN, WM, WN, OCC, OUT>; }
+    // resident workgroups on the current device (-1: HIP error)
+    static int slots() {
+        const int cus = prepare_kernel(reinterpret_cast<const void *>(kernel()), lds, state());
+        if (cus < 0) return -1;
+        if (OUT != OUT_Q4 && OUT != OUT_Q4M) return cus * OCC;    // no workgroup waits for another: any grid is safe
+        const int occ = resident_per_cu(reinterpret_cast<const void *>(kernel()), WM * WN * 64, lds, state());
+        if (occ < 0) return -1;
+        return cus * (occ < OCC ? occ : OCC);
+    }
+};
+
 template <int FM, int FN, int WM, int WN, int OCC, int OUT>
 static int launch_one(GemmArgs &g, hipStream_t st) {
-    constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr size_t lds = 3 * (size_t)(BM + BN) * (kBK / 2) + 2 * 2 * BM * 4 + (OUT == OUT_Q4 || OUT == OUT_Q4M ? 1024 : 0);
-    g.tiles_m = (g.M + BM - 1) / BM;
-    g.tiles_n = (g.N + BN - 1) / BN;
-    auto kern = gemm_olay_kernel<FM, FN, WM, WN, OCC, OUT>;
-    static KernelState ks;
-    const int cus = prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks);
-    if (cus < 0) return W4A4_ERR_HIP;
-    const int slots = cus * OCC;                                // workgroups that are resident at once on this device
+    using L = OlayLaunch<FM, FN, WM, WN, OCC, OUT>;
+    g.tiles_m = (g.M + L::BM - 1) / L::BM;
+    g.tiles_n = (g.N + L::BN - 1) / L::BN;
+    const int slots = L::slots();
+    if (slots < 0) return W4A4_ERR_HIP;
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
@@ -566,9 +569,18 @@ static int launch_one(GemmArgs &g, hipStream_t st) {
         const long most = (long)((g.tiles_m + kXcd - 1) / kXcd) * g.tiles_n * kXcd;
         grid = (unsigned)(most < (slots & ~(kXcd - 1)) ? most : (slots & ~(kXcd - 1)));
         if (g.tiles_n > (int)(grid / kXcd)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (g.wait_for == 0) g.wait_for = g.tiles_n;
     }
-    launch_gemm(kern, dim3(grid), dim3(WM * WN * 64), lds, st, g);
+    if (grid == 0) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    launch_gemm(L::kernel(), dim3(grid), dim3(WM * WN * 64), L::lds, st, g);
     return launch_status();
+}
+
+// Column tiles of a row panel that the fused requantize of the persistent kernel can keep co-resident on the
+// current device (0 = the kernel does not fit, -1 = HIP error): the limit on ceil(N / 256).
+int olay_requant_max_tiles_n(bool mfma_out) {
+    const int slots = mfma_out ? OlayLaunch<2, 4, 2, 2, 2, OUT_Q4M>::slots() : OlayLaunch<2, 4, 2, 2, 2, OUT_Q4>::slots();
+    return slots < 0 ? -1 : (slots & ~(kXcd - 1)) / kXcd;
 }
 
 template <int OUT>

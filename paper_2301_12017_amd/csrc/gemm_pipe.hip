@@ -171,27 +171,48 @@ void gemm_pipe_kernel(GemmArgs g) {
 }
 
 template <int FM, int FN, int WM, int WN, int OCC, int OUT>
+struct PipeLaunch {
+    static constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
+    static constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowB + BM * sizeof(float);
+    static KernelState &state() { static KernelState ks; return ks; }
+    static auto kernel() { return gemm_pipe_kernel<FM, FN, WM, WN, OCC, OUT>; }
+    // workgroups of this kernel that are resident at once on the current device (-1: HIP error)
+    static int slots() {
+        const int cus = prepare_kernel(reinterpret_cast<const void *>(kernel()), lds, state());
+        if (cus < 0) return -1;
+        const int occ = resident_per_cu(reinterpret_cast<const void *>(kernel()), WM * WN * 64, lds, state());
+        return occ < 0 ? -1 : cus * occ;
+    }
+};
+
+template <int FM, int FN, int WM, int WN, int OCC, int OUT>
 static int launch_one(GemmArgs &g, hipStream_t st) {
-    constexpr int BM = WM * FM * 32, BN = WN * FN * 32;
-    constexpr size_t lds = 2 * (size_t)(BM + BN) * kRowB + BM * sizeof(float);
-    g.tiles_m = (g.M + BM - 1) / BM;
-    g.tiles_n = (g.N + BN - 1) / BN;
-    auto kern = gemm_pipe_kernel<FM, FN, WM, WN, OCC, OUT>;
-    static KernelState ks;
-    if (prepare_kernel(reinterpret_cast<const void *>(kern), lds, ks) < 0) return W4A4_ERR_HIP;
+    using L = PipeLaunch<FM, FN, WM, WN, OCC, OUT>;
+    g.tiles_m = (g.M + L::BM - 1) / L::BM;
+    g.tiles_n = (g.N + L::BN - 1) / L::BN;
+    if (prepare_kernel(reinterpret_cast<const void *>(L::kernel()), L::lds, L::state()) < 0) return W4A4_ERR_HIP;
     const long tiles = (long)g.tiles_m * g.tiles_n;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    launch_gemm(kern, dim3((unsigned)tiles), dim3(WM * WN * 64), lds, st, g);
+    if (OUT == OUT_Q4) {
+        // the column tiles of a row panel wait for each other: the whole grid has to be resident
+        const int slots = L::slots();
+        if (slots < 0) return W4A4_ERR_HIP;
+        if (tiles > slots) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (g.wait_for == 0) g.wait_for = g.tiles_n;
+    }
+    launch_gemm(L::kernel(), dim3((unsigned)tiles), dim3(WM * WN * 64), L::lds, st, g);
     return launch_status();
 }
+
+// Tiles (128 x 256) that the fused requantize of the pipelined kernel may use on the current device: its whole
+// grid has to be resident (-1 = HIP error).
+int pipe_requant_max_tiles() { return PipeLaunch<2, 4, 2, 2, 2, OUT_Q4>::slots(); }
 
 template <int OUT>
 static int launch_variant(int variant, GemmArgs &g, hipStream_t st) {
     switch (variant) {
         case 0: return launch_one<2, 4, 2, 2, 2, OUT>(g, st);   // 128 x 256, two workgroups per CU
-        case 1: return launch_one<4, 4, 2, 2, 1, OUT>(g, st);   // 256 x 256, one workgroup per CU
-        case 2: return launch_one<3, 2, 2, 2, 2, OUT>(g, st);   // 192 x 128, two workgroups per CU
-        case 3: return launch_one<3, 4, 2, 2, 1, OUT>(g, st);   // 192 x 256, one workgroup per CU
+        case 1: return launch_one<3, 2, 2, 2, 2, OUT>(g, st);   // 192 x 128, two workgroups per CU
         default: return W4A4_ERR_INVALID_ARG;
     }
 }

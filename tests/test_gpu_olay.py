@@ -80,7 +80,7 @@ def test_layout_argument_errors(B):
         B.gemm_i32(A, Wc)                                          # layouts of the two operands differ
     Wm = B.quantize_weight(torch.zeros((8, 256), dtype=torch.float16, device="cuda"), SYM, 0, layout=MFMA)
     with pytest.raises(B.W4A4Error):
-        B.gemm_i32(A, Wm, schedule=1)                              # that kernel reads canonical codes
+        B.gemm_i32(A, Wm, schedule=B.schedule_number("pipe_128x256"))                              # that kernel reads canonical codes
 
 
 def _olay_schedules(B, K):
@@ -346,6 +346,67 @@ def test_fused_requantize_widest_output(B, orc):
     assert np.array_equal(host(out.scale)[rows].view(np.uint32), want["s"].view(np.uint32))
     sums = _codes(orc, want["q"])[:, 1::2].reshape(len(rows), 4, 1024).sum(axis=2)
     assert np.array_equal(host(out.osum)[rows].astype(np.int64), sums)
+
+
+def test_fused_requantize_gives_up_cleanly(B):
+    """The bounded wait of the fused requantize, forced from the host: the kernels are told to wait for one
+    more sibling tile than a row panel has and to poll a handful of times only.  Every workgroup then gives
+    up, raises both fault words and exits normally; the next, ordinary call is unaffected."""
+    rng = np.random.default_rng(985)
+    M, N, K = 300, 768, 256
+    A = B.quantize_act(dev(_rand_x(rng, M, K)), SYM, layout=MFMA)
+    Q = B.quantize_weight(dev(_rand_w(rng, N, K)), SYM, 0, layout=MFMA)
+    need = B.linear_workspace_bytes(A, Q, requant_layout=MFMA)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    assert B.fused_fault_check() is False
+    good = B.linear(A, Q, None, 0, requant=True, requant_layout=MFMA, workspace=ws)
+    torch.cuda.synchronize()
+    assert B.fused_fault(ws, need) == 0 and B.fused_fault_check() is False
+    B.debug_fused_wait(spin_limit=8, extra_arrivals=1)
+    try:
+        B.linear(A, Q, None, 0, requant=True, requant_layout=MFMA, workspace=ws)
+        torch.cuda.synchronize()                                   # returns: nobody hangs
+    finally:
+        B.debug_fused_wait(0, 0)
+    assert B.fused_fault(ws, need) != 0
+    assert B.fused_fault_check() is True and B.fused_fault_check() is False    # reported once, then cleared
+    again = B.linear(A, Q, None, 0, requant=True, requant_layout=MFMA, workspace=ws)
+    torch.cuda.synchronize()
+    assert B.fused_fault(ws, need) == 0 and B.fused_fault_check() is False
+    assert torch.equal(again.q, good.q) and torch.equal(again.scale, good.scale) and torch.equal(again.osum, good.osum)
+
+
+@pytest.mark.parametrize("N,K,gelu", [(3072, 1024, 0), (1024, 1024, 0), (4096, 1024, 1), (1024, 4096, 0)])
+def test_fused_requantize_equals_two_kernel_path_at_full_size(B, N, K, gelu):
+    """M = 32768 (the chained workload): the persistent kernel walks several rounds of tiles with panel waits on
+    every XCD.  Its codes, scales and odd-position sums must equal, bit for bit and for EVERY token, those of
+    the two-kernel path (fp32 rows, then the row quantizer), which involves no waiting."""
+    M = 32768
+    gen = torch.Generator(device="cuda").manual_seed(N + K)
+    X = torch.randn((M, K), device="cuda", generator=gen).half()
+    W = (torch.randn((N, K), device="cuda", generator=gen) * 0.02).half()
+    bias = (torch.randn((N,), device="cuda", generator=gen) * 0.01).half()
+    A = B.quantize_act(X, SYM, layout=MFMA)
+    Q = B.quantize_weight(W, SYM, 0, layout=MFMA)
+    need = B.linear_workspace_bytes(A, Q, requant_layout=MFMA)
+    assert need < 8 * M
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    fused = B.linear(A, Q, bias, gelu, requant=True, requant_layout=MFMA, workspace=ws)
+    torch.cuda.synchronize()
+    assert B.fused_fault(ws, need) == 0
+    other = B.schedule_number("olay_192x128")                      # a forced schedule other than the fused kernel's
+    assert B.linear_workspace_bytes(A, Q, requant_layout=MFMA, schedule=other) == M * N * 4
+    plain = B.linear(A, Q, bias, gelu, requant=True, requant_layout=MFMA, schedule=other)
+    assert torch.equal(fused.q, plain.q)
+    assert torch.equal(fused.scale.view(torch.int32), plain.scale.view(torch.int32))
+    assert torch.equal(fused.osum.reshape(M), plain.osum.reshape(M))
+    if N == 3072:                                                  # one sum per third: equal to sums over the code bytes
+        sl = B.linear(A, Q, bias, gelu, requant=True, requant_layout=MFMA, requant_group=1024, workspace=ws)
+        assert torch.equal(sl.q, plain.q)
+        hi = (sl.q.to(torch.int32) >> 4)                            # odd positions: two's-complement high nibbles
+        hi = torch.where(hi >= 8, hi - 16, hi).reshape(M, 3, 512).sum(dim=2)
+        assert torch.equal(sl.osum.reshape(M, 3), hi.to(torch.int32))
+    assert B.fused_fault_check() is False
 
 
 @pytest.mark.parametrize("layout,M,N,K", [(MFMA, 2048, 512, 512), (0, 300, 256, 384)])

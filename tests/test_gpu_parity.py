@@ -111,8 +111,8 @@ def _operands(B, orc, rng, M, N, K, mode, group, outliers=0):
 
 
 def _schedules(B, grouped, K=128):
-    """Schedule numbers to exercise: every one that supports the layer (the pipelined kernels
-    take symmetric per-channel layers with K % 128 == 0; some generic tiles are ungrouped only)."""
+    """Schedule numbers to exercise: every one that supports the layer (the pipelined kernel
+    takes symmetric per-channel layers with K % 128 == 0, the split-K kernel K % 64 == 0)."""
     out = []
     for i, name in enumerate(B.schedule_names()):
         if name.startswith("olay"):                 # reads the MFMA operand layout only (tests/test_gpu_olay.py)
@@ -121,12 +121,7 @@ def _schedules(B, grouped, K=128):
             continue
         if name.startswith("small") and (grouped or K % 64 or K > 4096):   # symmetric per-channel, K % 64 == 0
             continue
-        if name.startswith("pipe8"):
-            if grouped or K % 64:
-                continue
-        elif (name.startswith("pipe") or name.startswith("dma")) and (grouped or K % 128):
-            continue
-        if grouped and name == "generic_256x256":
+        if name.startswith("pipe") and (grouped or K % 128):
             continue
         out.append(i + 1)
     return out
@@ -158,7 +153,7 @@ def test_gemm_i32_extreme_codes(B, orc):
         one = torch.ones(max(M, N), dtype=torch.float32, device="cuda")
         A = B.QAct(Aq, one, None, None, M, K, K // 2, 0, SYM)
         Q = B.QWeight(Wq, one.reshape(-1, 1), None, None, None, N, K, 0, SYM)
-        for sch in (1, 2, 4, 7, 10, 11, 12, 13):
+        for sch in _schedules(B, False, K):                        # every kernel family that reads canonical symmetric codes
             P = host(B.gemm_i32(A, Q, schedule=sch))
             assert (P == val).all()
     Aq = torch.full((M, K // 2), 0xFF, dtype=torch.uint8, device="cuda")
@@ -166,7 +161,8 @@ def test_gemm_i32_extreme_codes(B, orc):
     zi = torch.zeros((M, 1), dtype=torch.int32, device="cuda")
     A = B.QAct(Aq, one, one, zi, M, K, K // 2, 0, ASYM)
     Q = B.QWeight(Aq, one.reshape(-1, 1), one.reshape(-1, 1), None, one, N, K, 0, ASYM)
-    assert (host(B.gemm_i32(A, Q, schedule=3)) == 225 * K).all()
+    for sch in _schedules(B, True, K):                              # ... and unsigned ones
+        assert (host(B.gemm_i32(A, Q, schedule=sch)) == 225 * K).all(), sch
 
 
 # ------------------------------------------------------------------ steps a2+a3 fused
@@ -290,6 +286,32 @@ def test_fused_requant_many_column_tiles(B, orc):
     assert float(host(gz.scale)[5]) == 1.0 and not host(gz.q)[5].any()
 
 
+def test_fused_requant_at_the_residency_limit(B, orc):
+    """The pipelined kernel's fused requantize needs its whole grid resident: 512 tiles (two workgroups on each
+    of 256 CUs) still fuse, one row panel more falls back to fp32 rows + row quantizer; both give the same bits."""
+    rng = np.random.default_rng(52)
+    N, K = 4096, 256
+    W = _rand_w(rng, N, K)
+    Q = B.quantize_weight(dev(W), SYM)
+    res = {}
+    for M in (4096, 4224):
+        X = _rand_x(rng, M, K)
+        A = B.quantize_act(dev(X), SYM)
+        need = B.linear_workspace_bytes(A, Q)
+        res[M] = need
+        got = B.linear(A, Q, None, 0, requant=True, requant_mode=SYM)
+        acc = B.gemm_i32(A, Q)
+        alone = B.dequant_epilogue(acc, A, Q, None, 0, requant=True, requant_mode=SYM)
+        assert torch.equal(got.q, alone.q) and torch.equal(got.scale.view(torch.int32), alone.scale.view(torch.int32)), M
+        rows = np.array([0, 127, 128, M // 2 + 3, M - 1])
+        a = qact_host(A)
+        a = dict(q=a["q"][rows], s=a["s"][rows], z=a["z"][rows], gsum=None)
+        want = orc.linear(a, qweight_host(Q), SYM, 0, None, 0, requant=True, requant_mode=SYM)
+        assert np.array_equal(host(got.q)[rows], want["q"])
+    assert res[4096] < 8 * 4096 and res[4224] == 4224 * N * 4
+    assert B.fused_fault_check() is False
+
+
 def test_linear_reads_a_column_slice_in_place(B, orc):
     """lda > K/2: the GEMM reads the last third of a wider packed matrix (as the chained stack does)."""
     rng = np.random.default_rng(43)
@@ -311,7 +333,7 @@ def test_degenerate_and_tiny_shapes(B, orc):
     for M, N, K in ((1, 8, 32), (2, 40, 64), (31, 8, 160), (257, 24, 32)):
         X, W, A, Q = _operands(B, orc, rng, M, N, K, SYM, 0)
         want = _oracle_layer(orc, A, Q, SYM, 0, None, 0)
-        for sch in (0, 4, 7):
+        for sch in (0, B.schedule_number("generic_64x64"), B.schedule_number("generic_32x32")):
             got = host(B.linear(A, Q, schedule=sch))
             assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16)), (M, N, K, sch)
     # M == 0: nothing is launched, nothing fails
