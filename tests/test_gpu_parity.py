@@ -137,7 +137,7 @@ def test_gemm_i32_bit_exact_every_schedule(B, orc, mode, group):
         X, W, A, Q = _operands(B, orc, rng, M, N, K, mode, group)
         want = orc.gemm_i32(host(A.q), host(Q.q), mode, group)
         scheds = _schedules(B, grouped, K)
-        assert len(scheds) >= 4
+        assert len(scheds) >= 3                                   # the generic tiles, plus what the layer allows
         for sch in scheds:
             got = host(B.gemm_i32(A, Q, schedule=sch))
             assert got.shape == want.shape
