@@ -347,6 +347,25 @@ int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
                 void *out, float *out_scale, float *out_zero, int32_t *out_gsum,
                 void *workspace, size_t workspace_bytes, void *stream);
 
+/* w4a4_linear for callers that cannot allocate device memory or carry a workspace around: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * checks as w4a4_linear minus the workspace: the exchange area of the fused requantize (per-token
+ * maxima, arrival counters, fault word) is a static device array inside the library, 264 208 bytes per
+ * GPU, which every GPU the library has run this call on holds until the process ends.  The call
+ * allocates nothing, frees nothing and does not synchronize; the array is cleared by a fill kernel on
+ * `stream` before each use.
+ *   - requant == 0: identical to w4a4_linear (no scratch is involved).
+ *   - requant == 1: only layers whose requantize w4a4_linear fuses into the GEMM kernel on this device
+ *     (w4a4_linear_workspace_bytes < M*N*4), with M <= 65536 tokens.  Anything else (an unfusable
+ *     requantize would need M*N*4 bytes of fp32 rows; more tokens than the array has room for) returns
+ *     W4A4_ERR_WORKSPACE before anything is launched or written.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents until the next
+ *     call clears it: two requantizing calls that overlap in time on one GPU (different streams, or
+ *     threads) race on it.  Order them on one stream, or use w4a4_linear with separate workspaces.
+ *   - A give-up of the bounded wait is reported through w4a4_fused_fault_check only. */
+int w4a4_linear_static(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep,
+                       void *out, float *out_scale, float *out_zero, int32_t *out_gsum, void *stream);
+
 /* Producer fusion (Sec. 4.2: the quantize of an activation shares a kernel with the bias-add,
  * GELU or LayerNorm that produces it): LayerNorm over the K features of every token of X (+ R),
  * then step a1 on the result, in one kernel.

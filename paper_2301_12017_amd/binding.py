@@ -78,6 +78,8 @@ _SIGNATURES = {
     "w4a4_quantize_act": (_i, [_vp, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _i, _vp, _vp]),
     "w4a4_linear": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
                          _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "w4a4_linear_static": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue),
+                                _vp, _vp, _vp, _vp, _vp]),
     "w8a8_quantize_rows": (_i, [_vp, _i, _i, _i, _vp, _vp, _vp]),
     "w8a8_linear": (_i, [_vp, _i, _vp, _i, _vp, _vp, _i, _i, ctypes.POINTER(_Epilogue), _vp, _vp]),
     "w8a8_linear_f16act": (_i, [_vp, _i, _i, _i, _vp, _vp, _i, ctypes.POINTER(_Epilogue), _vp, _vp]),
@@ -400,6 +402,25 @@ def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NON
     rc = lib().w4a4_linear(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), _ptr(o), _ptr(os_), _ptr(oz),
                            _ptr(og), _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream())
     _check(rc, "w4a4_linear")
+    if not requant:
+        return o
+    if requant_layout == LAYOUT_MFMA:
+        return QAct(o, os_, oz, None, A.M, W.N, W.N // 2, requant_group, requant_mode, 0, LAYOUT_MFMA, og)
+    return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)
+
+
+def linear_static(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NONE, requant=False,
+                  requant_mode=SYM, requant_group=0, schedule=0, out=None, requant_layout=LAYOUT_CANONICAL):
+    """w4a4_linear_static: w4a4_linear without a workspace argument (the library's static exchange area).
+    `out` as for linear(); when it is given this wrapper allocates nothing either."""
+    ep = _epilogue(bias, act, requant, requant_mode, requant_group, schedule, requant_layout)
+    if out is None:
+        out = _alloc_out(A, W, requant, requant_mode, requant_group, requant_layout)
+    o, os_, oz, og = out
+    a, w = A.c(), W.c()
+    rc = lib().w4a4_linear_static(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep), _ptr(o), _ptr(os_), _ptr(oz),
+                                  _ptr(og), _stream())
+    _check(rc, "w4a4_linear_static")
     if not requant:
         return o
     if requant_layout == LAYOUT_MFMA:

@@ -454,3 +454,45 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
     return linear_impl(A, W, ep, out, out_scale, out_zero, out_gsum, ng, fused, static_cast<uint32_t *>(workspace),
                        workspace, as_stream(stream));
 }
+
+// ---- w4a4_linear for callers that cannot allocate -----------------------------------------------------------
+// The exchange area of the fused requantize lives in a file-scope device array instead of a caller workspace.
+// Each GPU the library runs on holds its own copy of the array at its own address until the process ends; host
+// code never passes the array's name to a kernel or a copy (on the host the name is only a handle): it asks the
+// runtime once per device, with that device current, for the copy's address and uses that pointer.
+constexpr int kStaticMaxTokens = 65536;
+constexpr int kScratchWords = kStaticMaxTokens + kStaticMaxTokens / 128 + 4;      // 264 208 bytes per device
+static __device__ __align__(256) uint32_t scratch[kScratchWords];
+
+static uint32_t *scratch_address() {
+    static std::atomic<uint32_t *> addr[kMaxDevices] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    uint32_t *p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        void *sym = nullptr;
+        if (hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)) != hipSuccess || !sym) return nullptr;
+        p = static_cast<uint32_t *>(sym);
+        addr[dev].store(p, std::memory_order_release);
+    }
+    return p;
+}
+
+extern "C" int w4a4_linear_static(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, void *out,
+                                  float *out_scale, float *out_zero, int32_t *out_gsum, void *stream) {
+    int ng = 0, rng = 0;
+    int rc = check_layer(A, W, ep, out, out_scale, out_zero, &ng, &rng);
+    if (rc) return rc;
+    if (A->M == 0) return W4A4_OK;
+    int fused = 0;
+    uint32_t *exchange = nullptr;
+    if (ep->requant) {
+        fused = fused_requant_kind(A, W, ep, out_gsum != nullptr);
+        // a requantize that cannot be fused needs M*N*4 bytes of fp32 rows: beyond what a static array should hold
+        if (!fused) return W4A4_ERR_WORKSPACE;
+        if (A->M > kStaticMaxTokens) return W4A4_ERR_WORKSPACE;
+        exchange = scratch_address();
+        if (!exchange) return W4A4_ERR_HIP;
+    }
+    return linear_impl(A, W, ep, out, out_scale, out_zero, out_gsum, ng, fused, exchange, nullptr, as_stream(stream));
+}
