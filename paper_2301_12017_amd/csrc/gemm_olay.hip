@@ -50,8 +50,15 @@ struct ChanParams {
 };
 
 // Epilogue of one wave for the fp16 / fp32 / int32 outputs.  The accumulators already contain
-// -128*osum[m] (C operand of the tile's first MFMAs), so v = acc - 128*esum[n] = 16*P exactly; then y = ((float)v * sa[m]) * (sw[n]/16) (+ bias[n]) (GELU), each operation
-// separately rounded, which equals ((float)P * sa) * sw of the definition bit for bit.
+// -128*osum[m] (C operand of the tile's first MFMAs), so v = acc - 128*esum[n] = 16*P exactly.
+//   fp32 rows (they are quantized afterwards, where the operation order decides codes):
+//     y = ((float)v * sa[m]) * (sw[n]/16) (+ bias[n]) (GELU), each operation separately rounded, which equals
+//     ((float)P * sa) * sw of the definition bit for bit;
+//   fp16 stores: three instructions per value instead of five,
+//     y = fma(fma((float)acc, sw[n]/16, -128*esum[n]*sw[n]/16), sa[m], bias[n]),
+//     the same real number evaluated with two roundings less and the channel term moved behind the conversion
+//     (its product with the scale is formed once per tile).  The fp32 value differs from the definition's by a
+//     few units in the last place, the fp16 result by at most one step and only on near-ties of the fp16 grid.
 template <int FM, int FN, int OUT, bool BIAS, bool GELU>
 __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM][FN], const ChanParams<FN> &cp,
                                               uint32_t col_off, int m0, int row_w, int lane,
@@ -60,6 +67,12 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
     const __amdgpu_buffer_rsrc_t o_rsrc = make_rsrc(g.out, (uint32_t)((long)g.M * g.N * ESZ));
     const uint32_t row_bytes = (uint32_t)g.N * ESZ;
     const uint32_t lane_off = (uint32_t)(m0 + row_w + 4 * (lane >> 5)) * row_bytes + col_off;
+    float nsw[FN], bj[FN];                                      // channel term times the scale; bias (0 without one)
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        nsw[j] = (float)cp.ne[j] * cp.sw[j];
+        bj[j] = BIAS ? cp.bias[j] : 0.0f;
+    }
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -76,24 +89,23 @@ __device__ __forceinline__ void olay_epilogue(const GemmArgs &g, v16i (&acc)[FM]
 #pragma unroll
                     for (int j = 0; j < FN; ++j) w[j] = (uint32_t)((acc[i][j][r] + cp.ne[j]) >> 4);
                     store_words<FN, kStreamed>(o_rsrc, off, w);
+                } else if constexpr (OUT == OUT_F32) {
+                    uint32_t w[FN];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        const float t = (float)(acc[i][j][r] + cp.ne[j]) * sav[rr];
+                        float y = t * cp.sw[j];
+                        if constexpr (BIAS) y = y + cp.bias[j];
+                        w[j] = __float_as_uint(GELU ? gelu_erf(y) : y);
+                    }
+                    store_words<FN, kStreamed>(o_rsrc, off, w);
                 } else {
                     float y[FN];
 #pragma unroll
-                    for (int j = 0; j < FN; ++j) {
-                        float t = (float)(acc[i][j][r] + cp.ne[j]) * sav[rr];
-                        y[j] = t * cp.sw[j];
-                        if constexpr (BIAS) y[j] = y[j] + cp.bias[j];
-                    }
-                    if constexpr (OUT == OUT_F32) {
-                        uint32_t w[FN];
-#pragma unroll
-                        for (int j = 0; j < FN; ++j) w[j] = __float_as_uint(GELU ? gelu_erf(y[j]) : y[j]);
-                        store_words<FN, kStreamed>(o_rsrc, off, w);
-                    } else if constexpr (GELU) {
-                        store_gelu_halves<FN, kStreamed>(o_rsrc, off, y);
-                    } else {
-                        store_halves<FN, kStreamed>(o_rsrc, off, y);
-                    }
+                    for (int j = 0; j < FN; ++j)
+                        y[j] = __fmaf_rn(__fmaf_rn((float)acc[i][j][r], cp.sw[j], nsw[j]), sav[rr], bj[j]);
+                    if constexpr (GELU) store_gelu_halves<FN, kStreamed>(o_rsrc, off, y);
+                    else store_halves<FN, kStreamed>(o_rsrc, off, y);
                 }
             }
         }
@@ -245,7 +257,6 @@ void gemm_olay_kernel(GemmArgs g) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const unsigned slot_bit = __builtin_amdgcn_s_getreg(6148) & 1;   // HW_ID.WAVE_ID bit 0: which wave slot of the SIMD
     const int wm = wave / WN, wn = wave % WN;
     const int total = g.tiles_m * g.tiles_n, stride = gridDim.x;
     const int KT = g.K / kBK;
@@ -433,15 +444,6 @@ void gemm_olay_kernel(GemmArgs g) {
             const int nx2 = nxt == NS - 1 ? 0 : nxt + 1;       // stage of stream step +2 (= step -1)
             // stream step +2 is K step kt+2 of this tile, or K step kt+2-KT of the next one (when there
             // is none: a harmless in-bounds re-read, so that the load counting stays uniform)
-            // The two workgroups of a CU do not share a SIMD evenly: the older wave wins every issue
-            // conflict, finishes its tiles early and leaves the CU half empty at the end.  Each wave therefore
-            // raises its priority in alternate 10 us slices of the constant-rate clock, the two wave slots of a
-            // SIMD in opposite phase (measured: 1.5 - 2 % on the BERT-large shapes).
-            {
-                const unsigned long long now = __builtin_amdgcn_s_memrealtime();
-                if ((((unsigned)(now >> 10)) ^ slot_bit) & 1) __builtin_amdgcn_s_setprio(1);
-                else __builtin_amdgcn_s_setprio(0);
-            }
             const bool own = !LAST && kt + 2 < KT;
             const __amdgpu_buffer_rsrc_t ra = own ? a_cur : a_nxt, rb = own ? b_cur : b_nxt;
             const int so = (own ? kt + 2 : kt + 2 - KT) * ROWB;

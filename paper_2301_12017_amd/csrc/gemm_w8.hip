@@ -86,7 +86,6 @@ void gemm_w8_kernel(GemmArgs g) {
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const unsigned slot_bit = __builtin_amdgcn_s_getreg(6148) & 1;   // HW_ID.WAVE_ID bit 0: which wave slot of the SIMD
     const int wm = wave / WN, wn = wave % WN;
     const int total = g.tiles_m * g.tiles_n, stride = gridDim.x;
     const int KT = g.K / kW8Step;
@@ -226,12 +225,6 @@ void gemm_w8_kernel(GemmArgs g) {
             constexpr bool LAST = decltype(last_tag)::value;   // last K step of the tile
             const int nxt = cur == NS - 1 ? 0 : cur + 1;       // stage of stream step +1
             const int nx2 = nxt == NS - 1 ? 0 : nxt + 1;       // stage of stream step +2 (= step -1)
-            // alternate the priority of the two wave slots of a SIMD in 10 us slices (see gemm_olay.hip)
-            {
-                const unsigned long long now = __builtin_amdgcn_s_memrealtime();
-                if ((((unsigned)(now >> 10)) ^ slot_bit) & 1) __builtin_amdgcn_s_setprio(1);
-                else __builtin_amdgcn_s_setprio(0);
-            }
             // stream step +2 is K step kt+2 of this tile, or K step kt+2-KT of the next one (when there
             // is none: a harmless in-bounds re-read, so that the load counting stays uniform)
             const bool own = !LAST && kt + 2 < KT;

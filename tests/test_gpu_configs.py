@@ -10,7 +10,8 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import act_to_canonical, dev, f16_close, has_gpu, host, qact_host, qweight_host
+from tests.gpu_util import (GELU_SAME, OLAY_SAME, act_to_canonical, assert_f16, dev, f16_close, has_gpu, host, qact_host,
+                            qweight_host)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -41,11 +42,8 @@ def _check_linear_rows(orc, B, spec, layer, X_host, A, Y, rows, exact):
     got = host(Y)[rows]
     ok, ratio = f16_close(got, want["out"])
     assert ok, f"{spec.name}: tolerance ratio {ratio}"
-    same = np.mean(got.view(np.uint16) == want["out"].view(np.uint16))
-    if exact and not spec.gelu:
-        assert same == 1.0, f"{spec.name}: {same}"
-    else:
-        assert same > 0.98, f"{spec.name}: {same}"
+    olay = getattr(layer.W, "layout", 0) == 1                      # the persistent operand-layout kernel
+    assert_f16(got, want["out"], GELU_SAME if spec.gelu else OLAY_SAME if olay else 1.0 if exact else 0.98, spec.name)
     return oa, ow
 
 

@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import dev, f16_close, has_gpu, host
+from tests.gpu_util import GELU_SAME, OLAY_SAME, assert_f16, dev, f16_close, has_gpu, host
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -63,8 +63,7 @@ def test_gemm_and_linear(B, orc, M, N, K):
         want = orc.linear8(sub, w, b, act)["out"]
         ok, ratio = f16_close(got, want)
         assert ok, ratio
-        same = np.mean(got.view(np.uint16) == want.view(np.uint16))
-        assert same == 1.0 if act == 0 else same > 0.98
+        assert_f16(got, want, 1.0 if act == 0 else GELU_SAME, f"act {act}")
     plain = host(B.linear8(Aq, sa, Wq, sw, None, 0))[rows]
     assert np.array_equal(plain.view(np.uint16), orc.linear8(sub, w, None, 0)["out"].view(np.uint16))
 

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import dev, f16_close, has_gpu, host, qact_host, qweight_host
+from tests.gpu_util import GELU_SAME, assert_f16, dev, f16_close, has_gpu, host, qact_host, qweight_host
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -183,10 +183,7 @@ def test_linear_fp16_every_schedule(B, orc, mode, group, act):
         got = host(B.linear(A, Q, dev(bias), act, schedule=sch))
         ok, ratio = f16_close(got, want["out"])
         assert ok, f"schedule {sch}: tolerance ratio {ratio}"
-        if act == 0:
-            assert np.array_equal(got.view(np.uint16), want["out"].view(np.uint16)), f"schedule {sch}"
-        else:
-            assert np.mean(got.view(np.uint16) == want["out"].view(np.uint16)) > 0.98
+        assert_f16(got, want["out"], 1.0 if act == 0 else GELU_SAME, f"schedule {sch}")
 
 
 def test_linear_without_bias(B, orc):
