@@ -6,10 +6,13 @@ INT4 GEMM + dequantize/bias(/GELU) epilogue with an fp16 store -- over the four
 encoder linears of BERT-large at batch 32 x seq 384 (M = 12288; Sec. 4.1 shapes),
 with fp16 activations, quantized weights and biases already resident in HBM.
 `value` is 2*M*N*K summed over the four GEMMs divided by the step time (so the
-quantize kernels count against it).  The line also carries the latency of the
-BERT-base layer linears at batch 1 x seq 128, the roofline position of the GEMM
-kernel (HIP events around every w4a4_linear launch inside the timed region) and the
-CPU oracle timed on a sample of token rows of the same workload.
+quantize kernels count against it).  The line also carries
+  roofline         the GEMM kernels of the step against the int8 MFMA peak (HIP events at each kernel's own
+                   start and end), beside the ceilings measured in the same run (`ceilings`);
+  latency          the BERT-base layer linears at batch 1 x seq 128, warm and cold;
+  other_workloads  short legs of the asymmetric / grouped workload and of the chained requantizing stack;
+  cpu_baseline     the CPU oracle timed on a sample of token rows of the same workload, on all host cores
+                   and on one.
 """
 import argparse
 import json
@@ -23,16 +26,15 @@ if ROOT not in sys.path:
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix peak, 5.0 POP/s
 HBM_PEAK_GBS = 8000.0
-# HBM-side bytes of the four w4a4_linear launches of one step of configs[2], from the rocprofv3 --pmc
-# runs summarised in profiles/gemm_config3_hbm_traffic.txt (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the
-# factors a 256 MiB device copy gave in the same runs).  Not measured live; None for other workloads.
-PROFILED_TRAFFIC_BYTES = {3: int((18.52 + 10.36 + 22.82 + 42.86 + 72.0 + 24.0 + 96.0 + 24.0) * 2 ** 20)}
+METRIC = "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128"
+DTYPE = "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, {} out)"
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_config3_hbm_traffic.txt")
 
 
 def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=50)
+    p.add_argument("--steps", type=int, default=300)
     p.add_argument("--warmup", type=int, default=10)
     p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped, 5 = one layer of the chained stack)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
@@ -45,12 +47,17 @@ def parse():
                    help="instead of the step: INT4 and INT8 GEMM kernel time over the token count for the BERT-base and "
                         "BERT-large shapes (the comparison of Sec. 4.1 on this hardware); prints its own JSON line")
     p.add_argument("--step-only", action="store_true",
-                   help="only the timed step and its roofline: skip the latency, fusion, sibling, strategy and library legs "
-                        "(for profiler runs, so that a kernel trace holds the step's launches alone)")
+                   help="only the timed step and its roofline: skip every side leg (for profiler runs, so that a kernel "
+                        "trace holds the step's launches alone)")
+    p.add_argument("--latency-only", action="store_true",
+                   help="only the batch 1 x seq 128 latency leg (for profiler runs of the M = 128 kernels); prints its own JSON line")
+    p.add_argument("--quantize-only", action="store_true",
+                   help="only the token-wise quantizer at the workload's shapes, over rotating inputs (for profiler runs); "
+                        "prints its own JSON line")
     p.add_argument("--copy-probe-mb", type=int, default=0,
                    help="also run one plain device copy of this many MiB (a kernel of known traffic, used to "
                         "calibrate the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
-    p.add_argument("--cpu-rows", type=int, default=1024, help="token rows per GEMM the oracle is timed on")
+    p.add_argument("--cpu-rows", type=int, default=256, help="token rows per GEMM and worker the oracle is timed on")
     return p.parse_args()
 
 
@@ -65,62 +72,174 @@ def settle(fn, ms):
         torch.cuda.synchronize()
 
 
-def cpu_baseline(specs, cfg, rows):
-    """The oracle as it stands (single thread, plain C) on `rows` token rows of every GEMM."""
-    import numpy as np
+# ------------------------------------------------------------------------------------------ CPU oracle
+def _oracle_rows(job):
+    """One worker: the oracle's quantize_act + linear on `rows` token rows of every GEMM of the workload.
+    Returns the seconds the timed part took (weights are quantized beforehand, an offline step)."""
+    cfg, rows, worker = job
     import oracle
     from paper_2301_12017_amd import synth
-    ops = 0
+    specs = synth.config_linears(cfg)
     prepared = []
     for i, s in enumerate(specs):
-        X = synth.activations(rows, s.K, 0, cfg, 10 * i, outlier_channels=8 if cfg == 4 else 0)
+        X = synth.activations(rows, s.K, worker, cfg, 10 * i, outlier_channels=8 if cfg == 4 else 0)
         W = synth.weights(s.N, s.K, 0, cfg, 10 * i + 1)
         b = synth.bias(s.N, 0, cfg, 10 * i + 2)
-        Q = oracle.quantize_weight(W, s.mode, s.group)            # offline step, not timed
-        prepared.append((s, X, Q, b))
-        ops += 2 * rows * s.N * s.K
+        prepared.append((s, X, oracle.quantize_weight(W, s.mode, s.group), b))
     t0 = time.perf_counter()
     for s, X, Q, b in prepared:
         A = oracle.quantize_act(X, s.mode, s.group)
         oracle.linear(A, Q, s.mode, s.group, b, oracle.ACT_GELU if s.gelu else oracle.ACT_NONE)
-    dt = time.perf_counter() - t0
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": 1, "kind": "oracle",
-            "sample": f"{rows} of {specs[0].M} token rows of each of the {len(specs)} GEMMs "
-                      f"(all N, all K), {dt:.1f} s; rows are independent, so the whole workload "
-                      f"would take about {dt * specs[0].M / rows:.0f} s",
-            "seconds": dt}
+    return time.perf_counter() - t0
 
 
-def bench_chain(args):
+def host_cores():
+    """Worker count for the all-core figure: the machine's CPU share (the scheduler affinity of this process, capped by
+    OMP_NUM_THREADS where the environment sets it)."""
+    n = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    try:
+        cap = int(os.environ.get("OMP_NUM_THREADS", "0"))
+    except ValueError:
+        cap = 0
+    return max(1, min(n, cap) if cap > 0 else n)
+
+
+def cpu_baseline(cfg, rows):
+    """The oracle as it stands (plain C, one thread per process) on a sample of token rows of every GEMM: once on a
+    single core, once on all cores (one worker process per core, each with its own `rows` rows; token rows are
+    independent end to end).  Must run before this process touches the GPU: the workers are forked."""
+    import multiprocessing as mp
+    from paper_2301_12017_amd import synth
+    import oracle
+    specs = synth.config_linears(cfg)
+    ops_per_row = sum(2 * s.N * s.K for s in specs)
+    oracle.lib()                                                      # compiled before the workers start
+    one = _oracle_rows((cfg, rows, 0))
+    cores = host_cores()
+    t0 = time.perf_counter()
+    with mp.get_context("fork").Pool(cores) as pool:
+        secs = pool.map(_oracle_rows, [(cfg, rows, w) for w in range(cores)], chunksize=1)
+    wall = time.perf_counter() - t0
+    span = max(secs)                                                  # the timed part of the slowest worker
+    return {"value": ops_per_row * rows * cores / span / 1e12, "unit": "TOPS", "cores": cores, "kind": "oracle",
+            "sample": f"{rows} token rows of each of the {len(specs)} GEMMs (all N, all K) per worker process, {cores} "
+                      f"workers = {rows * cores} of {specs[0].M} rows, {span:.1f} s (slowest worker; {wall:.1f} s with "
+                      f"set-up); rows are independent, so the whole workload would take about "
+                      f"{span * specs[0].M / (rows * cores):.0f} s on these cores",
+            "seconds": span,
+            "single_thread": {"value": ops_per_row * rows / one / 1e12, "unit": "TOPS", "cores": 1, "seconds": one,
+                              "sample": f"{rows} token rows of each GEMM"},
+            "host_cores_visible": os.cpu_count()}
+
+
+# ------------------------------------------------------------------------------------------ workloads 3 and 4
+KERNEL_NAMES = {"olay": "gemm_olay_kernel", "group": "gemm_group_kernel", "pipe": "gemm_pipe_kernel",
+                "generic": "gemm_kernel", "small": "linear_f16act_kernel"}
+
+
+def kernel_label(schedules):
+    fam = sorted({n.split("_")[0] for n in schedules})
+    return " / ".join(KERNEL_NAMES.get(f, f) for f in fam) + " (w4a4_linear), the four launches of the step; schedules " \
+        + ", ".join(schedules)
+
+
+class StepWorkload:
+    """quantize_act + w4a4_linear for the four linears of workload `cfg`, everything allocated and marshalled once."""
+
+    def __init__(self, cfg, schedule=0):
+        import torch
+        from paper_2301_12017_amd import binding as B, synth, workloads as WL
+        self.cfg, self.B = cfg, B
+        self.specs = synth.config_linears(cfg)
+        self.layers = [WL.make_layer(s, cfg, i, keep_host=False) for i, s in enumerate(self.specs)]
+        self.Xs = [WL.dev(WL.make_input(s, cfg, i)) for i, s in enumerate(self.specs)]
+        self.qacts = [B.quantize_act(X, s.mode, s.group, layout=L.W.layout) for X, s, L in zip(self.Xs, self.specs, self.layers)]
+        self.outs = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(self.qacts, self.layers)]
+        self.q_calls = [B.PreparedQuantizeAct(X, qa) for X, qa in zip(self.Xs, self.qacts)]
+        self.l_calls = [B.PreparedLinear(qa, L.W, L.bias, L.act, schedule=schedule, out=o)
+                        for qa, L, o in zip(self.qacts, self.layers, self.outs)]
+        self.schedules = [B.pick_schedule(qa, L.W, schedule=schedule) for qa, L in zip(self.qacts, self.layers)]
+        self.stream = B._stream()
+        self.ops = sum(2 * s.M * s.N * s.K for s in self.specs)
+        torch.cuda.synchronize()
+
+    def step(self, tm=None, st=None):
+        st = self.stream if st is None else st
+        for i in range(len(self.specs)):
+            self.q_calls[i](st)
+            if tm:
+                tm[i].arm()                                     # stamps the GEMM kernel's own start and end
+            self.l_calls[i](st)
+
+    def measure(self, steps, warmup, settle_ms):
+        import torch
+        B = self.B
+        settle(self.step, settle_ms)
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        # the same steps once more with kernel-boundary HIP events on every w4a4_linear launch: the kernel
+        # durations behind the roofline figure (what a kernel trace reports; no dispatch gap in them)
+        timers = [[B.KernelTimer() for _ in self.specs] for _ in range(steps)]
+        for k in range(steps):
+            self.step(timers[k])
+        torch.cuda.synchronize()
+        gemm_ms = [sum(timers[k][i].elapsed_ms() for k in range(steps)) / steps for i in range(len(self.specs))]
+        ms = dt * 1e3 / steps
+        return {"ms_per_step": ms, "timed_region_s": dt, "TOPS": self.ops / (ms * 1e-3) / 1e12, "gemm_ms": gemm_ms,
+                "kernel_ms_per_step": sum(gemm_ms), "achieved_TOPS": self.ops / (sum(gemm_ms) * 1e-3) / 1e12}
+
+
+def profiled_traffic(schedules):
+    """HBM-side bytes of the four w4a4_linear launches of one step of the headline workload, from the rocprofv3 --pmc
+    summary under profiles/ -- only if that summary was taken on the schedules this run uses (its `schedules:` line),
+    else None: the figure is not measured live."""
+    try:
+        text = open(TRAFFIC_PROFILE).read()
+    except OSError:
+        return None
+    got_s = got_b = None
+    for line in text.splitlines():
+        if line.startswith("schedules:"):
+            got_s = [t.strip() for t in line.split(":", 1)[1].split(",")]
+        if line.startswith("traffic_bytes_per_step:"):
+            got_b = int(line.split(":", 1)[1].split()[0])
+    return got_b if got_s == list(schedules) else None
+
+
+# ------------------------------------------------------------------------------------------ workload 5
+def chain_leg(steps, warmup, settle_ms):
     """Workload 5: the chained BERT-large linear stack at M = 32768.  A step is one encoder layer's four
     GEMMs (QKV, out-proj on the V third, FFN1+GELU, FFN2), each with the dequantize / bias (/GELU) /
     per-token requantize epilogue fused, codes flowing from one GEMM to the next without an fp16 tensor.
     Four layers with distinct weights are cycled; the step input is the previous layer's output."""
     import torch
     from paper_2301_12017_amd import binding as B, synth, workloads as WL
-    B.lib()
-    torch.cuda.set_device(0)
     M, h, ffn, nl = 32768, 1024, 4096, 4
     layout = B.preferred_layout(M, 3 * h, h)
     layers = WL.make_chain(nl, h, ffn, M, 5, keep_host=False, layout=layout)
     A0 = B.quantize_act(WL.dev(synth.activations(M, h, 0, 5, 0)), B.SYM, layout=layout)
     ws = torch.empty(M * 8, dtype=torch.uint8, device="cuda")
     # build the 16 calls once: run the chain eagerly and keep every output as the next call's input
-    calls, names, A = [], [], A0
+    calls, names, A, scheds = [], [], A0, []
     for L in layers:
         for name, lay, slice_h in (("qkv", L.qkv, None), ("attn_out", L.out, h), ("ffn1", L.ffn1, None), ("ffn2", L.ffn2, None)):
             a_in = WL.v_slice(A, slice_h) if slice_h else A
             mfma = lay.W.layout == B.LAYOUT_MFMA
-            out = B._alloc_out(a_in, lay.W, True, B.SYM, h if (mfma and name == "qkv") else 0, lay.W.layout)
+            rg = h if (mfma and name == "qkv") else 0
+            out = B._alloc_out(a_in, lay.W, True, B.SYM, rg, lay.W.layout)
             calls.append(B.PreparedLinear(a_in, lay.W, lay.bias, lay.act, requant=True, requant_mode=B.SYM,
-                                          requant_group=h if (mfma and name == "qkv") else 0, out=out, workspace=ws,
-                                          requant_layout=lay.W.layout))
+                                          requant_group=rg, out=out, workspace=ws, requant_layout=lay.W.layout))
+            scheds.append(B.pick_schedule(a_in, lay.W, requant=True, requant_group=rg, requant_layout=lay.W.layout))
             names.append(name)
             A = B.QAct(out[0], out[1], None, None, M, lay.spec.N, lay.spec.N // 2, 0, B.SYM, 0, lay.W.layout,
                        out[3] if mfma else None)
     stream = B._stream()
-    steps = args.steps
-    timers = [[B.KernelTimer() for _ in range(4)] for _ in range(steps)]
 
     def step(k, tm=None):
         for j in range(4):
@@ -128,8 +247,8 @@ def bench_chain(args):
                 tm[j].arm()                                     # stamps the GEMM kernel's own start and end
             calls[(k % nl) * 4 + j](stream)
 
-    settle(lambda: step(0), args.settle_ms)
-    for k in range(args.warmup):
+    settle(lambda: step(0), settle_ms)
+    for k in range(warmup):
         step(k)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -137,7 +256,7 @@ def bench_chain(args):
         step(k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    # the same steps once more with kernel-boundary events on every GEMM launch (roofline figure)
+    timers = [[B.KernelTimer() for _ in range(4)] for _ in range(steps)]
     for k in range(steps):
         step(k, timers[k])
     torch.cuda.synchronize()
@@ -146,70 +265,262 @@ def bench_chain(args):
     shapes = [(3 * h, h), (h, h), (ffn, h), (h, ffn)]
     ops = sum(2 * M * n * k for n, k in shapes)
     gemm_ms = [sum(timers[k][j].elapsed_ms() for k in range(steps)) / steps for j in range(4)]
-    achieved = ops / (sum(gemm_ms) * 1e-3) / 1e12
+    return {"M": M, "layout": layout, "ms_per_step": ms, "timed_region_s": dt, "ops": ops, "TOPS": ops / (ms * 1e-3) / 1e12,
+            "gemm_ms": gemm_ms, "names": names[:4], "shapes": shapes, "schedules": scheds[:4],
+            "kernel_ms_per_step": sum(gemm_ms), "achieved_TOPS": ops / (sum(gemm_ms) * 1e-3) / 1e12}
+
+
+def bench_chain(args):
+    import torch
+    from paper_2301_12017_amd import binding as B
+    B.lib()
+    torch.cuda.set_device(0)
+    r = chain_leg(args.steps, args.warmup, args.settle_ms)
+    M = r["M"]
     line = {
-        "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
-        "value": ops / (ms * 1e-3) / 1e12, "unit": "TOPS", "n_gpus": 1, "steps": steps, "warmup": args.warmup, "settle_ms": args.settle_ms,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, int4 out)", "data": "synthetic",
+        "metric": METRIC, "value": r["TOPS"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "settle_ms": args.settle_ms, "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": DTYPE.format("int4"), "data": "synthetic",
         "config": {"workload": f"configs[4]: one layer of the chained BERT-large stack, M={M}: qkv, attn_out (V third in "
                                f"place), ffn1+GELU, ffn2, every output requantized per token in the GEMM epilogue",
-                   "step": "4 x w4a4_linear(requant)", "layout": layout},
-        "pct_int8_mfma_peak": 100.0 * ops / (ms * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
-        "per_gemm": [{"name": n, "ms": t, "TOPS": 2 * M * nn * kk / (t * 1e-3) / 1e12}
-                     for n, t, (nn, kk) in zip(names[:4], gemm_ms, shapes)],
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": achieved / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                     "kernel": "gemm_olay_kernel with the fused requantize epilogue, the four launches of the step",
-                     "ops_per_step": ops, "kernel_ms_per_step": sum(gemm_ms)},
+                   "step": "4 x w4a4_linear(requant)", "layout": r["layout"]},
+        "pct_int8_mfma_peak": 100.0 * r["TOPS"] / INT8_MFMA_PEAK_TOPS,
+        "per_gemm": [{"name": n, "ms": t, "TOPS": 2 * M * nn * kk / (t * 1e-3) / 1e12,
+                      "frac": 2 * M * nn * kk / (t * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS}
+                     for n, t, (nn, kk) in zip(r["names"], r["gemm_ms"], r["shapes"])],
+        "roofline": {"bound": "mfma", "achieved": r["achieved_TOPS"], "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                     "frac": r["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS, "traffic": None,
+                     "kernel": "gemm_olay_kernel with the fused requantize epilogue, the four launches of the step; schedules "
+                               + ", ".join(r["schedules"]),
+                     "ops_per_step": r["ops"], "kernel_ms_per_step": r["kernel_ms_per_step"]},
+        "consistency": {"timed_region_s": r["timed_region_s"]},
     }
     print(json.dumps(line))
 
 
-def bench_curve(args):
-    """Sec. 4.1 compares the INT4 with the INT8 GEMM over the token count M for the four encoder shapes.  Here: the
-    fused linears (GEMM + dequantize + fp16 store, operands already quantized), kernel-boundary times."""
+# ------------------------------------------------------------------------------------------ measured ceilings
+def ceilings_leg(settle_ms):
+    """What the device delivers on its own, in this run: the matrix pipe in a register-only MFMA loop (all-zero
+    operands, and INT4 codes with the value distribution of quantized Gaussian data, widened as the GEMM kernels widen
+    them), and the memory system under a coalesced read-only stream and a copy."""
+    import numpy as np
     import torch
-    from paper_2301_12017_amd import binding as B, synth
-    B.lib()
-    torch.cuda.set_device(0)
-    gen = torch.Generator(device="cuda").manual_seed(0)
-    reps = max(args.steps, 5)
-    rows = []
-    for model, h, ffn in (("bert-base", 768, 3072), ("bert-large", 1024, 4096)):
-        for M in (128, 512, 1024, 2048, 4096, 8192, 12288, 16384):
-            for spec in synth._encoder_linears(M, h, ffn):
-                X = torch.randn((M, spec.K), device="cuda", generator=gen).half()
-                W = (torch.randn((spec.N, spec.K), device="cuda", generator=gen) * 0.03).half()
-                layout = B.preferred_layout(M, spec.N, spec.K)
-                W4 = B.quantize_weight(W, B.SYM, 0, layout)
-                A4 = B.quantize_act(X, B.SYM, layout=layout)
-                c4 = B.PreparedLinear(A4, W4, schedule=args.schedule if layout == 1 else 0)
-                w8 = B.quantize_rows8(W)
-                a8 = B.quantize_rows8(X)
-                c8 = B.PreparedLinear8(a8[0], a8[1], w8[0], w8[1])
-                st = B._stream()
-                us = {}
-                for name, call in (("int4", c4), ("int8", c8)):
-                    tms = [B.KernelTimer() for _ in range(reps)]
-                    settle(lambda: call(st), min(args.settle_ms, 100.0))
-                    for t in tms:
-                        t.arm()
-                        call(st)
-                    torch.cuda.synchronize()
-                    us[name] = sum(t.elapsed_ms() for t in tms) / reps * 1e3
-                ops = 2.0 * M * spec.N * spec.K
-                rows.append({"model": model, "M": M, "gemm": spec.name, "N": spec.N, "K": spec.K,
-                             "int4_us": us["int4"], "int8_us": us["int8"],
-                             "int4_TOPS": ops / us["int4"] / 1e6, "int8_TOPS": ops / us["int8"] / 1e6,
-                             "int4_over_int8": us["int8"] / us["int4"]})
-                del X, W, W4, A4, c4, w8, a8, c8
-    print(json.dumps({"metric": "INT4 vs INT8 fused-linear kernel time over the token count (Sec. 4.1 shapes)", "unit": "us / TOPS",
-                      "n_gpus": 1, "data": "synthetic", "reps": reps,
-                      "note": "w4a4_linear against w8a8_linear on operands quantized beforehand, no bias, fp16 out; durations "
-                              "from HIP events at the kernel's own start and end, mean of `reps` launches after up to 100 ms "
-                              "of untimed launches of the same call",
-                      "curve": rows}))
+    from paper_2301_12017_amd import binding as B
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    rng = np.random.default_rng(0)
+    codes = np.clip(np.rint(rng.standard_normal((64, 16, 4)) * 1.9), -7, 7).astype(np.int64)   # per lane, per word, per byte
+    lo = (codes + 8) & 0xF                                            # offset-binary low nibbles: code + 8
+    hi = (codes & 0xF) << 4                                           # two's-complement high nibbles: 16 * code as int8
+    pick = np.zeros((64, 16), dtype=bool)                             # A operands: low type in even words; B: in odd words
+    for w in range(16):
+        pick[:, w] = ((w % 2) == 0) != ((w % 8) >= 4)
+    bytes_ = np.where(pick[:, :, None], lo, hi).astype(np.uint32)
+    words = (bytes_[:, :, 0] | (bytes_[:, :, 1] << 8) | (bytes_[:, :, 2] << 16) | (bytes_[:, :, 3] << 24)).astype(np.uint32)
+    ops_real = torch.from_numpy(words.view(np.int32).copy()).cuda()
+    ops_zero = torch.zeros_like(ops_real)
+    out = {}
+    iters = 4000
+    for name, ops in (("zero_operands", ops_zero), ("int4_codes", ops_real)):
+        settle(lambda: B.probe_mfma(ops, 500, sink), min(settle_ms, 100.0))
+        tms = [B.KernelTimer() for _ in range(5)]
+        n = 0
+        for t in tms:
+            t.arm()
+            n = B.probe_mfma(ops, iters, sink)
+        torch.cuda.synchronize()
+        ms = sorted(t.elapsed_ms() for t in tms)[len(tms) // 2]
+        out[f"mfma_{name}_TOPS"] = n * 65536.0 / (ms * 1e-3) / 1e12
+    nbytes = 1 << 30
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").random_(0, 255)
+    dst = torch.empty(nbytes // 2, dtype=torch.uint8, device="cuda")
+    for name, s_, d_, moved in (("read", src, None, nbytes), ("copy", src[:nbytes // 2], dst, nbytes)):
+        settle(lambda: B.probe_stream(s_, d_, sink), min(settle_ms, 50.0))
+        tms = [B.KernelTimer() for _ in range(5)]
+        for t in tms:
+            t.arm()
+            B.probe_stream(s_, d_, sink)
+        torch.cuda.synchronize()
+        ms = sorted(t.elapsed_ms() for t in tms)[len(tms) // 2]
+        out[f"hbm_{name}_GBps"] = moved / (ms * 1e-3) / 1e9
+    out["note"] = ("register-only v_mfma_i32_32x32x32_i8 loop, two waves per SIMD on every CU (w4a4_probe_mfma), median of five "
+                   "launches; a coalesced 1 GiB read-only stream and a 512 MiB -> 512 MiB copy (w4a4_probe_stream, bytes "
+                   "read + written); nominal peaks: 5000 TOP/s, 8000 GB/s")
+    del src, dst
+    return out
+
+
+# ------------------------------------------------------------------------------------------ latency (workload 2)
+def latency_leg(settle_ms, cold_sets=96):
+    """BERT-base layer linears at batch 1 x seq 128 (configs[1]): launch- and latency-bound."""
+    import torch
+    from paper_2301_12017_amd import binding as B, synth, workloads as WL
+    s2 = synth.config_linears(2)
+    l2 = [WL.make_layer(s, 2, i, keep_host=False) for i, s in enumerate(s2)]
+    x2 = [WL.dev(WL.make_input(s, 2, i)) for i, s in enumerate(s2)]
+    q2 = [B.quantize_act(X, s.mode, s.group) for X, s in zip(x2, s2)]
+    o2 = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(q2, l2)]
+    qc2 = [B.PreparedQuantizeAct(X, qa) for X, qa in zip(x2, q2)]
+    lc2 = [B.PreparedLinear(qa, L.W, L.bias, L.act, out=o) for qa, L, o in zip(q2, l2, o2)]
+
+    def layer2():
+        st = B._stream()
+        for qc, lc in zip(qc2, lc2):
+            qc(st)
+            lc(st)
+    lat_settle = min(settle_ms, 50.0)
+    settle(layer2, lat_settle)
+    reps = 200
+    t1 = time.perf_counter()
+    for _ in range(reps):
+        layer2()
+    torch.cuda.synchronize()
+    us = (time.perf_counter() - t1) * 1e6 / reps
+    # the same eight launches replayed from a HIP graph (Sec. 4.2: a captured graph removes the
+    # launch overhead that dominates at small batch x sequence)
+    graph_us = None
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            layer2()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            layer2()
+        for _ in range(5):
+            gr.replay()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for _ in range(reps):
+            gr.replay()
+        torch.cuda.synchronize()
+        graph_us = (time.perf_counter() - t2) * 1e6 / reps
+    except Exception as ex:                                   # report, never hide
+        graph_us = f"graph capture failed: {ex}"
+    # the same four linears through w4a4_linear_f16act: the activation quantize inside the GEMM kernel,
+    # four launches instead of eight
+    fc2 = [B.PreparedLinearF16Act(X, L.W, L.bias, L.act) for X, L in zip(x2, l2)]
+
+    def layer2_fused():
+        st = B._stream()
+        for fc in fc2:
+            fc(st)
+    settle(layer2_fused, lat_settle)
+    for fc, lc in zip(fc2, lc2):                                 # same bits as the two-call path
+        assert torch.equal(fc.out.view(torch.int16), lc.out[0].view(torch.int16))
+    t4 = time.perf_counter()
+    for _ in range(reps):
+        layer2_fused()
+    torch.cuda.synchronize()
+    fused_us = (time.perf_counter() - t4) * 1e6 / reps
+    # kernel-boundary durations of the four one-launch linears (what a kernel trace reports)
+    ktm = [[B.KernelTimer() for _ in fc2] for _ in range(20)]
+    for row in ktm:
+        st = B._stream()
+        for t, fc in zip(row, fc2):
+            t.arm()
+            fc(st)
+    torch.cuda.synchronize()
+    kernel_us = [sum(row[i].elapsed_ms() for row in ktm) / len(ktm) * 1e3 for i in range(len(fc2))]
+    # floor of eight back-to-back launches on this stream: the smallest quantize_act the library accepts
+    # (one token of 32 elements), eight times
+    tiny_x = torch.zeros((1, 32), dtype=torch.float16, device="cuda")
+    tiny = B.PreparedQuantizeAct(tiny_x, B.quantize_act(tiny_x, B.SYM))
+
+    def eight():
+        st = B._stream()
+        for _ in range(8):
+            tiny(st)
+    settle(eight, lat_settle)
+    t3 = time.perf_counter()
+    for _ in range(reps):
+        eight()
+    torch.cuda.synchronize()
+    floor_us = (time.perf_counter() - t3) * 1e6 / reps
+    # cold: `cold_sets` distinct sets of activations, weights, biases and outputs (about 6.7 MB each, 640 MB in all:
+    # more than the L2 caches and the on-package cache hold), visited round robin, so that every launch fetches its
+    # operands from HBM
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    sets = []
+    for _ in range(cold_sets):
+        calls = []
+        for s, L in zip(s2, l2):
+            X = torch.randn((s.M, s.K), device="cuda", generator=gen).half()
+            W = B.quantize_weight((torch.randn((s.N, s.K), device="cuda", generator=gen) * 0.02).half(), B.SYM)
+            b = (torch.randn((s.N,), device="cuda", generator=gen) * 0.01).half()
+            calls.append(B.PreparedLinearF16Act(X, W, b, L.act))
+        sets.append(calls)
+    torch.cuda.synchronize()
+
+    def cold_pass():
+        st = B._stream()
+        for calls in sets:
+            for c in calls:
+                c(st)
+    cold_pass()
+    torch.cuda.synchronize()
+    t5 = time.perf_counter()
+    for _ in range(2):
+        cold_pass()
+    torch.cuda.synchronize()
+    cold_us = (time.perf_counter() - t5) * 1e6 / (2 * cold_sets)
+    bytes1 = [s.M * s.K * 2 + s.N * s.K // 2 + s.M * s.N * 2 + s.N * 6 for s in s2]     # one-launch path, per linear
+    bytes2 = sum(bytes1)
+    del sets
+    return {"bert_base_layer_b1_s128_us": fused_us, "bert_base_layer_b1_s128_cold_us": cold_us,
+            "bert_base_layer_b1_s128_two_call_us": us, "bert_base_layer_b1_s128_two_call_graph_us": graph_us,
+            "eight_minimal_launches_us": floor_us,
+            "kernel_us": {s.name: t for s, t in zip(s2, kernel_us)},
+            "kernel_GBps_warm": {s.name: b_ / (t * 1e-6) / 1e9 for s, b_, t in zip(s2, bytes1, kernel_us)},
+            "algorithmic_bytes": bytes2,
+            "achieved_GBps_warm": bytes2 / (fused_us * 1e-6) / 1e9,
+            "achieved_GBps_cold": bytes2 / (cold_us * 1e-6) / 1e9,
+            "cold_working_set_MB": bytes2 * cold_sets / 2 ** 20,
+            "note": "bert_base_layer_b1_s128_us: 4 x w4a4_linear_f16act (quantize_act inside the GEMM kernel, "
+                    "one launch per linear, outputs identical to the two-call path), back-to-back layers on one set of "
+                    "operands (warm: weights stay in cache); ..._cold_us: the same four launches over 96 rotating sets of "
+                    "operands and outputs, every byte from HBM; two_call: 4 x (quantize_act + w4a4_linear), eager and "
+                    "replayed from a HIP graph; kernel_us: kernel-boundary durations of the four one-launch kernels; "
+                    "attention, LayerNorm and residuals are outside the path; eight_minimal_launches_us = eight "
+                    "one-token quantize_act launches, the launch floor of eight launches on this stream"}
+
+
+# ------------------------------------------------------------------------------------------ token-wise quantizer alone
+def quantize_leg(specs, layout, settle_ms, nset=8):
+    """w4a4_quantize_act alone at the shapes of the workload, over `nset` rotating inputs (so that nothing is served
+    from cache): HBM-bound, read 2 bytes and write half a byte per element."""
+    import torch
+    from paper_2301_12017_amd import binding as B
+    out = {}
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    for M, K in sorted({(s.M, s.K) for s in specs}):
+        xs = [torch.randn((M, K), device="cuda", generator=gen).half() for _ in range(nset)]
+        calls = [B.PreparedQuantizeAct(x, B._new_qact(M, K, specs[0].mode, specs[0].group, layout, x.device)) for x in xs]
+        st = B._stream()
+        settle(lambda: [c(st) for c in calls], min(settle_ms, 50.0))
+        reps = 25
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            for c in calls:
+                c(st)
+        torch.cuda.synchronize()
+        us = (time.perf_counter() - t0) * 1e6 / (reps * nset)
+        ng = 1 if specs[0].group == 0 else K // specs[0].group
+        nbytes = M * K * 2 + M * K // 2 + M * (8 + (4 * ng if specs[0].mode else 0))
+        out[f"{M}x{K}"] = {"us": us, "algorithmic_bytes": nbytes, "GBps": nbytes / (us * 1e-6) / 1e9,
+                           "frac_of_hbm_peak": nbytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS}
+        del xs, calls
+    out["note"] = "back-to-back launches over eight rotating inputs, launch gaps included; fp16 in, packed codes + scales out"
+    return out
+
+
+def copy_probe(mb):
+    import torch
+    src = torch.empty(mb << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
 
 
 def main():
@@ -218,60 +529,39 @@ def main():
         print("bench.py: this build runs on exactly one GPU (the path is token-parallel with no "
               "exchange); --gpus N with N > 1 is not supported.", file=sys.stderr)
         sys.exit(2)
+    # the CPU oracle first: its worker processes are forked, which must happen before this process touches the GPU
+    cpu = None
+    plain_step = not (args.gemm_curve or args.latency_only or args.quantize_only or args.config == 5)
+    if plain_step and not args.no_cpu_baseline and not args.step_only:
+        cpu = cpu_baseline(args.config, args.cpu_rows)
     if args.gemm_curve:
         return bench_curve(args)
     if args.config == 5:
         return bench_chain(args)
     import torch
-    from paper_2301_12017_amd import binding as B, synth, workloads as WL
+    from paper_2301_12017_amd import binding as B, workloads as WL
     B.lib()
     torch.cuda.set_device(0)
+    if args.latency_only:
+        lat = latency_leg(args.settle_ms)
+        if args.copy_probe_mb:
+            copy_probe(args.copy_probe_mb)
+        print(json.dumps({"metric": "BERT-base layer linears latency b1/s128", "unit": "us", "n_gpus": 1, "data": "synthetic",
+                          "latency": lat}))
+        return
     cfg = args.config
+    wl = StepWorkload(cfg, args.schedule)
+    specs, layers, Xs, outs, stream, schedules = wl.specs, wl.layers, wl.Xs, wl.outs, wl.stream, list(wl.schedules)
+    if args.quantize_only:
+        q = quantize_leg(specs, layers[0].W.layout, args.settle_ms)
+        if args.copy_probe_mb:
+            copy_probe(args.copy_probe_mb)
+        print(json.dumps({"metric": "w4a4_quantize_act alone", "unit": "GB/s", "n_gpus": 1, "data": "synthetic", "quantize_act": q}))
+        return
     side_legs = cfg == 3 and not args.step_only
-    specs = synth.config_linears(cfg)
-    layers = [WL.make_layer(s, cfg, i, keep_host=False) for i, s in enumerate(specs)]
-    Xs = [WL.dev(WL.make_input(s, cfg, i)) for i, s in enumerate(specs)]
-    # everything the step touches is allocated once, outside the timed region
-    qacts = [B.quantize_act(X, s.mode, s.group, layout=L.W.layout) for X, s, L in zip(Xs, specs, layers)]
-    outs = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(qacts, layers)]
-    timers = [[B.KernelTimer() for _ in specs] for _ in range(args.steps)]
-
-    # the calls of a step, with their arguments marshalled once (the timed loop only makes the C calls)
-    stream = B._stream()
-    q_calls = [B.PreparedQuantizeAct(X, qa) for X, qa in zip(Xs, qacts)]
-    l_calls = [B.PreparedLinear(qa, L.W, L.bias, L.act, schedule=args.schedule, out=o)
-               for qa, L, o in zip(qacts, layers, outs)]
-
-    def step(tm=None, st=None):
-        st = stream if st is None else st
-        for i in range(len(specs)):
-            q_calls[i](st)
-            if tm:
-                tm[i].arm()                                     # stamps the GEMM kernel's own start and end
-            l_calls[i](st)
-
-    settle(step, args.settle_ms)
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    ops = sum(2 * s.M * s.N * s.K for s in specs)
-    tops = ops / (ms_per_step * 1e-3) / 1e12
-
-    # the same steps once more with kernel-boundary HIP events on every w4a4_linear launch: the kernel
-    # durations behind the roofline figure (what a kernel trace reports; no dispatch gap in them)
-    for k in range(args.steps):
-        step(timers[k])
-    torch.cuda.synchronize()
-    gemm_ms = [sum(timers[k][i].elapsed_ms() for k in range(args.steps)) / args.steps
-               for i in range(len(specs))]
-    gemm_tops = [2 * s.M * s.N * s.K / (t * 1e-3) / 1e12 for s, t in zip(specs, gemm_ms)]
-    achieved = ops / (sum(gemm_ms) * 1e-3) / 1e12
+    r = wl.measure(args.steps, args.warmup, args.settle_ms)
+    ms_per_step, tops, gemm_ms, achieved, ops = r["ms_per_step"], r["TOPS"], r["gemm_ms"], r["achieved_TOPS"], wl.ops
+    step = wl.step
 
     # ---- the same step replayed from a HIP graph (Sec. 4.2 names graph capture as the cure for launch
     # overhead): reported beside the eager figure, never instead of it
@@ -295,96 +585,9 @@ def main():
     except Exception as ex:                                       # report, never hide
         graph_ms = f"graph capture failed: {ex}"
 
-    # ---- latency leg: BERT-base layer linears at batch 1 x seq 128 (launch/latency-bound)
-    lat = {}
-    if side_legs:
-        s2 = synth.config_linears(2)
-        l2 = [WL.make_layer(s, 2, i, keep_host=False) for i, s in enumerate(s2)]
-        x2 = [WL.dev(WL.make_input(s, 2, i)) for i, s in enumerate(s2)]
-        q2 = [B.quantize_act(X, s.mode, s.group) for X, s in zip(x2, s2)]
-        o2 = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(q2, l2)]
-
-        qc2 = [B.PreparedQuantizeAct(X, qa) for X, qa in zip(x2, q2)]
-        lc2 = [B.PreparedLinear(qa, L.W, L.bias, L.act, out=o) for qa, L, o in zip(q2, l2, o2)]
-
-        def layer2():
-            st = B._stream()
-            for qc, lc in zip(qc2, lc2):
-                qc(st)
-                lc(st)
-        lat_settle = min(args.settle_ms, 50.0)
-        settle(layer2, lat_settle)
-        reps = 200
-        t1 = time.perf_counter()
-        for _ in range(reps):
-            layer2()
-        torch.cuda.synchronize()
-        us = (time.perf_counter() - t1) * 1e6 / reps
-        # the same eight launches replayed from a HIP graph (Sec. 4.2: a captured graph removes the
-        # launch overhead that dominates at small batch x sequence)
-        graph_us = None
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                layer2()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            gr = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gr):
-                layer2()
-            for _ in range(5):
-                gr.replay()
-            torch.cuda.synchronize()
-            t2 = time.perf_counter()
-            for _ in range(reps):
-                gr.replay()
-            torch.cuda.synchronize()
-            graph_us = (time.perf_counter() - t2) * 1e6 / reps
-        except Exception as ex:                                   # report, never hide
-            graph_us = f"graph capture failed: {ex}"
-        # the same four linears through w4a4_linear_f16act: the activation quantize inside the GEMM kernel,
-        # four launches instead of eight
-        fc2 = [B.PreparedLinearF16Act(X, L.W, L.bias, L.act) for X, L in zip(x2, l2)]
-
-        def layer2_fused():
-            st = B._stream()
-            for fc in fc2:
-                fc(st)
-        settle(layer2_fused, lat_settle)
-        for fc, lc in zip(fc2, lc2):                                 # same bits as the two-call path
-            assert torch.equal(fc.out.view(torch.int16), lc.out[0].view(torch.int16))
-        t4 = time.perf_counter()
-        for _ in range(reps):
-            layer2_fused()
-        torch.cuda.synchronize()
-        fused_us = (time.perf_counter() - t4) * 1e6 / reps
-        # floor of eight back-to-back launches on this stream: the smallest quantize_act the library accepts
-        # (one token of 32 elements), eight times
-        tiny_x = torch.zeros((1, 32), dtype=torch.float16, device="cuda")
-        tiny = B.PreparedQuantizeAct(tiny_x, B.quantize_act(tiny_x, B.SYM))
-
-        def eight():
-            st = B._stream()
-            for _ in range(8):
-                tiny(st)
-        settle(eight, lat_settle)
-        t3 = time.perf_counter()
-        for _ in range(reps):
-            eight()
-        torch.cuda.synchronize()
-        floor_us = (time.perf_counter() - t3) * 1e6 / reps
-        bytes2 = sum(s.M * s.K * 2 + s.M * s.K // 2 * 2 + s.N * s.K // 2 + s.M * s.N * 2 for s in s2)
-        lat = {"bert_base_layer_b1_s128_us": fused_us, "bert_base_layer_b1_s128_two_call_us": us,
-               "bert_base_layer_b1_s128_two_call_graph_us": graph_us,
-               "eight_minimal_launches_us": floor_us,
-               "algorithmic_bytes": bytes2,
-               "achieved_GBps_warm": bytes2 / (fused_us * 1e-6) / 1e9,
-               "note": "bert_base_layer_b1_s128_us: 4 x w4a4_linear_f16act (quantize_act inside the GEMM kernel, "
-                       "one launch per linear, outputs identical to the two-call path); two_call: 4 x "
-                       "(quantize_act + w4a4_linear), eager and replayed from a HIP graph; weights warm in cache; "
-                       "attention, LayerNorm and residuals are outside the path; eight_minimal_launches_us = eight "
-                       "one-token quantize_act launches, the launch floor of eight launches on this stream"}
+    lat = latency_leg(args.settle_ms) if side_legs else {}
+    lat_settle = min(args.settle_ms, 50.0)
+    side_steps = min(args.steps, 50)                              # the side legs are context: shorter timed regions
 
     # ---- whole encoder layer at batch 1 x seq 128 (Sec. 4.2: FP16 attention and LayerNorms around the four linears,
     # the launch sequence replayed from a graph): w4a4_encoder_layer, eager and from a HIP graph, under the strategy
@@ -436,22 +639,23 @@ def main():
                          "stand-in (no mask), attention output, residual + LayerNorm, ffn1 + GELU, ffn2, residual + LayerNorm "
                          "= 7 launches in either precision (quantize inside the GEMM kernels); back-to-back calls, weights warm")
 
-    # ---- producer fusion (Sec. 4.2): LayerNorm(x + residual) fused with the token-wise quantize, at the
-    # hidden size of this workload; HBM-bound, so it is reported against the HBM peak.  Four rotating
-    # buffer sets (> the 256 MB on-package cache) so that nothing is served from cache.
-    ln = {}
+    # ---- the token-wise quantizer alone, and producer fusion (Sec. 4.2): LayerNorm(x + residual) fused with the
+    # token-wise quantize, at the hidden size of this workload; HBM-bound, so both are reported against the HBM peak.
+    # Rotating buffer sets (> the 256 MB on-package cache) so that nothing is served from cache.
+    ln, qleg = {}, {}
     if side_legs:
+        qleg = quantize_leg(specs, layers[0].W.layout, args.settle_ms)
         Mh, Kh, nset = specs[0].M, specs[0].K, 4
         rng_t = torch.Generator(device="cuda").manual_seed(0)
         sets = []
         for _ in range(nset):
             x = torch.randn((Mh, Kh), device="cuda", generator=rng_t).half()
-            r = torch.randn((Mh, Kh), device="cuda", generator=rng_t).half()
+            r_ = torch.randn((Mh, Kh), device="cuda", generator=rng_t).half()
             g = (1.0 + 0.1 * torch.randn((Kh,), device="cuda", generator=rng_t)).half()
             b = (0.1 * torch.randn((Kh,), device="cuda", generator=rng_t)).half()
             out = B._new_qact(Mh, Kh, B.SYM, 0, layers[0].W.layout, x.device)
             y = torch.empty((Mh, Kh), dtype=torch.float16, device="cuda")
-            sets.append(B.PreparedLayerNormQuantize(x, r, g, b, 1e-12, out, y))
+            sets.append(B.PreparedLayerNormQuantize(x, r_, g, b, 1e-12, out, y))
         settle(lambda: [c(stream) for c in sets], lat_settle)
         reps_ln = 200
         t5 = time.perf_counter()
@@ -464,6 +668,7 @@ def main():
               "achieved_GBps": ln_bytes / (ln_us * 1e-6) / 1e9, "frac_of_hbm_peak": ln_bytes / (ln_us * 1e-6) / 8e12,
               "note": "w4a4_layernorm_quantize with residual and fp16 copy; back-to-back launches over four "
                       "rotating buffer sets, launch gaps included"}
+        del sets
 
     # ---- the INT8 sibling on the same workload (the paper's Sec. 4.1 comparison, on this hardware): the same
     # step with w8a8_quantize_rows + w8a8_linear, timed the same way
@@ -474,7 +679,7 @@ def main():
         q8_calls = [B.PreparedQuantizeRows8(X, a[0], a[1]) for X, a in zip(Xs, a8)]
         l8_calls = [B.PreparedLinear8(a[0], a[1], w[0], w[1], L.bias, L.act, out=o[0])
                     for a, w, L, o in zip(a8, w8, layers, outs)]
-        t8 = [[B.KernelTimer() for _ in specs] for _ in range(args.steps)]
+        t8 = [[B.KernelTimer() for _ in specs] for _ in range(side_steps)]
 
         def step8(tm=None):
             for i in range(len(specs)):
@@ -487,14 +692,14 @@ def main():
             step8()
         torch.cuda.synchronize()
         t6 = time.perf_counter()
-        for _ in range(args.steps):
+        for _ in range(side_steps):
             step8()
         torch.cuda.synchronize()
-        ms8 = (time.perf_counter() - t6) * 1e3 / args.steps
-        for k in range(args.steps):
+        ms8 = (time.perf_counter() - t6) * 1e3 / side_steps
+        for k in range(side_steps):
             step8(t8[k])
         torch.cuda.synchronize()
-        g8 = [sum(t8[k][i].elapsed_ms() for k in range(args.steps)) / args.steps for i in range(len(specs))]
+        g8 = [sum(t8[k][i].elapsed_ms() for k in range(side_steps)) / side_steps for i in range(len(specs))]
         i8 = {"ms_per_step": ms8, "TOPS": ops / (ms8 * 1e-3) / 1e12, "kernel_ms_per_step": sum(g8),
               "frac_of_int8_mfma_peak": ops / (sum(g8) * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS,
               "per_gemm_ms": {s_.name: t for s_, t in zip(specs, g8)},
@@ -511,16 +716,17 @@ def main():
             Yh = [torch.empty((s_.M, s_.N), dtype=torch.float16, device="cuda") for s_ in specs]
             settle(lambda: [torch.matmul(X, W_.t(), out=Y_) for X, W_, Y_ in zip(Xs, Wh, Yh)], args.settle_ms)   # same treatment
             t7 = time.perf_counter()
-            for _ in range(args.steps):
+            for _ in range(side_steps):
                 for X, W_, Y_ in zip(Xs, Wh, Yh):
                     torch.matmul(X, W_.t(), out=Y_)
             torch.cuda.synchronize()
-            ms16 = (time.perf_counter() - t7) * 1e3 / args.steps
+            ms16 = (time.perf_counter() - t7) * 1e3 / side_steps
             fp16 = {"ms_per_step": ms16, "TFLOPS": ops / (ms16 * 1e-3) / 1e12,
                     "w4a4_step_speedup": ms16 / ms_per_step,
                     "note": "four torch.matmul calls (hipBLASLt FP16, fp32 accumulate) on the same activations and "
                             "shapes, launch gaps included; the W4A4 step it is compared with also contains the four "
                             "quantize_act kernels, bias and GELU"}
+            del Wh, Yh
         except Exception as ex:                                   # context only: never fail the bench over it
             fp16 = {"error": str(ex)}
         try:                                                          # and its INT8 GEMM (int32 out, no epilogue)
@@ -528,11 +734,11 @@ def main():
             w8l = [w[0].t() for w in w8]
             settle(lambda: [torch._int_mm(a_, w_) for a_, w_ in zip(a8l, w8l)], args.settle_ms)
             t8l = time.perf_counter()
-            for _ in range(args.steps):
+            for _ in range(side_steps):
                 for a_, w_ in zip(a8l, w8l):
                     torch._int_mm(a_, w_)
             torch.cuda.synchronize()
-            ms8l = (time.perf_counter() - t8l) * 1e3 / args.steps
+            ms8l = (time.perf_counter() - t8l) * 1e3 / side_steps
             fp16["int8_library_gemm_ms_per_step"] = ms8l
             fp16["int8_library_gemm_TOPS"] = ops / (ms8l * 1e-3) / 1e12
         except Exception as ex:
@@ -560,11 +766,44 @@ def main():
                  "note": "w4a4_strategy_tune: each option = quantize + linear from fp16 to fp16 on synthetic operands, "
                          "20 timed runs back to back; the paper's GPU wanted only ffn1 in INT4 at the three smallest points"}
 
+    # ---- measured ceilings, and the other two large workloads under this run's clock (short legs)
+    ceil, other = {}, {}
+    if side_legs:
+        ceil = ceilings_leg(args.settle_ms)
+        del wl, layers, Xs, outs, step
+        torch.cuda.empty_cache()
+        w4 = StepWorkload(4)
+        r4 = w4.measure(5, 2, args.settle_ms)
+        other["cfg4"] = {"workload": "configs[3]: asymmetric INT4, weight groups of 128, M=16384, BERT-base shapes; "
+                                     "quantize_act + w4a4_linear x 4",
+                         "steps": 5, "ms_per_step": r4["ms_per_step"], "TOPS": r4["TOPS"],
+                         "kernel_ms": r4["kernel_ms_per_step"], "frac": r4["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
+                         "per_gemm_ms": {s_.name: t for s_, t in zip(w4.specs, r4["gemm_ms"])},
+                         "kernel": kernel_label(w4.schedules)}
+        del w4
+        torch.cuda.empty_cache()
+        r5 = chain_leg(5, 2, args.settle_ms)
+        other["cfg5"] = {"workload": "configs[4]: one layer of the chained BERT-large stack, M=32768, every output "
+                                     "requantized in the GEMM epilogue; 4 x w4a4_linear(requant)",
+                         "steps": 5, "ms_per_step": r5["ms_per_step"], "TOPS": r5["TOPS"],
+                         "kernel_ms": r5["kernel_ms_per_step"], "frac": r5["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
+                         "per_gemm_ms": dict(zip(r5["names"], r5["gemm_ms"])),
+                         "kernel": "gemm_olay_kernel with the fused requantize epilogue; schedules " + ", ".join(r5["schedules"])}
+
+    roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+            "frac": achieved / INT8_MFMA_PEAK_TOPS,
+            "traffic": profiled_traffic(schedules) if cfg == 3 else None,
+            "traffic_unit": "HBM-side bytes per step (the four launches), from the rocprofv3 --pmc summary "
+                            "profiles/gemm_config3_hbm_traffic.txt when it was taken on these schedules, else null",
+            "kernel": kernel_label(schedules), "ops_per_step": ops, "kernel_ms_per_step": sum(gemm_ms)}
+    if ceil:
+        roof["measured_peak"] = ceil["mfma_int4_codes_TOPS"]
+        roof["frac_of_measured"] = achieved / ceil["mfma_int4_codes_TOPS"]
     line = {
-        "metric": "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128",
+        "metric": METRIC,
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "settle_ms": args.settle_ms,
         "ms_per_step": ms_per_step, "ms_per_step_graph_replay": graph_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, fp16 out)",
+        "dtype": DTYPE.format("fp16"),
         "data": "synthetic",
         "config": {"workload": f"configs[{cfg - 1}]: " + ", ".join(f"{s.name} {s.M}x{s.N}x{s.K}" for s in specs)
                    + ("; symmetric per-token / per-channel INT4" if cfg != 4 else
@@ -572,29 +811,72 @@ def main():
                    "step": "quantize_act + w4a4_linear (fused GEMM, dequant, bias, GELU on ffn1, fp16 store) x 4",
                    "schedule": args.schedule},
         "pct_int8_mfma_peak": 100.0 * tops / INT8_MFMA_PEAK_TOPS,
-        "per_gemm": [{"name": s.name, "ms": t, "TOPS": g} for s, t, g in zip(specs, gemm_ms, gemm_tops)],
+        "per_gemm": [{"name": s.name, "ms": t, "TOPS": 2 * s.M * s.N * s.K / (t * 1e-3) / 1e12,
+                      "frac": 2 * s.M * s.N * s.K / (t * 1e-3) / 1e12 / INT8_MFMA_PEAK_TOPS, "schedule": n}
+                     for s, t, n in zip(specs, gemm_ms, schedules)],
         "latency": lat,
         "whole_layer_b1_s128": whole,
+        "quantize_act": qleg,
         "producer_fusion": ln,
         "int8_sibling": i8,
         "per_part_strategy": strat,
         "fp16_library_gemm": fp16,
-        "roofline": {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                     "frac": achieved / INT8_MFMA_PEAK_TOPS,
-                     "traffic": PROFILED_TRAFFIC_BYTES.get(cfg) if args.schedule == 0 else None,
-                     "traffic_unit": "bytes per step (the four launches), profiled separately",
-                     "kernel": "gemm_olay_kernel (w4a4_linear), the four launches of the step"
-                               if cfg in (3, 5) else "gemm_kernel (w4a4_linear), the four launches of the step",
-                     "ops_per_step": ops, "kernel_ms_per_step": sum(gemm_ms)},
+        "ceilings": ceil,
+        "other_workloads": other,
+        "roofline": roof,
+        "consistency": {"timed_region_s": r["timed_region_s"]},
     }
     if args.copy_probe_mb:
-        src = torch.empty(args.copy_probe_mb << 20, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(specs, cfg, args.cpu_rows)
+        copy_probe(args.copy_probe_mb)
+    if cpu is not None:
+        line["cpu_baseline"] = cpu
     print(json.dumps(line))
+
+
+def bench_curve(args):
+    """Sec. 4.1 compares the INT4 with the INT8 GEMM over the token count M for the four encoder shapes.  Here: the
+    fused linears (GEMM + dequantize + fp16 store, operands already quantized), kernel-boundary times."""
+    import torch
+    from paper_2301_12017_amd import binding as B, synth
+    B.lib()
+    torch.cuda.set_device(0)
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    reps = max(min(args.steps, 20), 5)
+    rows = []
+    for model, h, ffn in (("bert-base", 768, 3072), ("bert-large", 1024, 4096)):
+        for M in (128, 512, 1024, 2048, 4096, 8192, 12288, 16384):
+            for spec in synth._encoder_linears(M, h, ffn):
+                X = torch.randn((M, spec.K), device="cuda", generator=gen).half()
+                W = (torch.randn((spec.N, spec.K), device="cuda", generator=gen) * 0.03).half()
+                layout = B.preferred_layout(M, spec.N, spec.K)
+                W4 = B.quantize_weight(W, B.SYM, 0, layout)
+                A4 = B.quantize_act(X, B.SYM, layout=layout)
+                c4 = B.PreparedLinear(A4, W4, schedule=args.schedule if layout == 1 else 0)
+                w8 = B.quantize_rows8(W)
+                a8 = B.quantize_rows8(X)
+                c8 = B.PreparedLinear8(a8[0], a8[1], w8[0], w8[1])
+                st = B._stream()
+                us = {}
+                for name, call in (("int4", c4), ("int8", c8)):
+                    tms = [B.KernelTimer() for _ in range(reps)]
+                    settle(lambda: call(st), min(args.settle_ms, 100.0))
+                    for t in tms:
+                        t.arm()
+                        call(st)
+                    torch.cuda.synchronize()
+                    us[name] = sum(t.elapsed_ms() for t in tms) / reps * 1e3
+                ops = 2.0 * M * spec.N * spec.K
+                rows.append({"model": model, "M": M, "gemm": spec.name, "N": spec.N, "K": spec.K,
+                             "int4_us": us["int4"], "int8_us": us["int8"],
+                             "int4_TOPS": ops / us["int4"] / 1e6, "int8_TOPS": ops / us["int8"] / 1e6,
+                             "int4_over_int8": us["int8"] / us["int4"]})
+                del X, W, W4, A4, c4, w8, a8, c8
+    print(json.dumps({"metric": "INT4 vs INT8 fused-linear kernel time over the token count (Sec. 4.1 shapes)", "unit": "us / TOPS",
+                      "n_gpus": 1, "data": "synthetic", "reps": reps,
+                      "note": "w4a4_linear against w8a8_linear on operands quantized beforehand, no bias, fp16 out; durations "
+                              "from HIP events at the kernel's own start and end, mean of `reps` launches after up to 100 ms "
+                              "of untimed launches of the same call",
+                      "curve": rows}))
 
 
 if __name__ == "__main__":

@@ -275,6 +275,25 @@ int w4a4_encoder_layer(const void *X_f16, int batch, int seq, const w4a4_encoder
  * include.  The arming is consumed by that one launch; two NULLs disarm.  Returns W4A4_OK. */
 int w4a4_time_next_gemm(void *start_event, void *stop_event);
 
+/* Measurement probes (no passage of the paper: they give the measured ceilings that a kernel's rate is read
+ * against beside the nominal peaks).  Both launch one kernel on `stream`; w4a4_time_next_gemm arms them like a
+ * GEMM launch, so the caller times them with the same pair of events.
+ *   w4a4_probe_mfma: a register-only loop of independent v_mfma_i32_32x32x32_i8 on every SIMD of the device
+ *     (two waves each, eight accumulators per wave, `iters` rounds).  operands [64 lanes][16] 32-bit words
+ *     (device): per lane two A operands (words 0..3, 8..11) and two B operands (words 4..7, 12..15) of sixteen
+ *     int8 each; the rate depends on their values through the clock the chip keeps (zeros: highest).  Returns
+ *     the number of wave-level MFMA instructions issued (65536 integer operations each) or a w4a4_status < 0.
+ *   w4a4_probe_stream: reads `bytes` (a multiple of 16, 16-byte aligned) from src with coalesced 16-byte loads
+ *     and either writes them to dst (a copy) or, with dst == NULL, stores nothing.  Returns a w4a4_status.
+ *   sink: one device word that the kernels never write in practice (it keeps their loops alive). */
+long w4a4_probe_mfma(const uint32_t *operands, int iters, uint32_t *sink, void *stream);
+int w4a4_probe_stream(const void *src, void *dst, size_t bytes, uint32_t *sink, void *stream);
+
+/* The schedule number (1-based, see w4a4_schedule_name) that w4a4_linear would run this layer on with
+ * ep->schedule as given (0 = the built-in shape table), or a w4a4_status < 0 if it would refuse the layer.
+ * Host arithmetic only; pointers inside A and W are not read. */
+int w4a4_pick_schedule(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep);
+
 /* The layout in which w4a4_linear is fastest for a layer of this shape (Sec. 4.2: the GEMM
  * schedule, and with it the operand layout it reads, is fixed per shape ahead of time).  Both
  * operands of a layer must use the same layout; every layout a layer supports gives identical

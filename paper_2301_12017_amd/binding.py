@@ -99,6 +99,9 @@ _SIGNATURES = {
     "w4a4_encoder_layer": (_i, [_vp, _i, _i, ctypes.POINTER(_LayerWeights), _i, _vp, _vp, _sz, _vp]),
     "w4a4_fused_fault_check": (_i, [_vp]),
     "w4a4_debug_fused_wait": (_i, [_i, _i]),
+    "w4a4_probe_mfma": (ctypes.c_long, [_vp, _i, _vp, _vp]),
+    "w4a4_probe_stream": (_i, [_vp, _vp, _sz, _vp, _vp]),
+    "w4a4_pick_schedule": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue)]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
     "w4a4_dequant_epilogue": (_i, [_vp, ctypes.POINTER(_Act), ctypes.POINTER(_Weight),
                                    ctypes.POINTER(_Epilogue), _vp, _vp, _vp, _vp, _vp]),
@@ -195,6 +198,31 @@ def fused_fault_check() -> bool:
 
 def debug_fused_wait(spin_limit: int = 0, extra_arrivals: int = 0):
     _check(lib().w4a4_debug_fused_wait(spin_limit, extra_arrivals), "w4a4_debug_fused_wait")
+
+
+def pick_schedule(A: "QAct", W: "QWeight", requant=False, requant_mode=SYM, requant_group=0, schedule=0,
+                  requant_layout=LAYOUT_CANONICAL) -> str:
+    """Name of the schedule w4a4_linear runs this layer on."""
+    ep = _Epilogue(None, 0, int(requant), requant_mode, requant_group, requant_layout, schedule)
+    a, w = A.c(), W.c()
+    rc = lib().w4a4_pick_schedule(ctypes.byref(a), ctypes.byref(w), ctypes.byref(ep))
+    if rc < 0:
+        raise W4A4Error(rc, "w4a4_pick_schedule")
+    return schedule_names()[rc - 1]
+
+
+def probe_mfma(operands: torch.Tensor, iters: int, sink: torch.Tensor) -> int:
+    """w4a4_probe_mfma; returns the number of wave-level MFMA instructions the launch issues."""
+    assert operands.dtype == torch.int32 and operands.numel() == 64 * 16 and operands.is_cuda
+    n = lib().w4a4_probe_mfma(_ptr(operands), iters, _ptr(sink), _stream())
+    if n < 0:
+        raise W4A4Error(int(n), "w4a4_probe_mfma")
+    return int(n)
+
+
+def probe_stream(src: torch.Tensor, dst: Optional[torch.Tensor], sink: torch.Tensor):
+    _check(lib().w4a4_probe_stream(_ptr(src), _ptr(dst), src.numel() * src.element_size(), _ptr(sink), _stream()),
+           "w4a4_probe_stream")
 
 
 def preferred_layout(M: int, N: int, K: int, mode=SYM, group=0) -> int:

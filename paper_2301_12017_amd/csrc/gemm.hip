@@ -369,6 +369,27 @@ extern "C" int w4a4_debug_fused_wait(int spin_limit, int extra_arrivals) {
 }
 constexpr int kSpinLimit = 1 << 22;
 
+extern "C" int w4a4_pick_schedule(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep) {
+    int ng = 0;
+    if (!A || !W || !ep) return W4A4_ERR_INVALID_ARG;
+    if (A->K <= 0 || W->N <= 0 || W->K != A->K || A->mode != W->mode || A->layout != W->layout) return W4A4_ERR_INVALID_ARG;
+    const int G = W->group == 0 ? A->K : W->group;
+    if (G <= 0 || A->K % G) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    ng = A->K / G;
+    GemmArgs g;
+    fill_args(g, A, W, ng);
+    if (A->layout == W4A4_LAYOUT_MFMA) g.osum = reinterpret_cast<const int32_t *>(1);   // only tested against NULL here
+    const bool grouped = A->mode == W4A4_ASYM || ng > 1;
+    int out_kind = OUT_F16, schedule = ep->schedule;
+    if (ep->requant) {
+        const int fused = fused_requant_kind(A, W, ep, false);
+        out_kind = !fused ? OUT_F32 : (fused == 2 && ep->requant_layout == W4A4_LAYOUT_MFMA) ? OUT_Q4M : OUT_Q4;
+        if (fused) schedule = fused == 1 ? S_PIPE_128x256 : S_OLAY_128x256;
+    }
+    const int rc = resolve_schedule(g, grouped, out_kind, &schedule);
+    return rc ? rc : schedule;
+}
+
 extern "C" int w4a4_gemm_i32(const w4a4_act *A, const w4a4_weight *W, int32_t *acc, int schedule, void *stream) {
     int ng = 0;
     int rc = check_operands(A, W, &ng);
