@@ -262,7 +262,7 @@ class QAct:
     def c(self) -> _Act:
         osum, ldo = None, 1
         if self.osum is not None:
-            ldo = 1 if self.osum.dim() == 1 else self.osum.shape[1]
+            ldo = 1 if (self.osum.dim() == 1 or self.mode == ASYM) else self.osum.shape[1]
             osum = self.osum.data_ptr() + 4 * self.osum_index
         return _Act(self.q.data_ptr() + self.q_offset_bytes, self.scale.data_ptr(),
                     None if self.zero is None else self.zero.data_ptr(),
@@ -307,7 +307,9 @@ def quantize_weight(W: torch.Tensor, mode=SYM, group=0, layout=LAYOUT_CANONICAL)
     zero = torch.empty((N, ng), dtype=torch.float32, device=dev) if mode == ASYM else None
     gsum = torch.empty((N, ng), dtype=torch.int32, device=dev)
     c = torch.empty((N,), dtype=torch.float32, device=dev)
-    esum = torch.empty((N,), dtype=torch.int32, device=dev) if layout == LAYOUT_MFMA else None
+    esum = None
+    if layout == LAYOUT_MFMA:                             # layout-private sums: [N] (symmetric) or [N, ng + 1] (unsigned)
+        esum = torch.empty((N,) if mode == SYM else (N, ng + 1), dtype=torch.int32, device=dev)
     rc = lib().w4a4_quantize_weight(_ptr(W), N, K, mode, group, _ptr(q), _ptr(scale), _ptr(zero),
                                     _ptr(gsum), _ptr(c), layout, _ptr(esum), _stream())
     _check(rc, "w4a4_quantize_weight")
@@ -325,8 +327,7 @@ def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None,
                    torch.empty((M,), dtype=torch.float32, device=dev),
                    torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
                    torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
-                   M, K, K // 2, group, mode, 0, layout,
-                   torch.empty((M,), dtype=torch.int32, device=dev) if layout == LAYOUT_MFMA else None)
+                   M, K, K // 2, group, mode, 0, layout, _new_osum(M, ng, mode, layout, dev))
     rc = lib().w4a4_quantize_act(_ptr(X), M, K, X.stride(0), mode, group, _ptr(out.q), _ptr(out.scale),
                                  _ptr(out.zero), _ptr(out.gsum), out.layout, _ptr(out.osum), _stream())
     _check(rc, "w4a4_quantize_act")
@@ -339,8 +340,15 @@ def _new_qact(M, K, mode, group, layout, dev) -> QAct:
                 torch.empty((M,), dtype=torch.float32, device=dev),
                 torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
                 torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
-                M, K, K // 2, group, mode, 0, layout,
-                torch.empty((M,), dtype=torch.int32, device=dev) if layout == LAYOUT_MFMA else None)
+                M, K, K // 2, group, mode, 0, layout, _new_osum(M, ng, mode, layout, dev))
+
+
+def _new_osum(M, ng, mode, layout, dev):
+    """Layout-private token sums of the MFMA operand layout: [M] odd-position sums (symmetric codes), or [ng, M]
+    = 128 x the even-position sums of every weight group (unsigned codes)."""
+    if layout != LAYOUT_MFMA:
+        return None
+    return torch.empty((M,) if mode == SYM else (ng, M), dtype=torch.int32, device=dev)
 
 
 def layernorm_quantize(X: torch.Tensor, R: Optional[torch.Tensor], gamma: torch.Tensor, beta: torch.Tensor,

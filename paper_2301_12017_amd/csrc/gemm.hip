@@ -50,10 +50,15 @@ static bool small_ok(const GemmArgs &g, bool grouped, int out_kind) {
            (long)g.M * g.lda < 0x7fffffffL && (long)g.N * g.ldw < 0x7fffffffL && ((long)g.M + 32) * g.N * 4 < 0x7fffffffL;
 }
 
+// LDS of the group kernel: three stages of a 128 x 128 tile (plus, in the operand layout, a column of token sums
+// each), token parameters, and the group tables zw[ng][128] and RA[ng][128]; two workgroups share a CU's 160 KB.
+static bool group_tables_fit(int ng, bool olay) {
+    return (size_t)ng * 256 * 4 + 3 * (256 * 64 + (olay ? 512 : 0)) + 2048 <= 80 * 1024;
+}
 static bool group_ok(const GemmArgs &g, bool grouped) {
     return grouped && g.K % kBK == 0 && g.K >= 2 * kBK && (long)g.M * g.lda < 0x7fffffffL &&
-           (long)g.N * g.ldw < 0x7fffffffL && (long)g.N * g.ng * 4 < 0x7fffffffL && (long)g.M * g.ng * 4 < 0x7fffffffL &&
-           (size_t)g.ng * 256 * 4 + 3 * 256 * 64 + 2048 <= 80 * 1024;
+           (long)g.N * g.ldw < 0x7fffffffL && (long)g.N * (g.ng + 1) * 4 < 0x7fffffffL && (long)g.M * g.ng * 4 < 0x7fffffffL &&
+           group_tables_fit(g.ng, g.osum != nullptr);
 }
 
 // Built-in shape table of the canonical layout: large problems take the pipelined tiles (192 x 128 when the
@@ -121,11 +126,13 @@ static int resolve_schedule(const GemmArgs &g, bool grouped, int out_kind, int *
     if (((long)g.M + 512) * g.N * 4 >= 0x80000000L) return W4A4_ERR_UNSUPPORTED_SHAPE;   // (tile overhang included)
     const bool olay = g.osum != nullptr;                        // operands in the MFMA operand layout
     int sch = *schedule;
-    if (sch == 0) sch = olay ? pick_olay(g) : pick_schedule(g, grouped, out_kind);
+    // operand layout: symmetric per-channel layers run on the persistent kernel, unsigned (grouped) ones on the group kernel
+    if (sch == 0) sch = olay ? (grouped ? S_GROUP : pick_olay(g)) : pick_schedule(g, grouped, out_kind);
     if (sch < 1 || sch > kNumSchedules) return W4A4_ERR_INVALID_ARG;
     const Schedule &s = kSchedules[sch - 1];
     if (grouped && !s.grouped_ok) return W4A4_ERR_INVALID_ARG;
-    if (olay != (s.family == F_OLAY)) return W4A4_ERR_INVALID_ARG;   // a kernel family understands one layout
+    // a kernel family understands one layout, except the group kernel, which reads grouped layers in either
+    if (olay ? !(s.family == (grouped ? F_GROUP : F_OLAY)) : s.family == F_OLAY) return W4A4_ERR_INVALID_ARG;
     const bool q4 = out_kind == OUT_Q4 || out_kind == OUT_Q4M;
     switch (s.family) {
         case F_OLAY:
@@ -183,10 +190,15 @@ static int check_operands(const w4a4_act *A, const w4a4_weight *W, int *ng_out) 
     if (A->layout != W->layout) return W4A4_ERR_INVALID_ARG;
     if (A->layout != W4A4_LAYOUT_CANONICAL && A->layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
     if (A->layout == W4A4_LAYOUT_MFMA) {
-        if (A->mode != W4A4_SYM || A->ldo < 1) return W4A4_ERR_INVALID_ARG;
+        if (A->ldo < 1) return W4A4_ERR_INVALID_ARG;
         if (A->M > 0 && (!A->osum || !W->esum)) return W4A4_ERR_INVALID_ARG;
-        if (W->group != 0 && W->group != W->K) return W4A4_ERR_UNSUPPORTED_SHAPE;
         if (A->K % kBK || A->K < 2 * kBK) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (A->mode == W4A4_SYM) {
+            if (W->group != 0 && W->group != W->K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        } else {                                                // unsigned codes: whole K steps per weight group
+            const int G = W->group == 0 ? W->K : W->group;
+            if (G % kBK || W->K % G || !group_tables_fit(W->K / G, true)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        }
     }
     const int K = A->K;
     if (K % 32 || W->N % 8) return W4A4_ERR_UNSUPPORTED_SHAPE;
@@ -260,9 +272,16 @@ extern "C" int w4a4_schedule_count(void) { return kNumSchedules; }
 
 extern "C" int w4a4_preferred_layout(int M, int N, int K, int mode, int group) {
     (void)N;
-    // the operand layout exists for symmetric per-channel layers whose K the persistent kernel accepts;
+    // the operand layout exists for symmetric per-channel layers whose K the persistent kernel accepts, and for
+    // unsigned codes with weight groups of whole K steps whose tables fit the group kernel's LDS;
     // small token counts (latency-bound, a handful of 128-row tiles) stay on the canonical kernels
-    if (mode != W4A4_SYM || (group != 0 && group != K) || K % kBK || K < 2 * kBK) return W4A4_LAYOUT_CANONICAL;
+    if (K % kBK || K < 2 * kBK || K <= 0) return W4A4_LAYOUT_CANONICAL;
+    if (mode == W4A4_SYM) {
+        if (group != 0 && group != K) return W4A4_LAYOUT_CANONICAL;
+    } else {
+        const int G = group == 0 ? K : group;
+        if (G <= 0 || G % kBK || K % G || !group_tables_fit(K / G, true)) return W4A4_LAYOUT_CANONICAL;
+    }
     return M >= 1536 ? W4A4_LAYOUT_MFMA : W4A4_LAYOUT_CANONICAL;   // (measured crossover between 1024 and 1536 tokens)
 }
 

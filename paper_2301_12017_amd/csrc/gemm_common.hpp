@@ -9,6 +9,32 @@ namespace w4a4 {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+// LDS reads the compiler cannot see.  A read it can see, issued while tile DMAs into LDS are in flight, makes it wait
+// for every one of those DMAs first (it cannot tell which bytes a DMA writes): at the end of a tile that would
+// expose the memory latency of the next tile's prefetch.  The caller guarantees that the bytes were published
+// (their DMA waited for by its wave, then a workgroup barrier) and calls lds_unseen_wait on every value before
+// its first use.  LDS reads return in order, so the compiler's own counts only become more conservative.
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+    return (uint32_t)(uintptr_t)p;                              // the low 32 bits of a generic LDS pointer are its LDS address
+}
+__device__ __forceinline__ v4f lds_unseen_b128(uint32_t addr) {
+    v4f v;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+__device__ __forceinline__ float lds_unseen_b32(uint32_t addr) {
+    float v;
+    asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(addr));
+    return v;
+}
+// waits for every LDS read of the wave; the values named here cannot be used before it
+template <class T>
+__device__ __forceinline__ void lds_unseen_wait(T &v) { asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(v)); }
+template <class T>
+__device__ __forceinline__ void lds_unseen_also(T &v) { asm volatile("" : "+v"(v)); }   // ... behind an earlier wait
 
 constexpr int kBK = 128;           // codes per K step
 constexpr int kRowB = 80;          // LDS row pitch in bytes: 64 of codes + 16 of padding

@@ -503,11 +503,7 @@ void gemm_olay_kernel(GemmArgs g) {
         // ---- epilogue of this tile ------------------------------------------------------------------
         {
             constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
-#ifdef W4A4_EXP_NOSTORE
-            const uint32_t col_off = kPoison;
-#else
             const uint32_t col_off = n_lane < g.N ? (uint32_t)n_lane * ESZ : kPoison;
-#endif
             ChanParams<FN> cp;
 #pragma unroll
             for (int j = 0; j < FN; ++j) {

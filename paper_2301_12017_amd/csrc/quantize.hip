@@ -39,16 +39,25 @@ template <> struct Load8<float> {
 // X: [rows, ldx] elements, first K used.  q: [rows, K/2] bytes.  s,z: [rows].
 // gsum: [rows, ng] code sums over runs of G elements (NULL = not wanted).
 // ITERS = ceil(K / 512): every lane holds ITERS chunks of eight elements.
-// LAYOUT: 0 = canonical nibbles; 1 = MFMA operand layout of activations (even elements in
-// offset binary, psum[row] = sum of the odd-position codes); 2 = MFMA operand layout of
-// weights (nibbles of a byte swapped, odd elements in offset binary, psum[row] = sum of
-// the even-position codes).  Layouts 1 and 2 exist for symmetric codes only.
+// LAYOUT: 0 = canonical nibbles; 1 = MFMA operand layout of activations; 2 = MFMA operand layout of
+// weights (the nibbles of a byte swapped).  In both, the element that lands in the HIGH nibble is stored as a
+// two's-complement value and the one in the LOW nibble as an unsigned one, so that `byte & 0xF0` and `byte & 0x0F`
+// are int8 MFMA operands as they stand:
+//   symmetric codes c in [-8,7]:  high nibble c, low nibble c + 8;
+//   unsigned codes u in [0,15]:   high nibble u - 8, low nibble u.
+// psum receives the code sums the GEMM needs to take the offsets out again:
+//   symmetric, layout 1: psum[row] = sum of the odd-position codes; layout 2: of the even-position codes;
+//   unsigned,  layout 1: psum[g * rows + row] = 128 * (sum of the even-position codes of K-group g), the C operand
+//                        of that group's first MFMAs;
+//   unsigned,  layout 2: psum[row + row / psum_per] = sum of the odd-position codes (rows are (channel, group)
+//                        pairs, psum_per groups per channel: one spare word per channel follows its sums).
 template <int MODE, typename T, int ITERS, int LAYOUT>
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
     const T *__restrict__ X, long ldx, int rows, int K, int G, uint8_t *__restrict__ q,
     float *__restrict__ s, float *__restrict__ z, int32_t *__restrict__ gsum, int ng,
-    int32_t *__restrict__ psum) {
+    int32_t *__restrict__ psum, int psum_per) {
     __shared__ int32_t gs[kRowsPerBlock][kMaxGroups];
+    __shared__ int32_t es[LAYOUT == 1 && MODE == W4A4_ASYM ? kRowsPerBlock : 1][LAYOUT == 1 && MODE == W4A4_ASYM ? kMaxGroups : 1];
     const int wave = threadIdx.x / kWave;
     const int lane = threadIdx.x % kWave;
     const long row = (long)blockIdx.x * kRowsPerBlock + wave;
@@ -80,8 +89,12 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
         s[row] = r.S;
         if (MODE == W4A4_ASYM) z[row] = r.lo;
     }
-    if (gsum) {
-        for (int g = lane; g < ng; g += kWave) gs[wave][g] = 0;
+    constexpr bool GROUP_PSUM = LAYOUT == 1 && MODE == W4A4_ASYM;    // even-position sums per K-group
+    if (gsum || GROUP_PSUM) {
+        for (int g = lane; g < ng; g += kWave) {
+            gs[wave][g] = 0;
+            if (GROUP_PSUM) es[wave][g] = 0;
+        }
         // lanes of one wave run in lockstep and LDS operations of a wave complete in
         // order, so the zeroes land before the adds below.
         __builtin_amdgcn_wave_barrier();
@@ -94,33 +107,42 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_rows_kernel(
         const int c = lane + it * kWave;
         if (c < nchunks) {
             uint32_t packed = 0;
-            int sum = 0;
+            int sum = 0, esum_c = 0;
+            // offset that turns a code into the nibble stored for it: symmetric codes gain 8 in the low nibble,
+            // unsigned ones lose 8 in the high nibble
+            constexpr int kLowAdd = MODE == W4A4_SYM ? 8 : 0, kHighAdd = MODE == W4A4_SYM ? 0 : -8;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 int code = code_of<MODE>(v[it][e], r);
                 sum += code;
                 if (LAYOUT == 0) {
                     packed |= (uint32_t)(code & 0xF) << (4 * e);
-                } else if (LAYOUT == 1) {
-                    if (e & 1) part += code;
-                    packed |= (uint32_t)((code + ((e & 1) ? 0 : 8)) & 0xF) << (4 * e);
-                } else {
-                    if (!(e & 1)) part += code;
-                    packed |= (uint32_t)((code + ((e & 1) ? 8 : 0)) & 0xF) << (4 * (e ^ 1));
+                } else if (LAYOUT == 1) {                        // odd elements sit in the high nibbles
+                    if (MODE == W4A4_SYM) { if (e & 1) part += code; }
+                    else if (!(e & 1)) esum_c += code;
+                    packed |= (uint32_t)((code + ((e & 1) ? kHighAdd : kLowAdd)) & 0xF) << (4 * e);
+                } else {                                         // nibbles swapped: even elements sit in the high nibbles
+                    if (MODE == W4A4_SYM) { if (!(e & 1)) part += code; }
+                    else if (e & 1) part += code;
+                    packed |= (uint32_t)((code + ((e & 1) ? kLowAdd : kHighAdd)) & 0xF) << (4 * (e ^ 1));
                 }
             }
             qr[c] = packed;
             if (gsum) atomicAdd(&gs[wave][c / cpg], sum);
+            if (GROUP_PSUM) atomicAdd(&es[wave][c / cpg], esum_c);
         }
     }
-    if (LAYOUT != 0) {
+    if (LAYOUT != 0 && !GROUP_PSUM) {
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
-        if (lane == 0) psum[row] = part;
+        if (lane == 0) psum[MODE == W4A4_ASYM ? row + row / psum_per : row] = part;
     }
-    if (gsum) {
+    if (gsum || GROUP_PSUM) {
         __builtin_amdgcn_wave_barrier();
-        for (int g = lane; g < ng; g += kWave) gsum[row * (long)ng + g] = gs[wave][g];
+        for (int g = lane; g < ng; g += kWave) {
+            if (gsum) gsum[row * (long)ng + g] = gs[wave][g];
+            if (GROUP_PSUM) psum[(long)g * rows + row] = 128 * es[wave][g];
+        }
     }
 }
 
@@ -212,7 +234,10 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
         // Symmetric codes are produced in offset binary (code + 8: the +8 rides in the constant) so that nibble
         // sums are plain byte sums; one XOR per dword then gives the layout wanted.
         constexpr float kMagic = MODE == W4A4_SYM ? 12582920.0f : 12582912.0f;
-        constexpr uint32_t kFlip = MODE == W4A4_ASYM ? 0u : LAYOUT == 0 ? 0x88888888u : 0x80808080u;
+        // symmetric codes leave offset binary where two's complement is wanted; unsigned codes of the operand
+        // layout lose 8 in the high nibbles (u - 8 in two's complement is u with its top bit flipped)
+        constexpr uint32_t kFlip = LAYOUT != 0 ? 0x80808080u : MODE == W4A4_ASYM ? 0u : 0x88888888u;
+        constexpr bool GROUP_PSUM = LAYOUT != 0 && MODE == W4A4_ASYM;   // 128 * even-position sums per K-group
         uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
         int part = 0, total = 0;
 #pragma unroll
@@ -231,18 +256,27 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
             }
             const bool in = c < nchunks;
             const uint32_t even = packed & 0x0F0F0F0Fu, odd = (packed >> 4) & 0x0F0F0F0Fu;
-            int sum = 0;
+            int sum = 0, esum_c = 0;
             if (gsum) sum = (int)__builtin_amdgcn_sad_u8(even, 0u, __builtin_amdgcn_sad_u8(odd, 0u, 0u)) - (MODE == W4A4_SYM ? 64 : 0);
-            if (LAYOUT != 0 && in) part += (int)__builtin_amdgcn_sad_u8(odd, 0u, 0u) - 32;
+            if (GROUP_PSUM) esum_c = (int)__builtin_amdgcn_sad_u8(even, 0u, 0u);
+            if (LAYOUT != 0 && MODE == W4A4_SYM && in) part += (int)__builtin_amdgcn_sad_u8(odd, 0u, 0u) - 32;
             if (in) {
                 qr[c] = packed ^ kFlip;
                 total += sum;
+                if (GROUP_PSUM) part += esum_c;
             } else {
                 sum = 0;
+                esum_c = 0;
             }
-            if (gsum && ng > 1) {                               // groups of cpg lanes, all inside this `it`
-                for (int o = 1; o < cpg; o <<= 1) sum += __shfl_xor(sum, o, kWave);
-                if ((lane & (cpg - 1)) == 0 && in) gsum[row * (long)ng + c / cpg] = sum;
+            if ((gsum || GROUP_PSUM) && ng > 1) {               // groups of cpg lanes, all inside this `it`
+                for (int o = 1; o < cpg; o <<= 1) {
+                    if (gsum) sum += __shfl_xor(sum, o, kWave);
+                    if (GROUP_PSUM) esum_c += __shfl_xor(esum_c, o, kWave);
+                }
+                if ((lane & (cpg - 1)) == 0 && in) {
+                    if (gsum) gsum[row * (long)ng + c / cpg] = sum;
+                    if (GROUP_PSUM) psum[(long)(c / cpg) * rows + row] = 128 * esum_c;
+                }
             }
         }
         if (gsum && ng == 1) {
@@ -250,10 +284,10 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_stream_kernel(
             for (int o = 32; o > 0; o >>= 1) total += __shfl_xor(total, o, kWave);
             if (lane == 0) gsum[row] = total;
         }
-        if (LAYOUT != 0) {
+        if (LAYOUT != 0 && (!GROUP_PSUM || ng == 1)) {
 #pragma unroll
             for (int o = 32; o > 0; o >>= 1) part += __shfl_xor(part, o, kWave);
-            if (lane == 0) psum[row] = part;
+            if (lane == 0) psum[row] = GROUP_PSUM ? 128 * part : part;
         }
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) cur[it] = nxt[it];
@@ -282,13 +316,13 @@ __global__ void weight_rowsum_kernel(const float *__restrict__ scale, const floa
 
 template <int MODE, typename T, int LAYOUT = 0>
 static int launch_rows(const T *X, long ldx, int rows, int K, int G, uint8_t *q, float *s, float *z,
-                       int32_t *gsum, int ng, hipStream_t st, int32_t *psum = nullptr) {
+                       int32_t *gsum, int ng, hipStream_t st, int32_t *psum = nullptr, int psum_per = 1) {
     if (rows == 0) return W4A4_OK;
     const int iters = (K / 8 + kWave - 1) / kWave;
     dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock), block(kRowsPerBlock * kWave);
 #define W4A4_QL(I)                                                                                  \
     hipLaunchKernelGGL((quantize_rows_kernel<MODE, T, I, LAYOUT>), grid, block, 0, st, X, ldx, rows, K, G, q, \
-                       s, z, gsum, ng, psum)
+                       s, z, gsum, ng, psum, psum_per)
     if (iters <= 1) W4A4_QL(1);
     else if (iters <= 2) W4A4_QL(2);
     else if (iters <= 4) W4A4_QL(4);
@@ -307,7 +341,7 @@ static int launch_stream(const __half *X, long ldx, int rows, int K, int G, uint
                          int32_t *gsum, int ng, hipStream_t st, int32_t *psum) {
     if (rows == 0) return W4A4_OK;
     const int cpg = G / 8;
-    if (gsum && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return -100;
+    if ((gsum || (LAYOUT != 0 && MODE == W4A4_ASYM)) && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return -100;
     const int iters = (K / 8 + kWave - 1) / kWave;
     // One row per wave measured fastest on MI355X (a 12288 x 1024 activation matrix: 8.1 us against 9.6 us
     // with two rows per wave and the second row's loads in flight under the first row's arithmetic): the
@@ -358,15 +392,35 @@ int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int gr
                             : launch_rows<W4A4_ASYM, float>(Y, ld, rows, K, G, q, s, z, gsum, ng, st);
 }
 
-// Layout check shared by the two quantizer entry points.
+// Layout check shared by the two quantizer entry points.  The operand layout exists for symmetric codes with one
+// weight scale per channel and for unsigned codes with weight groups that are multiples of 128 (or one group).
 static int check_layout(int layout, int mode, int group, int K, const void *psum, int rows) {
     if (layout != W4A4_LAYOUT_CANONICAL && layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
     if (layout == W4A4_LAYOUT_MFMA) {
-        if (mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
-        if (group != 0 && group != K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (mode == W4A4_SYM) {
+            if (group != 0 && group != K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        } else {
+            const int G = group == 0 ? K : group;
+            if (G % 128 || K % 128) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        }
         if (rows > 0 && !psum) return W4A4_ERR_INVALID_ARG;
     }
     return W4A4_OK;
+}
+
+// Last word of a channel's row of the operand-layout sums of unsigned weights: the fp32 bits of
+// 8 * sum_g sw[n,g] * (float)WO[n,g], WO = the odd-position code sums in the words before it (ascending g, every
+// operation rounded): what the offsets of the layout add to sum_g sw[n,g] * P_g for every token.
+__global__ void weight_odd_term_kernel(const float *__restrict__ scale, int32_t *__restrict__ esum, int N, int ng) {
+    int n = blockIdx.x * blockDim.x + threadIdx.x;
+    if (n >= N) return;
+    float acc = 0.0f;
+    for (int g = 0; g < ng; ++g) {
+        const float t = scale[(long)n * ng + g] * 8.0f;
+        const float u = t * (float)esum[(long)n * (ng + 1) + g];
+        acc = acc + u;
+    }
+    esum[(long)n * (ng + 1) + ng] = __float_as_int(acc);
 }
 
 }  // namespace w4a4
@@ -384,12 +438,16 @@ extern "C" int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int m
     const int G = group == 0 ? K : group;
     const __half *X = static_cast<const __half *>(X_f16);
     hipStream_t st = as_stream(stream);
-    rc = layout == W4A4_LAYOUT_MFMA ? launch_stream<W4A4_SYM, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, osum)
-         : mode == W4A4_SYM         ? launch_stream<W4A4_SYM, 0>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, nullptr)
-                                    : launch_stream<W4A4_ASYM, 0>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, nullptr);
+    const bool olay = layout == W4A4_LAYOUT_MFMA;
+    rc = olay ? (mode == W4A4_SYM ? launch_stream<W4A4_SYM, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, osum)
+                                  : launch_stream<W4A4_ASYM, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, osum))
+         : mode == W4A4_SYM ? launch_stream<W4A4_SYM, 0>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, nullptr)
+                            : launch_stream<W4A4_ASYM, 0>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, nullptr);
     if (rc != -100) return rc;                                  // else: a shape only the general kernel takes
-    if (layout == W4A4_LAYOUT_MFMA)
-        return launch_rows<W4A4_SYM, __half, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream), osum);
+    if (olay)
+        return mode == W4A4_SYM
+                   ? launch_rows<W4A4_SYM, __half, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream), osum)
+                   : launch_rows<W4A4_ASYM, __half, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream), osum);
     return mode == W4A4_SYM
                ? launch_rows<W4A4_SYM, __half>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream))
                : launch_rows<W4A4_ASYM, __half>(X, ldx, M, K, G, q, scale, zero, gsum, ng, as_stream(stream));
@@ -414,8 +472,10 @@ extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, i
     if (rc) return rc;
     hipStream_t st = as_stream(stream);
     const __half *W = static_cast<const __half *>(W_f16);
-    if (layout == W4A4_LAYOUT_MFMA)
+    if (layout == W4A4_LAYOUT_MFMA && mode == W4A4_SYM)
         rc = launch_rows<W4A4_SYM, __half, 2>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st, esum);
+    else if (layout == W4A4_LAYOUT_MFMA)
+        rc = launch_rows<W4A4_ASYM, __half, 2>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st, esum, ng);
     else
         rc = mode == W4A4_SYM
                  ? launch_rows<W4A4_SYM, __half>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st)
@@ -424,6 +484,10 @@ extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, i
     if (rowsum_deq && N > 0) {
         hipLaunchKernelGGL(weight_rowsum_kernel, dim3((N + 255) / 256), dim3(256), 0, st, scale,
                            mode == W4A4_ASYM ? zero : nullptr, gsum, N, ng, G, rowsum_deq);
+        rc = launch_status();
+    }
+    if (rc == W4A4_OK && layout == W4A4_LAYOUT_MFMA && mode == W4A4_ASYM && N > 0) {
+        hipLaunchKernelGGL(weight_odd_term_kernel, dim3((N + 255) / 256), dim3(256), 0, st, scale, esum, N, ng);
         rc = launch_status();
     }
     return rc;

@@ -43,7 +43,7 @@ ActBuffers carve_act4(Carver &c, int M, int K, const w4a4_weight &w) {
     b.scale = c.take<float>(M);
     b.zero = c.take<float>(M);
     b.gsum = c.take<int32_t>((size_t)M * groups_of(w));
-    b.osum = c.take<int32_t>(M);
+    b.osum = c.take<int32_t>((size_t)M * groups_of(w));         // one word per token (symmetric) or per token and group
     return b;
 }
 w4a4_act view_act4(const ActBuffers &b, int M, int K, const w4a4_weight &w) {

@@ -15,22 +15,25 @@ def host(t):
     return None if t is None else t.detach().cpu().numpy()
 
 
-def act_to_canonical(q):
-    """Bytes of activations in the MFMA operand layout -> canonical bytes (the low nibble is
-    offset binary: flip its top bit).  A pure re-encoding; no arithmetic of the method."""
-    return q ^ np.uint8(0x08)
+def act_to_canonical(q, mode=0):
+    """Bytes of activations in the MFMA operand layout -> canonical bytes.  Symmetric codes: the low nibble is
+    offset binary (flip its top bit); unsigned codes: the high nibble holds u - 8 (flip ITS top bit).
+    A pure re-encoding; no arithmetic of the method."""
+    return q ^ np.uint8(0x08 if mode == 0 else 0x80)
 
 
-def wgt_to_canonical(q):
-    """Bytes of weights in the MFMA operand layout -> canonical bytes (the nibbles are swapped
-    and the low one, the odd element, is offset binary)."""
-    return ((q >> 4) | (((q & 0x0F) ^ 0x08) << 4)).astype(np.uint8)
+def wgt_to_canonical(q, mode=0):
+    """Bytes of weights in the MFMA operand layout -> canonical bytes: the nibbles are swapped; symmetric codes
+    keep the odd element (low nibble) in offset binary, unsigned codes the even element (high nibble) as u - 8."""
+    if mode == 0:
+        return ((q >> 4) | (((q & 0x0F) ^ 0x08) << 4)).astype(np.uint8)
+    return (((q >> 4) ^ 0x08) | ((q & 0x0F) << 4)).astype(np.uint8)
 
 
 def qact_host(A):
     """QAct (device) -> the dict layout the oracle uses (codes in the canonical packing)."""
     q = host(A.q)
-    d = dict(q=act_to_canonical(q) if getattr(A, "layout", 0) == 1 else q, s=host(A.scale))
+    d = dict(q=act_to_canonical(q, A.mode) if getattr(A, "layout", 0) == 1 else q, s=host(A.scale))
     d["z"] = host(A.zero) if A.zero is not None else np.zeros(A.M, np.float32)
     d["gsum"] = host(A.gsum) if A.gsum is not None else None
     return d
@@ -38,7 +41,7 @@ def qact_host(A):
 
 def qweight_host(W):
     q = host(W.q)
-    d = dict(q=wgt_to_canonical(q) if getattr(W, "layout", 0) == 1 else q, s=host(W.scale),
+    d = dict(q=wgt_to_canonical(q, W.mode) if getattr(W, "layout", 0) == 1 else q, s=host(W.scale),
              gsum=host(W.gsum), c=host(W.rowsum_deq))
     d["z"] = host(W.zero) if W.zero is not None else np.zeros_like(d["s"])
     return d
@@ -94,6 +97,33 @@ def assert_f16(got, want, min_same, what=""):
     tiny = np.abs(g - w) <= 2.0 ** -18 * np.sqrt(np.mean(w ** 2))
     same = float(np.mean(steps == 0))
     assert np.all((steps <= 1) | tiny) and same >= min_same, f"{what}: {same:.5f} identical, {int(steps[~tiny].max(initial=0))} steps"
+
+
+def asym_budget(orc, a, w, group):
+    """fp32 rounding noise that ANY evaluation order of the unsigned mapping's dequantize carries, per output element:
+    y = sa*sum_g sw*P_g + sa*sum_g zw*RA + za*c + b is a small difference of large terms (with outlier channels
+    |sa*t1| is hundreds of times |y|), and every one of the ng + 4 roundings on the way costs up to half a unit in
+    the last place of those terms.  Two faithful fp32 evaluations (the oracle's order, a kernel's fused order) can
+    differ by twice that.  a, w: the oracle-style dicts of the (sampled) activations and of the weights."""
+    K = a["q"].shape[1] * 2
+    G = K if group == 0 else group
+    ng = K // G
+    P = orc.gemm_i32(a["q"], w["q"], 1, group).astype(np.float64)              # [ng, M, N]
+    sw, zw = w["s"].reshape(-1, ng).astype(np.float64), w["z"].reshape(-1, ng).astype(np.float64)
+    ra = a["gsum"].reshape(-1, ng).astype(np.float64)
+    sa, za = a["s"].astype(np.float64)[:, None], a["z"].astype(np.float64)[:, None]
+    t1 = np.einsum("gmn,ng->mn", np.abs(P), np.abs(sw))
+    t2 = np.abs(ra) @ np.abs(zw).T
+    mag = np.abs(sa) * (t1 + t2) + np.abs(za) * np.abs(w["c"].astype(np.float64))[None, :]
+    return 2.0 * (ng + 4) * 2.0 ** -24 * mag
+
+
+def f16_close_budget(got_f16, want_f16, budget):
+    """f16_close with a per-element absolute allowance added to the tolerance.  Returns (ok, worst ratio)."""
+    g, w = got_f16.astype(np.float64), want_f16.astype(np.float64)
+    tol = 1e-2 * np.abs(w) + 1e-3 * np.sqrt(np.mean(w ** 2)) + budget
+    ratio = float(np.max(np.abs(g - w) / tol))
+    return ratio <= 1.0, ratio
 
 
 def olay_schedules(B, K):

@@ -107,7 +107,9 @@ def test_quantize_argument_errors(b):
     assert L.w4a4_quantize_act(p, 4, 32768, 32768, 0, 0, p, p, None, None, 0, None, None) == -2
     assert L.w4a4_quantize_act(p, 0, 64, 64, 0, 0, p, p, None, None, 0, None, None) == 0
     assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 0, p, p, None, None, 1, None, None) == -1      # operand layout needs osum
-    assert L.w4a4_quantize_act(p, 4, 64, 64, 1, 0, p, p, p, None, 1, p, None) == -1            # ... and symmetric codes
+    assert L.w4a4_quantize_act(p, 4, 64, 64, 1, 0, p, p, p, None, 1, p, None) == -2            # unsigned codes: whole K steps of 128
+    assert L.w4a4_quantize_act(p, 4, 256, 256, 1, 64, p, p, p, None, 1, p, None) == -2         # ... per weight group
+    assert L.w4a4_quantize_act(p, 4, 256, 256, 1, 128, p, p, p, None, 1, None, None) == -1     # ... and the token sums
     assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 32, p, p, None, None, 1, p, None) == -2        # ... and no K-groups
     assert L.w4a4_quantize_act(p, 4, 64, 64, 0, 0, p, p, None, None, 5, p, None) == -1
     assert L.w4a4_quantize_weight(p, 4, 64, 0, 48, p, p, None, None, None, 0, None, None) == -2

@@ -10,8 +10,8 @@ import numpy as np
 import pytest
 import torch
 
-from tests.gpu_util import (GELU_SAME, OLAY_SAME, act_to_canonical, assert_f16, dev, f16_close, has_gpu, host, qact_host,
-                            qweight_host)
+from tests.gpu_util import (GELU_SAME, OLAY_SAME, act_to_canonical, assert_f16, asym_budget, dev, f16_close,
+                            f16_close_budget, has_gpu, host, qact_host, qweight_host)
 
 pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
 
@@ -40,9 +40,20 @@ def _check_linear_rows(orc, B, spec, layer, X_host, A, Y, rows, exact):
         assert np.array_equal(gw["c"].view(np.uint32), ow["c"].view(np.uint32))
     want = orc.linear(oa, ow, spec.mode, spec.group, layer.host_b, 1 if spec.gelu else 0)
     got = host(Y)[rows]
+    olay = getattr(layer.W, "layout", 0) == 1                      # the kernels that read the MFMA operand layout
+    if spec.mode == 1 and olay:
+        # unsigned codes on the group kernel: same real number, fused operations in another order; the mapping's large
+        # cancelling terms carry fp32 rounding noise in ANY order (see asym_budget), so: tolerance + that budget, and
+        # no further from the float64 evaluation of the dequantized operands than the oracle's own fp32 order is
+        ok, ratio = f16_close_budget(got, want["out"], asym_budget(orc, oa, ow, spec.group))
+        assert ok, f"{spec.name}: tolerance ratio {ratio}"
+        truth = orc.truth64(oa, ow, spec.mode, layer.host_b, 1 if spec.gelu else 0)
+        e_gpu = np.sqrt(np.mean((got.astype(np.float64) - truth) ** 2))
+        e_orc = np.sqrt(np.mean((want["out"].astype(np.float64) - truth) ** 2))
+        assert e_gpu <= 1.5 * e_orc + 1e-7, (spec.name, e_gpu, e_orc)
+        return oa, ow
     ok, ratio = f16_close(got, want["out"])
     assert ok, f"{spec.name}: tolerance ratio {ratio}"
-    olay = getattr(layer.W, "layout", 0) == 1                      # the persistent operand-layout kernel
     assert_f16(got, want["out"], GELU_SAME if spec.gelu else OLAY_SAME if olay else 1.0 if exact else 0.98, spec.name)
     return oa, ow
 
@@ -74,9 +85,11 @@ def test_large_workloads_sampled_rows(env, orc, cfg, nrows):
         oa, ow = _check_linear_rows(orc, B, spec, layer, X, A, Y, rows, exact=True)
         # int32 accumulators of the sampled rows, through the export entry point
         rt = torch.from_numpy(rows).cuda()
-        sub = B.QAct(A.q[rt].contiguous(), A.scale, A.zero, A.gsum, len(rows), spec.K,
-                     spec.K // 2, spec.group, spec.mode, 0, A.layout,
-                     None if A.osum is None else A.osum[rt].contiguous())
+        # (the layout-private token sums are [M] for symmetric codes, [ng, M] for unsigned ones)
+        osum = None if A.osum is None else (A.osum[rt] if spec.mode == 0 else A.osum[:, rt]).contiguous()
+        sub = B.QAct(A.q[rt].contiguous(), A.scale[rt].contiguous(), None if A.zero is None else A.zero[rt].contiguous(),
+                     None if A.gsum is None else A.gsum[rt].contiguous(), len(rows), spec.K,
+                     spec.K // 2, spec.group, spec.mode, 0, A.layout, osum)
         P = host(B.gemm_i32(sub, layer.W))
         assert np.array_equal(P, orc.gemm_i32(oa["q"], ow["q"], spec.mode, spec.group))
         del Y, A, layer

@@ -73,8 +73,8 @@ def test_quantize_weight_operand_layout(B, orc):
 
 def test_layout_argument_errors(B):
     X = torch.zeros((4, 256), dtype=torch.float16, device="cuda")
-    with pytest.raises(B.W4A4Error):
-        B.quantize_act(X, 1, 0, layout=MFMA)                       # asymmetric codes have no operand layout
+    with pytest.raises(B.W4A4Error):                               # unsigned codes: the operand layout needs K % 128 == 0
+        B.quantize_act(torch.zeros((4, 160), dtype=torch.float16, device="cuda"), 1, 0, layout=MFMA)
     A = B.quantize_act(X, SYM, layout=MFMA)
     Wc = B.quantize_weight(torch.zeros((8, 256), dtype=torch.float16, device="cuda"), SYM, 0)
     with pytest.raises(B.W4A4Error):
