@@ -25,5 +25,20 @@ def build(force: bool = False) -> str:
     return LIB
 
 
+CHECK_SRC = os.path.join(HERE, "sanitize_check.c")
+CHECK_BIN = os.path.join(HERE, "sanitize_check")
+CHECK_FLAGS = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-ffp-contract=off",
+               "-fno-fast-math", "-std=c11", "-Wall", "-Wextra"]
+
+
+def build_sanitize_check() -> str:
+    """Compile sanitize_check.c (which includes the oracle's source) with AddressSanitizer and
+    UndefinedBehaviorSanitizer into the executable oracle/sanitize_check; host code only."""
+    newest = max(os.path.getmtime(SRC), os.path.getmtime(CHECK_SRC))
+    if not (os.path.exists(CHECK_BIN) and os.path.getmtime(CHECK_BIN) >= newest):
+        subprocess.run(["gcc", *CHECK_FLAGS, CHECK_SRC, "-o", CHECK_BIN, "-lm"], check=True)
+    return CHECK_BIN
+
+
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))

@@ -3,7 +3,8 @@
 Workloads 1 and 2 are small enough for the oracle to evaluate whole.  For 3, 4 and 5 the GPU
 runs the full problem and the oracle re-computes a seeded sample of token rows (every step of
 the path is independent per token: per-token scales, row-wise GEMM, row-wise requantize), all
-N columns and all K.  Bars as in test_gpu_parity.py: codes / scales / int32 sums bit for bit,
+N columns and all K: 256 rows for workloads 3 and 4, 64 rows of every GEMM of workload 5, spread
+over all 128-row panels.  Bars as in test_gpu_parity.py: codes / scales / int32 sums bit for bit,
 fp16 outputs within 1e-2*|oracle| + 1e-3*rms(oracle) and identical where no GELU is involved.
 """
 import numpy as np
@@ -72,7 +73,21 @@ def test_small_workloads_whole(env, orc, cfg):
         assert np.array_equal(P, orc.gemm_i32(oa["q"], ow["q"], spec.mode, spec.group))
 
 
-@pytest.mark.parametrize("cfg,nrows", [(3, 48), (4, 48)])
+def _stratified_rows(M, nrows, rng):
+    """Rows 0 and M-1 plus an even share of every 128-row panel (the tile row a workgroup owns), so that every
+    XCD's tile range and every round of the persistent walk is sampled."""
+    panels = (M + 127) // 128
+    order = rng.permutation(panels)
+    rows = {0, M - 1}
+    i = 0
+    while len(rows) < nrows:
+        p = int(order[i % panels])
+        rows.add(min(M - 1, p * 128 + int(rng.integers(128))))
+        i += 1
+    return np.array(sorted(rows))
+
+
+@pytest.mark.parametrize("cfg,nrows", [(3, 256), (4, 256)])
 def test_large_workloads_sampled_rows(env, orc, cfg, nrows):
     B, synth, WL = env
     rng = np.random.default_rng(cfg)
@@ -81,7 +96,7 @@ def test_large_workloads_sampled_rows(env, orc, cfg, nrows):
         X = WL.make_input(spec, cfg, i)
         A = B.quantize_act(dev(X), spec.mode, spec.group, layout=layer.W.layout)
         Y = B.linear(A, layer.W, layer.bias, layer.act)
-        rows = np.sort(np.concatenate([[0, spec.M - 1], rng.choice(spec.M, nrows - 2, replace=False)]))
+        rows = _stratified_rows(spec.M, nrows, rng)
         oa, ow = _check_linear_rows(orc, B, spec, layer, X, A, Y, rows, exact=True)
         # int32 accumulators of the sampled rows, through the export entry point
         rt = torch.from_numpy(rows).cuda()
@@ -104,11 +119,11 @@ def test_chained_stack_teacher_forced(env, orc, layout, n_layers):
     Runs in the layout the library prefers for these shapes (the MFMA operand layout, whole stack)
     and, for six layers, in the canonical layout."""
     B, synth, WL = env
-    M, h, ffn, nrows = 32768, 1024, 4096, 6
+    M, h, ffn, nrows = 32768, 1024, 4096, 64
     assert B.preferred_layout(M, 3 * h, h) == 1
     canon = (lambda q: act_to_canonical(q)) if layout == 1 else (lambda q: q)
     rng = np.random.default_rng(5)
-    rows = np.sort(np.concatenate([[0, M - 1], rng.choice(M, nrows - 2, replace=False)]))
+    rows = _stratified_rows(M, nrows, rng)
     rows_t = torch.from_numpy(rows).cuda()
     X = synth.activations(M, h, 0, 5, 0)
     A0 = B.quantize_act(dev(X), B.SYM, layout=layout)
@@ -124,6 +139,7 @@ def test_chained_stack_teacher_forced(env, orc, layout, n_layers):
     del probe
     A = A0
     mismatched = total = 0
+    worst_frac = 0.0
     for l in range(n_layers):
         layer = WL.make_chain(1, h, ffn, M, 5, seed=l, layout=layout)[0]
         rec = []
@@ -147,11 +163,18 @@ def test_chained_stack_teacher_forced(env, orc, layout, n_layers):
                 diff = gc != wc
                 t = want["y"].astype(np.float64) / want["s"].astype(np.float64)[:, None]
                 frac = np.abs(t - np.floor(t) - 0.5)
-                assert np.all(np.abs(gc - wc)[diff] == 1) and np.all(frac[diff] < 1e-3)
+                assert np.all(np.abs(gc - wc)[diff] == 1) and np.all(frac[diff] < 1e-4)
                 mismatched += int(diff.sum())
                 total += diff.size
+                if diff.any():
+                    worst_frac = max(worst_frac, float(frac[diff].max()))
             else:
                 assert np.array_equal(gs.view(np.uint32), want["s"].view(np.uint32)), (l, name)
                 assert np.array_equal(gq, want["q"]), (l, name)
         del layer, rec
-    assert mismatched <= 2e-3 * max(total, 1)
+    # the device GELU is a polynomial, the definition's the erf form: codes after GELU may differ by one where
+    # y / scale lies within 1e-3 of a rounding boundary; how often that happens is printed and bounded
+    rate = mismatched / max(total, 1)
+    print(f"GELU -> requantize, layout {layout}: {mismatched} of {total} codes differ by one ({rate:.2e}); "
+          f"largest distance from the rounding boundary among them {worst_frac:.2e}")
+    assert rate <= 5e-5                                          # measured: 3e-6, boundary distance below 1e-5

@@ -198,8 +198,10 @@ def _requant_compare(orc, want, out, gelu, M, N):
     diff = gc != wc
     t = want["y"].astype(np.float64) / want["s"].astype(np.float64)[:, None]
     frac = np.abs(t - np.floor(t) - 0.5)
-    assert np.all(np.abs(gc - wc)[diff] == 1) and np.all(frac[diff] < 1e-3)
-    assert diff.mean() < 2e-3
+    assert np.all(np.abs(gc - wc)[diff] == 1) and np.all(frac[diff] < 1e-4)
+    print(f"GELU -> requantize {M}x{N}: {int(diff.sum())} of {diff.size} codes differ by one ({diff.mean():.2e}); "
+          f"largest distance from the rounding boundary among them {float(frac[diff].max()) if diff.any() else 0.0:.2e}")
+    assert diff.mean() <= 5e-5
     return gq
 
 
