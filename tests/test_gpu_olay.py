@@ -201,7 +201,7 @@ def _requant_compare(orc, want, out, gelu, M, N):
     assert np.all(np.abs(gc - wc)[diff] == 1) and np.all(frac[diff] < 1e-4)
     print(f"GELU -> requantize {M}x{N}: {int(diff.sum())} of {diff.size} codes differ by one ({diff.mean():.2e}); "
           f"largest distance from the rounding boundary among them {float(frac[diff].max()) if diff.any() else 0.0:.2e}")
-    assert diff.mean() <= 5e-5
+    assert diff.sum() <= max(2, 5e-5 * diff.size)
     return gq
 
 
