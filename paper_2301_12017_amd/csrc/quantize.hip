@@ -334,12 +334,147 @@ static int launch_rows(const T *X, long ldx, int rows, int K, int G, uint8_t *q,
     return launch_status();
 }
 
+// ---- the run-time quantizer of symmetric layers, several tokens per wave ---------------------------------------
+// quantize_stream_kernel spends most of its instructions on what a row costs once (two wave-wide reductions
+// through the LDS crossbar, the division, addressing), and at K = 1024 a lane holds only sixteen elements: a
+// 12288 x 1024 matrix took 6 us of vector-ALU issue per SIMD against 5 us of memory time.  Here a row is owned by
+// LPR = 16, 32 or 64 lanes (the smallest that keeps <= 8 chunks of eight elements per lane), so a wave quantizes
+// 64 / LPR tokens with one instruction stream; reductions inside 16 lanes use the cross-lane operand modes (quad
+// permutes, half-row and row mirror) instead of the LDS; and a code costs four instructions: conversion, multiply,
+// the rounding add, and one shift-add that appends it to the packed word.  The last works because
+// bits(t + 1.5*2^23 + 8) = 0x4B400000 + (code + 8): shifted left by 4e and summed over e (mod 2^32) that is the
+// packed offset-binary word plus the constant 0x3F400000, taken off once per word.
+// Symmetric mapping (Sec. 3.1) only, no K-group sums; LAYOUT 0 (canonical) or 1 (MFMA operand layout of
+// activations, psum[row] = sum of the odd-position codes).  Same arithmetic, same codes as the kernels above.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
+template <int LPR>
+__device__ __forceinline__ float sub_max(float v) {                 // maximum over the LPR lanes that own a row
+    v = fmaxf(v, __int_as_float(dpp_move<0xB1>(__float_as_int(v))));     // quad_perm [1,0,3,2]
+    v = fmaxf(v, __int_as_float(dpp_move<0x4E>(__float_as_int(v))));     // quad_perm [2,3,0,1]
+    v = fmaxf(v, __int_as_float(dpp_move<0x141>(__float_as_int(v))));    // half-row mirror
+    v = fmaxf(v, __int_as_float(dpp_move<0x140>(__float_as_int(v))));    // row mirror
+    if (LPR >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    if (LPR >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+template <int LPR>
+__device__ __forceinline__ int sub_sum(int v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x141>(v);
+    v += dpp_move<0x140>(v);
+    if (LPR >= 32) v += __shfl_xor(v, 16, kWave);
+    if (LPR >= 64) v += __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+template <int LPR, int CPL, int LAYOUT, bool EXACT>          // EXACT: K / 8 == LPR * CPL, no chunk of a lane lies past K
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_sym_rows_kernel(
+    const __half *__restrict__ X, long ldx, int rows, int K, uint8_t *__restrict__ q, float *__restrict__ s,
+    int32_t *__restrict__ psum) {
+    constexpr int RPW = kWave / LPR;                            // tokens per wave
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x % kWave, l = lane % LPR;
+    const long row = ((long)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave) * RPW + lane / LPR;
+    const int nchunks = K / 8;
+    const bool live = row < rows;
+    const u4 *src = reinterpret_cast<const u4 *>(X + (live ? row : (long)rows - 1) * ldx);
+    u4 raw[CPL];
+#pragma unroll
+    for (int it = 0; it < CPL; ++it) {
+        const int c = l + it * LPR;
+        raw[it] = (EXACT || c < nchunks) ? src[c] : u4{0u, 0u, 0u, 0u};   // chunks past K: zeros (code 0, no effect on absmax)
+    }
+    // ---- absmax: |x| of finite fp16 values orders like its 15-bit pattern, so the maximum is taken on packed
+    // unsigned 16-bit integers (exact, and no NaN canonicalisation as a floating-point maximum would add)
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    us2 hi2 = {0, 0};
+#pragma unroll
+    for (int it = 0; it < CPL; ++it)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t d = raw[it][i] & 0x7FFF7FFFu;
+            hi2 = __builtin_elementwise_max(hi2, *reinterpret_cast<const us2 *>(&d));
+        }
+    const unsigned short hmax = hi2[0] > hi2[1] ? hi2[0] : hi2[1];
+    const Range r = range_sym(sub_max<LPR>(__half2float(__ushort_as_half(hmax))));
+    if (l == 0 && live) s[row] = r.S;
+    // ---- codes
+    constexpr float kMagic = 12582920.0f;                       // 1.5 * 2^23 + 8
+    constexpr uint32_t kBits = 0x3F400000u;                     // sum over e of (0x4B400000 << 4e) mod 2^32
+    constexpr uint32_t kFlip = LAYOUT != 0 ? 0x80808080u : 0x88888888u;
+    uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
+    int part = 0;
+#pragma unroll
+    for (int it = 0; it < CPL; ++it) {
+        const int c = l + it * LPR;
+        uint32_t acc = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            // t = (float)x * inv in one instruction: the mixed-precision fused multiply-add with a zero addend reads
+            // the fp16 half directly and rounds the exact product once, as the conversion and the fp32 multiply do
+            const uint32_t w = raw[it][e >> 1];
+            float t;
+            if (e & 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+            else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+            const float u = t + kMagic;
+            acc = (__float_as_uint(u) << (4 * e)) + acc;
+        }
+        const uint32_t packed = acc - kBits;                    // offset binary: nibble e = code + 8
+        if (LAYOUT != 0) part += (int)__builtin_amdgcn_sad_u8((packed >> 4) & 0x0F0F0F0Fu, 0u, 0u) - 32;
+        if (live && (EXACT || c < nchunks)) qr[c] = packed ^ kFlip;
+    }
+    if (LAYOUT != 0) {
+        part = sub_sum<LPR>(part);
+        if (l == 0 && live) psum[row] = part;
+    }
+}
+
+template <int LAYOUT>
+static int launch_sym_rows(const __half *X, long ldx, int rows, int K, uint8_t *q, float *s, hipStream_t st,
+                           int32_t *psum) {
+    if (rows == 0) return W4A4_OK;
+    const int nchunks = K / 8;
+    if (nchunks > 8 * kWave) return -100;
+    const int lpr = nchunks <= 8 * 16 ? 16 : nchunks <= 8 * 32 ? 32 : 64;
+    const int cpl = (nchunks + lpr - 1) / lpr;
+    const long per_block = (long)kRowsPerBlock * (kWave / lpr);
+    dim3 grid((unsigned)((rows + per_block - 1) / per_block)), block(kRowsPerBlock * kWave);
+#define W4A4_QF(L, C)                                                                                       \
+    do {                                                                                                    \
+        if (nchunks == L * C)                                                                               \
+            hipLaunchKernelGGL((quantize_sym_rows_kernel<L, C, LAYOUT, true>), grid, block, 0, st, X, ldx, rows, K, q, s, psum); \
+        else                                                                                                \
+            hipLaunchKernelGGL((quantize_sym_rows_kernel<L, C, LAYOUT, false>), grid, block, 0, st, X, ldx, rows, K, q, s, psum); \
+    } while (0)
+#define W4A4_QFL(L)                                                                                         \
+    do {                                                                                                    \
+        if (cpl <= 2) W4A4_QF(L, 2);                                                                        \
+        else if (cpl <= 4) W4A4_QF(L, 4);                                                                   \
+        else if (cpl <= 6) W4A4_QF(L, 6);                                                                   \
+        else W4A4_QF(L, 8);                                                                                 \
+    } while (0)
+    if (lpr == 16) W4A4_QFL(16);
+    else if (lpr == 32) W4A4_QFL(32);
+    else W4A4_QFL(64);
+#undef W4A4_QFL
+#undef W4A4_QF
+    return launch_status();
+}
+
 // Streaming launch for fp16 activations; returns -100 when the shape needs the general kernel
 // (K-groups whose chunk count is not a power of two <= 64).
 template <int MODE, int LAYOUT>
 static int launch_stream(const __half *X, long ldx, int rows, int K, int G, uint8_t *q, float *s, float *z,
                          int32_t *gsum, int ng, hipStream_t st, int32_t *psum) {
     if (rows == 0) return W4A4_OK;
+    if constexpr (MODE == W4A4_SYM) {                           // no K-group sums wanted: several tokens per wave
+        if (!gsum) {
+            const int rc = launch_sym_rows<LAYOUT>(X, ldx, rows, K, q, s, st, psum);
+            if (rc != -100) return rc;
+        }
+    }
     const int cpg = G / 8;
     if ((gsum || (LAYOUT != 0 && MODE == W4A4_ASYM)) && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return -100;
     const int iters = (K / 8 + kWave - 1) / kWave;
