@@ -51,21 +51,34 @@ typedef enum {
 typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
 
 /* Sec. 4.2 packs two INT4 codes per byte and leaves the nibble encoding open.  Two encodings
- * of SYMMETRIC codes are understood:
- *   CANONICAL  both nibbles are two's complement; element 2j in bits 0..3, 2j+1 in bits 4..7.
+ * are understood:
+ *   CANONICAL  element 2j in bits 0..3, element 2j+1 in bits 4..7; symmetric codes as two's
+ *              complement nibbles, unsigned (asymmetric) codes as they are.
  *   MFMA       chosen so that ONE bitwise AND per register turns packed codes into int8 MFMA
- *              operands.  The int8 value of (byte & 0xF0) is 16*code for a two's-complement
- *              high nibble, and (byte & 0x0F) is code+8 for an offset-binary low nibble, so
- *                activations: low nibble = element 2j   + 8 (offset binary), high nibble =
- *                             element 2j+1 (two's complement)   [= canonical byte XOR 0x08]
- *                weights:     low nibble = element 2j+1 + 8 (offset binary), high nibble =
- *                             element 2j   (two's complement)
- *              and low(A) meets high(W), high(A) meets low(W) in the contraction, which then
- *              yields 16*P + 128*(esum[n] + osum[m]) with
- *                osum[m] = sum of the ODD-position codes of token m   (kept beside the codes),
- *                esum[n] = sum of the EVEN-position codes of channel n (kept beside the codes);
- *              the GEMM removes both terms exactly, in integer arithmetic.
- * The MFMA layout needs mode == SYM, per-channel weight scales (group == 0) and K % 128 == 0. */
+ *              operands: the int8 value of (byte & 0xF0) is 16*v for a two's-complement high
+ *              nibble v, and (byte & 0x0F) is the low nibble read as an unsigned number.  The
+ *              activation byte keeps element 2j in the low and element 2j+1 in the high nibble,
+ *              the weight byte has its nibbles swapped, so that low(A) meets high(W) and
+ *              high(A) meets low(W) in the contraction and every product carries the factor 16.
+ *              The element in the HIGH nibble is stored as a two's-complement value, the one in
+ *              the LOW nibble as an unsigned one:
+ *                symmetric codes c in [-8,7]:  high = c,     low = c + 8
+ *                    [activations: canonical byte XOR 0x08]
+ *                    the contraction yields 16*P + 128*(esum[n] + osum[m]) with
+ *                      osum[m] = sum of the ODD-position codes of token m,
+ *                      esum[n] = sum of the EVEN-position codes of channel n;
+ *                unsigned codes u in [0,15]:   high = u - 8, low = u
+ *                    [activations: canonical byte XOR 0x80]
+ *                    per weight K-group g the contraction yields
+ *                      16*(P_g - 8*AE[m,g] - 8*WO[n,g]) with
+ *                      AE[m,g] = sum of the EVEN-position codes of token m inside group g,
+ *                      WO[n,g] = sum of the ODD-position codes of channel n inside group g.
+ *              The sums travel beside the codes (osum / esum below) and the GEMM removes
+ *              their terms again; int32 results (w4a4_gemm_i32) are exact in both layouts.
+ * The MFMA layout needs K % 128 == 0 and, for symmetric codes, per-channel weight scales
+ * (group == 0); for unsigned codes, weight groups that are multiples of 128 (or one group) whose
+ * tables fit the kernel (K / group <= 32 at K <= 4096).  w4a4_preferred_layout tells whether
+ * w4a4_linear is faster in it for a shape. */
 typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1 } w4a4_layout;
 
 /* Sec. 4.2: GELU (erf form) may sit between the GEMM and the next quantize. */
@@ -84,9 +97,11 @@ typedef struct {
     int group;             /* K-group length the gsum was taken over (0 = whole row)     */
     int mode;              /* w4a4_mode */
     int layout;            /* w4a4_layout of q                                           */
-    const int32_t *osum;   /* layout == MFMA: osum[m*ldo] = sum of the odd-position codes
-                              of the K codes of token m that this view covers; else NULL */
-    int ldo;               /* stride of osum in ELEMENTS (>= 1): a column slice of a wider
+    const int32_t *osum;   /* layout == MFMA, SYM: osum[m*ldo] = sum of the odd-position codes
+                              of the K codes of token m that this view covers.
+                              layout == MFMA, ASYM: osum[g*M + m] = 128 * AE[m,g], group-major
+                              [K/group, M] (ldo is ignored).  Else NULL.                  */
+    int ldo;               /* SYM: stride of osum in ELEMENTS (>= 1): a column slice of a wider
                               matrix points into a [M, slices] array of partial sums     */
 } w4a4_act;
 
@@ -101,8 +116,11 @@ typedef struct {
     int group;                 /* 0 = one group per output channel, else multiple of 128 */
     int mode;                  /* w4a4_mode */
     int layout;                /* w4a4_layout of q                                       */
-    const int32_t *esum;       /* [N] layout == MFMA: sum of the even-position codes of a
-                                  channel; else NULL                                     */
+    const int32_t *esum;       /* layout == MFMA, SYM: [N] sum of the even-position codes of a
+                                  channel.  layout == MFMA, ASYM: [N, ng+1]: WO[n,g] for the ng
+                                  groups of channel n, then one word with the fp32 bits of
+                                  8 * sum_g scale[n,g] * (float)WO[n,g] (ascending g, every
+                                  operation rounded).  Else NULL.                          */
 } w4a4_weight;
 
 /* What happens between the int32 accumulators and memory (Sec. 4.2). */
@@ -339,7 +357,8 @@ int w4a4_debug_fused_wait(int spin_limit, int extra_arrivals);
  * Outputs: q[N,K/2], scale[N,ng], zero[N,ng] (ASYM; may be NULL for SYM),
  * gsum[N,ng] code sums (may be NULL), rowsum_deq[N] (may be NULL; needed for ASYM layers).
  * group: 0 or a multiple of 32 that divides K.
- * layout == W4A4_LAYOUT_MFMA (SYM, group == 0 only) also needs esum[N]; else esum is ignored. */
+ * layout == W4A4_LAYOUT_MFMA also needs esum ([N] for SYM with group == 0; [N, K/group + 1] for ASYM
+ * with K % 128 == 0 and group % 128 == 0, see w4a4_weight); else esum is ignored. */
 int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
                          uint8_t *q, float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
                          int layout, int32_t *esum, void *stream);
@@ -348,7 +367,8 @@ int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
  * ELEMENTS) with the Sec. 3.1 mapping, packed two codes per byte (Sec. 4.2).
  * Outputs: q[M,K/2] (dense rows), scale[M], zero[M] (ASYM only, else may be NULL),
  * gsum[M, K/group] (may be NULL).  K <= 16384.
- * layout == W4A4_LAYOUT_MFMA (SYM only) also needs osum[M]; else osum is ignored. */
+ * layout == W4A4_LAYOUT_MFMA also needs osum ([M] for SYM; [K/group, M] for ASYM with K % 128 == 0 and
+ * group % 128 == 0, see w4a4_act); else osum is ignored. */
 int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
                       uint8_t *q, float *scale, float *zero, int32_t *gsum,
                       int layout, int32_t *osum, void *stream);
@@ -395,7 +415,8 @@ int w4a4_linear_static(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilo
  *   X_f16, R_f16  [M, ldx] fp16 (device; R_f16 may be NULL; 16-byte aligned, ldx*2 % 16 == 0)
  *   gamma_f16, beta_f16  [K] fp16 (device, 16-byte aligned)
  *   Y_f16  [M, K] fp16 or NULL
- *   K % 32 == 0, K <= 4096; groups as for w4a4_quantize_act. */
+ *   K % 32 == 0, K <= 4096; groups as for w4a4_quantize_act.  The MFMA operand layout is produced for
+ *   symmetric codes only (mode == W4A4_ASYM with layout == W4A4_LAYOUT_MFMA returns W4A4_ERR_INVALID_ARG). */
 int w4a4_layernorm_quantize(const void *X_f16, const void *R_f16, int M, int K, int ldx,
                             const void *gamma_f16, const void *beta_f16, float eps, void *Y_f16,
                             int mode, int group, uint8_t *q, float *scale, float *zero, int32_t *gsum,
