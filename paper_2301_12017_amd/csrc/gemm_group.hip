@@ -121,7 +121,7 @@ void gemm_group_kernel(GemmArgs g) {
     // number of loads per K step and one wait count fits all)
     auto dma_col = [&](int stage, int m0, int kt) {
         if constexpr (OLAY)
-            dma4(ae_rsrc, smem + stage * STAGE + CODES + wm * 256, (wm * 64 + lane) * 4, ((kt / spg) * g.M + m0) * 4);
+            dma4(ae_rsrc, smem + stage * STAGE + CODES + wm * 256, (wm * 64 + lane) * 4, ((SPG1 ? kt : kt / spg) * g.M + m0) * 4);
     };
     const __amdgpu_buffer_rsrc_t sa_rsrc = make_rsrc(g.sa, (uint32_t)g.M * 4u);
     const __amdgpu_buffer_rsrc_t za_rsrc = make_rsrc(g.za, MODE == W4A4_ASYM ? (uint32_t)g.M * 4u : 0u);
