@@ -334,18 +334,23 @@ static int launch_rows(const T *X, long ldx, int rows, int K, int G, uint8_t *q,
     return launch_status();
 }
 
-// ---- the run-time quantizer of symmetric layers, several tokens per wave ---------------------------------------
+// ---- the run-time quantizer, several tokens per wave ------------------------------------------------------------
 // quantize_stream_kernel spends most of its instructions on what a row costs once (two wave-wide reductions
 // through the LDS crossbar, the division, addressing), and at K = 1024 a lane holds only sixteen elements: a
 // 12288 x 1024 matrix took 6 us of vector-ALU issue per SIMD against 5 us of memory time.  Here a row is owned by
 // LPR = 16, 32 or 64 lanes (the smallest that keeps <= 8 chunks of eight elements per lane), so a wave quantizes
 // 64 / LPR tokens with one instruction stream; reductions inside 16 lanes use the cross-lane operand modes (quad
-// permutes, half-row and row mirror) instead of the LDS; and a code costs four instructions: conversion, multiply,
-// the rounding add, and one shift-add that appends it to the packed word.  The last works because
-// bits(t + 1.5*2^23 + 8) = 0x4B400000 + (code + 8): shifted left by 4e and summed over e (mod 2^32) that is the
-// packed offset-binary word plus the constant 0x3F400000, taken off once per word.
-// Symmetric mapping (Sec. 3.1) only, no K-group sums; LAYOUT 0 (canonical) or 1 (MFMA operand layout of
-// activations, psum[row] = sum of the odd-position codes).  Same arithmetic, same codes as the kernels above.
+// permutes, half-row and row mirror) instead of the LDS; and a code costs four instructions: conversion fused
+// with the first arithmetic step, the second step, the rounding add, and one shift-add that appends it to the
+// packed word.  The last works because bits(t + 1.5*2^23 + b) = 0x4B400000 + (code + b) (b = 8 for the symmetric
+// mapping, offset binary; 0 for the asymmetric one): shifted left by 4e and summed over e (mod 2^32) that is the
+// packed word plus the constant 0x3F400000, taken off once per word.
+// LAYOUT 0 (canonical) or 1 (MFMA operand layout of activations).  Symmetric mapping (Sec. 3.1): no K-group sums;
+// with LAYOUT 1, psum[row] = sum of the odd-position codes.  Asymmetric mapping: gsum[row * ng + g] = sum of the
+// codes of K-group g (when asked for) and, with LAYOUT 1, psum[g * rows + row] = 128 * (sum of its even-position
+// codes), for groups of 128 elements (the sixteen chunks of a group are the sixteen lanes of a DPP row in one
+// register slot) or one group per row.
+// Same arithmetic, same codes as the kernels above.
 template <int CTRL>
 __device__ __forceinline__ int dpp_move(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true); }
 template <int LPR>
@@ -358,22 +363,28 @@ __device__ __forceinline__ float sub_max(float v) {                 // maximum o
     if (LPR >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
     return v;
 }
-template <int LPR>
-__device__ __forceinline__ int sub_sum(int v) {
+__device__ __forceinline__ int row16_sum(int v) {                   // sum over the sixteen lanes of a DPP row
     v += dpp_move<0xB1>(v);
     v += dpp_move<0x4E>(v);
     v += dpp_move<0x141>(v);
     v += dpp_move<0x140>(v);
+    return v;
+}
+template <int LPR>
+__device__ __forceinline__ int sub_sum(int v) {
+    v = row16_sum(v);
     if (LPR >= 32) v += __shfl_xor(v, 16, kWave);
     if (LPR >= 64) v += __shfl_xor(v, 32, kWave);
     return v;
 }
 
-template <int LPR, int CPL, int LAYOUT, bool EXACT>          // EXACT: K / 8 == LPR * CPL, no chunk of a lane lies past K
-__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_sym_rows_kernel(
+// EXACT: K / 8 == LPR * CPL, no chunk of a lane lies past K.  ng: K-groups of the asymmetric psum (1 or K / 128).
+template <int MODE, int LPR, int CPL, int LAYOUT, bool EXACT>
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_tok_rows_kernel(
     const __half *__restrict__ X, long ldx, int rows, int K, uint8_t *__restrict__ q, float *__restrict__ s,
-    int32_t *__restrict__ psum) {
+    float *__restrict__ z, int32_t *__restrict__ gsum, int32_t *__restrict__ psum, int ng) {
     constexpr int RPW = kWave / LPR;                            // tokens per wave
+    constexpr bool ASYM = MODE == W4A4_ASYM;
     typedef unsigned int u4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x % kWave, l = lane % LPR;
     const long row = ((long)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave) * RPW + lane / LPR;
@@ -381,59 +392,120 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_sym_rows_kernel
     const bool live = row < rows;
     const u4 *src = reinterpret_cast<const u4 *>(X + (live ? row : (long)rows - 1) * ldx);
     u4 raw[CPL];
+    // chunks past K: zeros under the symmetric mapping (code 0, no effect on absmax); the row's first chunk under
+    // the asymmetric one (no effect on minimum and maximum; their codes are neither stored nor summed)
+    u4 fill = {0u, 0u, 0u, 0u};
+    if (ASYM && !EXACT) fill = src[0];
 #pragma unroll
     for (int it = 0; it < CPL; ++it) {
         const int c = l + it * LPR;
-        raw[it] = (EXACT || c < nchunks) ? src[c] : u4{0u, 0u, 0u, 0u};   // chunks past K: zeros (code 0, no effect on absmax)
+        raw[it] = (EXACT || c < nchunks) ? src[c] : fill;
     }
-    // ---- absmax: |x| of finite fp16 values orders like its 15-bit pattern, so the maximum is taken on packed
-    // unsigned 16-bit integers (exact, and no NaN canonicalisation as a floating-point maximum would add)
-    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-    us2 hi2 = {0, 0};
+    Range r;
+    if constexpr (!ASYM) {
+        // ---- absmax: |x| of finite fp16 values orders like its 15-bit pattern, so the maximum is taken on packed
+        // unsigned 16-bit integers (exact, and no NaN canonicalisation as a floating-point maximum would add)
+        typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+        us2 hi2 = {0, 0};
 #pragma unroll
-    for (int it = 0; it < CPL; ++it)
+        for (int it = 0; it < CPL; ++it)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t d = raw[it][i] & 0x7FFF7FFFu;
-            hi2 = __builtin_elementwise_max(hi2, *reinterpret_cast<const us2 *>(&d));
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t d = raw[it][i] & 0x7FFF7FFFu;
+                hi2 = __builtin_elementwise_max(hi2, *reinterpret_cast<const us2 *>(&d));
+            }
+        const unsigned short hmax = hi2[0] > hi2[1] ? hi2[0] : hi2[1];
+        r = range_sym(sub_max<LPR>(__half2float(__ushort_as_half(hmax))));
+        if (l == 0 && live) s[row] = r.S;
+    } else {
+        // ---- minimum and maximum on packed fp16 (exact: the extremes of fp16 values are fp16 values)
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        auto halves = [](uint32_t w) { return __builtin_bit_cast(h2, w); };
+        h2 hi2 = halves(raw[0][0]), lo2 = hi2;
+#pragma unroll
+        for (int it = 0; it < CPL; ++it)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (it == 0 && i == 0) continue;
+                const h2 d = halves(raw[it][i]);
+                hi2 = __builtin_elementwise_max(hi2, d);
+                lo2 = __builtin_elementwise_min(lo2, d);
+            }
+        const float hi = sub_max<LPR>(fmaxf((float)hi2[0], (float)hi2[1]));
+        const float lo = -sub_max<LPR>(-fminf((float)lo2[0], (float)lo2[1]));
+        r = range_asym(lo, hi);
+        if (l == 0 && live) {
+            s[row] = r.S;
+            z[row] = r.lo;
         }
-    const unsigned short hmax = hi2[0] > hi2[1] ? hi2[0] : hi2[1];
-    const Range r = range_sym(sub_max<LPR>(__half2float(__ushort_as_half(hmax))));
-    if (l == 0 && live) s[row] = r.S;
+    }
     // ---- codes
-    constexpr float kMagic = 12582920.0f;                       // 1.5 * 2^23 + 8
+    constexpr float kMagic = ASYM ? 12582912.0f : 12582920.0f;  // 1.5 * 2^23 (+ 8: offset binary)
     constexpr uint32_t kBits = 0x3F400000u;                     // sum over e of (0x4B400000 << 4e) mod 2^32
-    constexpr uint32_t kFlip = LAYOUT != 0 ? 0x80808080u : 0x88888888u;
+    // symmetric codes leave offset binary where two's complement is wanted; unsigned codes of the operand layout
+    // lose 8 in the high nibbles (u - 8 in two's complement is u with its top bit flipped)
+    constexpr uint32_t kFlip = LAYOUT != 0 ? 0x80808080u : ASYM ? 0u : 0x88888888u;
+    const float neg_lo = -r.lo;
     uint32_t *qr = reinterpret_cast<uint32_t *>(q + row * (long)(K / 2));
-    int part = 0;
+    int part = 0, total = 0;
 #pragma unroll
     for (int it = 0; it < CPL; ++it) {
         const int c = l + it * LPR;
+        const bool in = EXACT || c < nchunks;
         uint32_t acc = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            // t = (float)x * inv in one instruction: the mixed-precision fused multiply-add with a zero addend reads
-            // the fp16 half directly and rounds the exact product once, as the conversion and the fp32 multiply do
+            // the mixed-precision fused multiply-add reads the fp16 half directly and rounds once: with a zero
+            // addend it is the conversion and the fp32 multiply, t = (float)x * inv; with the factor 1 it is the
+            // conversion and the fp32 subtraction, d = (float)x - lo
             const uint32_t w = raw[it][e >> 1];
             float t;
-            if (e & 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
-            else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+            if constexpr (!ASYM) {
+                if (e & 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+                else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+            } else {
+                float d;
+                if (e & 1) asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(neg_lo));
+                else asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(w), "v"(neg_lo));
+                t = d * r.inv;
+            }
             const float u = t + kMagic;
             acc = (__float_as_uint(u) << (4 * e)) + acc;
         }
-        const uint32_t packed = acc - kBits;                    // offset binary: nibble e = code + 8
-        if (LAYOUT != 0) part += (int)__builtin_amdgcn_sad_u8((packed >> 4) & 0x0F0F0F0Fu, 0u, 0u) - 32;
-        if (live && (EXACT || c < nchunks)) qr[c] = packed ^ kFlip;
+        const uint32_t packed = acc - kBits;                    // nibble e = code (+ 8 under the symmetric mapping)
+        if (live && in) qr[c] = packed ^ kFlip;
+        if (LAYOUT != 0 && !ASYM) part += (int)__builtin_amdgcn_sad_u8((packed >> 4) & 0x0F0F0F0Fu, 0u, 0u) - 32;
+        if constexpr (ASYM) {
+            // both sums of a chunk ride in one register: all eight codes above bit 16, the even positions below
+            // (a K-group of 128 holds at most 64 * 15 there)
+            const uint32_t ev = __builtin_amdgcn_sad_u8(packed & 0x0F0F0F0Fu, 0u, 0u);
+            const uint32_t all = __builtin_amdgcn_sad_u8((packed >> 4) & 0x0F0F0F0Fu, 0u, ev);
+            const int both = in ? (int)((all << 16) | ev) : 0;
+            if (ng == 1) {
+                part += both & 0xFFFF;
+                total += both >> 16;
+            } else if (LAYOUT != 0 || gsum) {                   // chunks 16 j .. 16 j + 15 are K-group j
+                const int gs = row16_sum(both);
+                if ((l & 15) == 0 && live && in) {
+                    if (LAYOUT != 0) psum[(long)(c >> 4) * rows + row] = 128 * (gs & 0xFFFF);
+                    if (gsum) gsum[row * (long)ng + (c >> 4)] = gs >> 16;
+                }
+            }
+        }
     }
-    if (LAYOUT != 0) {
+    if (ASYM && ng == 1 && gsum) {
+        total = sub_sum<LPR>(total);
+        if (l == 0 && live) gsum[row] = total;
+    }
+    if (LAYOUT != 0 && (!ASYM || ng == 1)) {
         part = sub_sum<LPR>(part);
-        if (l == 0 && live) psum[row] = part;
+        if (l == 0 && live) psum[row] = ASYM ? 128 * part : part;
     }
 }
 
-template <int LAYOUT>
-static int launch_sym_rows(const __half *X, long ldx, int rows, int K, uint8_t *q, float *s, hipStream_t st,
-                           int32_t *psum) {
+template <int MODE, int LAYOUT>
+static int launch_tok_rows(const __half *X, long ldx, int rows, int K, uint8_t *q, float *s, float *z,
+                           int32_t *gsum, hipStream_t st, int32_t *psum, int ng) {
     if (rows == 0) return W4A4_OK;
     const int nchunks = K / 8;
     if (nchunks > 8 * kWave) return -100;
@@ -444,9 +516,9 @@ static int launch_sym_rows(const __half *X, long ldx, int rows, int K, uint8_t *
 #define W4A4_QF(L, C)                                                                                       \
     do {                                                                                                    \
         if (nchunks == L * C)                                                                               \
-            hipLaunchKernelGGL((quantize_sym_rows_kernel<L, C, LAYOUT, true>), grid, block, 0, st, X, ldx, rows, K, q, s, psum); \
+            hipLaunchKernelGGL((quantize_tok_rows_kernel<MODE, L, C, LAYOUT, true>), grid, block, 0, st, X, ldx, rows, K, q, s, z, gsum, psum, ng); \
         else                                                                                                \
-            hipLaunchKernelGGL((quantize_sym_rows_kernel<L, C, LAYOUT, false>), grid, block, 0, st, X, ldx, rows, K, q, s, psum); \
+            hipLaunchKernelGGL((quantize_tok_rows_kernel<MODE, L, C, LAYOUT, false>), grid, block, 0, st, X, ldx, rows, K, q, s, z, gsum, psum, ng); \
     } while (0)
 #define W4A4_QFL(L)                                                                                         \
     do {                                                                                                    \
@@ -469,13 +541,13 @@ template <int MODE, int LAYOUT>
 static int launch_stream(const __half *X, long ldx, int rows, int K, int G, uint8_t *q, float *s, float *z,
                          int32_t *gsum, int ng, hipStream_t st, int32_t *psum) {
     if (rows == 0) return W4A4_OK;
-    if constexpr (MODE == W4A4_SYM) {                           // no K-group sums wanted: several tokens per wave
-        if (!gsum) {
-            const int rc = launch_sym_rows<LAYOUT>(X, ldx, rows, K, q, s, st, psum);
-            if (rc != -100) return rc;
-        }
-    }
     const int cpg = G / 8;
+    // several tokens per wave: symmetric layers that want no K-group sums, asymmetric ones whose sums are per
+    // row or per group of 128
+    if (MODE == W4A4_SYM ? !gsum : (ng == 1 || cpg == 16)) {
+        const int rc = launch_tok_rows<MODE, LAYOUT>(X, ldx, rows, K, q, s, z, gsum, st, psum, ng);
+        if (rc != -100) return rc;
+    }
     if ((gsum || (LAYOUT != 0 && MODE == W4A4_ASYM)) && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return -100;
     const int iters = (K / 8 + kWave - 1) / kWave;
     // One row per wave measured fastest on MI355X (a 12288 x 1024 activation matrix: 8.1 us against 9.6 us

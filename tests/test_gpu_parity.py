@@ -399,3 +399,35 @@ def test_quantize_act_many_short_rows(B, orc, layout, M, K, ldx):
     if layout == 1:
         odd = orc.unpack(want["q"], 0).astype(np.int64)[:, 1::2].sum(axis=1)
         assert np.array_equal(host(A.osum).astype(np.int64), odd)
+
+
+@pytest.mark.parametrize("layout", [0, 1])
+@pytest.mark.parametrize("M,K,ldx,group", [(8193, 640, 648, 128), (8195, 1280, 1280, 128), (4100, 2560, 2568, 128),
+                                           (9001, 96, 104, 0), (8200, 992, 1000, 0), (8191, 384, 384, 0),
+                                           (4097, 3072, 3072, 128)])
+def test_quantize_act_many_rows_asymmetric(B, orc, layout, M, K, ldx, group):
+    """Thousands of asymmetric rows, several tokens per wave: odd row counts, chunk counts that do not fill the lanes
+    of a token, strided rows, K-groups of 128 and one group per row, in both layouts; every output against the
+    oracle (codes, scales, minima, K-group code sums, and the operand layout's 128 x even-position sums)."""
+    from tests.gpu_util import act_to_canonical
+    if layout == 1 and K % 128:
+        pytest.skip("the operand layout of unsigned codes takes K in multiples of 128")
+    rng = np.random.default_rng(M + K + group)
+    Xw = (rng.standard_normal((M, ldx)) * rng.uniform(0.1, 4.0, size=(M, 1)) + rng.uniform(-2.0, 2.0, size=(M, 1)))
+    Xw = Xw.astype(np.float32).astype(np.float16)
+    Xw[5, :] = 0                                              # an all-zero token
+    Xw[6, :] = np.float16(-3.25)                              # a constant token
+    Xw[M - 1, :K] = np.float16(65504.0)                       # the last row: top of the fp16 range ...
+    Xw[M - 1, K - 1] = np.float16(-65504.0)                   # ... to its bottom, in the last chunk
+    Xd = dev(Xw)
+    A = B.quantize_act(Xd[:, :K], ASYM, group, layout=layout)
+    want = orc.quantize_act(np.ascontiguousarray(Xw[:, :K]), ASYM, group)
+    q = host(A.q)
+    assert np.array_equal(act_to_canonical(q, ASYM) if layout == 1 else q, want["q"])
+    assert np.array_equal(host(A.scale).view(np.uint32), want["s"].view(np.uint32))
+    assert np.array_equal(host(A.zero).view(np.uint32), want["z"].view(np.uint32))
+    assert np.array_equal(host(A.gsum), want["gsum"])
+    if layout == 1:
+        G = K if group == 0 else group
+        even = orc.unpack(want["q"], ASYM).astype(np.int64).reshape(M, K // G, G)[:, :, 0::2].sum(axis=2)
+        assert np.array_equal(host(A.osum).astype(np.int64), 128 * even.T)
