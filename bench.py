@@ -38,6 +38,9 @@ def parse():
     p.add_argument("--warmup", type=int, default=10)
     p.add_argument("--config", type=int, default=3, help="workload number (3 = headline, 4 = asymmetric/grouped, 5 = one layer of the chained stack)")
     p.add_argument("--schedule", type=int, default=0, help="force a GEMM tile schedule (0 = built-in table)")
+    p.add_argument("--layout", type=int, default=-1,
+                   help="operand layout of the step's layers (-1 = what the library prefers for the shape; 0 canonical, "
+                        "1 int8-MFMA operand layout, 2 FP6 operand layout)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--settle-ms", type=float, default=300.0,
                    help="untimed steps run for this long before the warm-up steps: after an idle phase the chip's "
@@ -134,7 +137,7 @@ def cpu_baseline(cfg, rows):
 
 # ------------------------------------------------------------------------------------------ workloads 3 and 4
 KERNEL_NAMES = {"olay": "gemm_olay_kernel", "group": "gemm_group_kernel", "pipe": "gemm_pipe_kernel",
-                "generic": "gemm_kernel", "small": "linear_f16act_kernel"}
+                "generic": "gemm_kernel", "small": "linear_f16act_kernel", "fp6": "gemm_fp6_kernel"}
 
 
 def kernel_label(schedules):
@@ -146,12 +149,13 @@ def kernel_label(schedules):
 class StepWorkload:
     """quantize_act + w4a4_linear for the four linears of workload `cfg`, everything allocated and marshalled once."""
 
-    def __init__(self, cfg, schedule=0):
+    def __init__(self, cfg, schedule=0, layout=-1):
         import torch
         from paper_2301_12017_amd import binding as B, synth, workloads as WL
         self.cfg, self.B = cfg, B
         self.specs = synth.config_linears(cfg)
-        self.layers = [WL.make_layer(s, cfg, i, keep_host=False) for i, s in enumerate(self.specs)]
+        self.layers = [WL.make_layer(s, cfg, i, keep_host=False, layout=None if layout < 0 else layout)
+                       for i, s in enumerate(self.specs)]
         self.Xs = [WL.dev(WL.make_input(s, cfg, i)) for i, s in enumerate(self.specs)]
         self.qacts = [B.quantize_act(X, s.mode, s.group, layout=L.W.layout) for X, s, L in zip(self.Xs, self.specs, self.layers)]
         self.outs = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(self.qacts, self.layers)]
@@ -550,7 +554,7 @@ def main():
                           "latency": lat}))
         return
     cfg = args.config
-    wl = StepWorkload(cfg, args.schedule)
+    wl = StepWorkload(cfg, args.schedule, args.layout)
     specs, layers, Xs, outs, stream, schedules = wl.specs, wl.layers, wl.Xs, wl.outs, wl.stream, list(wl.schedules)
     if args.quantize_only:
         q = quantize_leg(specs, layers[0].W.layout, args.settle_ms)

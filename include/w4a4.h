@@ -78,8 +78,24 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  * The MFMA layout needs K % 128 == 0 and, for symmetric codes, per-channel weight scales
  * (group == 0); for unsigned codes, weight groups that are multiples of 128 (or one group) whose
  * tables fit the kernel (K / group <= 32 at K <= 4096).  w4a4_preferred_layout tells whether
- * w4a4_linear is faster in it for a shape. */
-typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1 } w4a4_layout;
+ * w4a4_linear is faster in it for a shape.
+ *   FP6        not a nibble encoding: every symmetric code c in [-7, 7] (the range the quantizers
+ *              produce; -8 does not exist here) is stored as the 6-bit FP6 E2M3 number of the same
+ *              value (sign, two exponent bits, three mantissa bits), 3/4 byte per code, so that the
+ *              GEMM runs on the FP6 form of the matrix instruction with FP32 accumulation: products
+ *              and sums of such integers are exact in FP32 below 2^24, i.e. the accumulator IS the
+ *              INT32 result of the integer GEMM (Sec. 4.2 counts on INT4 tensor cores at twice the
+ *              INT8 rate; on gfx950 that pipe is the FP6 one).  A row of K codes is K/32 operands of
+ *              32 codes = 24 bytes; operand 2b + h lies in the row's 48-byte block b as 16 bytes at
+ *              16h and 8 bytes at 32 + 8h.  Which codes an operand holds depends on K alone:
+ *              with LPR the largest of 64, 32, 16, 8 that divides K/32 with a quotient OPL <= 6,
+ *              operand o*LPR + l holds the four 8-code chunks l + LPR*(4o + j), j = 0..3, element e
+ *              of chunk j in 6-bit field 2*(8*(j&1) + e) + (j>>1) (fields little-endian in the 24
+ *              bytes).  Activations and weights use the same rule, so the contraction over K is
+ *              unchanged.  Rows are 3K/4 bytes (lda of a w4a4_act in bytes, as always).
+ * The FP6 layout needs symmetric codes, one scale per token / output channel (group == 0),
+ * K % 256 == 0 with such an LPR, and K >= 512 for the GEMM; no code sums travel with it. */
+typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1, W4A4_LAYOUT_FP6 = 2 } w4a4_layout;
 
 /* Sec. 4.2: GELU (erf form) may sit between the GEMM and the next quantize. */
 typedef enum { W4A4_ACT_NONE = 0, W4A4_ACT_GELU = 1 } w4a4_act_fn;
@@ -358,7 +374,9 @@ int w4a4_debug_fused_wait(int spin_limit, int extra_arrivals);
  * gsum[N,ng] code sums (may be NULL), rowsum_deq[N] (may be NULL; needed for ASYM layers).
  * group: 0 or a multiple of 32 that divides K.
  * layout == W4A4_LAYOUT_MFMA also needs esum ([N] for SYM with group == 0; [N, K/group + 1] for ASYM
- * with K % 128 == 0 and group % 128 == 0, see w4a4_weight); else esum is ignored. */
+ * with K % 128 == 0 and group % 128 == 0, see w4a4_weight); else esum is ignored.
+ * layout == W4A4_LAYOUT_FP6 (SYM, group == 0, a K the layout exists for: see w4a4_layout): q is
+ * [N, 3K/4]; gsum[N] = the code sum of a channel. */
 int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
                          uint8_t *q, float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
                          int layout, int32_t *esum, void *stream);
@@ -368,7 +386,9 @@ int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
  * Outputs: q[M,K/2] (dense rows), scale[M], zero[M] (ASYM only, else may be NULL),
  * gsum[M, K/group] (may be NULL).  K <= 16384.
  * layout == W4A4_LAYOUT_MFMA also needs osum ([M] for SYM; [K/group, M] for ASYM with K % 128 == 0 and
- * group % 128 == 0, see w4a4_act); else osum is ignored. */
+ * group % 128 == 0, see w4a4_act); else osum is ignored.
+ * layout == W4A4_LAYOUT_FP6 (SYM, group == 0, a K the layout exists for): q is [M, 3K/4] dense rows; gsum
+ * must be NULL (W4A4_ERR_UNSUPPORTED_SHAPE otherwise). */
 int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
                       uint8_t *q, float *scale, float *zero, int32_t *gsum,
                       int layout, int32_t *osum, void *stream);

@@ -14,7 +14,19 @@ import torch
 
 SYM, ASYM = 0, 1
 ACT_NONE, ACT_GELU = 0, 1
-LAYOUT_CANONICAL, LAYOUT_MFMA = 0, 1
+LAYOUT_CANONICAL, LAYOUT_MFMA, LAYOUT_FP6 = 0, 1, 2
+
+
+def _row_bytes(K, layout):
+    """Bytes of a row of K codes: two per byte, or 3/4 byte each in the FP6 operand layout."""
+    return K // 4 * 3 if layout == LAYOUT_FP6 else K // 2
+
+
+def _rows_alloc(rows, layout, weight):
+    """Rows to allocate for a matrix of codes: the FP6 operand layout stores whole panels (64 tokens, 128 channels)."""
+    if layout != LAYOUT_FP6:
+        return rows
+    return (rows + 127) // 128 * 128 if weight else (rows + 63) // 64 * 64
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libw4a4.so")
@@ -302,7 +314,7 @@ def quantize_weight(W: torch.Tensor, mode=SYM, group=0, layout=LAYOUT_CANONICAL)
     N, K = W.shape
     ng = _ng(K, group)
     dev = W.device
-    q = torch.empty((N, K // 2), dtype=torch.uint8, device=dev)
+    q = torch.empty((_rows_alloc(N, layout, True), _row_bytes(K, layout)), dtype=torch.uint8, device=dev)
     scale = torch.empty((N, ng), dtype=torch.float32, device=dev)
     zero = torch.empty((N, ng), dtype=torch.float32, device=dev) if mode == ASYM else None
     gsum = torch.empty((N, ng), dtype=torch.int32, device=dev)
@@ -323,11 +335,11 @@ def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None,
     ng = _ng(K, group)
     dev = X.device
     if out is None:
-        out = QAct(torch.empty((M, K // 2), dtype=torch.uint8, device=dev),
+        out = QAct(torch.empty((_rows_alloc(M, layout, False), _row_bytes(K, layout)), dtype=torch.uint8, device=dev),
                    torch.empty((M,), dtype=torch.float32, device=dev),
                    torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
                    torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
-                   M, K, K // 2, group, mode, 0, layout, _new_osum(M, ng, mode, layout, dev))
+                   M, K, _row_bytes(K, layout), group, mode, 0, layout, _new_osum(M, ng, mode, layout, dev))
     rc = lib().w4a4_quantize_act(_ptr(X), M, K, X.stride(0), mode, group, _ptr(out.q), _ptr(out.scale),
                                  _ptr(out.zero), _ptr(out.gsum), out.layout, _ptr(out.osum), _stream())
     _check(rc, "w4a4_quantize_act")
@@ -336,11 +348,11 @@ def quantize_act(X: torch.Tensor, mode=SYM, group=0, out: Optional[QAct] = None,
 
 def _new_qact(M, K, mode, group, layout, dev) -> QAct:
     ng = _ng(K, group)
-    return QAct(torch.empty((M, K // 2), dtype=torch.uint8, device=dev),
+    return QAct(torch.empty((_rows_alloc(M, layout, False), _row_bytes(K, layout)), dtype=torch.uint8, device=dev),
                 torch.empty((M,), dtype=torch.float32, device=dev),
                 torch.empty((M,), dtype=torch.float32, device=dev) if mode == ASYM else None,
                 torch.empty((M, ng), dtype=torch.int32, device=dev) if mode == ASYM else None,
-                M, K, K // 2, group, mode, 0, layout, _new_osum(M, ng, mode, layout, dev))
+                M, K, _row_bytes(K, layout), group, mode, 0, layout, _new_osum(M, ng, mode, layout, dev))
 
 
 def _new_osum(M, ng, mode, layout, dev):

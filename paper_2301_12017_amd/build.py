@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libw4a4.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "quantize.hip", "epilogue.hip", "gemm.hip", "gemm_generic.hip", "gemm_pipe.hip", "gemm_olay.hip", "gemm_group.hip", "gemm_small.hip", "layernorm.hip", "gemm_w8.hip", "quantize_w8.hip", "strategy.hip", "attention.hip", "probe.hip"]
+SOURCES = ["api.hip", "quantize.hip", "epilogue.hip", "gemm.hip", "gemm_generic.hip", "gemm_pipe.hip", "gemm_olay.hip", "gemm_fp6.hip", "gemm_group.hip", "gemm_small.hip", "layernorm.hip", "gemm_w8.hip", "quantize_w8.hip", "strategy.hip", "attention.hip", "probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fhip-fp32-correctly-rounded-divide-sqrt",

@@ -236,6 +236,20 @@ inline int resident_per_cu(const void *kern, int threads, size_t lds, KernelStat
     return occ;
 }
 
+// The FP6 operand layout of a row of K codes (see w4a4_layout): lanes per token of the quantizer and operands per
+// lane, which fix the permutation of K that both GEMM operands share.  False if the layout does not exist for K.
+inline bool fp6_plan(int K, int *lpr, int *opl) {
+    if (K <= 0 || K % 64) return false;
+    const int n_op = K / 32;
+    for (int l = 64; l >= 8; l >>= 1)
+        if (n_op % l == 0 && n_op / l <= 6) {
+            *lpr = l;
+            *opl = n_op / l;
+            return true;
+        }
+    return false;
+}
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace w4a4

@@ -14,7 +14,8 @@ enum Family {
     F_GENERIC,   // any mode / grouping / K % 32: small and odd shapes
     F_OLAY,      // persistent kernel on operands in the MFMA operand layout
     F_GROUP,     // persistent kernel for K-grouped / asymmetric layers
-    F_SMALL      // small-problem kernel: the waves of a workgroup split K (symmetric per-channel, K % 64 == 0)
+    F_SMALL,     // small-problem kernel: the waves of a workgroup split K (symmetric per-channel, K % 64 == 0)
+    F_FP6        // persistent kernel on operands in the FP6 operand layout (FP6 matrix pipe, exact integer results)
 };
 struct Schedule {
     const char *name;
@@ -34,10 +35,13 @@ static const Schedule kSchedules[] = {
     {"olay_128x128", F_OLAY, 2, false},
     {"group_128x128", F_GROUP, 0, true},
     {"small_splitk", F_SMALL, 0, false},
+    {"fp6_128x256", F_FP6, 0, false},
+    {"fp6_192x128", F_FP6, 1, false},
+    {"fp6_128x128", F_FP6, 2, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 enum { S_PIPE_128x256 = 1, S_PIPE_192x128, S_GEN_64x128, S_GEN_64x64, S_GEN_32x32, S_OLAY_128x256, S_OLAY_192x128,
-       S_OLAY_128x128, S_GROUP, S_SMALL };
+       S_OLAY_128x128, S_GROUP, S_SMALL, S_FP6_128x256, S_FP6_192x128, S_FP6_128x128 };
 
 static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
     // 32-bit buffer offsets and whole K steps
@@ -82,6 +86,13 @@ static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
     return S_GEN_32x32;
 }
 
+// The FP6 kernel: both operands in the FP6 layout, whole pairs of 64-code half steps, at least eight of them.
+static bool fp6_ok(const GemmArgs &g, bool grouped) {
+    int lpr = 0, opl = 0;
+    return !grouped && g.K % kBK == 0 && g.K >= 4 * kBK && fp6_plan(g.K, &lpr, &opl) &&
+           ((long)g.M + 64) * (g.K / 4 * 3) < 0x7fffffffL && ((long)g.N + 128) * (g.K / 4 * 3) < 0x7fffffffL;
+}
+
 // CU count of the current device (the tile choice of the persistent kernel depends on it); 256 if it cannot be read.
 static int device_cus() {
     static std::atomic<int> cached[kMaxDevices] = {};
@@ -119,22 +130,33 @@ static int pick_olay(const GemmArgs &g) {
     return best;
 }
 
+// The same choice among the tiles of the FP6 kernel.
+static int pick_fp6(const GemmArgs &g) {
+    const int o = pick_olay(g);
+    return o == S_OLAY_128x256 ? S_FP6_128x256 : o == S_OLAY_192x128 ? S_FP6_192x128 : S_FP6_128x128;
+}
+
 // Resolves schedule 0 to the table's choice and checks everything a launcher of that family requires, so that
 // a caller can still refuse the call with its outputs untouched.  Nothing is launched here.
 static int resolve_schedule(const GemmArgs &g, bool grouped, int out_kind, int *schedule) {
     // the epilogue addresses the output with 32-bit byte offsets below 2^31
     if (((long)g.M + 512) * g.N * 4 >= 0x80000000L) return W4A4_ERR_UNSUPPORTED_SHAPE;   // (tile overhang included)
-    const bool olay = g.osum != nullptr;                        // operands in the MFMA operand layout
+    const bool olay = g.layout == W4A4_LAYOUT_MFMA;             // operands in the MFMA operand layout
+    const bool fp6 = g.layout == W4A4_LAYOUT_FP6;
     int sch = *schedule;
     // operand layout: symmetric per-channel layers run on the persistent kernel, unsigned (grouped) ones on the group kernel
-    if (sch == 0) sch = olay ? (grouped ? S_GROUP : pick_olay(g)) : pick_schedule(g, grouped, out_kind);
+    if (sch == 0) sch = fp6 ? pick_fp6(g) : olay ? (grouped ? S_GROUP : pick_olay(g)) : pick_schedule(g, grouped, out_kind);
     if (sch < 1 || sch > kNumSchedules) return W4A4_ERR_INVALID_ARG;
     const Schedule &s = kSchedules[sch - 1];
     if (grouped && !s.grouped_ok) return W4A4_ERR_INVALID_ARG;
     // a kernel family understands one layout, except the group kernel, which reads grouped layers in either
-    if (olay ? !(s.family == (grouped ? F_GROUP : F_OLAY)) : s.family == F_OLAY) return W4A4_ERR_INVALID_ARG;
+    if (fp6 != (s.family == F_FP6)) return W4A4_ERR_INVALID_ARG;
+    if (!fp6 && (olay ? !(s.family == (grouped ? F_GROUP : F_OLAY)) : s.family == F_OLAY)) return W4A4_ERR_INVALID_ARG;
     const bool q4 = out_kind == OUT_Q4 || out_kind == OUT_Q4M;
     switch (s.family) {
+        case F_FP6:
+            if (!fp6_ok(g, grouped) || q4) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            break;
         case F_OLAY:
             if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
             if (q4) {
@@ -173,6 +195,7 @@ static int run_gemm(GemmArgs &g, int mode, bool grouped, int out_kind, int sched
     const Schedule &s = kSchedules[schedule - 1];
     switch (s.family) {
         case F_OLAY: return launch_olay(s.variant, out_kind, g, st);
+        case F_FP6: return launch_fp6(s.variant, out_kind, g, st);
         case F_SMALL: return launch_small_packed(out_kind, g, st);
         case F_GROUP: return launch_group(mode, out_kind, g, st);
         case F_PIPE: return launch_pipe(s.variant, out_kind, g, st);
@@ -188,7 +211,13 @@ static int check_operands(const w4a4_act *A, const w4a4_weight *W, int *ng_out) 
     if (A->mode != W->mode || (A->mode != W4A4_SYM && A->mode != W4A4_ASYM)) return W4A4_ERR_INVALID_ARG;
     if (W->group < 0 || A->group < 0) return W4A4_ERR_INVALID_ARG;
     if (A->layout != W->layout) return W4A4_ERR_INVALID_ARG;
-    if (A->layout != W4A4_LAYOUT_CANONICAL && A->layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
+    if (A->layout != W4A4_LAYOUT_CANONICAL && A->layout != W4A4_LAYOUT_MFMA && A->layout != W4A4_LAYOUT_FP6) return W4A4_ERR_INVALID_ARG;
+    if (A->layout == W4A4_LAYOUT_FP6) {
+        int lpr = 0, opl = 0;
+        if (A->mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+        if ((W->group != 0 && W->group != W->K) || (A->group != 0 && A->group != A->K)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (A->K % kBK || A->K < 4 * kBK || !fp6_plan(A->K, &lpr, &opl)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    }
     if (A->layout == W4A4_LAYOUT_MFMA) {
         if (A->ldo < 1) return W4A4_ERR_INVALID_ARG;
         if (A->M > 0 && (!A->osum || !W->esum)) return W4A4_ERR_INVALID_ARG;
@@ -205,7 +234,7 @@ static int check_operands(const w4a4_act *A, const w4a4_weight *W, int *ng_out) 
     const int G = W->group == 0 ? K : W->group;
     if (K % G || (W->group != 0 && G % kBK)) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const int ng = K / G;
-    if (A->lda < K / 2) return W4A4_ERR_INVALID_ARG;
+    if (A->lda < (A->layout == W4A4_LAYOUT_FP6 ? K / 4 * 3 : K / 2)) return W4A4_ERR_INVALID_ARG;
     if (A->lda % 16) return W4A4_ERR_UNSUPPORTED_SHAPE;
     if (A->M > 0) {
         if (!A->q || !A->scale || !W->q || !W->scale) return W4A4_ERR_INVALID_ARG;
@@ -250,7 +279,8 @@ int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int gr
                       float *s, float *z, int32_t *gsum, hipStream_t st, int layout = 0);
 
 static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int ng) {
-    g.Aq = A->q; g.lda = A->lda; g.Wq = W->q; g.ldw = W->K / 2;
+    g.Aq = A->q; g.lda = A->lda; g.Wq = W->q; g.ldw = A->layout == W4A4_LAYOUT_FP6 ? W->K / 4 * 3 : W->K / 2;
+    g.layout = A->layout;
     g.M = A->M; g.N = W->N; g.K = A->K;
     g.ng = ng; g.steps_per_group = (A->K / ng + kBK - 1) / kBK;
     g.sa = A->scale; g.za = A->zero; g.RA = A->gsum;
@@ -397,7 +427,6 @@ extern "C" int w4a4_pick_schedule(const w4a4_act *A, const w4a4_weight *W, const
     ng = A->K / G;
     GemmArgs g;
     fill_args(g, A, W, ng);
-    if (A->layout == W4A4_LAYOUT_MFMA) g.osum = reinterpret_cast<const int32_t *>(1);   // only tested against NULL here
     const bool grouped = A->mode == W4A4_ASYM || ng > 1;
     int out_kind = OUT_F16, schedule = ep->schedule;
     if (ep->requant) {

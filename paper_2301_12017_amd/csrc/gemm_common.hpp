@@ -65,6 +65,7 @@ struct GemmArgs {
     const int32_t *esum;           // [N]        even-position code sums of the channels
     int32_t *out_osum; int osum_slices, slice_tiles;   // requantized output: [M, osum_slices] sums, column
                                                        // tiles per slice
+    int layout;                    // w4a4_layout of both operands
 };
 
 // Widening of packed codes to int8 without sign extension.  For a packed dword d (codes
@@ -450,6 +451,7 @@ __device__ __forceinline__ void tile_epilogue_requant(const GemmArgs &g, v16i (&
 int launch_generic(int variant, int mode, bool grouped, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_pipe(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_olay(int variant, int out_kind, GemmArgs &g, hipStream_t st);
+int launch_fp6(int variant, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_group(int mode, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_small_packed(int out_kind, GemmArgs &g, hipStream_t st);
 // Residency limits of the fused requantize on the current device (see the definitions)

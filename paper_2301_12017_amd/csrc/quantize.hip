@@ -358,7 +358,7 @@ __device__ __forceinline__ float sub_max(float v) {                 // maximum o
     v = fmaxf(v, __int_as_float(dpp_move<0xB1>(__float_as_int(v))));     // quad_perm [1,0,3,2]
     v = fmaxf(v, __int_as_float(dpp_move<0x4E>(__float_as_int(v))));     // quad_perm [2,3,0,1]
     v = fmaxf(v, __int_as_float(dpp_move<0x141>(__float_as_int(v))));    // half-row mirror
-    v = fmaxf(v, __int_as_float(dpp_move<0x140>(__float_as_int(v))));    // row mirror
+    if (LPR >= 16) v = fmaxf(v, __int_as_float(dpp_move<0x140>(__float_as_int(v))));   // row mirror
     if (LPR >= 32) v = fmaxf(v, __shfl_xor(v, 16, kWave));
     if (LPR >= 64) v = fmaxf(v, __shfl_xor(v, 32, kWave));
     return v;
@@ -535,6 +535,151 @@ static int launch_tok_rows(const __half *X, long ldx, int rows, int K, uint8_t *
     return launch_status();
 }
 
+// ---- the FP6 operand layout (symmetric codes as FP6 E2M3 numbers; see w4a4_layout) -------------------------------
+// A row of K codes is K / 32 MFMA operands of 32 codes (24 bytes); operands 2b and 2b + 1 form the row's 48-byte
+// block b, [16 bytes at 16h | 8 bytes at 32 + 8h] for operand 2b + h.  Rows are stored in panels (64 tokens, or 128
+// output channels in the order that gives a lane of the GEMM adjacent channels), block b of all rows of a panel
+// contiguously, so that the GEMM's tile loads are whole kilobytes of consecutive addresses; matrices are padded
+// with zero rows to whole panels.  Which codes an operand holds is fixed per K so that the token-wise
+// quantizer loads coalesced and needs no shuffles: a token is owned by LPR lanes, lane l holds the 16-byte chunks
+// (eight fp16 values) l + LPR*j, j = 0 .. 4*OPL-1, and its operand o (index o*LPR + l in the row) is made of chunks
+// j = 4o .. 4o+3.  Inside an operand, element e of chunk j sits in 6-bit field 2*(8*(j&1) + e) + ((j>>1)&1): the order
+// in which the hardware conversion interleaves its two sixteen-value sources.  Weights are laid out by the same
+// rule, so both MFMA operands see the same permutation of K, which a contraction over K does not notice.
+typedef float v16f_q __attribute__((ext_vector_type(16)));
+typedef unsigned int v6u_q __attribute__((ext_vector_type(6)));
+
+// Token-wise symmetric quantizer into the FP6 layout: same range and same codes as the kernels above (t = x * 7/absmax
+// in fp32, round to nearest even; |t| <= 7(1+2^-23), so the clamp of the definition cannot bind); the rounded value,
+// an integer of magnitude <= 7, is exactly representable in FP6 E2M3, so the hardware conversion of 32 fp32 values
+// to 32 packed FP6 fields is exact.  Two vector instructions per code plus one conversion per 32.
+template <int LPR, int OPL>
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_fp6_rows_kernel(
+    const __half *__restrict__ X, long ldx, int rows, uint8_t *__restrict__ q, float *__restrict__ s) {
+    constexpr int RPW = kWave / LPR, NJ = 4 * OPL;
+    constexpr int KB = LPR * OPL / 2;                           // 48-byte blocks (64 codes) per row
+    typedef unsigned int u4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+    const int lane = threadIdx.x % kWave, l = lane % LPR;
+    const long row = ((long)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave) * RPW + lane / LPR;
+    const bool live = row < rows;                               // rows up to the end of the last 64-row panel are written as zeros
+    const bool padded = row < (((long)rows + 63) & ~63L);
+    const u4 *src = reinterpret_cast<const u4 *>(X + (live ? row : (long)rows - 1) * ldx);
+    u4 raw[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) raw[j] = src[l + LPR * j];
+    typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+    us2 hi2 = {0, 0};
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t d = raw[j][i] & 0x7FFF7FFFu;
+            hi2 = __builtin_elementwise_max(hi2, *reinterpret_cast<const us2 *>(&d));
+        }
+    const unsigned short hmax = hi2[0] > hi2[1] ? hi2[0] : hi2[1];
+    const Range r = range_sym(sub_max<LPR>(__half2float(__ushort_as_half(hmax))));
+    if (l == 0 && live) s[row] = r.S;
+    // row m of the matrix: panel m / 64, and inside every 3072-byte block of the panel the 48 bytes at (m % 64) * 48
+    uint8_t *qrow = q + (row >> 6) * ((long)KB * 3072) + (row & 63) * 48;
+#pragma unroll
+    for (int o = 0; o < OPL; ++o) {
+        v16f_q a, b;
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t w = raw[4 * o + jj][e >> 1];
+                float t;
+                if (e & 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+                else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
+                const float c = __builtin_rintf(t);
+                if (jj < 2) a[8 * jj + e] = c;
+                else b[8 * (jj - 2) + e] = c;
+            }
+        v6u_q w6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(a, b, 1.0f);
+        if (!live) w6 = v6u_q{0u, 0u, 0u, 0u, 0u, 0u};
+        const int idx = o * LPR + l;
+        uint8_t *blk = qrow + (long)(idx >> 1) * 3072 + (idx & 1) * 16;
+        if (padded) {
+            *reinterpret_cast<u4 *>(blk) = u4{w6[0], w6[1], w6[2], w6[3]};
+            // the 8-byte part: at 32 + 8h, the two halves exchanged in rows 16 .. 31 of every 32 (LDS banks of the GEMM's reads)
+            *reinterpret_cast<u2 *>(qrow + (long)(idx >> 1) * 3072 + 32 + (((idx & 1) ^ (int)((row >> 4) & 1)) * 8)) = u2{w6[4], w6[5]};
+        }
+    }
+}
+
+static int launch_fp6_rows(const __half *X, long ldx, int rows, int K, uint8_t *q, float *s, hipStream_t st) {
+    if (rows == 0) return W4A4_OK;
+    int lpr = 0, opl = 0;
+    if (!fp6_plan(K, &lpr, &opl)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    const long per_block = (long)kRowsPerBlock * (kWave / lpr);
+    const long padded = ((long)rows + 63) & ~63L;
+    dim3 grid((unsigned)((padded + per_block - 1) / per_block)), block(kRowsPerBlock * kWave);
+#define W4A4_Q6(L, O) \
+    case O: hipLaunchKernelGGL((quantize_fp6_rows_kernel<L, O>), grid, block, 0, st, X, ldx, rows, q, s); break
+#define W4A4_Q6L(L)                                                                                        \
+    switch (opl) { W4A4_Q6(L, 1); W4A4_Q6(L, 2); W4A4_Q6(L, 3); W4A4_Q6(L, 4); W4A4_Q6(L, 5); W4A4_Q6(L, 6); default: return W4A4_ERR_UNSUPPORTED_SHAPE; }
+    if (lpr == 8) { W4A4_Q6L(8) }
+    else if (lpr == 16) { W4A4_Q6L(16) }
+    else if (lpr == 32) { W4A4_Q6L(32) }
+    else { W4A4_Q6L(64) }
+#undef W4A4_Q6L
+#undef W4A4_Q6
+    return launch_status();
+}
+
+// FP6 E2M3 field of a code in [-7, 7]: sign, then the magnitude as (exponent, three mantissa bits)
+__device__ __forceinline__ uint32_t fp6_field(int c) {
+    const int m = c < 0 ? -c : c;
+    const uint32_t mag = m == 0 ? 0u : m == 1 ? 8u : m < 4 ? 8u + 4u * (uint32_t)m : 16u + 2u * (uint32_t)m;   // 1 | 2, 3 | 4 .. 7
+    return (c < 0 ? 32u : 0u) | mag;
+}
+
+// Offline weight quantizer into the FP6 layout (symmetric, one scale per output channel): one wave per channel of
+// the padded matrix (channels past N are written as zeros), the range over the whole row, then every lane assembles
+// whole operands from the chunks the layout assigns to them.  Same range and codes as quantize_rows_kernel;
+// gsum[n] = sum of the codes of the row.  Channel n lives in panel n / 128, storage row (n % 4) * 32 + (n % 128) / 4.
+__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_weight_fp6_kernel(
+    const __half *__restrict__ W, int N, int K, int lpr, uint8_t *__restrict__ q, float *__restrict__ s,
+    int32_t *__restrict__ gsum) {
+    const int lane = threadIdx.x % kWave;
+    const long n = (long)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave;
+    if (n >= (((long)N + 127) & ~127L)) return;
+    const bool live = n < N;
+    const __half *w = W + (live ? n : 0) * K;
+    float amax = 0.0f;
+    for (int k = lane; k < K; k += kWave) amax = fmaxf(amax, fabsf(__half2float(w[k])));
+    const Range r = range_sym(wave_max(amax));
+    if (lane == 0 && live) s[n] = r.S;
+    const int p = (int)(n & 3) * 32 + (int)((n & 127) >> 2);
+    uint8_t *qrow = q + (n >> 7) * ((long)(K / 64) * 6144) + p * 48;
+    int total = 0;
+    for (int idx = lane; idx < K / 32; idx += kWave) {
+        const int o = idx / lpr, l = idx % lpr;
+        uint32_t words[6] = {0, 0, 0, 0, 0, 0};
+        for (int jj = 0; jj < 4; ++jj)
+            for (int e = 0; e < 8; ++e) {
+                const int k = 8 * (l + lpr * (4 * o + jj)) + e;
+                const int c = live ? code_of<W4A4_SYM>(__half2float(w[k]), r) : 0;
+                total += c;
+                const int bit = 6 * (2 * (8 * (jj & 1) + e) + (jj >> 1));
+                const uint32_t f = fp6_field(c);
+                words[bit >> 5] |= f << (bit & 31);
+                if ((bit & 31) > 26) words[(bit >> 5) + 1] |= f >> (32 - (bit & 31));
+            }
+        uint8_t *blk = qrow + (long)(idx >> 1) * 6144;
+        uint32_t *lo = reinterpret_cast<uint32_t *>(blk + (idx & 1) * 16);
+        lo[0] = words[0]; lo[1] = words[1]; lo[2] = words[2]; lo[3] = words[3];
+        uint32_t *tl = reinterpret_cast<uint32_t *>(blk + 32 + (((idx & 1) ^ ((p >> 4) & 1)) * 8));   // halves exchanged in storage rows 16 .. 31 of every 32
+        tl[0] = words[4]; tl[1] = words[5];
+    }
+    if (gsum && live) {
+        for (int o = 32; o > 0; o >>= 1) total += __shfl_xor(total, o, kWave);
+        if (lane == 0) gsum[n] = total;
+    }
+}
+
 // Streaming launch for fp16 activations; returns -100 when the shape needs the general kernel
 // (K-groups whose chunk count is not a power of two <= 64).
 template <int MODE, int LAYOUT>
@@ -602,6 +747,12 @@ int quantize_rows_f32(const float *Y, int rows, int K, long ld, int mode, int gr
 // Layout check shared by the two quantizer entry points.  The operand layout exists for symmetric codes with one
 // weight scale per channel and for unsigned codes with weight groups that are multiples of 128 (or one group).
 static int check_layout(int layout, int mode, int group, int K, const void *psum, int rows) {
+    if (layout == W4A4_LAYOUT_FP6) {                            // symmetric codes, one scale per row, a K the layout exists for
+        int lpr = 0, opl = 0;
+        if (mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+        if ((group != 0 && group != K) || !fp6_plan(K, &lpr, &opl)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        return W4A4_OK;
+    }
     if (layout != W4A4_LAYOUT_CANONICAL && layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
     if (layout == W4A4_LAYOUT_MFMA) {
         if (mode == W4A4_SYM) {
@@ -645,6 +796,10 @@ extern "C" int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int m
     const int G = group == 0 ? K : group;
     const __half *X = static_cast<const __half *>(X_f16);
     hipStream_t st = as_stream(stream);
+    if (layout == W4A4_LAYOUT_FP6) {
+        if (gsum) return W4A4_ERR_UNSUPPORTED_SHAPE;            // no K-group code sums in this layout
+        return launch_fp6_rows(X, ldx, M, K, q, scale, st);
+    }
     const bool olay = layout == W4A4_LAYOUT_MFMA;
     rc = olay ? (mode == W4A4_SYM ? launch_stream<W4A4_SYM, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, osum)
                                   : launch_stream<W4A4_ASYM, 1>(X, ldx, M, K, G, q, scale, zero, gsum, ng, st, osum))
@@ -679,7 +834,15 @@ extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, i
     if (rc) return rc;
     hipStream_t st = as_stream(stream);
     const __half *W = static_cast<const __half *>(W_f16);
-    if (layout == W4A4_LAYOUT_MFMA && mode == W4A4_SYM)
+    if (layout == W4A4_LAYOUT_FP6) {
+        int lpr = 0, opl = 0;
+        fp6_plan(K, &lpr, &opl);
+        if (N > 0) {
+            hipLaunchKernelGGL(quantize_weight_fp6_kernel, dim3((((N + 127) & ~127) + kRowsPerBlock - 1) / kRowsPerBlock),
+                               dim3(kRowsPerBlock * kWave), 0, st, W, N, K, lpr, q, scale, gsum);
+            rc = launch_status();
+        }
+    } else if (layout == W4A4_LAYOUT_MFMA && mode == W4A4_SYM)
         rc = launch_rows<W4A4_SYM, __half, 2>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st, esum);
     else if (layout == W4A4_LAYOUT_MFMA)
         rc = launch_rows<W4A4_ASYM, __half, 2>(W, G, (int)rows, G, G, q, scale, zero, gsum, 1, st, esum, ng);

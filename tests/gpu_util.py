@@ -130,3 +130,64 @@ def olay_schedules(B, K):
     """Schedule numbers of the persistent operand-layout kernel (every tile shape takes any K % 128 == 0, K >= 256)."""
     assert K % 128 == 0 and K >= 256
     return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("olay")]
+
+
+# ---- the FP6 operand layout (a re-encoding of the codes; no arithmetic of the method) -------------------------------
+_FP6_VALUE = {0: 0, 8: 1, 16: 2, 20: 3, 24: 4, 26: 5, 28: 6, 30: 7}     # E2M3 magnitude field -> integer it encodes
+
+
+def fp6_plan(K):
+    """(lanes per row, operands per lane) of the layout's permutation of K, or None where the layout does not exist."""
+    n_op = K // 32
+    if K % 64:
+        return None
+    for lpr in (64, 32, 16, 8):
+        if n_op % lpr == 0 and n_op // lpr <= 6:
+            return lpr, n_op // lpr
+    return None
+
+
+def fp6_to_codes(q, K, rows, weight=False):
+    """A matrix in the FP6 operand layout -> int8 codes [rows, K] in the order of K.
+    Rows come in panels (64 tokens; 128 channels, channel n in storage row (n % 4) * 32 + (n % 128) / 4); a panel is
+    K/64 blocks of [rows of the panel][48 bytes]; operand 2b + h of a row lies in its 48 bytes of block b as 16 bytes
+    at 16h and 8 bytes at 32 + 8h (at 40 - 8h in storage rows 16 .. 31 of every 32); its 32 six-bit fields (little-endian) hold, in field 2*(8*(j&1) + e) + (j>>1),
+    element e of the 8-code chunk l + LPR*(4o + j) of the row, for operand index o*LPR + l.  Padding rows must be zero."""
+    lpr, _ = fp6_plan(K)
+    R = 128 if weight else 64
+    n_op, kb = K // 32, K // 64
+    flat = np.ascontiguousarray(q).reshape(-1)
+    padded = (rows + R - 1) // R * R
+    assert flat.size == padded * K // 4 * 3
+    blocks = flat.reshape(padded // R, kb, R, 48)                                # [panel, block, storage row, 48]
+    r = np.arange(padded)
+    srow = ((r % 4) * 32 + (r % 128) // 4) if weight else (r % 64)
+    blocks = blocks[r // R, :, srow, :]                                          # [row, block, 48]
+    assert not blocks[rows:].any(), "padding rows are not zero"
+    blocks = blocks[:rows]
+    ops = np.empty((rows, n_op, 24), np.uint8)
+    swap = ((srow[:rows] >> 4) & 1).astype(bool)                                 # storage rows 16 .. 31 of every 32: 8-byte parts exchanged
+    for h in (0, 1):
+        ops[:, h::2, :16] = blocks[:, :, 16 * h:16 * h + 16]
+        ops[:, h::2, 16:] = np.where(swap[:, None, None], blocks[:, :, 40 - 8 * h:48 - 8 * h], blocks[:, :, 32 + 8 * h:40 + 8 * h])
+    bits = np.unpackbits(ops, axis=2, bitorder="little").reshape(rows, n_op, 32, 6)
+    fields = (bits * (1 << np.arange(6, dtype=np.int64))).sum(axis=3)            # [rows, n_op, 32]
+    mag = fields & 31
+    assert np.isin(mag, list(_FP6_VALUE)).all(), "a field that is not an integer of magnitude <= 7"
+    lut = np.zeros(32, np.int64)
+    for k_, v_ in _FP6_VALUE.items():
+        lut[k_] = v_
+    val = np.where(fields & 32, -lut[mag], lut[mag])
+    out = np.empty((rows, K), np.int8)
+    idx = np.arange(n_op)
+    o, l = idx // lpr, idx % lpr
+    for f in range(32):
+        i, s_ = f >> 1, f & 1
+        j, e = (i >> 3) + 2 * s_, i & 7
+        k = 8 * (l + lpr * (4 * o + j)) + e
+        out[:, k] = val[:, :, f]
+    return out
+
+
+def fp6_schedules(B):
+    return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("fp6")]

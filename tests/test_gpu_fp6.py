@@ -1,0 +1,161 @@
+"""GPU parity of the FP6 path: symmetric INT4 codes stored as FP6 E2M3 numbers, the GEMM on the FP6 matrix
+instruction with FP32 accumulation (Sec. 4.2: INT4 arithmetic at twice the INT8 rate).  Codes, scales and int32
+sums must equal the oracle's bit for bit; fp16 outputs without GELU too (the epilogue follows the definition's
+operation order), with GELU within one fp16 step."""
+import numpy as np
+import pytest
+import torch
+
+from tests.gpu_util import GELU_SAME, assert_f16, dev, fp6_plan, fp6_schedules, fp6_to_codes, has_gpu, host
+
+pytestmark = [pytest.mark.gpu, pytest.mark.skipif(not has_gpu(), reason="needs a GPU")]
+SYM, FP6 = 0, 2
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2301_12017_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture(scope="module")
+def orc():
+    import oracle
+    return oracle
+
+
+def _x(rng, M, K, outliers=4):
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    if outliers:
+        x[:, rng.choice(K, outliers, replace=False)] *= 20.0
+    return x.astype(np.float16)
+
+
+def _w(rng, N, K):
+    return (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+
+
+def test_plan_matches_the_library(B):
+    """The permutation of K is a function of K alone; K the layout does not exist for are refused."""
+    X = torch.zeros((8, 1792), dtype=torch.float16, device="cuda")          # 1792 / 32 = 56 = 8 * 7: seven operands per lane
+    assert fp6_plan(1792) is None
+    with pytest.raises(RuntimeError):
+        B.quantize_act(X, SYM, layout=FP6)
+    with pytest.raises(RuntimeError):
+        B.quantize_act(torch.zeros((8, 320), dtype=torch.float16, device="cuda"), SYM, layout=FP6)   # K % 256 != 0
+    with pytest.raises(RuntimeError):
+        B.quantize_act(torch.zeros((8, 512), dtype=torch.float16, device="cuda"), 1, layout=FP6)     # unsigned codes
+
+
+@pytest.mark.parametrize("M,K,ldx", [(1, 256, 256), (77, 512, 520), (300, 768, 768), (8193, 1024, 1024), (130, 1280, 1288),
+                                     (67, 1536, 1536), (515, 2048, 2048), (2100, 3072, 3072), (1030, 4096, 4104),
+                                     (33, 8192, 8192), (9, 12288, 12288)])
+def test_quantize_act_fp6_layout(B, orc, M, K, ldx):
+    rng = np.random.default_rng(M + K)
+    Xw = (rng.standard_normal((M, ldx)) * rng.uniform(0.1, 4.0, size=(M, 1))).astype(np.float32).astype(np.float16)
+    Xw[0, :] = 0                                              # an all-zero token
+    Xw[M - 1, :K] = np.float16(65504.0)                       # top of the fp16 range ...
+    Xw[M - 1, K - 1] = np.float16(-65504.0)                   # ... and its bottom
+    if M > 2:
+        Xw[1, :K] = np.float16(6e-8)                          # subnormals only
+    A = B.quantize_act(dev(Xw)[:, :K], SYM, layout=FP6)
+    want = orc.quantize_act(np.ascontiguousarray(Xw[:, :K]), SYM)
+    assert A.q.shape == ((M + 63) // 64 * 64, K // 4 * 3) and A.lda == K // 4 * 3
+    assert np.array_equal(fp6_to_codes(host(A.q), K, M), orc.unpack(want["q"], SYM))
+    assert np.array_equal(host(A.scale).view(np.uint32), want["s"].view(np.uint32))
+
+
+@pytest.mark.parametrize("N,K", [(8, 256), (520, 768), (64, 1024), (1032, 3072), (136, 4096)])
+def test_quantize_weight_fp6_layout(B, orc, N, K):
+    rng = np.random.default_rng(N + K)
+    W = _w(rng, N, K)
+    W[0, :] = 0
+    Q = B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    want = orc.quantize_weight(W, SYM, 0)
+    assert np.array_equal(fp6_to_codes(host(Q.q), K, N, weight=True), orc.unpack(want["q"], SYM))
+    assert np.array_equal(host(Q.scale).view(np.uint32), want["s"].view(np.uint32))
+    assert np.array_equal(host(Q.gsum), want["gsum"])
+    assert np.array_equal(host(Q.rowsum_deq).view(np.uint32), want["c"].view(np.uint32))
+
+
+def _layer(B, orc, rng, M, N, K):
+    X, W = _x(rng, M, K), _w(rng, N, K)
+    A, Q = B.quantize_act(dev(X), SYM, layout=FP6), B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    return A, Q, orc.quantize_act(X, SYM), orc.quantize_weight(W, SYM, 0)
+
+
+@pytest.mark.parametrize("M,N,K", [(128, 256, 512), (300, 520, 768), (77, 136, 1024), (1, 8, 512), (515, 1032, 1280), (260, 264, 4096)])
+def test_gemm_i32_bit_exact(B, orc, M, N, K):
+    rng = np.random.default_rng(M * 3 + N + K)
+    A, Q, a, w = _layer(B, orc, rng, M, N, K)
+    want = orc.gemm_i32(a["q"], w["q"], SYM, 0)
+    scheds = fp6_schedules(B)
+    assert len(scheds) == 3
+    for sch in scheds:
+        got = host(B.gemm_i32(A, Q, schedule=sch))
+        assert np.array_equal(got, want), f"schedule {B.schedule_names()[sch - 1]}"
+    assert B.pick_schedule(A, Q).startswith("fp6")
+
+
+def test_gemm_i32_extreme_codes(B, orc):
+    """Every code at +-7 over K = 4096: the largest sums the layout can produce, 49 * 4096 = 200704 < 2^24."""
+    M, N, K = 160, 264, 4096
+    X = np.full((M, K), 3.0, np.float16)
+    X[::2, ::3] = -3.0
+    W = np.full((N, K), 0.5, np.float16)
+    W[1::3, 1::2] = -0.5
+    A, Q = B.quantize_act(dev(X), SYM, layout=FP6), B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    a, w = orc.quantize_act(X, SYM), orc.quantize_weight(W, SYM, 0)
+    want = orc.gemm_i32(a["q"], w["q"], SYM, 0)
+    assert np.abs(want).max() == 49 * 4096
+    for sch in fp6_schedules(B):
+        assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch)), want)
+
+
+@pytest.mark.parametrize("act,with_bias", [(0, False), (0, True), (1, True), (1, False)])
+def test_linear_fp16(B, orc, act, with_bias):
+    M, N, K = 389, 1032, 1024
+    rng = np.random.default_rng(7 + act + 2 * with_bias)
+    A, Q, a, w = _layer(B, orc, rng, M, N, K)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float16) if with_bias else None
+    want = orc.linear(a, w, SYM, 0, bias, act)["out"]
+    for sch in fp6_schedules(B):
+        got = host(B.linear(A, Q, dev(bias) if with_bias else None, act, schedule=sch))
+        assert_f16(got, want, GELU_SAME if act else 1.0, f"schedule {B.schedule_names()[sch - 1]}")
+
+
+@pytest.mark.parametrize("K", [512, 1024, 3072])
+def test_many_tiles_per_workgroup(B, orc, K):
+    """More tiles than resident workgroups: the stream of half steps runs across tile boundaries, in every tile shape;
+    sampled rows (first, last, around panel boundaries) against the oracle."""
+    M, N = 6144 + 70, 3072 + 8
+    rng = np.random.default_rng(K)
+    X, W = _x(rng, M, K), _w(rng, N, K)
+    bias = (rng.standard_normal(N) * 0.1).astype(np.float16)
+    A, Q = B.quantize_act(dev(X), SYM, layout=FP6), B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(126, 130), np.arange(190, 194), np.arange(3070, 3074),
+                                     rng.choice(M, 24, replace=False), np.arange(M - 3, M)]))
+    a, w = orc.quantize_act(X[rows], SYM), orc.quantize_weight(W, SYM, 0)
+    want_i = orc.gemm_i32(a["q"], w["q"], SYM, 0)
+    want = orc.linear(a, w, SYM, 0, bias, 0)["out"]
+    for sch in fp6_schedules(B):
+        assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch))[0][rows], want_i[0]), B.schedule_names()[sch - 1]
+        got = host(B.linear(A, Q, dev(bias), 0, schedule=sch))[rows]
+        assert_f16(got, want, 1.0, B.schedule_names()[sch - 1])
+
+
+def test_argument_errors(B):
+    rng = np.random.default_rng(3)
+    X, W = _x(rng, 64, 512), _w(rng, 64, 512)
+    A = B.quantize_act(dev(X), SYM, layout=FP6)
+    Qc = B.quantize_weight(dev(W), SYM, 0)                      # canonical weights against FP6 activations
+    with pytest.raises(RuntimeError):
+        B.linear(A, Qc, None, 0)
+    Q = B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    with pytest.raises(RuntimeError):
+        B.linear(A, Q, None, 0, schedule=B.schedule_number("olay_128x256"))   # a kernel of another layout
+    X2, W2 = _x(rng, 64, 256), _w(rng, 64, 256)                 # the layout exists for K = 256, the GEMM wants K >= 512
+    A2, Q2 = B.quantize_act(dev(X2), SYM, layout=FP6), B.quantize_weight(dev(W2), SYM, 0, layout=FP6)
+    with pytest.raises(RuntimeError):
+        B.linear(A2, Q2, None, 0)

@@ -115,7 +115,7 @@ def _schedules(B, grouped, K=128):
     takes symmetric per-channel layers with K % 128 == 0, the split-K kernel K % 64 == 0)."""
     out = []
     for i, name in enumerate(B.schedule_names()):
-        if name.startswith("olay"):                 # reads the MFMA operand layout only (tests/test_gpu_olay.py)
+        if name.startswith("olay") or name.startswith("fp6"):   # read their own operand layouts (tests/test_gpu_olay.py, test_gpu_fp6.py)
             continue
         if name.startswith("group") and (not grouped or K % 128 or K < 256):
             continue
