@@ -38,10 +38,11 @@ static const Schedule kSchedules[] = {
     {"fp6_128x256", F_FP6, 0, false},
     {"fp6_192x128", F_FP6, 1, false},
     {"fp6_128x128", F_FP6, 2, false},
+    {"fp6_192x256", F_FP6, 3, false},
 };
 constexpr int kNumSchedules = sizeof(kSchedules) / sizeof(kSchedules[0]);
 enum { S_PIPE_128x256 = 1, S_PIPE_192x128, S_GEN_64x128, S_GEN_64x64, S_GEN_32x32, S_OLAY_128x256, S_OLAY_192x128,
-       S_OLAY_128x128, S_GROUP, S_SMALL, S_FP6_128x256, S_FP6_192x128, S_FP6_128x128 };
+       S_OLAY_128x128, S_GROUP, S_SMALL, S_FP6_128x256, S_FP6_192x128, S_FP6_128x128, S_FP6_192x256 };
 
 static bool pipe_ok(const GemmArgs &g, bool grouped, int kstep = kBK) {
     // 32-bit buffer offsets and whole K steps
@@ -130,8 +131,17 @@ static int pick_olay(const GemmArgs &g) {
     return best;
 }
 
-// The same choice among the tiles of the FP6 kernel.
+// Tile choice of the FP6 kernel, from kernel times on the BERT-large shapes at 12288 tokens (TOP/s of 192 x 256 with
+// one wave per SIMD / 128 x 256 / 192 x 128): K = 4096 3350 / 3040 / 3110; K = 1024 with N = 3072 2450 / 2490 / 1950, with
+// N = 4096 + GELU 2030 / 2260 / 2080, with N = 1024 1890 / 1960 / 1790.  Long K favours the big tile (least operand traffic per
+// product, one workgroup per CU); otherwise two 128 x 256 workgroups per CU, whose epilogues and stores overlap better;
+// few tiles fall back to the mid-range rule of the int8 kernel.
 static int pick_fp6(const GemmArgs &g) {
+    const long cus = device_cus();
+    const long big = (long)((g.M + 191) / 192) * ((g.N + 255) / 256);
+    if (g.K >= 2048 && g.K / 64 >= 9 && big * 4 >= 3 * cus) return S_FP6_192x256;
+    const long mid = (long)((g.M + 127) / 128) * ((g.N + 255) / 256);
+    if (mid >= cus) return S_FP6_128x256;
     const int o = pick_olay(g);
     return o == S_OLAY_128x256 ? S_FP6_128x256 : o == S_OLAY_192x128 ? S_FP6_192x128 : S_FP6_128x128;
 }

@@ -28,8 +28,6 @@
 //   * persistent workgroups, the half steps of successive tiles form one stream through the ring, token scales go
 //     to LDS by 4-byte DMA one tile ahead;
 //   * two (three for the 128 x 128 tile) workgroups share a CU.
-#include <cstdlib>
-
 #include "gemm_common.hpp"
 
 namespace w4a4 {
@@ -211,20 +209,10 @@ void gemm_fp6_kernel(GemmArgs g) {
     v16f acc[FM][FN];                                           // written by the first half step of every tile
 
     // Tile of virtual block id v (workgroup id + k * grid size; v % 8 = the XCD it runs on): every XCD owns a
-    // contiguous range of tiles.  Inside a round, workgroups pair_dist ids apart (in units of eight: the same XCD)
-    // take neighbouring tiles of a row panel, so that the two workgroups that share a CU read the same
-    // activation rows at about the same time and the second reads them from the CU's cache.
-    const int pair_dist = g.slice_tiles;
+    // contiguous range of tiles, so that the tiles of a row panel run on one XCD and share its L2.
     auto tile_of = [&](int v, int &t) {
-        int vv = v;
-        if (pair_dist > 1) {
-            const int per_x = stride >> 3, x = v & 7, i = v >> 3;
-            const int round = i / per_x, ii = i % per_x;
-            const int pair = (ii / (2 * pair_dist)) * pair_dist + (ii % pair_dist), member = (ii / pair_dist) & 1;
-            vv = ((round * per_x + 2 * pair + member) << 3) | x;
-        }
-        t = xcd_tile(vv < total ? vv : 0, total);
-        return vv < total;
+        t = xcd_tile(v < total ? v : 0, total);
+        return v < total;
     };
     int vb = blockIdx.x;                                        // virtual block id of the current tile
     int tile;
@@ -237,15 +225,6 @@ void gemm_fp6_kernel(GemmArgs g) {
 #pragma unroll
         for (int i = 0; i < LD; ++i) dma_one(i, s, a_cur, b_cur, s);
     dma_params(m0, 0);
-#ifdef W4A4_EXP6_STAGGER
-    if (g.osum_slices > 0) {
-        const uint32_t lds_base = __builtin_amdgcn_s_getreg(6 | (0 << 6) | (7 << 11));   // LDS_ALLOC.LDS_BASE
-        if (lds_base != 0) {
-            const uint64_t t0 = __builtin_amdgcn_s_memrealtime();
-            while (__builtin_amdgcn_s_memrealtime() - t0 < (uint64_t)g.osum_slices) __builtin_amdgcn_s_sleep(4);
-        }
-    }
-#endif
     __builtin_amdgcn_s_waitcnt(vmcnt_and_lds(0));
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
@@ -338,7 +317,9 @@ void gemm_fp6_kernel(GemmArgs g) {
         int hs = 1;
         if constexpr (NS >= 4) { half_step(no{}, nowait{}, no{}, Pb, Pa, 1); hs = 2; }
         if constexpr (NS >= 5) { half_step(no{}, nowait{}, no{}, Pa, Pb, 2); hs = 3; }
-        static_assert(NS <= 5, "unrolled prologue of a tile");
+        if constexpr (NS >= 6) { half_step(no{}, nowait{}, no{}, Pb, Pa, 3); hs = 4; }
+        if constexpr (NS >= 7) { half_step(no{}, nowait{}, no{}, Pa, Pb, 4); hs = 5; }
+        static_assert(NS <= 7, "unrolled prologue of a tile");
         if (hs & 1) {                                           // Pb holds the operands of half step hs
             for (; hs < KT - 1; hs += 2) {
                 half_step(no{}, wait{}, no{}, Pb, Pa, hs);
@@ -406,13 +387,6 @@ static int launch_one6(GemmArgs &g, hipStream_t st) {
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
     if (grid == 0) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    g.slice_tiles = 0;
-    g.osum_slices = 0;
-    if (const char *e = getenv("W4A4_EXP_STAGGER")) g.osum_slices = atoi(e);
-    if (const char *e = getenv("W4A4_EXP_PAIR")) {
-        const int d = atoi(e);
-        if (d > 1 && grid % (16 * d) == 0 && (d & (d - 1)) == 0) g.slice_tiles = d;
-    }
     launch_gemm(L::kernel(), dim3(grid), dim3(WM * WN * 64), L::lds, st, g);
     return launch_status();
 }
@@ -423,6 +397,7 @@ static int launch_variant6(int variant, GemmArgs &g, hipStream_t st) {
         case 0: return launch_one6<2, 4, 2, 2, 2, 4, OUT>(g, st);   // 128 x 256, two workgroups per CU
         case 1: return launch_one6<3, 2, 2, 2, 2, 5, OUT>(g, st);   // 192 x 128, two workgroups per CU
         case 2: return launch_one6<2, 2, 2, 2, 3, 4, OUT>(g, st);   // 128 x 128, three workgroups per CU
+        case 3: return launch_one6<3, 4, 2, 2, 1, 7, OUT>(g, st);   // 192 x 256, one workgroup per CU, one wave per SIMD
         default: return W4A4_ERR_INVALID_ARG;
     }
 }

@@ -189,5 +189,7 @@ def fp6_to_codes(q, K, rows, weight=False):
     return out
 
 
-def fp6_schedules(B):
-    return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("fp6")]
+def fp6_schedules(B, K):
+    """Schedule numbers of the FP6 kernels that take this K (the seven-stage ring of the 192 x 256 tile wants at least
+    nine half steps of 64 codes)."""
+    return [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("fp6") and not (n == "fp6_192x256" and K < 640)]

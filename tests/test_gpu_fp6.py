@@ -90,8 +90,8 @@ def test_gemm_i32_bit_exact(B, orc, M, N, K):
     rng = np.random.default_rng(M * 3 + N + K)
     A, Q, a, w = _layer(B, orc, rng, M, N, K)
     want = orc.gemm_i32(a["q"], w["q"], SYM, 0)
-    scheds = fp6_schedules(B)
-    assert len(scheds) == 3
+    scheds = fp6_schedules(B, K)
+    assert len(scheds) == (4 if K >= 640 else 3)
     for sch in scheds:
         got = host(B.gemm_i32(A, Q, schedule=sch))
         assert np.array_equal(got, want), f"schedule {B.schedule_names()[sch - 1]}"
@@ -109,7 +109,7 @@ def test_gemm_i32_extreme_codes(B, orc):
     a, w = orc.quantize_act(X, SYM), orc.quantize_weight(W, SYM, 0)
     want = orc.gemm_i32(a["q"], w["q"], SYM, 0)
     assert np.abs(want).max() == 49 * 4096
-    for sch in fp6_schedules(B):
+    for sch in fp6_schedules(B, K):
         assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch)), want)
 
 
@@ -120,7 +120,7 @@ def test_linear_fp16(B, orc, act, with_bias):
     A, Q, a, w = _layer(B, orc, rng, M, N, K)
     bias = (rng.standard_normal(N) * 0.1).astype(np.float16) if with_bias else None
     want = orc.linear(a, w, SYM, 0, bias, act)["out"]
-    for sch in fp6_schedules(B):
+    for sch in fp6_schedules(B, K):
         got = host(B.linear(A, Q, dev(bias) if with_bias else None, act, schedule=sch))
         assert_f16(got, want, GELU_SAME if act else 1.0, f"schedule {B.schedule_names()[sch - 1]}")
 
@@ -139,7 +139,7 @@ def test_many_tiles_per_workgroup(B, orc, K):
     a, w = orc.quantize_act(X[rows], SYM), orc.quantize_weight(W, SYM, 0)
     want_i = orc.gemm_i32(a["q"], w["q"], SYM, 0)
     want = orc.linear(a, w, SYM, 0, bias, 0)["out"]
-    for sch in fp6_schedules(B):
+    for sch in fp6_schedules(B, K):
         assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch))[0][rows], want_i[0]), B.schedule_names()[sch - 1]
         got = host(B.linear(A, Q, dev(bias), 0, schedule=sch))[rows]
         assert_f16(got, want, 1.0, B.schedule_names()[sch - 1])
