@@ -154,8 +154,10 @@ class StepWorkload:
         from paper_2301_12017_amd import binding as B, synth, workloads as WL
         self.cfg, self.B = cfg, B
         self.specs = synth.config_linears(cfg)
-        self.layers = [WL.make_layer(s, cfg, i, keep_host=False, layout=None if layout < 0 else layout)
-                       for i, s in enumerate(self.specs)]
+        # layout: -1 = what the library prefers per shape, a number = that layout for every layer, a list = per layer
+        lays = layout if isinstance(layout, (list, tuple)) else [layout] * len(self.specs)
+        self.layers = [WL.make_layer(s, cfg, i, keep_host=False, layout=None if lay < 0 else lay)
+                       for i, (s, lay) in enumerate(zip(self.specs, lays))]
         self.Xs = [WL.dev(WL.make_input(s, cfg, i)) for i, s in enumerate(self.specs)]
         self.qacts = [B.quantize_act(X, s.mode, s.group, layout=L.W.layout) for X, s, L in zip(self.Xs, self.specs, self.layers)]
         self.outs = [B._alloc_out(qa, L.W, False, 0, 0) for qa, L in zip(self.qacts, self.layers)]
@@ -324,6 +326,25 @@ def ceilings_leg(settle_ms):
     ops_zero = torch.zeros_like(ops_real)
     out = {}
     iters = 4000
+    # the same codes as FP6 E2M3 fields (sign, then the magnitude's exponent and mantissa), 32 per operand
+    mag6 = np.array([0, 8, 16, 20, 24, 26, 28, 30], dtype=np.uint8)
+    c6 = np.clip(np.rint(rng.standard_normal((64, 4, 32)) * 1.9), -7, 7).astype(np.int64)      # per lane: A0, B0, A1, B1
+    f6 = (np.where(c6 < 0, 32, 0) | mag6[np.abs(c6)]).astype(np.uint8)
+    bits6 = ((f6[..., None] >> np.arange(6, dtype=np.uint8)) & 1).astype(np.uint8).reshape(64, 4, 192)
+    bytes6 = np.packbits(bits6, axis=2, bitorder="little")                                      # [64, 4, 24]
+    ops6 = np.zeros((64, 4, 32), dtype=np.uint8)
+    ops6[:, :, :24] = bytes6
+    ops6_real = torch.from_numpy(ops6.reshape(64, 128).view(np.int32).copy()).cuda()            # [64 lanes][32 words]
+    for name, ops in (("zero_operands", torch.zeros_like(ops6_real)), ("int4_codes", ops6_real)):
+        settle(lambda: B.probe_mfma_fp6(ops, 500, sink), min(settle_ms, 100.0))
+        tms = [B.KernelTimer() for _ in range(5)]
+        n = 0
+        for t in tms:
+            t.arm()
+            n = B.probe_mfma_fp6(ops, iters, sink)
+        torch.cuda.synchronize()
+        ms = sorted(t.elapsed_ms() for t in tms)[len(tms) // 2]
+        out[f"mfma_fp6_{name}_TOPS"] = n * 131072.0 / (ms * 1e-3) / 1e12
     for name, ops in (("zero_operands", ops_zero), ("int4_codes", ops_real)):
         settle(lambda: B.probe_mfma(ops, 500, sink), min(settle_ms, 100.0))
         tms = [B.KernelTimer() for _ in range(5)]
@@ -346,7 +367,8 @@ def ceilings_leg(settle_ms):
         torch.cuda.synchronize()
         ms = sorted(t.elapsed_ms() for t in tms)[len(tms) // 2]
         out[f"hbm_{name}_GBps"] = moved / (ms * 1e-3) / 1e9
-    out["note"] = ("register-only v_mfma_i32_32x32x32_i8 loop, two waves per SIMD on every CU (w4a4_probe_mfma), median of five "
+    out["note"] = ("register-only v_mfma_i32_32x32x32_i8 loop, two waves per SIMD on every CU (w4a4_probe_mfma), and the same loop of "
+                   "v_mfma_f32_32x32x64_f8f6f4 on FP6 E2M3 operands (w4a4_probe_mfma_fp6; nominal 10100 TOP/s), median of five "
                    "launches; a coalesced 1 GiB read-only stream and a 512 MiB -> 512 MiB copy (w4a4_probe_stream, bytes "
                    "read + written); nominal peaks: 5000 TOP/s, 8000 GB/s")
     del src, dst
@@ -793,6 +815,30 @@ def main():
                          "kernel_ms": r5["kernel_ms_per_step"], "frac": r5["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
                          "per_gemm_ms": dict(zip(r5["names"], r5["gemm_ms"])),
                          "kernel": "gemm_olay_kernel with the fused requantize epilogue; schedules " + ", ".join(r5["schedules"])}
+
+        if cfg == 3:
+            # the same step with the layers of at least 2M weights in the FP6 operand layout: their GEMMs run on the FP6
+            # matrix instruction (exact integer sums in its FP32 accumulator); the others stay on the int8 MFMA
+            torch.cuda.empty_cache()
+            lay6 = [B.LAYOUT_FP6 if s_.N * s_.K >= (1 << 21) else B.LAYOUT_MFMA for s_ in specs]
+            w6 = StepWorkload(3, 0, lay6)
+            r6 = w6.measure(side_steps, args.warmup, args.settle_ms)
+            ops6 = sum(2 * s_.M * s_.N * s_.K for s_, l_ in zip(specs, lay6) if l_ == B.LAYOUT_FP6)
+            ms6 = sum(t for t, l_ in zip(r6["gemm_ms"], lay6) if l_ == B.LAYOUT_FP6)
+            other["cfg3_fp6_path"] = {
+                "workload": "configs[2] again, " + ", ".join(s_.name for s_, l_ in zip(specs, lay6) if l_ == B.LAYOUT_FP6)
+                            + " in the FP6 operand layout (v_mfma_f32_32x32x64_f8f6f4, FP6 E2M3 x FP6 E2M3 -> FP32, exact for "
+                              "symmetric INT4 codes), the rest on the int8 MFMA; quantize_act + w4a4_linear x 4",
+                "steps": side_steps, "ms_per_step": r6["ms_per_step"], "TOPS": r6["TOPS"],
+                "step_speedup_over_int8_path": ms_per_step / r6["ms_per_step"],
+                "kernel_ms": r6["kernel_ms_per_step"], "kernel_TOPS": r6["achieved_TOPS"],
+                "frac_of_int8_mfma_peak": r6["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
+                "fp6_kernels": {"ops": ops6, "ms": ms6, "TOPS": ops6 / (ms6 * 1e-3) / 1e12,
+                                "frac_of_fp6_mfma_peak": ops6 / (ms6 * 1e-3) / 1e12 / 10100.0,
+                                "frac_of_measured_fp6": ops6 / (ms6 * 1e-3) / 1e12 / ceil["mfma_fp6_int4_codes_TOPS"]},
+                "per_gemm_ms": {s_.name: t for s_, t in zip(w6.specs, r6["gemm_ms"])},
+                "kernel": kernel_label(w6.schedules)}
+            del w6
 
     roof = {"bound": "mfma", "achieved": achieved, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
             "frac": achieved / INT8_MFMA_PEAK_TOPS,

@@ -85,16 +85,27 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  *              GEMM runs on the FP6 form of the matrix instruction with FP32 accumulation: products
  *              and sums of such integers are exact in FP32 below 2^24, i.e. the accumulator IS the
  *              INT32 result of the integer GEMM (Sec. 4.2 counts on INT4 tensor cores at twice the
- *              INT8 rate; on gfx950 that pipe is the FP6 one).  A row of K codes is K/32 operands of
- *              32 codes = 24 bytes; operand 2b + h lies in the row's 48-byte block b as 16 bytes at
- *              16h and 8 bytes at 32 + 8h.  Which codes an operand holds depends on K alone:
- *              with LPR the largest of 64, 32, 16, 8 that divides K/32 with a quotient OPL <= 6,
- *              operand o*LPR + l holds the four 8-code chunks l + LPR*(4o + j), j = 0..3, element e
- *              of chunk j in 6-bit field 2*(8*(j&1) + e) + (j>>1) (fields little-endian in the 24
- *              bytes).  Activations and weights use the same rule, so the contraction over K is
- *              unchanged.  Rows are 3K/4 bytes (lda of a w4a4_act in bytes, as always).
+ *              INT8 rate; on gfx950 that pipe is the FP6 one).  Private to the library in every detail:
+ *              - a row of K codes is K/32 operands of 32 codes = 24 bytes; operands 2b and 2b+1 form
+ *                the row's 48-byte block b: operand 2b+h as 16 bytes at 16h and 8 bytes at 32 + 8h
+ *                (the two 8-byte parts exchanged in storage rows 16..31 of every 32);
+ *              - which codes an operand holds depends on K alone: with LPR the smallest of 8, 16, 32,
+ *                64 that divides K/32 with OPL = K/32/LPR <= 2 (else <= 3, 4, 6), operand o*LPR + l
+ *                holds the four 8-code chunks l + LPR*(4o + j), j = 0..3, element e of chunk j in
+ *                6-bit field 2*(8*(j&1) + e) + (j>>1) (fields little-endian in the 24 bytes).
+ *                Activations and weights use the same rule, so the contraction over K is unchanged;
+ *              - rows are stored in panels, block b of all rows of a panel contiguously (what lets the
+ *                GEMM fetch whole kilobytes of consecutive addresses): activations in panels of 64
+ *                tokens, token m in storage row m % 64 of panel m / 64; weights in panels of 128
+ *                output channels, channel n in storage row (n % 4) * 32 + (n % 128) / 4 of panel
+ *                n / 128; a panel is K/64 blocks of [storage row][48 bytes]; matrices are padded with
+ *                zero rows to whole panels.  q therefore holds ceil(M/64)*64 (ceil(N/128)*128) rows
+ *                of 3K/4 bytes; lda of such a w4a4_act is 3K/4 and is not a stride.
  * The FP6 layout needs symmetric codes, one scale per token / output channel (group == 0),
- * K % 256 == 0 with such an LPR, and K >= 512 for the GEMM; no code sums travel with it. */
+ * K % 256 == 0 with such an LPR, K <= 10240, and K >= 512 for the GEMM; no code sums travel with it.
+ * w4a4_quantize_act, w4a4_quantize_weight, w4a4_gemm_i32 and w4a4_linear (any epilogue; a requantized
+ * output is produced in the canonical or the MFMA layout, through the fp32 rows of the workspace)
+ * understand it; the fused-producer, strategy and whole-layer calls do not. */
 typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1, W4A4_LAYOUT_FP6 = 2 } w4a4_layout;
 
 /* Sec. 4.2: GELU (erf form) may sit between the GEMM and the next quantize. */
@@ -317,10 +328,15 @@ int w4a4_time_next_gemm(void *start_event, void *stop_event);
  *     (device): per lane two A operands (words 0..3, 8..11) and two B operands (words 4..7, 12..15) of sixteen
  *     int8 each; the rate depends on their values through the clock the chip keeps (zeros: highest).  Returns
  *     the number of wave-level MFMA instructions issued (65536 integer operations each) or a w4a4_status < 0.
+ *   w4a4_probe_mfma_fp6: the same loop of v_mfma_f32_32x32x64_f8f6f4 with both operands FP6 E2M3 (what the FP6
+ *     operand layout runs on).  operands [64 lanes][32] words: per lane two A operands (words 0..5, 16..21) and
+ *     two B operands (words 8..13, 24..29) of 32 six-bit fields each.  Returns the number of wave-level MFMA
+ *     instructions issued (131072 operations each) or a w4a4_status < 0.
  *   w4a4_probe_stream: reads `bytes` (a multiple of 16, 16-byte aligned) from src with coalesced 16-byte loads
  *     and either writes them to dst (a copy) or, with dst == NULL, stores nothing.  Returns a w4a4_status.
  *   sink: one device word that the kernels never write in practice (it keeps their loops alive). */
 long w4a4_probe_mfma(const uint32_t *operands, int iters, uint32_t *sink, void *stream);
+long w4a4_probe_mfma_fp6(const uint32_t *operands, int iters, uint32_t *sink, void *stream);
 int w4a4_probe_stream(const void *src, void *dst, size_t bytes, uint32_t *sink, void *stream);
 
 /* The schedule number (1-based, see w4a4_schedule_name) that w4a4_linear would run this layer on with

@@ -112,6 +112,7 @@ _SIGNATURES = {
     "w4a4_fused_fault_check": (_i, [_vp]),
     "w4a4_debug_fused_wait": (_i, [_i, _i]),
     "w4a4_probe_mfma": (ctypes.c_long, [_vp, _i, _vp, _vp]),
+    "w4a4_probe_mfma_fp6": (ctypes.c_long, [_vp, _i, _vp, _vp]),
     "w4a4_probe_stream": (_i, [_vp, _vp, _sz, _vp, _vp]),
     "w4a4_pick_schedule": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), ctypes.POINTER(_Epilogue)]),
     "w4a4_gemm_i32": (_i, [ctypes.POINTER(_Act), ctypes.POINTER(_Weight), _vp, _i, _vp]),
@@ -229,6 +230,15 @@ def probe_mfma(operands: torch.Tensor, iters: int, sink: torch.Tensor) -> int:
     n = lib().w4a4_probe_mfma(_ptr(operands), iters, _ptr(sink), _stream())
     if n < 0:
         raise W4A4Error(int(n), "w4a4_probe_mfma")
+    return int(n)
+
+
+def probe_mfma_fp6(operands: torch.Tensor, iters: int, sink: torch.Tensor) -> int:
+    """w4a4_probe_mfma_fp6; returns the number of wave-level MFMA instructions the launch issues."""
+    assert operands.dtype == torch.int32 and operands.numel() == 64 * 32 and operands.is_cuda
+    n = lib().w4a4_probe_mfma_fp6(_ptr(operands), iters, _ptr(sink), _stream())
+    if n < 0:
+        raise W4A4Error(int(n), "w4a4_probe_mfma_fp6")
     return int(n)
 
 

@@ -340,6 +340,7 @@ extern "C" const char *w4a4_schedule_name(int schedule) {
 // The residency limits come from the runtime's occupancy figure for the kernel on the current device.
 static int fused_requant_kind(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
     if (!ep->requant || ep->requant_mode != W4A4_SYM) return 0;
+    if (A->layout == W4A4_LAYOUT_FP6) return 0;                // the FP6 kernel stores fp32 rows; the row quantizer packs them
     if (A->mode != W4A4_SYM || (W->group != 0 && W->group != W->K)) return 0;
     if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return 0;
     if (((long)A->M + 512) * W->N * 4 >= 0x80000000L) return 0;

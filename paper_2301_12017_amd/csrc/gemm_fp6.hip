@@ -282,21 +282,12 @@ void gemm_fp6_kernel(GemmArgs g) {
                     if constexpr (LAST) __builtin_amdgcn_s_waitcnt(vmcnt_and_lds(0));
                     else if constexpr (WAIT) __builtin_amdgcn_s_waitcnt(vmcnt_and_lds((NS - 2) * LD));
                     else __builtin_amdgcn_s_waitcnt(vmcnt_and_lds(63));
-#ifndef W4A4_EXP6_NOBAR
                     __builtin_amdgcn_s_barrier();
-#endif
                     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
                 } else {
-#ifndef W4A4_EXP6_NOREAD
 #pragma unroll
                     for (int x = (k - 1) * RPS; x < k * RPS && x < NF; ++x) Pn[frag_in_order(x)] = read_frag(frag_in_order(x), nxt);
-#else
-#pragma unroll
-                    for (int x = (k - 1) * RPS; x < k * RPS && x < NF; ++x) Pn[frag_in_order(x)] = Pc[frag_in_order(x)];
-#endif
-#ifndef W4A4_EXP6_NODMA
                     if (k - 1 < LD) dma_one(k - 1, cur, ra, rb, so);
-#endif
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -339,11 +330,7 @@ void gemm_fp6_kernel(GemmArgs g) {
         // ---- epilogue of this tile ------------------------------------------------------------------
         {
             constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
-#ifdef W4A4_EXP6_NOSTORE
-            const uint32_t col_off = kPoison;
-#else
             const uint32_t col_off = n_lane < g.N ? (uint32_t)n_lane * ESZ : kPoison;
-#endif
             ChanParams6<FN> cp;
 #pragma unroll
             for (int j = 0; j < FN; ++j) {

@@ -39,6 +39,39 @@ __global__ __launch_bounds__(256) void mfma_probe_kernel(const uint32_t *__restr
     if (s == 0x7fffffff) sink[0] = (uint32_t)s;                   // keeps the loop alive; practically never taken
 }
 
+// The same loop on the FP6 form of the matrix instruction (v_mfma_f32_32x32x64_f8f6f4, both operands E2M3): per
+// lane two A and two B operands of 32 six-bit fields each (24 bytes, the first six of eight words).
+typedef int v8i_p __attribute__((ext_vector_type(8)));
+__global__ __launch_bounds__(256) void mfma_fp6_probe_kernel(const uint32_t *__restrict__ operands, int iters, uint32_t *sink) {
+    const int lane = threadIdx.x & 63;
+    v8i_p a[2], b[2];
+#pragma unroll
+    for (int s = 0; s < 2; ++s)
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            a[s][r] = r < 6 ? (int)operands[lane * 32 + s * 16 + r] : 0;
+            b[s][r] = r < 6 ? (int)operands[lane * 32 + s * 16 + 8 + r] : 0;
+        }
+    v16f acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i & 1], b[(i >> 1) & 1], acc[i], 2, 2, 0, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s += acc[i][r];
+    if (s == 12345.678f) sink[0] = 1u;                            // keeps the loop alive; practically never taken
+}
+
 // Streaming kernel: every lane reads 16 bytes per step, consecutive lanes consecutive addresses, grid-stride;
 // with a destination it writes what it read (a copy), without one it folds the data into one word per lane and
 // stores nothing: the rate a read-mostly, HBM-bound kernel such as the token-wise quantizer can hope for.
@@ -70,6 +103,16 @@ extern "C" long w4a4_probe_mfma(const uint32_t *operands, int iters, uint32_t *s
     if (cus < 0) return W4A4_ERR_HIP;
     const unsigned grid = (unsigned)cus * 2;                      // two waves on every SIMD, as the GEMM kernels run
     launch_gemm(mfma_probe_kernel, dim3(grid), dim3(256), 0, as_stream(stream), operands, iters, sink);
+    if (launch_status() != W4A4_OK) return W4A4_ERR_HIP;
+    return (long)grid * 4 * 8 * (long)iters;                      // wave-level MFMA instructions issued
+}
+
+extern "C" long w4a4_probe_mfma_fp6(const uint32_t *operands, int iters, uint32_t *sink, void *stream) {
+    if (!operands || !sink || iters <= 0) return W4A4_ERR_INVALID_ARG;
+    const int cus = probe_cus();
+    if (cus < 0) return W4A4_ERR_HIP;
+    const unsigned grid = (unsigned)cus * 2;                      // two waves on every SIMD
+    launch_gemm(mfma_fp6_probe_kernel, dim3(grid), dim3(256), 0, as_stream(stream), operands, iters, sink);
     if (launch_status() != W4A4_OK) return W4A4_ERR_HIP;
     return (long)grid * 4 * 8 * (long)iters;                      // wave-level MFMA instructions issued
 }

@@ -554,14 +554,16 @@ typedef unsigned int v6u_q __attribute__((ext_vector_type(6)));
 // an integer of magnitude <= 7, is exactly representable in FP6 E2M3, so the hardware conversion of 32 fp32 values
 // to 32 packed FP6 fields is exact.  Two vector instructions per code plus one conversion per 32.
 template <int LPR, int OPL>
-__global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_fp6_rows_kernel(
+__global__ __launch_bounds__(8 * kWave) void quantize_fp6_rows_kernel(
     const __half *__restrict__ X, long ldx, int rows, uint8_t *__restrict__ q, float *__restrict__ s) {
     constexpr int RPW = kWave / LPR, NJ = 4 * OPL;
     constexpr int KB = LPR * OPL / 2;                           // 48-byte blocks (64 codes) per row
     typedef unsigned int u4 __attribute__((ext_vector_type(4)));
     typedef unsigned int u2 __attribute__((ext_vector_type(2)));
     const int lane = threadIdx.x % kWave, l = lane % LPR;
-    const long row = ((long)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave) * RPW + lane / LPR;
+    // a workgroup owns a multiple of eight consecutive rows: 384 contiguous bytes of every block, whole cache lines
+    // that no other workgroup (on another XCD, behind another L2) writes to
+    const long row = ((long)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave) * RPW + lane / LPR;
     const bool live = row < rows;                               // rows up to the end of the last 64-row panel are written as zeros
     const bool padded = row < (((long)rows + 63) & ~63L);
     const u4 *src = reinterpret_cast<const u4 *>(X + (live ? row : (long)rows - 1) * ldx);
@@ -580,8 +582,13 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_fp6_rows_kernel
     const unsigned short hmax = hi2[0] > hi2[1] ? hi2[0] : hi2[1];
     const Range r = range_sym(sub_max<LPR>(__half2float(__ushort_as_half(hmax))));
     if (l == 0 && live) s[row] = r.S;
-    // row m of the matrix: panel m / 64, and inside every 3072-byte block of the panel the 48 bytes at (m % 64) * 48
-    uint8_t *qrow = q + (row >> 6) * ((long)KB * 3072) + (row & 63) * 48;
+    // The operands go to LDS first, laid out as this workgroup's part of the panel ([block][row of the workgroup][48
+    // bytes]), and from there to memory in runs of whole cache lines: written straight from the lanes, every store
+    // instruction would touch 32 blocks 3 KB apart with 32 bytes each, which costs a 12288 x 4096 matrix 6 of 32 us.
+    extern __shared__ __attribute__((aligned(16))) uint8_t stage6[];
+    const int rows_wg = (blockDim.x / kWave) * RPW;             // 8, 16 or 32: a multiple of 8, so 384-byte multiples per block
+    const int r_wg = (threadIdx.x / kWave) * RPW + lane / LPR;
+    uint8_t *srow = stage6 + r_wg * 48;
 #pragma unroll
     for (int o = 0; o < OPL; ++o) {
         v16f_q a, b;
@@ -600,11 +607,21 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_fp6_rows_kernel
         v6u_q w6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(a, b, 1.0f);
         if (!live) w6 = v6u_q{0u, 0u, 0u, 0u, 0u, 0u};
         const int idx = o * LPR + l;
-        uint8_t *blk = qrow + (long)(idx >> 1) * 3072 + (idx & 1) * 16;
-        if (padded) {
-            *reinterpret_cast<u4 *>(blk) = u4{w6[0], w6[1], w6[2], w6[3]};
-            // the 8-byte part: at 32 + 8h, the two halves exchanged in rows 16 .. 31 of every 32 (LDS banks of the GEMM's reads)
-            *reinterpret_cast<u2 *>(qrow + (long)(idx >> 1) * 3072 + 32 + (((idx & 1) ^ (int)((row >> 4) & 1)) * 8)) = u2{w6[4], w6[5]};
+        uint8_t *blk = srow + (idx >> 1) * (rows_wg * 48);
+        *reinterpret_cast<u4 *>(blk + (idx & 1) * 16) = u4{w6[0], w6[1], w6[2], w6[3]};
+        // the 8-byte part: at 32 + 8h, the two halves exchanged in rows 16 .. 31 of every 32 (LDS banks of the GEMM's reads)
+        *reinterpret_cast<u2 *>(blk + 32 + (((idx & 1) ^ (int)((row >> 4) & 1)) * 8)) = u2{w6[4], w6[5]};
+    }
+    __syncthreads();
+    // rows of the workgroup: row0 .. row0 + rows_wg - 1 (inside one panel: rows_wg divides 64); block b of them lies at
+    // panel + b * 3072 + (row0 % 64) * 48, rows_wg * 48 bytes long
+    const long row0 = (long)blockIdx.x * rows_wg;
+    if (row0 < (((long)rows + 63) & ~63L)) {
+        uint8_t *dst = q + (row0 >> 6) * ((long)KB * 3072) + (row0 & 63) * 48;
+        const int per_block = rows_wg * 3;                      // 16-byte pieces per block
+        for (int pc = threadIdx.x; pc < KB * per_block; pc += blockDim.x) {
+            const int bq = pc / per_block, within = pc - bq * per_block;
+            *reinterpret_cast<u4 *>(dst + (long)bq * 3072 + within * 16) = *reinterpret_cast<const u4 *>(stage6 + pc * 16);
         }
     }
 }
@@ -613,11 +630,14 @@ static int launch_fp6_rows(const __half *X, long ldx, int rows, int K, uint8_t *
     if (rows == 0) return W4A4_OK;
     int lpr = 0, opl = 0;
     if (!fp6_plan(K, &lpr, &opl)) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const long per_block = (long)kRowsPerBlock * (kWave / lpr);
+    const int rpw = kWave / lpr, waves = rpw >= 2 ? 4 : 8;      // 8 .. 32 rows per workgroup
+    const long per_block = (long)waves * rpw;
     const long padded = ((long)rows + 63) & ~63L;
-    dim3 grid((unsigned)((padded + per_block - 1) / per_block)), block(kRowsPerBlock * kWave);
+    dim3 grid((unsigned)(padded / per_block)), block(waves * kWave);
+    const size_t lds = (size_t)per_block * (K / 64) * 48;       // the workgroup's rows, staged (60 KB at most: fp6_plan)
+    if (lds > 64 * 1024) return W4A4_ERR_UNSUPPORTED_SHAPE;
 #define W4A4_Q6(L, O) \
-    case O: hipLaunchKernelGGL((quantize_fp6_rows_kernel<L, O>), grid, block, 0, st, X, ldx, rows, q, s); break
+    case O: hipLaunchKernelGGL((quantize_fp6_rows_kernel<L, O>), grid, block, lds, st, X, ldx, rows, q, s); break
 #define W4A4_Q6L(L)                                                                                        \
     switch (opl) { W4A4_Q6(L, 1); W4A4_Q6(L, 2); W4A4_Q6(L, 3); W4A4_Q6(L, 4); W4A4_Q6(L, 5); W4A4_Q6(L, 6); default: return W4A4_ERR_UNSUPPORTED_SHAPE; }
     if (lpr == 8) { W4A4_Q6L(8) }

@@ -68,7 +68,8 @@ size_t part_bytes(int M, const w4a4_part &p) {
 }
 
 bool part_ok(const w4a4_part *p) {
-    return p && p->w4.N > 0 && p->w4.K > 0 && p->w4.K % 32 == 0 &&
+    // (the workspaces carved here hold nibble-packed activations: weights in the FP6 operand layout are not taken)
+    return p && p->w4.N > 0 && p->w4.K > 0 && p->w4.K % 32 == 0 && p->w4.layout != W4A4_LAYOUT_FP6 &&
            (p->act == W4A4_ACT_NONE || p->act == W4A4_ACT_GELU);
 }
 

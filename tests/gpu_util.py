@@ -137,13 +137,15 @@ _FP6_VALUE = {0: 0, 8: 1, 16: 2, 20: 3, 24: 4, 26: 5, 28: 6, 30: 7}     # E2M3 m
 
 
 def fp6_plan(K):
-    """(lanes per row, operands per lane) of the layout's permutation of K, or None where the layout does not exist."""
+    """(lanes per row, operands per lane) of the layout's permutation of K, or None where the layout does not exist:
+    the fewest lanes (8, 16, 32, 64; a divisor of K/32) that keep the operands per lane <= 2, else <= 3, 4, 6."""
     n_op = K // 32
-    if K % 64:
+    if K % 64 or K > 10240:
         return None
-    for lpr in (64, 32, 16, 8):
-        if n_op % lpr == 0 and n_op // lpr <= 6:
-            return lpr, n_op // lpr
+    for most in (2, 3, 4, 6):
+        for lpr in (8, 16, 32, 64):
+            if n_op % lpr == 0 and n_op // lpr <= most:
+                return lpr, n_op // lpr
     return None
 
 

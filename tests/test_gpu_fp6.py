@@ -50,7 +50,7 @@ def test_plan_matches_the_library(B):
 
 @pytest.mark.parametrize("M,K,ldx", [(1, 256, 256), (77, 512, 520), (300, 768, 768), (8193, 1024, 1024), (130, 1280, 1288),
                                      (67, 1536, 1536), (515, 2048, 2048), (2100, 3072, 3072), (1030, 4096, 4104),
-                                     (33, 8192, 8192), (9, 12288, 12288)])
+                                     (33, 8192, 8192), (9, 10240, 10240)])
 def test_quantize_act_fp6_layout(B, orc, M, K, ldx):
     rng = np.random.default_rng(M + K)
     Xw = (rng.standard_normal((M, ldx)) * rng.uniform(0.1, 4.0, size=(M, 1))).astype(np.float32).astype(np.float16)
@@ -159,3 +159,66 @@ def test_argument_errors(B):
     A2, Q2 = B.quantize_act(dev(X2), SYM, layout=FP6), B.quantize_weight(dev(W2), SYM, 0, layout=FP6)
     with pytest.raises(RuntimeError):
         B.linear(A2, Q2, None, 0)
+
+
+@pytest.mark.parametrize("rmode,rlayout", [(SYM, 0), (1, 0), (SYM, 1)])
+def test_requantized_output_from_fp6_operands(B, orc, rmode, rlayout):
+    """A requantized output of a layer in the FP6 layout: the GEMM leaves fp32 rows (the definition's operation order) and the
+    row quantizer packs them, in the canonical or the int8-MFMA operand layout: codes and scales equal the oracle's."""
+    from tests.gpu_util import act_to_canonical
+    M, N, K = 200, 512, 768
+    rng = np.random.default_rng(11 + rmode + rlayout)
+    A, Q, a, w = _layer(B, orc, rng, M, N, K)
+    bias = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    rg = 0 if rlayout == 1 else 128
+    want = orc.linear(a, w, SYM, 0, bias, 0, requant=True, requant_mode=rmode, requant_group=rg)
+    got = B.linear(A, Q, dev(bias), 0, requant=True, requant_mode=rmode, requant_group=rg, requant_layout=rlayout)
+    q = host(got.q)
+    assert np.array_equal(act_to_canonical(q) if rlayout == 1 else q, want["q"])
+    assert np.array_equal(host(got.scale).view(np.uint32), want["s"].view(np.uint32))
+    if rmode == 1:
+        assert np.array_equal(host(got.zero).view(np.uint32), want["z"].view(np.uint32))
+
+
+def test_calls_that_do_not_take_the_layout_refuse_it(B):
+    rng = np.random.default_rng(5)
+    W = _w(rng, 768, 768)
+    Q = B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    X = dev(_x(rng, 64, 768))
+    with pytest.raises(RuntimeError):                          # LayerNorm + quantize writes nibble layouts only
+        B.layernorm_quantize(X, None, torch.ones(768, dtype=torch.float16, device="cuda"),
+                             torch.zeros(768, dtype=torch.float16, device="cuda"), 1e-5, SYM, 0, layout=FP6)
+    with pytest.raises(RuntimeError):                          # one-launch small-token kernel: canonical weights only
+        B.linear_f16act(X, Q, None, 0)
+
+
+def test_headline_workload_at_full_size(B, orc):
+    """Workload configs[2] (12288 tokens, BERT-large shapes) in the FP6 layout, in the launch configuration the bench
+    times: codes and scales of sampled tokens, every weight code, and the fp16 outputs of 256 stratified rows per GEMM
+    against the oracle (bit for bit without GELU; within one fp16 step behind it)."""
+    from paper_2301_12017_amd import synth, workloads as WL
+    rng = np.random.default_rng(33)
+    for i, spec in enumerate(synth.config_linears(3)):
+        layer = WL.make_layer(spec, 3, i, layout=FP6)
+        X = WL.make_input(spec, 3, i)
+        A = B.quantize_act(dev(X), SYM, layout=FP6)
+        Y = B.linear(A, layer.W, layer.bias, layer.act)
+        assert B.pick_schedule(A, layer.W).startswith("fp6")
+        panels = (spec.M + 127) // 128
+        rows = {0, spec.M - 1}
+        order = rng.permutation(panels)
+        k = 0
+        while len(rows) < 256:
+            rows.add(min(spec.M - 1, int(order[k % panels]) * 128 + int(rng.integers(128))))
+            k += 1
+        rows = np.array(sorted(rows))
+        codes = fp6_to_codes(host(A.q), spec.K, spec.M)
+        oa = orc.quantize_act(X[rows], SYM)
+        assert np.array_equal(codes[rows], orc.unpack(oa["q"], SYM))
+        assert np.array_equal(host(A.scale)[rows].view(np.uint32), oa["s"].view(np.uint32))
+        ow = orc.quantize_weight(layer.host_W, SYM, 0)
+        assert np.array_equal(fp6_to_codes(host(layer.W.q), spec.K, spec.N, weight=True), orc.unpack(ow["q"], SYM))
+        want = orc.linear(oa, ow, SYM, 0, layer.host_b, 1 if spec.gelu else 0)["out"]
+        assert_f16(host(Y)[rows], want, GELU_SAME if spec.gelu else 1.0, spec.name)
+        del Y, A, layer
+        torch.cuda.empty_cache()
