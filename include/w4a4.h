@@ -391,8 +391,9 @@ int w4a4_debug_fused_wait(int spin_limit, int extra_arrivals);
  * group: 0 or a multiple of 32 that divides K.
  * layout == W4A4_LAYOUT_MFMA also needs esum ([N] for SYM with group == 0; [N, K/group + 1] for ASYM
  * with K % 128 == 0 and group % 128 == 0, see w4a4_weight); else esum is ignored.
- * layout == W4A4_LAYOUT_FP6 (SYM, group == 0, a K the layout exists for: see w4a4_layout): q is
- * [N, 3K/4]; gsum[N] = the code sum of a channel. */
+ * layout == W4A4_LAYOUT_FP6 (SYM, group == 0, a K the layout exists for: see w4a4_layout): q receives
+ * ceil(N/128)*128 rows of 3K/4 bytes (whole panels; the rows past N are written as zeros); gsum[N] = the
+ * code sum of a channel. */
 int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
                          uint8_t *q, float *scale, float *zero, int32_t *gsum, float *rowsum_deq,
                          int layout, int32_t *esum, void *stream);
@@ -403,8 +404,9 @@ int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, int group,
  * gsum[M, K/group] (may be NULL).  K <= 16384.
  * layout == W4A4_LAYOUT_MFMA also needs osum ([M] for SYM; [K/group, M] for ASYM with K % 128 == 0 and
  * group % 128 == 0, see w4a4_act); else osum is ignored.
- * layout == W4A4_LAYOUT_FP6 (SYM, group == 0, a K the layout exists for): q is [M, 3K/4] dense rows; gsum
- * must be NULL (W4A4_ERR_UNSUPPORTED_SHAPE otherwise). */
+ * layout == W4A4_LAYOUT_FP6 (SYM, group == 0, a K the layout exists for): q receives ceil(M/64)*64 rows of
+ * 3K/4 bytes (whole panels; the rows past M are written as zeros); gsum must be NULL
+ * (W4A4_ERR_UNSUPPORTED_SHAPE otherwise). */
 int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int group,
                       uint8_t *q, float *scale, float *zero, int32_t *gsum,
                       int layout, int32_t *osum, void *stream);
