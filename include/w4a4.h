@@ -113,14 +113,16 @@ typedef enum { W4A4_ACT_NONE = 0, W4A4_ACT_GELU = 1 } w4a4_act_fn;
 
 /* A token-wise quantized activation matrix (App. A, activation quantization). */
 typedef struct {
-    const uint8_t *q;      /* [M, lda] bytes, first K/2 bytes of a row are codes          */
+    const uint8_t *q;      /* [M, lda] bytes, first K/2 bytes of a row are codes; layout == FP6:
+                              ceil(M/64)*64 * 3K/4 bytes in panels (see w4a4_layout)       */
     const float   *scale;  /* [M]   S of each token                                       */
     const float   *zero;   /* [M]   x_zero of each token; NULL when mode == SYM           */
     const int32_t *gsum;   /* [M, ng] sum of the codes of a token inside each weight
                               K-group; required when mode == ASYM, else may be NULL      */
     int M, K;
     int lda;               /* row stride of q in BYTES (>= K/2, multiple of 16): lets a
-                              GEMM read a column slice of a wider packed matrix in place */
+                              GEMM read a column slice of a wider packed matrix in place;
+                              layout == FP6: 3K/4, not a stride (no slices there)        */
     int group;             /* K-group length the gsum was taken over (0 = whole row)     */
     int mode;              /* w4a4_mode */
     int layout;            /* w4a4_layout of q                                           */
@@ -135,7 +137,7 @@ typedef struct {
 /* A weight matrix quantized offline (App. A, weight quantization), row n = output
  * channel n, groups = contiguous runs of `group` elements along K. ng = K/group. */
 typedef struct {
-    const uint8_t *q;          /* [N, K/2]                                               */
+    const uint8_t *q;          /* [N, K/2]; layout == FP6: ceil(N/128)*128 * 3K/4 bytes   */
     const float   *scale;      /* [N, ng]                                                */
     const float   *zero;       /* [N, ng]; NULL when mode == SYM                         */
     const float   *rowsum_deq; /* [N] sum over k of the dequantized weight; ASYM only    */
