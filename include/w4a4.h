@@ -89,11 +89,8 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  *              - a row of K codes is K/32 operands of 32 codes = 24 bytes; operands 2b and 2b+1 form
  *                the row's 48-byte block b: operand 2b+h as 16 bytes at 16h and 8 bytes at 32 + 8h
  *                (the two 8-byte parts exchanged in storage rows 16..31 of every 32);
- *              - which codes an operand holds depends on K alone: with LPR the smallest of 8, 16, 32,
- *                64 that divides K/32 with OPL = K/32/LPR <= 2 (else <= 3, 4, 6), operand o*LPR + l
- *                holds the four 8-code chunks l + LPR*(4o + j), j = 0..3, element e of chunk j in
- *                6-bit field 2*(8*(j&1) + e) + (j>>1) (fields little-endian in the 24 bytes).
- *                Activations and weights use the same rule, so the contraction over K is unchanged;
+ *              - operand o of a row holds codes 32o .. 32o+31 in its 6-bit fields 0 .. 31 (fields
+ *                little-endian in the 24 bytes), for activations and weights alike;
  *              - rows are stored in panels, block b of all rows of a panel contiguously (what lets the
  *                GEMM fetch whole kilobytes of consecutive addresses): activations in panels of 64
  *                tokens, token m in storage row m % 64 of panel m / 64; weights in panels of 128
@@ -102,7 +99,8 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  *                zero rows to whole panels.  q therefore holds ceil(M/64)*64 (ceil(N/128)*128) rows
  *                of 3K/4 bytes; lda of such a w4a4_act is 3K/4 and is not a stride.
  * The FP6 layout needs symmetric codes, one scale per token / output channel (group == 0),
- * K % 256 == 0 with such an LPR, K <= 10240, and K >= 512 for the GEMM; no code sums travel with it.
+ * K % 256 == 0, K <= 10240 (the token-wise quantizer stages its rows on chip), and K >= 512 for the GEMM; no code
+ * sums travel with it.
  * w4a4_quantize_act, w4a4_quantize_weight, w4a4_gemm_i32 and w4a4_linear (any epilogue; a requantized
  * output is produced in the canonical or the MFMA layout, through the fp32 rows of the workspace)
  * understand it; the fused-producer, strategy and whole-layer calls do not. */

@@ -236,10 +236,10 @@ inline int resident_per_cu(const void *kern, int threads, size_t lds, KernelStat
     return occ;
 }
 
-// The FP6 operand layout of a row of K codes (see w4a4_layout): lanes per token of the quantizer (LPR: 8, 16, 32 or
-// 64, a divisor of K / 32) and operands of 32 codes per lane (OPL = K / 32 / LPR), which fix the permutation of K that
-// both GEMM operands share.  The fewest lanes that keep OPL <= 2 (a lane then holds at most eight 16-byte chunks,
-// what the token-wise quantizer runs fastest with), else <= 3, 4, 6.  False if the layout does not exist for K.
+// How the token-wise quantizer of the FP6 operand layout (see w4a4_layout) splits a row of K codes: lanes per token
+// (LPR: 8, 16, 32 or 64, a divisor of K / 32) and operands of 32 codes per lane (OPL = K / 32 / LPR).  The fewest lanes
+// that keep OPL <= 2 (a lane then holds at most eight 16-byte chunks, what the quantizer runs fastest with), else
+// <= 3, 4, 6.  False for a K the layout is not offered for.
 inline bool fp6_plan(int K, int *lpr, int *opl) {
     if (K <= 0 || K % 64 || K > 10240) return false;           // (the quantizer stages eight rows in 64 KB of LDS)
     const int n_op = K / 32;

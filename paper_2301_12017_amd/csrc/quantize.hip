@@ -540,12 +540,12 @@ static int launch_tok_rows(const __half *X, long ldx, int rows, int K, uint8_t *
 // block b, [16 bytes at 16h | 8 bytes at 32 + 8h] for operand 2b + h.  Rows are stored in panels (64 tokens, or 128
 // output channels in the order that gives a lane of the GEMM adjacent channels), block b of all rows of a panel
 // contiguously, so that the GEMM's tile loads are whole kilobytes of consecutive addresses; matrices are padded
-// with zero rows to whole panels.  Which codes an operand holds is fixed per K so that the token-wise
-// quantizer loads coalesced and needs no shuffles: a token is owned by LPR lanes, lane l holds the 16-byte chunks
-// (eight fp16 values) l + LPR*j, j = 0 .. 4*OPL-1, and its operand o (index o*LPR + l in the row) is made of chunks
-// j = 4o .. 4o+3.  Inside an operand, element e of chunk j sits in 6-bit field 2*(8*(j&1) + e) + ((j>>1)&1): the order
-// in which the hardware conversion interleaves its two sixteen-value sources.  Weights are laid out by the same
-// rule, so both MFMA operands see the same permutation of K, which a contraction over K does not notice.
+// with zero rows to whole panels.  Operand o of a row holds codes 32o .. 32o+31 in its 6-bit fields 0 .. 31 (little
+// endian), for activations and weights alike.  In the token-wise quantizer a token is owned by LPR lanes and lane l
+// converts operands l, l + LPR, ...: it loads the 64 bytes of an operand's fp16 values itself (four 16-byte loads; a
+// wave's loads cover every cache line they touch completely), and the hardware conversion, which interleaves its two
+// sixteen-value sources, takes the even-position values as one source and the odd-position ones as the other - the two
+// halves of the dwords as loaded.
 typedef float v16f_q __attribute__((ext_vector_type(16)));
 typedef unsigned int v6u_q __attribute__((ext_vector_type(6)));
 
@@ -569,7 +569,7 @@ __global__ __launch_bounds__(8 * kWave) void quantize_fp6_rows_kernel(
     const u4 *src = reinterpret_cast<const u4 *>(X + (live ? row : (long)rows - 1) * ldx);
     u4 raw[NJ];
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) raw[j] = src[l + LPR * j];
+    for (int j = 0; j < NJ; ++j) raw[j] = src[4 * ((j >> 2) * LPR + l) + (j & 3)];
     typedef unsigned short us2 __attribute__((ext_vector_type(2)));
     us2 hi2 = {0, 0};
 #pragma unroll
@@ -601,8 +601,8 @@ __global__ __launch_bounds__(8 * kWave) void quantize_fp6_rows_kernel(
                 if (e & 1) asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
                 else asm("v_fma_mix_f32 %0, %1, %2, 0 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(t) : "v"(w), "v"(r.inv));
                 const float c = __builtin_rintf(t);
-                if (jj < 2) a[8 * jj + e] = c;
-                else b[8 * (jj - 2) + e] = c;
+                if (e & 1) b[4 * jj + (e >> 1)] = c;            // field 2i of the conversion's result is a[i], field 2i+1 is b[i]
+                else a[4 * jj + (e >> 1)] = c;
             }
         v6u_q w6 = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(a, b, 1.0f);
         if (!live) w6 = v6u_q{0u, 0u, 0u, 0u, 0u, 0u};
@@ -658,10 +658,10 @@ __device__ __forceinline__ uint32_t fp6_field(int c) {
 
 // Offline weight quantizer into the FP6 layout (symmetric, one scale per output channel): one wave per channel of
 // the padded matrix (channels past N are written as zeros), the range over the whole row, then every lane assembles
-// whole operands from the chunks the layout assigns to them.  Same range and codes as quantize_rows_kernel;
+// whole operands of 32 consecutive codes.  Same range and codes as quantize_rows_kernel;
 // gsum[n] = sum of the codes of the row.  Channel n lives in panel n / 128, storage row (n % 4) * 32 + (n % 128) / 4.
 __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_weight_fp6_kernel(
-    const __half *__restrict__ W, int N, int K, int lpr, uint8_t *__restrict__ q, float *__restrict__ s,
+    const __half *__restrict__ W, int N, int K, uint8_t *__restrict__ q, float *__restrict__ s,
     int32_t *__restrict__ gsum) {
     const int lane = threadIdx.x % kWave;
     const long n = (long)blockIdx.x * kRowsPerBlock + threadIdx.x / kWave;
@@ -676,18 +676,15 @@ __global__ __launch_bounds__(kRowsPerBlock *kWave) void quantize_weight_fp6_kern
     uint8_t *qrow = q + (n >> 7) * ((long)(K / 64) * 6144) + p * 48;
     int total = 0;
     for (int idx = lane; idx < K / 32; idx += kWave) {
-        const int o = idx / lpr, l = idx % lpr;
         uint32_t words[6] = {0, 0, 0, 0, 0, 0};
-        for (int jj = 0; jj < 4; ++jj)
-            for (int e = 0; e < 8; ++e) {
-                const int k = 8 * (l + lpr * (4 * o + jj)) + e;
-                const int c = live ? code_of<W4A4_SYM>(__half2float(w[k]), r) : 0;
-                total += c;
-                const int bit = 6 * (2 * (8 * (jj & 1) + e) + (jj >> 1));
-                const uint32_t f = fp6_field(c);
-                words[bit >> 5] |= f << (bit & 31);
-                if ((bit & 31) > 26) words[(bit >> 5) + 1] |= f >> (32 - (bit & 31));
-            }
+        for (int e = 0; e < 32; ++e) {
+            const int c = live ? code_of<W4A4_SYM>(__half2float(w[32 * idx + e]), r) : 0;
+            total += c;
+            const int bit = 6 * e;
+            const uint32_t f = fp6_field(c);
+            words[bit >> 5] |= f << (bit & 31);
+            if ((bit & 31) > 26) words[(bit >> 5) + 1] |= f >> (32 - (bit & 31));
+        }
         uint8_t *blk = qrow + (long)(idx >> 1) * 6144;
         uint32_t *lo = reinterpret_cast<uint32_t *>(blk + (idx & 1) * 16);
         lo[0] = words[0]; lo[1] = words[1]; lo[2] = words[2]; lo[3] = words[3];
@@ -855,11 +852,9 @@ extern "C" int w4a4_quantize_weight(const void *W_f16, int N, int K, int mode, i
     hipStream_t st = as_stream(stream);
     const __half *W = static_cast<const __half *>(W_f16);
     if (layout == W4A4_LAYOUT_FP6) {
-        int lpr = 0, opl = 0;
-        fp6_plan(K, &lpr, &opl);
         if (N > 0) {
             hipLaunchKernelGGL(quantize_weight_fp6_kernel, dim3((((N + 127) & ~127) + kRowsPerBlock - 1) / kRowsPerBlock),
-                               dim3(kRowsPerBlock * kWave), 0, st, W, N, K, lpr, q, scale, gsum);
+                               dim3(kRowsPerBlock * kWave), 0, st, W, N, K, q, scale, gsum);
             rc = launch_status();
         }
     } else if (layout == W4A4_LAYOUT_MFMA && mode == W4A4_SYM)

@@ -137,8 +137,8 @@ _FP6_VALUE = {0: 0, 8: 1, 16: 2, 20: 3, 24: 4, 26: 5, 28: 6, 30: 7}     # E2M3 m
 
 
 def fp6_plan(K):
-    """(lanes per row, operands per lane) of the layout's permutation of K, or None where the layout does not exist:
-    the fewest lanes (8, 16, 32, 64; a divisor of K/32) that keep the operands per lane <= 2, else <= 3, 4, 6."""
+    """(lanes per row, operands per lane) of the token-wise quantizer of the FP6 layout, or None for a K the layout is not
+    offered for: the fewest lanes (8, 16, 32, 64; a divisor of K/32) that keep the operands per lane <= 2, else <= 3, 4, 6."""
     n_op = K // 32
     if K % 64 or K > 10240:
         return None
@@ -153,9 +153,8 @@ def fp6_to_codes(q, K, rows, weight=False):
     """A matrix in the FP6 operand layout -> int8 codes [rows, K] in the order of K.
     Rows come in panels (64 tokens; 128 channels, channel n in storage row (n % 4) * 32 + (n % 128) / 4); a panel is
     K/64 blocks of [rows of the panel][48 bytes]; operand 2b + h of a row lies in its 48 bytes of block b as 16 bytes
-    at 16h and 8 bytes at 32 + 8h (at 40 - 8h in storage rows 16 .. 31 of every 32); its 32 six-bit fields (little-endian) hold, in field 2*(8*(j&1) + e) + (j>>1),
-    element e of the 8-code chunk l + LPR*(4o + j) of the row, for operand index o*LPR + l.  Padding rows must be zero."""
-    lpr, _ = fp6_plan(K)
+    at 16h and 8 bytes at 32 + 8h (at 40 - 8h in storage rows 16 .. 31 of every 32); its 32 six-bit fields (little-endian) hold
+    codes 32o .. 32o+31 of the row, for operand index o.  Padding rows must be zero."""
     R = 128 if weight else 64
     n_op, kb = K // 32, K // 64
     flat = np.ascontiguousarray(q).reshape(-1)
@@ -180,15 +179,7 @@ def fp6_to_codes(q, K, rows, weight=False):
     for k_, v_ in _FP6_VALUE.items():
         lut[k_] = v_
     val = np.where(fields & 32, -lut[mag], lut[mag])
-    out = np.empty((rows, K), np.int8)
-    idx = np.arange(n_op)
-    o, l = idx // lpr, idx % lpr
-    for f in range(32):
-        i, s_ = f >> 1, f & 1
-        j, e = (i >> 3) + 2 * s_, i & 7
-        k = 8 * (l + lpr * (4 * o + j)) + e
-        out[:, k] = val[:, :, f]
-    return out
+    return val.reshape(rows, K).astype(np.int8)                                   # operand o, field f: code 32 o + f
 
 
 def fp6_schedules(B, K):

@@ -37,7 +37,7 @@ def _w(rng, N, K):
 
 
 def test_plan_matches_the_library(B):
-    """The permutation of K is a function of K alone; K the layout does not exist for are refused."""
+    """Row lengths the layout is not offered for (the quantizer's lane plan has no entry), and unsigned codes, are refused."""
     X = torch.zeros((8, 1792), dtype=torch.float16, device="cuda")          # 1792 / 32 = 56 = 8 * 7: seven operands per lane
     assert fp6_plan(1792) is None
     with pytest.raises(RuntimeError):
