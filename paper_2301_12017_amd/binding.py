@@ -438,7 +438,7 @@ def _alloc_out(A: QAct, W: QWeight, requant, requant_mode, requant_group, requan
         return torch.empty((A.M, W.N), dtype=torch.float16, device=dev), None, None, None
     rng = _ng(W.N, requant_group)
     sums = requant_mode == ASYM or requant_layout == LAYOUT_MFMA
-    return (torch.empty((A.M, W.N // 2), dtype=torch.uint8, device=dev),
+    return (torch.empty((_rows_alloc(A.M, requant_layout, False), _row_bytes(W.N, requant_layout)), dtype=torch.uint8, device=dev),
             torch.empty((A.M,), dtype=torch.float32, device=dev),
             torch.empty((A.M,), dtype=torch.float32, device=dev) if requant_mode == ASYM else None,
             torch.empty((A.M, rng), dtype=torch.int32, device=dev) if sums else None)
@@ -464,6 +464,8 @@ def linear(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=ACT_NON
         return o
     if requant_layout == LAYOUT_MFMA:
         return QAct(o, os_, oz, None, A.M, W.N, W.N // 2, requant_group, requant_mode, 0, LAYOUT_MFMA, og)
+    if requant_layout == LAYOUT_FP6:
+        return QAct(o, os_, None, None, A.M, W.N, _row_bytes(W.N, LAYOUT_FP6), requant_group, requant_mode, 0, LAYOUT_FP6, None)
     return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)
 
 
@@ -483,6 +485,8 @@ def linear_static(A: QAct, W: QWeight, bias: Optional[torch.Tensor] = None, act=
         return o
     if requant_layout == LAYOUT_MFMA:
         return QAct(o, os_, oz, None, A.M, W.N, W.N // 2, requant_group, requant_mode, 0, LAYOUT_MFMA, og)
+    if requant_layout == LAYOUT_FP6:
+        return QAct(o, os_, None, None, A.M, W.N, _row_bytes(W.N, LAYOUT_FP6), requant_group, requant_mode, 0, LAYOUT_FP6, None)
     return QAct(o, os_, oz, og, A.M, W.N, W.N // 2, requant_group, requant_mode)
 
 

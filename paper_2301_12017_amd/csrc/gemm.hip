@@ -162,10 +162,21 @@ static int resolve_schedule(const GemmArgs &g, bool grouped, int out_kind, int *
     // a kernel family understands one layout, except the group kernel, which reads grouped layers in either
     if (fp6 != (s.family == F_FP6)) return W4A4_ERR_INVALID_ARG;
     if (!fp6 && (olay ? !(s.family == (grouped ? F_GROUP : F_OLAY)) : s.family == F_OLAY)) return W4A4_ERR_INVALID_ARG;
-    const bool q4 = out_kind == OUT_Q4 || out_kind == OUT_Q4M;
+    const bool q4 = out_kind == OUT_Q4 || out_kind == OUT_Q4M || out_kind == OUT_Q6;
+    if ((out_kind == OUT_Q6) != (q4 && fp6)) return W4A4_ERR_UNSUPPORTED_SHAPE;   // FP6 codes come from the FP6 kernel, and only they
     switch (s.family) {
         case F_FP6:
-            if (!fp6_ok(g, grouped) || q4) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            if (!fp6_ok(g, grouped)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            if (q4) {
+                int lpr = 0, opl = 0;
+                if (s.variant != 0) return W4A4_ERR_INVALID_ARG;
+                // the output is the next layer's activation operand: whole 256-column tiles, a row length the layout is
+                // offered for, 32-bit byte offsets
+                if (g.N % 256 || !fp6_plan(g.N, &lpr, &opl) || (((long)g.M + 191) * g.N / 4 * 3) >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
+                const int lim = fp6_requant_max_tiles_n();
+                if (lim < 0) return W4A4_ERR_HIP;
+                if (g.N / 256 > lim) return W4A4_ERR_UNSUPPORTED_SHAPE;
+            }
             break;
         case F_OLAY:
             if (!pipe_ok(g, grouped) || g.K < 2 * kBK || (long)g.M * g.ldo * 4 >= 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
@@ -269,8 +280,12 @@ int check_layer(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep
     if (ep->requant) {
         if (ep->requant_mode != W4A4_SYM && ep->requant_mode != W4A4_ASYM) return W4A4_ERR_INVALID_ARG;
         if (ep->requant_group < 0) return W4A4_ERR_INVALID_ARG;
-        if (ep->requant_layout != W4A4_LAYOUT_CANONICAL && ep->requant_layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
-        if (ep->requant_layout == W4A4_LAYOUT_MFMA && ep->requant_mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+        if (ep->requant_layout != W4A4_LAYOUT_CANONICAL && ep->requant_layout != W4A4_LAYOUT_MFMA &&
+            ep->requant_layout != W4A4_LAYOUT_FP6) return W4A4_ERR_INVALID_ARG;
+        if (ep->requant_layout != W4A4_LAYOUT_CANONICAL && ep->requant_mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+        // FP6 codes are written by the FP6 kernel's own epilogue, for one range per token
+        if (ep->requant_layout == W4A4_LAYOUT_FP6 &&
+            (A->layout != W4A4_LAYOUT_FP6 || (ep->requant_group != 0 && ep->requant_group != W->N))) return W4A4_ERR_UNSUPPORTED_SHAPE;
         const int N = W->N;
         if (N % 32 || N > 8192) return W4A4_ERR_UNSUPPORTED_SHAPE;
         const int rG = ep->requant_group == 0 ? N : ep->requant_group;
@@ -336,11 +351,19 @@ extern "C" const char *w4a4_schedule_name(int schedule) {
 //   2 = the persistent kernel on operands in the MFMA operand layout; symmetric codes out in either
 //       layout (the operand layout with odd-position sums per column slice of requant_group, which
 //       must be whole 256-column tiles); the column tiles of a panel must fit one XCD's resident share.
+//   3 = the FP6 kernel on operands in the FP6 layout, codes out in the FP6 layout (no sums); N in whole 256-column
+//       tiles that fit one XCD's resident share.
 // 0 = not fusable: the GEMM stores fp32 rows and the row quantizer packs them.
 // The residency limits come from the runtime's occupancy figure for the kernel on the current device.
 static int fused_requant_kind(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilogue *ep, bool want_gsum) {
     if (!ep->requant || ep->requant_mode != W4A4_SYM) return 0;
-    if (A->layout == W4A4_LAYOUT_FP6) return 0;                // the FP6 kernel stores fp32 rows; the row quantizer packs them
+    if (A->layout == W4A4_LAYOUT_FP6) {
+        // FP6 codes out: the FP6 kernel's own requantizing epilogue; other layouts: fp32 rows and the row quantizer
+        if (ep->requant_layout != W4A4_LAYOUT_FP6 || want_gsum) return 0;
+        if (ep->schedule != 0 && ep->schedule != S_FP6_128x256) return 0;
+        if ((ep->requant_group != 0 && ep->requant_group != W->N) || W->N % 256) return 0;
+        return W->N / 256 <= fp6_requant_max_tiles_n() ? 3 : 0;
+    }
     if (A->mode != W4A4_SYM || (W->group != 0 && W->group != W->K)) return 0;
     if (A->K % kBK || (long)A->M * A->lda >= 0x7fffffffL || (long)W->N * (W->K / 2) >= 0x7fffffffL) return 0;
     if (((long)A->M + 512) * W->N * 4 >= 0x80000000L) return 0;
@@ -442,8 +465,8 @@ extern "C" int w4a4_pick_schedule(const w4a4_act *A, const w4a4_weight *W, const
     int out_kind = OUT_F16, schedule = ep->schedule;
     if (ep->requant) {
         const int fused = fused_requant_kind(A, W, ep, false);
-        out_kind = !fused ? OUT_F32 : (fused == 2 && ep->requant_layout == W4A4_LAYOUT_MFMA) ? OUT_Q4M : OUT_Q4;
-        if (fused) schedule = fused == 1 ? S_PIPE_128x256 : S_OLAY_128x256;
+        out_kind = !fused ? OUT_F32 : fused == 3 ? OUT_Q6 : (fused == 2 && ep->requant_layout == W4A4_LAYOUT_MFMA) ? OUT_Q4M : OUT_Q4;
+        if (fused) schedule = fused == 1 ? S_PIPE_128x256 : fused == 3 ? S_FP6_128x256 : S_OLAY_128x256;
     }
     const int rc = resolve_schedule(g, grouped, out_kind, &schedule);
     return rc ? rc : schedule;
@@ -501,8 +524,8 @@ static int linear_impl(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilo
         g.out_scale = out_scale;
         g.out = out;
         g.out_osum = out_gsum; g.osum_slices = slices; g.slice_tiles = sums && slices > 1 ? rg / 256 : 0x40000000;
-        const int out_kind = fused == 1 ? OUT_Q4 : (sums ? OUT_Q4M : OUT_Q4);
-        int schedule = fused == 1 ? S_PIPE_128x256 : S_OLAY_128x256;
+        const int out_kind = fused == 3 ? OUT_Q6 : fused == 1 ? OUT_Q4 : (sums ? OUT_Q4M : OUT_Q4);
+        int schedule = fused == 1 ? S_PIPE_128x256 : fused == 3 ? S_FP6_128x256 : S_OLAY_128x256;
         // everything that can refuse the launch is checked before the outputs are touched
         const int rc = resolve_schedule(g, false, out_kind, &schedule);
         if (rc) return rc;
@@ -513,6 +536,7 @@ static int linear_impl(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilo
     // Requantize: the per-token range needs the whole output row, which no single tile
     // sees.  The GEMM leaves the fp32 rows in the workspace and the row quantizer turns
     // them into packed codes.
+    if (ep->requant_layout == W4A4_LAYOUT_FP6) return W4A4_ERR_UNSUPPORTED_SHAPE;   // FP6 codes exist only fused
     g.out = rows_f32;
     const int rc = run_gemm(g, A->mode, grouped, OUT_F32, ep->schedule, st);
     if (rc) return rc;
@@ -529,6 +553,10 @@ extern "C" int w4a4_linear(const w4a4_act *A, const w4a4_weight *W, const w4a4_e
     if (rc) return rc;
     if (A->M == 0) return W4A4_OK;
     const int fused = fused_requant_kind(A, W, ep, out_gsum != nullptr);
+    if (ep->requant && ep->requant_layout == W4A4_LAYOUT_FP6) {     // no code sums in that layout, and only the fused kernel writes it
+        if (out_gsum) return W4A4_ERR_INVALID_ARG;
+        if (!fused) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    }
     const size_t need = !ep->requant ? 0 : fused ? fused_workspace_bytes(A->M) : (size_t)A->M * (size_t)W->N * sizeof(float);
     if (need && (!workspace || workspace_bytes < need || !aligned16(workspace))) return W4A4_ERR_WORKSPACE;
     return linear_impl(A, W, ep, out, out_scale, out_zero, out_gsum, ng, fused, static_cast<uint32_t *>(workspace),
@@ -567,6 +595,7 @@ extern "C" int w4a4_linear_static(const w4a4_act *A, const w4a4_weight *W, const
     int fused = 0;
     uint32_t *exchange = nullptr;
     if (ep->requant) {
+        if (ep->requant_layout == W4A4_LAYOUT_FP6 && out_gsum) return W4A4_ERR_INVALID_ARG;
         fused = fused_requant_kind(A, W, ep, out_gsum != nullptr);
         // a requantize that cannot be fused needs M*N*4 bytes of fp32 rows: beyond what a static array should hold
         if (!fused) return W4A4_ERR_WORKSPACE;

@@ -40,7 +40,7 @@ constexpr int kBK = 128;           // codes per K step
 constexpr int kRowB = 80;          // LDS row pitch in bytes: 64 of codes + 16 of padding
 constexpr int kXcd = 8;
 
-enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2, OUT_Q4 = 3, OUT_Q4M = 4 };   // Q4: per-token requantized codes, canonical; Q4M: in the MFMA operand layout
+enum { OUT_F16 = 0, OUT_F32 = 1, OUT_I32 = 2, OUT_Q4 = 3, OUT_Q4M = 4, OUT_Q6 = 5 };   // Q4: per-token requantized codes, canonical; Q4M: in the MFMA operand layout; Q6: in the FP6 operand layout
 
 struct GemmArgs {
     const uint8_t *Aq; long lda;
@@ -456,6 +456,7 @@ int launch_group(int mode, int out_kind, GemmArgs &g, hipStream_t st);
 int launch_small_packed(int out_kind, GemmArgs &g, hipStream_t st);
 // Residency limits of the fused requantize on the current device (see the definitions)
 int olay_requant_max_tiles_n(bool mfma_out);
+int fp6_requant_max_tiles_n();
 int pipe_requant_max_tiles();
 
 }  // namespace w4a4

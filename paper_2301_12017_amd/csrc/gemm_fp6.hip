@@ -96,6 +96,122 @@ __device__ __forceinline__ void fp6_epilogue(const GemmArgs &g, v16f (&acc)[FM][
         }
 }
 
+// Fused per-token requantize of one wave's part of a 128 x 256 tile into the FP6 operand layout of activations
+// (Sec. 4.2: the next layer's quantize rides behind bias-add / GELU; here the next layer's GEMM operand is written
+// directly, 3/4 byte per output instead of the two bytes of an fp16 row).  The range of a token needs its whole
+// output row, spread over the tiles_n workgroups that hold the row panel's column tiles at that moment, so the
+// steps are those of the int8 kernel's requantizing epilogue: fp32 outputs in place (the definition's operation
+// order), row maxima by a register butterfly and one atomic max per row, a bounded wait for the panel's siblings,
+// then the codes.  A code t = rne(y * 7/max) is an integer of magnitude <= 7 (the clamp of the definition cannot
+// bind); the FP8 E4M3 encoding of t / 64 - which the hardware's pack conversion produces for two values at a time,
+// with the division as its scale operand - is `sign, 0, 0, e1, e0, m2, m1, m0` with exactly the exponent and
+// mantissa bits of the FP6 E2M3 encoding of t (zero included), so a field is that byte without its two zero
+// bits.  A lane's four adjacent channels are 24 bits; the lanes of a quad own twelve consecutive bytes of an
+// operand, which three of them store as one dword each.  No code sums travel with this layout.
+template <int FM, int FN>
+__device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&acc)[FM][FN], const ChanParams6<FN> &cp,
+                                                     int n_lane, int m0, int row_w, int lane, int tid, int panel,
+                                                     bool first_cols, const float *sa_lds, float *scratch) {
+    static_assert(FN == 4 && FM == 2, "32 rows per half wave; a lane holds four adjacent channels");
+    typedef short v2s __attribute__((ext_vector_type(2)));
+    const bool gelu = g.act == W4A4_ACT_GELU;
+    const int h = lane >> 5, c = lane & 31;
+    // 1. outputs in fp32, kept in place; vmax[i*16 + r] = bits of the max over this lane's channels (a non-negative,
+    //    non-NaN float: such bit patterns order like unsigned integers).  N is a multiple of the tile width here.
+    uint32_t vmax[32];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int rl = row_w + i * 32 + 8 * q + 4 * h;
+            const float4 sa4 = *reinterpret_cast<const float4 *>(sa_lds + rl);
+            const float sav[4] = {sa4.x, sa4.y, sa4.z, sa4.w};
+            float y[4][FN];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    float t = acc[i][j][q * 4 + rr] * sav[rr];
+                    t = t * cp.sw[j];
+                    y[rr][j] = t + cp.bias[j];                    // 0 without a bias: changes at most the sign of a zero
+                }
+            if (gelu) {                                           // uniform branch around 16 straight-line evaluations
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) y[rr][j] = gelu_erf(y[rr][j]);
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                float v = 0.0f;
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    acc[i][j][q * 4 + rr] = y[rr][j];
+                    v = fmaxf(v, fabsf(y[rr][j]));
+                }
+                vmax[i * 16 + q * 4 + rr] = __float_as_uint(v);
+            }
+        }
+    // 2. butterfly: lane c ends with the maximum of row c of the wave's 64 (two halves of 32)
+    reduce_scatter32(vmax, lane, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+    const int m_c = m0 + row_w + frag_row(c >> 4, c & 15, lane);  // the row this lane is responsible for
+    if (m_c < g.M) atomicMax(g.rowmax + m_c, vmax[0]);
+    // 3. wait for the siblings of the row panel (bounded)
+    panel_arrive_and_wait(g, panel, tid);
+    // 4. ranges
+    {
+        const __amdgpu_buffer_rsrc_t mx_rsrc = make_rsrc(g.rowmax, (uint32_t)g.M * 4u);
+        // an ordinary load that bypasses the non-coherent cache levels (sc0 | sc1); rows >= M read 0
+        const float amax = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(mx_rsrc, m_c * 4, 0, 17));
+        const Range rg = range_sym(amax);
+        if (m_c < g.M && first_cols) g.out_scale[m_c] = rg.S;     // the wave that holds channel 0 of the row
+        scratch[(tid & ~63) + lane] = rg.inv;                     // 0 for rows >= M: their codes are written as zeros
+        __builtin_amdgcn_wave_barrier();
+    }
+    // 5. codes.  The output is an activation matrix of N codes per row in the FP6 layout: panels of 64 tokens, block b
+    //    (64 codes) of a panel's rows contiguous, a row's 48 bytes of a block = operand 2b+e as 16 bytes at 16e and 8
+    //    bytes at 32 + 8e (at 40 - 8e in rows 16 .. 31 of every 32).  Lane c holds channels 4c .. 4c+3 of the wave's
+    //    128-channel panel: bytes 3(c%8) .. +2 of operand c/8; quad lane j < 3 stores dword j of the quad's twelve bytes.
+    const int KBo = g.N / kHalf;
+    const long out_bytes = (((long)g.M + 63) & ~63L) * KBo * kRow6;
+    const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(g.out, (uint32_t)out_bytes);
+    const int op = (n_lane >> 5), ob = 12 * ((c >> 2) & 1) + 4 * (lane & 3);   // operand of the row, byte of this lane's dword in it
+    const uint32_t blk = (uint32_t)(op >> 1) * (64 * kRow6);
+    const int e = op & 1;
+    uint32_t lane_q[2];                                           // by bit 4 of the row inside its panel
+#pragma unroll
+    for (int sw = 0; sw < 2; ++sw)
+        lane_q[sw] = (lane & 3) == 3 ? kPoison
+                     : (uint32_t)((m0 + row_w) >> 6) * ((uint32_t)KBo * (64 * kRow6)) + blk + (uint32_t)(4 * h) * kRow6 +
+                           (uint32_t)(ob < 16 ? 16 * e + ob : 32 + 8 * (e ^ sw) + (ob - 16));
+    // bytes of {next lane's 24 bits, own 24 bits} that make dword j: own[j..2], then next[0..j]
+    const uint32_t sel = (lane & 3) == 0 ? 0x04020100u : (lane & 3) == 1 ? 0x05040201u : 0x06050402u;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 iv4 = *reinterpret_cast<const float4 *>(scratch + (tid & ~63) + h * 32 + i * 16 + q * 4);
+            const float ivv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = q * 4 + rr;
+                float t[FN];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) t[j] = __builtin_rintf(acc[i][j][r] * ivv[rr]);
+                v2s pk = {0, 0};
+                pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, t[0], t[1], 64.0f, false);
+                pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, t[2], t[3], 64.0f, true);
+                const uint32_t b4 = __builtin_bit_cast(uint32_t, pk);              // four bytes s00eemmm
+                const uint32_t f4 = (b4 & 0x1F1F1F1Fu) | ((b4 >> 2) & 0x20202020u);  // four 6-bit fields, one per byte
+                const uint32_t p2 = (f4 & 0x003F003Fu) | ((f4 >> 2) & 0x0FC00FC0u);  // two 12-bit pairs, one per half
+                const uint32_t own = (p2 & 0x00000FFFu) | ((p2 >> 4) & 0x00FFF000u); // 24 bits
+                const uint32_t nxt = dpp_fetch<0xF9>(own);                          // quad permute [1,2,3,3]: the next lane's
+                const uint32_t word = __builtin_amdgcn_perm(nxt, own, sel);
+                __builtin_amdgcn_raw_buffer_store_b32(word, q_rsrc, lane_q[q >> 1] + (uint32_t)(i * 32 + 8 * q + rr) * kRow6, 0, 0);
+            }
+        }
+}
+
 template <int FM, int FN, int WM, int WN, int OCC, int NS, int OUT>
 __global__ __attribute__((amdgpu_flat_work_group_size(WM *WN * 64, WM *WN * 64), amdgpu_waves_per_eu(OCC, OCC)))
 void gemm_fp6_kernel(GemmArgs g) {
@@ -116,6 +232,7 @@ void gemm_fp6_kernel(GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     uint8_t *dummy = smem + NS * STAGE;                         // where the padding blocks of every stage land (zeros)
     uint8_t *par = dummy + (BLOCKS > REAL ? 1024 : 0);          // token scales of the tile, double buffered: [2][BM]
+                                                                // (OUT_Q6: followed by 64 floats per wave for the row ranges)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -210,9 +327,19 @@ void gemm_fp6_kernel(GemmArgs g) {
 
     // Tile of virtual block id v (workgroup id + k * grid size; v % 8 = the XCD it runs on): every XCD owns a
     // contiguous range of tiles, so that the tiles of a row panel run on one XCD and share its L2.
+    // For the requantizing output the ranges are whole row panels: the column tiles of a panel wait for each other, and
+    // a workgroup walks its XCD's tiles in increasing order, which together rule out a cycle of waits.
     auto tile_of = [&](int v, int &t) {
-        t = xcd_tile(v < total ? v : 0, total);
-        return v < total;
+        if constexpr (OUT == OUT_Q6) {
+            const int x = v & (kXcd - 1), i = v >> 3;
+            const int per = g.tiles_m / kXcd, rem = g.tiles_m % kXcd;
+            const int cnt = per + (x < rem ? 1 : 0);
+            t = (x * per + (x < rem ? x : rem)) * g.tiles_n + i;
+            return i < cnt * g.tiles_n;
+        } else {
+            t = xcd_tile(v < total ? v : 0, total);
+            return v < total;
+        }
     };
     int vb = blockIdx.x;                                        // virtual block id of the current tile
     int tile;
@@ -331,6 +458,7 @@ void gemm_fp6_kernel(GemmArgs g) {
         {
             constexpr int ESZ = OUT == OUT_F16 ? 2 : 4;
             const uint32_t col_off = n_lane < g.N ? (uint32_t)n_lane * ESZ : kPoison;
+            (void)col_off;
             ChanParams6<FN> cp;
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
@@ -341,6 +469,13 @@ void gemm_fp6_kernel(GemmArgs g) {
             const float *sa_lds = reinterpret_cast<const float *>(par + parity * (BM * 4));
             const int row_w = wm * FM * 32;
             const bool bias = g.bias != nullptr, gelu = g.act == W4A4_ACT_GELU;
+            if constexpr (OUT == OUT_Q6) {
+                if constexpr (FM == 2 && FN == 4) {
+                    const int tn = tile % g.tiles_n;
+                    fp6_epilogue_requant<FM, FN>(g, acc, cp, n_lane, m0, row_w, lane, tid, tile / g.tiles_n, tn == 0 && wn == 0,
+                                                 sa_lds, reinterpret_cast<float *>(par + 2 * BM * 4));
+                }
+            } else
             if (OUT == OUT_I32 || (!bias && !gelu)) fp6_epilogue<FM, FN, OUT, false, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
             else if (bias && !gelu) fp6_epilogue<FM, FN, OUT, true, false>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
             else if (!bias && gelu) fp6_epilogue<FM, FN, OUT, false, true>(g, acc, cp, col_off, m0, row_w, lane, sa_lds);
@@ -356,9 +491,20 @@ template <int FM, int FN, int WM, int WN, int OCC, int NS, int OUT>
 struct Fp6Launch {
     static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN;
     static constexpr int REAL = (BM + BN) * 3 / 64, BLOCKS = (REAL + NW - 1) / NW * NW;
-    static constexpr size_t lds = (size_t)NS * REAL * 1024 + (BLOCKS > REAL ? 1024 : 0) + 2 * BM * 4;
+    static constexpr size_t lds = (size_t)NS * REAL * 1024 + (BLOCKS > REAL ? 1024 : 0) + 2 * BM * 4 + (OUT == OUT_Q6 ? NW * 256 : 0);
     static KernelState &state() { static KernelState ks; return ks; }
     static auto kernel() { return gemm_fp6_kernel<FM, FN, WM, WN, OCC, NS, OUT>; }
+    // resident workgroups on the current device (-1: HIP error).  The requantizing output makes the column tiles of a
+    // row panel wait for each other, so its grid is sized from what the runtime reports for this kernel, capped by the
+    // occupancy it was compiled for.
+    static int slots() {
+        const int cus = prepare_kernel(reinterpret_cast<const void *>(kernel()), lds, state());
+        if (cus < 0) return -1;
+        if (OUT != OUT_Q6) return cus * OCC;
+        const int occ = resident_per_cu(reinterpret_cast<const void *>(kernel()), NW * 64, lds, state());
+        if (occ < 0) return -1;
+        return cus * (occ < OCC ? occ : OCC);
+    }
 };
 
 template <int FM, int FN, int WM, int WN, int OCC, int NS, int OUT>
@@ -368,11 +514,18 @@ static int launch_one6(GemmArgs &g, hipStream_t st) {
     if (g.K / kHalf < NS + 2) return W4A4_ERR_UNSUPPORTED_SHAPE;
     g.tiles_m = (g.M + L::BM - 1) / L::BM;
     g.tiles_n = (g.N + L::BN - 1) / L::BN;
-    const int cus = prepare_kernel(reinterpret_cast<const void *>(L::kernel()), L::lds, L::state());
-    if (cus < 0) return W4A4_ERR_HIP;
-    const long slots = (long)cus * OCC, tiles = (long)g.tiles_m * g.tiles_n;
+    const long slots = L::slots(), tiles = (long)g.tiles_m * g.tiles_n;
+    if (slots < 0) return W4A4_ERR_HIP;
     if (tiles > 0x7fffffffL) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    const unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
+    unsigned grid = (unsigned)(tiles < slots ? tiles : slots);
+    if (OUT == OUT_Q6) {
+        // every XCD walks whole row panels: ids up to 8 * (tiles of the fullest XCD); and the column tiles of a panel
+        // must sit in different workgroups at the same time
+        const long most = (long)((g.tiles_m + kXcd - 1) / kXcd) * g.tiles_n * kXcd;
+        grid = (unsigned)(most < (slots & ~(long)(kXcd - 1)) ? most : (slots & ~(long)(kXcd - 1)));
+        if (g.N % L::BN || g.tiles_n > (int)(grid / kXcd)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+        if (g.wait_for == 0) g.wait_for = g.tiles_n;
+    }
     if (grid == 0) return W4A4_ERR_UNSUPPORTED_SHAPE;
     launch_gemm(L::kernel(), dim3(grid), dim3(WM * WN * 64), L::lds, st, g);
     return launch_status();
@@ -389,10 +542,19 @@ static int launch_variant6(int variant, GemmArgs &g, hipStream_t st) {
     }
 }
 
+// Column tiles of a row panel that the fused requantize can keep co-resident on the current device (0 = the kernel
+// does not fit, -1 = HIP error): the limit on N / 256.
+int fp6_requant_max_tiles_n() {
+    const int slots = Fp6Launch<2, 4, 2, 2, 2, 4, OUT_Q6>::slots();
+    return slots < 0 ? -1 : (slots & ~(kXcd - 1)) / kXcd;
+}
+
 // Requires: FP6 operand layout on both sides (symmetric codes in [-7, 7], per-channel weight scales),
-// K % 128 == 0, K >= 512, both padded operand matrices below 2^31 bytes.
+// K % 128 == 0, K >= 512, both padded operand matrices below 2^31 bytes; OUT_Q6: N % 256 == 0, the padded output
+// matrix below 2^31 bytes, N / 256 within fp6_requant_max_tiles_n().
 int launch_fp6(int variant, int out_kind, GemmArgs &g, hipStream_t st) {
     switch (out_kind) {
+        case OUT_Q6: return variant == 0 ? launch_one6<2, 4, 2, 2, 2, 4, OUT_Q6>(g, st) : W4A4_ERR_INVALID_ARG;
         case OUT_F16: return launch_variant6<OUT_F16>(variant, g, st);
         case OUT_F32: return launch_variant6<OUT_F32>(variant, g, st);
         case OUT_I32: return launch_variant6<OUT_I32>(variant, g, st);

@@ -154,7 +154,7 @@ def fp6_to_codes(q, K, rows, weight=False):
     Rows come in panels (64 tokens; 128 channels, channel n in storage row (n % 4) * 32 + (n % 128) / 4); a panel is
     K/64 blocks of [rows of the panel][48 bytes]; operand 2b + h of a row lies in its 48 bytes of block b as 16 bytes
     at 16h and 8 bytes at 32 + 8h (at 40 - 8h in storage rows 16 .. 31 of every 32); its 32 six-bit fields (little-endian) hold
-    codes 32o .. 32o+31 of the row, for operand index o.  Padding rows must be zero."""
+    codes 32o .. 32o+31 of the row, for operand index o.  Padding rows must be zeros (of either sign)."""
     R = 128 if weight else 64
     n_op, kb = K // 32, K // 64
     flat = np.ascontiguousarray(q).reshape(-1)
@@ -164,15 +164,16 @@ def fp6_to_codes(q, K, rows, weight=False):
     r = np.arange(padded)
     srow = ((r % 4) * 32 + (r % 128) // 4) if weight else (r % 64)
     blocks = blocks[r // R, :, srow, :]                                          # [row, block, 48]
-    assert not blocks[rows:].any(), "padding rows are not zero"
-    blocks = blocks[:rows]
-    ops = np.empty((rows, n_op, 24), np.uint8)
-    swap = ((srow[:rows] >> 4) & 1).astype(bool)                                 # storage rows 16 .. 31 of every 32: 8-byte parts exchanged
+    ops = np.empty((padded, n_op, 24), np.uint8)
+    swap = ((srow >> 4) & 1).astype(bool)                                        # storage rows 16 .. 31 of every 32: 8-byte parts exchanged
     for h in (0, 1):
         ops[:, h::2, :16] = blocks[:, :, 16 * h:16 * h + 16]
         ops[:, h::2, 16:] = np.where(swap[:, None, None], blocks[:, :, 40 - 8 * h:48 - 8 * h], blocks[:, :, 32 + 8 * h:40 + 8 * h])
-    bits = np.unpackbits(ops, axis=2, bitorder="little").reshape(rows, n_op, 32, 6)
-    fields = (bits * (1 << np.arange(6, dtype=np.int64))).sum(axis=3)            # [rows, n_op, 32]
+    bits = np.unpackbits(ops, axis=2, bitorder="little").reshape(padded, n_op, 32, 6)
+    fields = (bits * (1 << np.arange(6, dtype=np.int64))).sum(axis=3)            # [padded rows, n_op, 32]
+    # padding rows hold zeros; a fused epilogue may write them as negative zeros (the sign bit of a field set)
+    assert not (fields[rows:] & 31).any(), "padding rows are not zero"
+    fields = fields[:rows]
     mag = fields & 31
     assert np.isin(mag, list(_FP6_VALUE)).all(), "a field that is not an integer of magnitude <= 7"
     lut = np.zeros(32, np.int64)
