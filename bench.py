@@ -219,15 +219,18 @@ def profiled_traffic(schedules):
 
 
 # ------------------------------------------------------------------------------------------ workload 5
-def chain_leg(steps, warmup, settle_ms):
+def chain_leg(steps, warmup, settle_ms, layout=None):
     """Workload 5: the chained BERT-large linear stack at M = 32768.  A step is one encoder layer's four
     GEMMs (QKV, out-proj on the V third, FFN1+GELU, FFN2), each with the dequantize / bias (/GELU) /
     per-token requantize epilogue fused, codes flowing from one GEMM to the next without an fp16 tensor.
-    Four layers with distinct weights are cycled; the step input is the previous layer's output."""
+    Four layers with distinct weights are cycled; the step input is the previous layer's output.
+    `layout`: the operand layout of every GEMM and of every requantized output (default: the one the library prefers
+    on the int8 MFMA; the FP6 layout runs the chain on the FP6 matrix instruction)."""
     import torch
     from paper_2301_12017_amd import binding as B, synth, workloads as WL
     M, h, ffn, nl = 32768, 1024, 4096, 4
-    layout = B.preferred_layout(M, 3 * h, h)
+    if layout is None or layout < 0:
+        layout = B.preferred_layout(M, 3 * h, h)
     layers = WL.make_chain(nl, h, ffn, M, 5, keep_host=False, layout=layout)
     A0 = B.quantize_act(WL.dev(synth.activations(M, h, 0, 5, 0)), B.SYM, layout=layout)
     ws = torch.empty(M * 8, dtype=torch.uint8, device="cuda")
@@ -243,7 +246,7 @@ def chain_leg(steps, warmup, settle_ms):
                                           requant_group=rg, out=out, workspace=ws, requant_layout=lay.W.layout))
             scheds.append(B.pick_schedule(a_in, lay.W, requant=True, requant_group=rg, requant_layout=lay.W.layout))
             names.append(name)
-            A = B.QAct(out[0], out[1], None, None, M, lay.spec.N, lay.spec.N // 2, 0, B.SYM, 0, lay.W.layout,
+            A = B.QAct(out[0], out[1], None, None, M, lay.spec.N, B._row_bytes(lay.spec.N, lay.W.layout), 0, B.SYM, 0, lay.W.layout,
                        out[3] if mfma else None)
     stream = B._stream()
 
@@ -281,8 +284,9 @@ def bench_chain(args):
     from paper_2301_12017_amd import binding as B
     B.lib()
     torch.cuda.set_device(0)
-    r = chain_leg(args.steps, args.warmup, args.settle_ms)
+    r = chain_leg(args.steps, args.warmup, args.settle_ms, args.layout)
     M = r["M"]
+    fp6 = r["layout"] == B.LAYOUT_FP6
     line = {
         "metric": METRIC, "value": r["TOPS"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "settle_ms": args.settle_ms, "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
@@ -296,7 +300,8 @@ def bench_chain(args):
                      for n, t, (nn, kk) in zip(r["names"], r["gemm_ms"], r["shapes"])],
         "roofline": {"bound": "mfma", "achieved": r["achieved_TOPS"], "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
                      "frac": r["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS, "traffic": None,
-                     "kernel": "gemm_olay_kernel with the fused requantize epilogue, the four launches of the step; schedules "
+                     "kernel": ("gemm_fp6_kernel" if fp6 else "gemm_olay_kernel")
+                               + " with the fused requantize epilogue, the four launches of the step; schedules "
                                + ", ".join(r["schedules"]),
                      "ops_per_step": r["ops"], "kernel_ms_per_step": r["kernel_ms_per_step"]},
         "consistency": {"timed_region_s": r["timed_region_s"]},

@@ -90,8 +90,8 @@ static int pick_schedule(const GemmArgs &g, bool grouped, int out_kind) {
 // The FP6 kernel: both operands in the FP6 layout, whole pairs of 64-code half steps, at least eight of them.
 static bool fp6_ok(const GemmArgs &g, bool grouped) {
     int lpr = 0, opl = 0;
-    return !grouped && g.K % kBK == 0 && g.K >= 4 * kBK && fp6_plan(g.K, &lpr, &opl) &&
-           ((long)g.M + 64) * (g.K / 4 * 3) < 0x7fffffffL && ((long)g.N + 128) * (g.K / 4 * 3) < 0x7fffffffL;
+    return !grouped && g.K % kBK == 0 && g.K >= 4 * kBK && fp6_plan(g.K, &lpr, &opl) && g.lda % 48 == 0 &&
+           ((long)g.M + 64) * g.lda < 0x7fffffffL && ((long)g.N + 128) * (g.K / 4 * 3) < 0x7fffffffL;
 }
 
 // CU count of the current device (the tile choice of the persistent kernel depends on it); 256 if it cannot be read.
@@ -317,6 +317,7 @@ static void fill_args(GemmArgs &g, const w4a4_act *A, const w4a4_weight *W, int 
     const bool olay = A->layout == W4A4_LAYOUT_MFMA;
     g.osum = olay ? A->osum : nullptr; g.ldo = olay ? A->ldo : 0; g.esum = olay ? W->esum : nullptr;
     g.out_osum = nullptr; g.osum_slices = 1; g.slice_tiles = 0;
+    g.stagger = 0;
 }
 
 }  // namespace w4a4

@@ -66,6 +66,7 @@ struct GemmArgs {
     int32_t *out_osum; int osum_slices, slice_tiles;   // requantized output: [M, osum_slices] sums, column
                                                        // tiles per slice
     int layout;                    // w4a4_layout of both operands
+    int stagger;                   // fused requantize of the FP6 kernel: sleeps by which every second row panel starts late
 };
 
 // Widening of packed codes to int8 without sign extension.  For a packed dword d (codes

@@ -103,17 +103,15 @@ __device__ __forceinline__ void fp6_epilogue(const GemmArgs &g, v16f (&acc)[FM][
 // steps are those of the int8 kernel's requantizing epilogue: fp32 outputs in place (the definition's operation
 // order), row maxima by a register butterfly and one atomic max per row, a bounded wait for the panel's siblings,
 // then the codes.  A code t = rne(y * 7/max) is an integer of magnitude <= 7 (the clamp of the definition cannot
-// bind); the FP8 E4M3 encoding of t / 64 - which the hardware's pack conversion produces for two values at a time,
-// with the division as its scale operand - is `sign, 0, 0, e1, e0, m2, m1, m0` with exactly the exponent and
-// mantissa bits of the FP6 E2M3 encoding of t (zero included), so a field is that byte without its two zero
-// bits.  A lane's four adjacent channels are 24 bits; the lanes of a quad own twelve consecutive bytes of an
-// operand, which three of them store as one dword each.  No code sums travel with this layout.
+// bind) and exactly an FP6 E2M3 number, so the hardware conversion of 32 fp32 values to 32 packed fields serves here
+// as in the token-wise quantizer: two conversions per 32 x 32 block of a lane's four channels, from whose results a
+// row's 24 bits are cut.  A lane's four adjacent channels are those 24 bits; the lanes of a quad own twelve
+// consecutive bytes of an operand, which three of them store as one dword each.  No code sums travel with this layout.
 template <int FM, int FN>
 __device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&acc)[FM][FN], const ChanParams6<FN> &cp,
                                                      int n_lane, int m0, int row_w, int lane, int tid, int panel,
                                                      bool first_cols, const float *sa_lds, float *scratch) {
     static_assert(FN == 4 && FM == 2, "32 rows per half wave; a lane holds four adjacent channels");
-    typedef short v2s __attribute__((ext_vector_type(2)));
     const bool gelu = g.act == W4A4_ACT_GELU;
     const int h = lane >> 5, c = lane & 31;
     // 1. outputs in fp32, kept in place; vmax[i*16 + r] = bits of the max over this lane's channels (a non-negative,
@@ -186,30 +184,40 @@ __device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&a
                            (uint32_t)(ob < 16 ? 16 * e + ob : 32 + 8 * (e ^ sw) + (ob - 16));
     // bytes of {next lane's 24 bits, own 24 bits} that make dword j: own[j..2], then next[0..j]
     const uint32_t sel = (lane & 3) == 0 ? 0x04020100u : (lane & 3) == 1 ? 0x05040201u : 0x06050402u;
+    typedef unsigned int v6u __attribute__((ext_vector_type(6)));
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM; ++i) {
+        // t = rne(y * 7/max), in place
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float4 iv4 = *reinterpret_cast<const float4 *>(scratch + (tid & ~63) + h * 32 + i * 16 + q * 4);
             const float ivv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
 #pragma unroll
-            for (int rr = 0; rr < 4; ++rr) {
-                const int r = q * 4 + rr;
-                float t[FN];
+            for (int rr = 0; rr < 4; ++rr)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) t[j] = __builtin_rintf(acc[i][j][r] * ivv[rr]);
-                v2s pk = {0, 0};
-                pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, t[0], t[1], 64.0f, false);
-                pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, t[2], t[3], 64.0f, true);
-                const uint32_t b4 = __builtin_bit_cast(uint32_t, pk);              // four bytes s00eemmm
-                const uint32_t f4 = (b4 & 0x1F1F1F1Fu) | ((b4 >> 2) & 0x20202020u);  // four 6-bit fields, one per byte
-                const uint32_t p2 = (f4 & 0x003F003Fu) | ((f4 >> 2) & 0x0FC00FC0u);  // two 12-bit pairs, one per half
-                const uint32_t own = (p2 & 0x00000FFFu) | ((p2 >> 4) & 0x00FFF000u); // 24 bits
-                const uint32_t nxt = dpp_fetch<0xF9>(own);                          // quad permute [1,2,3,3]: the next lane's
-                const uint32_t word = __builtin_amdgcn_perm(nxt, own, sel);
-                __builtin_amdgcn_raw_buffer_store_b32(word, q_rsrc, lane_q[q >> 1] + (uint32_t)(i * 32 + 8 * q + rr) * kRow6, 0, 0);
-            }
+                for (int j = 0; j < FN; ++j) acc[i][j][q * 4 + rr] = __builtin_rintf(acc[i][j][q * 4 + rr] * ivv[rr]);
         }
+        // 32 values -> 32 fields per conversion; it interleaves its two sources, so fields 2r and 2r+1 of `lo` are
+        // channels 0 and 1 of row register r, of `hi` channels 2 and 3: twelve bits each per row
+        const v6u lo = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(acc[i][0], acc[i][1], 1.0f);
+        const v6u hi = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(acc[i][2], acc[i][3], 1.0f);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int d = (12 * r) >> 5, o = (12 * r) & 31;
+            uint32_t a12, b12;                                    // b12 may keep bits above its twelve: they end up past bit 23
+            if (o + 12 <= 32) {
+                a12 = __builtin_amdgcn_ubfe(lo[d], o, 12);
+                b12 = hi[d] >> o;
+            } else {
+                a12 = __builtin_amdgcn_alignbit(lo[d + 1], lo[d], o) & 0xFFFu;
+                b12 = __builtin_amdgcn_alignbit(hi[d + 1], hi[d], o);
+            }
+            const uint32_t own = (b12 << 12) | a12;               // 24 bits (and junk above, which the byte select drops)
+            const uint32_t nxt = dpp_fetch<0xF9>(own);            // quad permute [1,2,3,3]: the next lane's
+            const uint32_t word = __builtin_amdgcn_perm(nxt, own, sel);
+            __builtin_amdgcn_raw_buffer_store_b32(word, q_rsrc, lane_q[r >> 3] + (uint32_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * kRow6, 0, 0);
+        }
+    }
 }
 
 template <int FM, int FN, int WM, int WN, int OCC, int NS, int OUT>
@@ -245,13 +253,16 @@ void gemm_fp6_kernel(GemmArgs g) {
     // h of a 64-token panel is 3 KB, of a 128-channel panel 6 KB, each contiguous.  DMA instruction i of this wave
     // moves kilobyte bi = wave + i*NW of the stage, every lane sixteen consecutive bytes: whole cache lines, in order.
     const int KB = g.K / kHalf;                                 // blocks per row = half steps per tile
+    // a token panel is lda * 64 bytes long: KB blocks, or more when the activations are a column slice (whole blocks)
+    // of a wider matrix, whose pointer then addresses the slice's first block in panel 0
+    const int a_panel = (int)g.lda * 64;
     int dma_base[LD], dma_step[LD];                             // byte offset of the kilobyte in half step 0, and per half step
     int voff[LD];
 #pragma unroll
     for (int i = 0; i < LD; ++i) {
         const int bi = wave + i * NW;
         if (bi < A_BLOCKS) {
-            dma_base[i] = (bi / 3) * KB * 3072 + (bi % 3) * 1024;
+            dma_base[i] = (bi / 3) * a_panel + (bi % 3) * 1024;
             dma_step[i] = 3072;
         } else {
             const int bb = bi - A_BLOCKS;
@@ -260,10 +271,11 @@ void gemm_fp6_kernel(GemmArgs g) {
         }
         voff[i] = bi < REAL ? lane * 16 : (int)kPoison;         // padding blocks: outside every descriptor, read as zero
     }
-    // descriptors of a tile: from its first panel to the end of the (panel-padded) matrix
-    const long a_bytes = (((long)g.M + 63) & ~63L) * KB * 48, b_bytes = (((long)g.N + 127) & ~127L) * KB * 48;
+    // descriptors of a tile: from its first panel to the end of the (panel-padded) matrix - for a column slice, to the
+    // end of the slice's blocks in the last panel
+    const long a_bytes = ((((long)g.M + 63) >> 6) - 1) * a_panel + (long)KB * 3072, b_bytes = (((long)g.N + 127) & ~127L) * KB * 48;
     auto a_desc = [&](int m0) {
-        const long off = (long)(m0 >> 6) * KB * 3072;
+        const long off = (long)(m0 >> 6) * a_panel;
         return make_rsrc(g.Aq + off, (uint32_t)(a_bytes > off ? a_bytes - off : 0));
     };
     auto b_desc = [&](int n0) {
@@ -344,6 +356,14 @@ void gemm_fp6_kernel(GemmArgs g) {
     int vb = blockIdx.x;                                        // virtual block id of the current tile
     int tile;
     if (!tile_of(vb, tile)) return;                             // (uniform) nothing to do for this workgroup
+    if constexpr (OUT == OUT_Q6) {
+        // Every second row panel of an XCD starts a few microseconds late.  The requantizing epilogue is vector-ALU work
+        // and a wait, the main loop matrix and memory work: two workgroups of a CU that are in different phases overlap
+        // them, and the panel waits keep whatever phases the workgroups start with (the grid holds whole panels, so the
+        // same workgroups meet at every wait).
+        if (((int)(blockIdx.x >> 3) / g.tiles_n) & 1)
+            for (int s = 0; s < g.stagger; ++s) __builtin_amdgcn_s_sleep(32);
+    }
     int m0 = (tile / g.tiles_n) * BM, n0 = (tile % g.tiles_n) * BN;
     __amdgpu_buffer_rsrc_t a_cur = a_desc(m0), b_cur = b_desc(n0);
     // ---- first tile: its first NS half steps and its token scales -----------------------------------
@@ -525,6 +545,13 @@ static int launch_one6(GemmArgs &g, hipStream_t st) {
         grid = (unsigned)(most < (slots & ~(long)(kXcd - 1)) ? most : (slots & ~(long)(kXcd - 1)));
         if (g.N % L::BN || g.tiles_n > (int)(grid / kXcd)) return W4A4_ERR_UNSUPPORTED_SHAPE;
         if (g.wait_for == 0) g.wait_for = g.tiles_n;
+        // Whole panels only, when the workgroups walk more than one round: the same tiles_n workgroups then meet at every
+        // wait, and the half-tile offset between neighbouring panels (see the kernel) survives the rounds.
+        const int per = (int)(grid / kXcd) / g.tiles_n;
+        if (per >= 2 && most > (long)grid) {
+            grid = (unsigned)(per * g.tiles_n * kXcd);
+            g.stagger = 5;                                      // sleeps of 2048 cycles: measured best of 0 .. 17 at K = 1024 and 4096
+        }
     }
     if (grid == 0) return W4A4_ERR_UNSUPPORTED_SHAPE;
     launch_gemm(L::kernel(), dim3(grid), dim3(WM * WN * 64), L::lds, st, g);

@@ -1,7 +1,8 @@
 """GPU parity of the FP6 path: symmetric INT4 codes stored as FP6 E2M3 numbers, the GEMM on the FP6 matrix
 instruction with FP32 accumulation (Sec. 4.2: INT4 arithmetic at twice the INT8 rate).  Codes, scales and int32
 sums must equal the oracle's bit for bit; fp16 outputs without GELU too (the epilogue follows the definition's
-operation order), with GELU within one fp16 step."""
+operation order), with GELU within one fp16 step; outputs requantized in the GEMM epilogue (Sec. 4.2: the next
+layer's quantize fused behind bias-add / GELU) equal the oracle's codes and scales bit for bit without GELU."""
 import numpy as np
 import pytest
 import torch
@@ -178,6 +179,143 @@ def test_requantized_output_from_fp6_operands(B, orc, rmode, rlayout):
     assert np.array_equal(host(got.scale).view(np.uint32), want["s"].view(np.uint32))
     if rmode == 1:
         assert np.array_equal(host(got.zero).view(np.uint32), want["z"].view(np.uint32))
+
+
+def _codes(want_q, N):
+    """canonical packed nibbles (two's complement, low nibble first) -> int8 codes"""
+    lo = (want_q & 15).astype(np.int8)
+    hi = (want_q >> 4).astype(np.int8)
+    c = np.empty(want_q.shape[:-1] + (N,), np.int8)
+    c[..., 0::2] = np.where(lo > 7, lo - 16, lo)
+    c[..., 1::2] = np.where(hi > 7, hi - 16, hi)
+    return c
+
+
+@pytest.mark.parametrize("M,N,K,bias", [(128, 256, 512, False), (200, 512, 768, True), (1000, 1024, 1024, True), (77, 768, 512, True),
+                                        (2500, 3072, 1024, True)])
+def test_fused_requantize_fp6(B, orc, M, N, K, bias):
+    rng = np.random.default_rng(M + N + K)
+    X, W = _x(rng, M, K), (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    A, Q = B.quantize_act(dev(X), SYM, layout=FP6), B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    a, w = orc.quantize_act(X, SYM), orc.quantize_weight(W, SYM, 0)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float16) if bias else None
+    want = orc.linear(a, w, SYM, 0, b, 0, requant=True, requant_mode=SYM, requant_group=0)
+    got = B.linear(A, Q, dev(b) if bias else None, 0, requant=True, requant_mode=SYM, requant_group=0, requant_layout=FP6)
+    torch.cuda.synchronize()
+    assert B.fused_fault_check() == 0
+    assert np.array_equal(host(got.scale).view(np.uint32), want["s"].view(np.uint32))
+    codes = fp6_to_codes(host(got.q), N, M)
+    assert np.array_equal(codes, _codes(want["q"], N))
+    # the entry point without a workspace argument runs the same kernel on the library's static exchange area
+    st = B.linear_static(A, Q, dev(b) if bias else None, 0, requant=True, requant_mode=SYM, requant_group=0, requant_layout=FP6)
+    assert torch.equal(st.q, got.q) and torch.equal(st.scale, got.scale)
+
+
+def test_chained_layers_and_column_slice(B, orc):
+    """Two GEMMs in a row without an fp16 tensor between them: the requantized output of the first (GELU behind it) is the
+    second's FP6 operand as it stands, once whole and once as its last third of columns read in place."""
+    from paper_2301_12017_amd import workloads as WL
+    M, K, N1, N2 = 300, 512, 1536, 256
+    rng = np.random.default_rng(7)
+    X, W1 = _x(rng, M, K), (rng.standard_normal((N1, K)) * 0.02).astype(np.float16)
+    b1 = (rng.standard_normal(N1) * 0.01).astype(np.float16)
+    A, Q1 = B.quantize_act(dev(X), SYM, layout=FP6), B.quantize_weight(dev(W1), SYM, 0, layout=FP6)
+    H = B.linear(A, Q1, dev(b1), 0, requant=True, requant_layout=FP6)
+    a, w1 = orc.quantize_act(X, SYM), orc.quantize_weight(W1, SYM, 0)
+    h = orc.linear(a, w1, SYM, 0, b1, 0, requant=True, requant_mode=SYM, requant_group=0)
+    assert np.array_equal(fp6_to_codes(host(H.q), N1, M), _codes(h["q"], N1))
+    assert np.array_equal(host(H.scale).view(np.uint32), h["s"].view(np.uint32))
+    # whole output as the next operand
+    W2 = (rng.standard_normal((N2, N1)) * 0.02).astype(np.float16)
+    Q2, w2 = B.quantize_weight(dev(W2), SYM, 0, layout=FP6), orc.quantize_weight(W2, SYM, 0)
+    want = orc.gemm_i32(h["q"], w2["q"], SYM, 0)
+    assert np.array_equal(host(B.gemm_i32(H, Q2)), want)
+    # its last third of columns, in place
+    third = N1 // 3
+    W3 = (rng.standard_normal((N2, third)) * 0.02).astype(np.float16)
+    Q3, w3 = B.quantize_weight(dev(W3), SYM, 0, layout=FP6), orc.quantize_weight(W3, SYM, 0)
+    V = WL.v_slice(H, third)
+    codes_v = _codes(h["q"], N1)[:, 2 * third:].astype(np.int64)
+    want3 = codes_v @ _codes(w3["q"], third).astype(np.int64).T
+    for sch in [i + 1 for i, n in enumerate(B.schedule_names()) if n.startswith("fp6") and n != "fp6_192x256"]:
+        assert np.array_equal(host(B.gemm_i32(V, Q3, schedule=sch)).astype(np.int64).reshape(M, N2), want3)
+
+
+def test_gelu_and_give_up(B, orc):
+    """Behind a GELU the codes may differ from the oracle's by one step where the scaled value is next to a half-integer
+    (the device's GELU is a polynomial); and a wait that cannot be satisfied ends with the fault flag, not a hang."""
+    M, N, K = 640, 1024, 512
+    rng = np.random.default_rng(9)
+    X, W = _x(rng, M, K), (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    b = (rng.standard_normal(N) * 0.01).astype(np.float16)
+    A, Q = B.quantize_act(dev(X), SYM, layout=FP6), B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    a, w = orc.quantize_act(X, SYM), orc.quantize_weight(W, SYM, 0)
+    want = orc.linear(a, w, SYM, 0, b, 1, requant=True, requant_mode=SYM, requant_group=0)
+    got = B.linear(A, Q, dev(b), 1, requant=True, requant_layout=FP6)
+    codes, wc = fp6_to_codes(host(got.q), N, M).astype(np.int32), _codes(want["q"], N).astype(np.int32)
+    np.testing.assert_allclose(host(got.scale), want["s"], rtol=2e-5)
+    diff = np.abs(codes - wc)
+    print("GELU requant: mismatching codes", int((diff != 0).sum()), "of", diff.size, flush=True)
+    assert diff.max() <= 1 and (diff != 0).mean() <= 5e-5
+    # the canonical output of the same layer (fp32 rows, then the row quantizer) holds the same codes
+    ref = B.linear(A, Q, dev(b), 1, requant=True, requant_layout=0)
+    assert np.array_equal(_codes(host(ref.q), N), codes)
+    assert np.array_equal(host(ref.scale).view(np.uint32), host(got.scale).view(np.uint32))
+    B.debug_fused_wait(64, 1)
+    try:
+        B.linear(A, Q, dev(b), 0, requant=True, requant_layout=FP6)
+        torch.cuda.synchronize()
+        assert B.fused_fault_check() is True
+    finally:
+        B.debug_fused_wait(0, 0)
+    assert B.fused_fault_check() is False
+
+
+@pytest.mark.parametrize("N,K,gelu", [(3072, 1024, False), (1024, 1024, False), (4096, 1024, True), (1024, 4096, False)])
+def test_fused_requantize_fp6_at_full_size(B, N, K, gelu):
+    """The four GEMMs of the chained workload at its 32768 tokens (several rounds of tiles per workgroup, every XCD's
+    range of row panels): the fused kernel's FP6 codes and scales against the two-kernel path of the same operands
+    (fp32 rows, then the row quantizer - the path compared with the oracle above), bit for bit, on both panels of every
+    other row tile."""
+    from paper_2301_12017_amd import synth
+    M = 32768
+    rng = np.random.default_rng(N + K)
+    X = dev(synth.activations(M, K, 0, 5, 0))
+    W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+    b = dev((rng.standard_normal(N) * 0.01).astype(np.float16))
+    A, Q = B.quantize_act(X, SYM, layout=FP6), B.quantize_weight(dev(W), SYM, 0, layout=FP6)
+    got = B.linear(A, Q, b, int(gelu), requant=True, requant_layout=FP6)
+    assert B.pick_schedule(A, Q, requant=True, requant_layout=FP6) == "fp6_128x256"
+    ref = B.linear(A, Q, b, int(gelu), requant=True, requant_layout=0)
+    torch.cuda.synchronize()
+    assert B.fused_fault_check() is False
+    assert torch.equal(got.scale.view(torch.int32), ref.scale.view(torch.int32))
+    panels = torch.arange(M // 64, device="cuda").view(-1, 2)[0::2].reshape(-1)          # both panels of every other 128-row tile
+    q = got.q.view(M // 64, -1)[panels].cpu().numpy()
+    rows = (panels[:, None] * 64 + torch.arange(64, device="cuda")[None, :]).reshape(-1)
+    want = _codes(ref.q[rows].cpu().numpy(), N)
+    for c0 in range(0, len(panels), 64):                                                   # 4096 rows at a time
+        codes = fp6_to_codes(q[c0:c0 + 64], N, 64 * len(q[c0:c0 + 64]))
+        assert np.array_equal(codes, want[64 * c0:64 * (c0 + 64)]), f"panels {c0} .. {c0 + 63} of the sample"
+
+
+def test_fused_requantize_fp6_refusals(B):
+    """What the fused FP6 output does not take is refused before anything is written."""
+    rng = np.random.default_rng(2)
+    X = dev(_x(rng, 128, 512))
+    A = B.quantize_act(X, SYM, layout=FP6)
+    Q = B.quantize_weight(dev(_w(rng, 384, 512)), SYM, 0, layout=FP6)                      # N not a multiple of 256
+    with pytest.raises(RuntimeError):
+        B.linear(A, Q, None, 0, requant=True, requant_layout=FP6)
+    Q = B.quantize_weight(dev(_w(rng, 512, 512)), SYM, 0, layout=FP6)
+    with pytest.raises(RuntimeError):                                                       # one range per token only
+        B.linear(A, Q, None, 0, requant=True, requant_group=128, requant_layout=FP6)
+    with pytest.raises(RuntimeError):                                                       # unsigned output codes
+        B.linear(A, Q, None, 0, requant=True, requant_mode=1, requant_layout=FP6)
+    Am = B.quantize_act(X, SYM, layout=1)
+    Qm = B.quantize_weight(dev(_w(rng, 512, 512)), SYM, 0, layout=1)
+    with pytest.raises(RuntimeError):                                                       # FP6 codes come from the FP6 kernel only
+        B.linear(Am, Qm, None, 0, requant=True, requant_layout=FP6)
 
 
 def test_calls_that_do_not_take_the_layout_refuse_it(B):
