@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 INT8_MFMA_PEAK_TOPS = 5000.0      # MI355X dense int8 matrix peak, 5.0 POP/s
+FP6_MFMA_PEAK_TOPS = 10100.0      # MI355X dense FP6 / FP4 matrix peak, 10.1 PFLOP/s
 HBM_PEAK_GBS = 8000.0
 METRIC = "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128"
 DTYPE = "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, {} out)"
@@ -820,6 +821,19 @@ def main():
                          "kernel_ms": r5["kernel_ms_per_step"], "frac": r5["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
                          "per_gemm_ms": dict(zip(r5["names"], r5["gemm_ms"])),
                          "kernel": "gemm_olay_kernel with the fused requantize epilogue; schedules " + ", ".join(r5["schedules"])}
+        # the same chained layer with every operand and every requantized output in the FP6 operand layout: the GEMMs run
+        # on the FP6 matrix instruction and write the next GEMM's operand themselves (3/4 byte per output)
+        torch.cuda.empty_cache()
+        r56 = chain_leg(5, 2, args.settle_ms, B.LAYOUT_FP6)
+        other["cfg5_fp6_path"] = {"workload": "configs[4] again, every GEMM on the FP6 matrix instruction, every output requantized "
+                                              "in its epilogue into the FP6 operand layout; 4 x w4a4_linear(requant)",
+                                  "steps": 5, "ms_per_step": r56["ms_per_step"], "TOPS": r56["TOPS"],
+                                  "step_speedup_over_int8_path": r5["ms_per_step"] / r56["ms_per_step"],
+                                  "kernel_ms": r56["kernel_ms_per_step"],
+                                  "frac_of_int8_mfma_peak": r56["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
+                                  "frac_of_fp6_mfma_peak": r56["achieved_TOPS"] / FP6_MFMA_PEAK_TOPS,
+                                  "per_gemm_ms": dict(zip(r56["names"], r56["gemm_ms"])),
+                                  "kernel": "gemm_fp6_kernel with the fused requantize epilogue; schedules " + ", ".join(r56["schedules"])}
 
         if cfg == 3:
             # the same step with the layers of at least 2M weights in the FP6 operand layout: their GEMMs run on the FP6
@@ -839,7 +853,7 @@ def main():
                 "kernel_ms": r6["kernel_ms_per_step"], "kernel_TOPS": r6["achieved_TOPS"],
                 "frac_of_int8_mfma_peak": r6["achieved_TOPS"] / INT8_MFMA_PEAK_TOPS,
                 "fp6_kernels": {"ops": ops6, "ms": ms6, "TOPS": ops6 / (ms6 * 1e-3) / 1e12,
-                                "frac_of_fp6_mfma_peak": ops6 / (ms6 * 1e-3) / 1e12 / 10100.0,
+                                "frac_of_fp6_mfma_peak": ops6 / (ms6 * 1e-3) / 1e12 / FP6_MFMA_PEAK_TOPS,
                                 "frac_of_measured_fp6": ops6 / (ms6 * 1e-3) / 1e12 / ceil["mfma_fp6_int4_codes_TOPS"]},
                 "per_gemm_ms": {s_.name: t for s_, t in zip(w6.specs, r6["gemm_ms"])},
                 "kernel": kernel_label(w6.schedules)}

@@ -101,9 +101,12 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  * The FP6 layout needs symmetric codes, one scale per token / output channel (group == 0),
  * K % 256 == 0, K <= 10240 (the token-wise quantizer stages its rows on chip), and K >= 512 for the GEMM; no code
  * sums travel with it.
- * w4a4_quantize_act, w4a4_quantize_weight, w4a4_gemm_i32 and w4a4_linear (any epilogue; a requantized
- * output is produced in the canonical or the MFMA layout, through the fp32 rows of the workspace)
- * understand it; the fused-producer, strategy and whole-layer calls do not. */
+ * w4a4_quantize_act, w4a4_quantize_weight, w4a4_gemm_i32 and w4a4_linear understand it (any epilogue: a
+ * requantized output in the FP6 layout is written by the GEMM kernel itself, as the next layer's operand - one
+ * range per token, N % 256 == 0, N / 256 column tiles co-resident, else UNSUPPORTED_SHAPE -, one in the
+ * canonical or the MFMA layout goes through the fp32 rows of the workspace); the fused-producer, strategy and
+ * whole-layer calls do not.  Padding rows of a matrix written by the GEMM kernel hold zeros of either sign
+ * (the sign bit of a field may be set). */
 typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1, W4A4_LAYOUT_FP6 = 2 } w4a4_layout;
 
 /* Sec. 4.2: GELU (erf form) may sit between the GEMM and the next quantize. */
@@ -120,7 +123,11 @@ typedef struct {
     int M, K;
     int lda;               /* row stride of q in BYTES (>= K/2, multiple of 16): lets a
                               GEMM read a column slice of a wider packed matrix in place;
-                              layout == FP6: 3K/4, not a stride (no slices there)        */
+                              layout == FP6: 3/4 byte times the row length of the matrix q
+                              points into (a multiple of 48; a 64-token panel is 64*lda
+                              bytes).  A column slice of whole 64-code blocks [b0, b0+K/64)
+                              of a wider matrix is q = matrix + b0*3072, K = its length,
+                              lda = the wider matrix's                                    */
     int group;             /* K-group length the gsum was taken over (0 = whole row)     */
     int mode;              /* w4a4_mode */
     int layout;            /* w4a4_layout of q                                           */
@@ -161,8 +168,9 @@ typedef struct {
                                with requant_layout == MFMA: length of the column slices
                                the odd-position sums are kept for (0 = whole row, else a
                                multiple of 256 that divides N)                            */
-    int requant_layout;     /* w4a4_layout of the requantized codes (MFMA needs
-                               requant_mode == SYM)                                       */
+    int requant_layout;     /* w4a4_layout of the requantized codes (MFMA and FP6 need
+                               requant_mode == SYM; FP6 needs operands in the FP6 layout
+                               and requant_group 0 or N, and takes no out_gsum)           */
     int schedule;           /* 0 = pick the tile schedule from the built-in shape table
                                (Sec. 4.2: schedules are pre-tuned per shape); > 0 forces
                                schedule number `schedule` (see w4a4_schedule_count)       */
@@ -414,7 +422,8 @@ int w4a4_quantize_act(const void *X_f16, int M, int K, int ldx, int mode, int gr
 /* Steps a2+a3 fused: INT4 x INT4 -> INT32 GEMM (Sec. 4.1 shapes, activations [M,K],
  * weights [N,K]) with the dequantize / zero-point terms / bias / GELU epilogue and
  * either an fp16 store or a per-token requantize (Sec. 4.2) behind it.
- *   out:       fp16 [M,N] (requant == 0) or u8 [M,N/2] (requant == 1)
+ *   out:       fp16 [M,N] (requant == 0) or u8 [M,N/2] (requant == 1; requant_layout == FP6:
+ *              ceil(M/64)*64 * 3N/4 bytes, all of them written)
  *   out_scale: [M], out_zero: [M] (requant_mode ASYM), out_gsum: [M, N/requant_group]
  *              (may be NULL; with requant_layout == MFMA it is REQUIRED and receives the
  *              odd-position code sums of each column slice); all ignored when requant == 0.

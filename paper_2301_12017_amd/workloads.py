@@ -80,3 +80,24 @@ def v_slice(qkv: B.QAct, h: int) -> B.QAct:
     off = (2 * h // 64) * 3072 if qkv.layout == B.LAYOUT_FP6 else h
     return B.QAct(qkv.q, qkv.scale, qkv.zero, None, qkv.M, h, qkv.lda, 0, qkv.mode, q_offset_bytes=off,
                   layout=qkv.layout, osum=qkv.osum, osum_index=2 if qkv.osum is not None else 0)
+
+
+def run_chain(A: B.QAct, layers: List[ChainLayer], workspace: Optional[torch.Tensor] = None, record=None,
+              schedule: int = 0) -> B.QAct:
+    """quantize -> GEMM -> dequant+bias(+GELU) -> requantize, four GEMMs per layer, without
+    an fp16 activation tensor in between.  `record` (a list) receives (name, input, output).
+    The requantized outputs keep the layout of the operands; the QKV output keeps one
+    odd-position sum per third so that the V slice can be consumed in place."""
+    h = layers[0].out.spec.K
+    for li, L in enumerate(layers):
+        steps = (("qkv", L.qkv, None), ("attn_out", L.out, h), ("ffn1", L.ffn1, None), ("ffn2", L.ffn2, None))
+        for name, lay, slice_h in steps:
+            a_in = v_slice(A, slice_h) if slice_h else A
+            mfma = lay.W.layout == B.LAYOUT_MFMA
+            out = B.linear(a_in, lay.W, lay.bias, lay.act, requant=True, requant_mode=B.SYM, schedule=schedule,
+                           workspace=workspace, requant_layout=lay.W.layout,
+                           requant_group=h if (mfma and name == "qkv") else 0)
+            if record is not None:
+                record.append((li, name, a_in, out, lay))
+            A = out
+    return A
