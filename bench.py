@@ -29,6 +29,7 @@ FP6_MFMA_PEAK_TOPS = 10100.0      # MI355X dense FP6 / FP4 matrix peak, 10.1 PFL
 HBM_PEAK_GBS = 8000.0
 METRIC = "W4A4 linear TOPS (% int8-MFMA peak); BERT-base layer latency b1/s128"
 DTYPE = "int8 (int4 operands widened for the int8 MFMA, int32 accumulate, fp32 epilogue, {} out)"
+DTYPE_FP6 = "fp6 (int4 codes as FP6 E2M3 operands of the f8f6f4 MFMA, fp32 accumulate: exact integer sums, fp32 epilogue, {} out)"
 TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "gemm_config3_hbm_traffic.txt")
 
 
@@ -291,7 +292,7 @@ def bench_chain(args):
     line = {
         "metric": METRIC, "value": r["TOPS"], "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "settle_ms": args.settle_ms, "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": DTYPE.format("int4"), "data": "synthetic",
+        "vs_baseline": None, "dtype": (DTYPE_FP6 if fp6 else DTYPE).format("int4"), "data": "synthetic",
         "config": {"workload": f"configs[4]: one layer of the chained BERT-large stack, M={M}: qkv, attn_out (V third in "
                                f"place), ffn1+GELU, ffn2, every output requantized per token in the GEMM epilogue",
                    "step": "4 x w4a4_linear(requant)", "layout": r["layout"]},
@@ -584,6 +585,7 @@ def main():
     cfg = args.config
     wl = StepWorkload(cfg, args.schedule, args.layout)
     specs, layers, Xs, outs, stream, schedules = wl.specs, wl.layers, wl.Xs, wl.outs, wl.stream, list(wl.schedules)
+    all_fp6 = all(l_.W.layout == B.LAYOUT_FP6 for l_ in layers)
     if args.quantize_only:
         q = quantize_leg(specs, layers[0].W.layout, args.settle_ms)
         if args.copy_probe_mb:
@@ -872,7 +874,7 @@ def main():
         "metric": METRIC,
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "settle_ms": args.settle_ms,
         "ms_per_step": ms_per_step, "ms_per_step_graph_replay": graph_ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": DTYPE.format("fp16"),
+        "dtype": (DTYPE_FP6 if all_fp6 else DTYPE).format("fp16"),
         "data": "synthetic",
         "config": {"workload": f"configs[{cfg - 1}]: " + ", ".join(f"{s.name} {s.M}x{s.N}x{s.K}" for s in specs)
                    + ("; symmetric per-token / per-channel INT4" if cfg != 4 else
