@@ -163,25 +163,32 @@ __device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&a
         const float amax = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(mx_rsrc, m_c * 4, 0, 17));
         const Range rg = range_sym(amax);
         if (m_c < g.M && first_cols) g.out_scale[m_c] = rg.S;     // the wave that holds channel 0 of the row
-        scratch[(tid & ~63) + lane] = rg.inv;                     // 0 for rows >= M: their codes are written as zeros
+        scratch[(tid & ~63) * 4 + lane] = rg.inv;                 // 0 for rows >= M: their codes are written as zeros
         __builtin_amdgcn_wave_barrier();
     }
     // 5. codes.  The output is an activation matrix of N codes per row in the FP6 layout: panels of 64 tokens, block b
     //    (64 codes) of a panel's rows contiguous, a row's 48 bytes of a block = operand 2b+e as 16 bytes at 16e and 8
     //    bytes at 32 + 8e (at 40 - 8e in rows 16 .. 31 of every 32).  Lane c holds channels 4c .. 4c+3 of the wave's
-    //    128-channel panel: bytes 3(c%8) .. +2 of operand c/8; quad lane j < 3 stores dword j of the quad's twelve bytes.
+    //    128-channel panel: bytes 3(c%8) .. +2 of operand c/8; quad lane j < 3 makes dword j of the quad's twelve bytes.
+    //    The wave's 64 rows are one token panel and its 128 channels two blocks of it, so eight consecutive rows are 384
+    //    consecutive bytes in each of the two blocks: the dwords of eight rows meet in LDS (768 bytes per wave, behind
+    //    the wave's 64 ranges) and leave as 48 sixteen-byte stores.
     const int KBo = g.N / kHalf;
     const long out_bytes = (((long)g.M + 63) & ~63L) * KBo * kRow6;
     const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(g.out, (uint32_t)out_bytes);
-    const int op = (n_lane >> 5), ob = 12 * ((c >> 2) & 1) + 4 * (lane & 3);   // operand of the row, byte of this lane's dword in it
-    const uint32_t blk = (uint32_t)(op >> 1) * (64 * kRow6);
+    const int op = (n_lane >> 5) & 3, ob = 12 * ((c >> 2) & 1) + 4 * (lane & 3);   // operand of the wave's four, byte of this lane's dword in it
     const int e = op & 1;
-    uint32_t lane_q[2];                                           // by bit 4 of the row inside its panel
+    uint8_t *stage8 = reinterpret_cast<uint8_t *>(scratch + (tid & ~63) * 4) + 256;
+    uint32_t put[2];                                              // where this lane's dword goes in the staging area, by bit 4 of the row
 #pragma unroll
     for (int sw = 0; sw < 2; ++sw)
-        lane_q[sw] = (lane & 3) == 3 ? kPoison
-                     : (uint32_t)((m0 + row_w) >> 6) * ((uint32_t)KBo * (64 * kRow6)) + blk + (uint32_t)(4 * h) * kRow6 +
-                           (uint32_t)(ob < 16 ? 16 * e + ob : 32 + 8 * (e ^ sw) + (ob - 16));
+        put[sw] = (uint32_t)(op >> 1) * 384u + (uint32_t)(4 * h) * kRow6 + (uint32_t)(ob < 16 ? 16 * e + ob : 32 + 8 * (e ^ sw) + (ob - 16));
+    // lane L < 48 stores bytes 16L .. 16L+15 of the staging area: block L / 24 of the two, byte 16 (L % 24) of its eight rows
+    const uint32_t blk0 = (uint32_t)(n_lane >> 7) * 2u;          // first of the wave's two blocks in the row
+    const uint32_t get = lane >= 48 ? 0u : (uint32_t)lane * 16u;   // (the idle lanes re-read the first piece)
+    const uint32_t lane_q = lane >= 48 ? kPoison
+                            : (uint32_t)((m0 + row_w) >> 6) * ((uint32_t)KBo * (64 * kRow6)) +
+                                  (blk0 + (uint32_t)(lane / 24)) * (64 * kRow6) + (uint32_t)(lane % 24) * 16u;
     // bytes of {next lane's 24 bits, own 24 bits} that make dword j: own[j..2], then next[0..j]
     const uint32_t sel = (lane & 3) == 0 ? 0x04020100u : (lane & 3) == 1 ? 0x05040201u : 0x06050402u;
     typedef unsigned int v6u __attribute__((ext_vector_type(6)));
@@ -190,7 +197,7 @@ __device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&a
         // t = rne(y * 7/max), in place
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const float4 iv4 = *reinterpret_cast<const float4 *>(scratch + (tid & ~63) + h * 32 + i * 16 + q * 4);
+            const float4 iv4 = *reinterpret_cast<const float4 *>(scratch + (tid & ~63) * 4 + h * 32 + i * 16 + q * 4);
             const float ivv[4] = {iv4.x, iv4.y, iv4.z, iv4.w};
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr)
@@ -202,20 +209,28 @@ __device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&a
         const v6u lo = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(acc[i][0], acc[i][1], 1.0f);
         const v6u hi = __builtin_amdgcn_cvt_scalef32_2xpk16_fp6_f32(acc[i][2], acc[i][3], 1.0f);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int d = (12 * r) >> 5, o = (12 * r) & 31;
-            uint32_t a12, b12;                                    // b12 may keep bits above its twelve: they end up past bit 23
-            if (o + 12 <= 32) {
-                a12 = __builtin_amdgcn_ubfe(lo[d], o, 12);
-                b12 = hi[d] >> o;
-            } else {
-                a12 = __builtin_amdgcn_alignbit(lo[d + 1], lo[d], o) & 0xFFFu;
-                b12 = __builtin_amdgcn_alignbit(hi[d + 1], hi[d], o);
+        for (int q = 0; q < 4; ++q) {                             // rows 8q .. 8q+7 of the 32: 4h + rr in this lane
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = 4 * q + rr;
+                const int d = (12 * r) >> 5, o = (12 * r) & 31;
+                uint32_t a12, b12;                                // b12 may keep bits above its twelve: they end up past bit 23
+                if (o + 12 <= 32) {
+                    a12 = __builtin_amdgcn_ubfe(lo[d], o, 12);
+                    b12 = hi[d] >> o;
+                } else {
+                    a12 = __builtin_amdgcn_alignbit(lo[d + 1], lo[d], o) & 0xFFFu;
+                    b12 = __builtin_amdgcn_alignbit(hi[d + 1], hi[d], o);
+                }
+                const uint32_t own = (b12 << 12) | a12;           // 24 bits (and junk above, which the byte select drops)
+                const uint32_t nxt = dpp_fetch<0xF9>(own);        // quad permute [1,2,3,3]: the next lane's
+                const uint32_t word = __builtin_amdgcn_perm(nxt, own, sel);
+                if ((lane & 3) != 3) *reinterpret_cast<uint32_t *>(stage8 + put[q >> 1] + rr * kRow6) = word;
             }
-            const uint32_t own = (b12 << 12) | a12;               // 24 bits (and junk above, which the byte select drops)
-            const uint32_t nxt = dpp_fetch<0xF9>(own);            // quad permute [1,2,3,3]: the next lane's
-            const uint32_t word = __builtin_amdgcn_perm(nxt, own, sel);
-            __builtin_amdgcn_raw_buffer_store_b32(word, q_rsrc, lane_q[r >> 3] + (uint32_t)(i * 32 + 8 * (r >> 2) + (r & 3)) * kRow6, 0, 0);
+            asm volatile("" ::: "memory");                        // the wave's LDS operations execute in program order
+            const u32x4 out16 = *reinterpret_cast<const u32x4 *>(stage8 + get);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_raw_buffer_store_b128(out16, q_rsrc, lane_q + (uint32_t)(i * 32 + 8 * q) * kRow6, 0, 0);
         }
     }
 }
@@ -240,7 +255,7 @@ void gemm_fp6_kernel(GemmArgs g) {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     uint8_t *dummy = smem + NS * STAGE;                         // where the padding blocks of every stage land (zeros)
     uint8_t *par = dummy + (BLOCKS > REAL ? 1024 : 0);          // token scales of the tile, double buffered: [2][BM]
-                                                                // (OUT_Q6: followed by 64 floats per wave for the row ranges)
+                                                                // (OUT_Q6: followed by a kilobyte per wave: 64 row ranges, 768 bytes of codes on their way out)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -511,7 +526,7 @@ template <int FM, int FN, int WM, int WN, int OCC, int NS, int OUT>
 struct Fp6Launch {
     static constexpr int BM = WM * FM * 32, BN = WN * FN * 32, NW = WM * WN;
     static constexpr int REAL = (BM + BN) * 3 / 64, BLOCKS = (REAL + NW - 1) / NW * NW;
-    static constexpr size_t lds = (size_t)NS * REAL * 1024 + (BLOCKS > REAL ? 1024 : 0) + 2 * BM * 4 + (OUT == OUT_Q6 ? NW * 256 : 0);
+    static constexpr size_t lds = (size_t)NS * REAL * 1024 + (BLOCKS > REAL ? 1024 : 0) + 2 * BM * 4 + (OUT == OUT_Q6 ? NW * 1024 : 0);
     static KernelState &state() { static KernelState ks; return ks; }
     static auto kernel() { return gemm_fp6_kernel<FM, FN, WM, WN, OCC, NS, OUT>; }
     // resident workgroups on the current device (-1: HIP error).  The requantizing output makes the column tiles of a
