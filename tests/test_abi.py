@@ -90,6 +90,17 @@ def test_argument_errors_are_reported_before_any_launch(b):
     assert lin(_act(b, K=256, layout=7, osum=o), _wt(b, K=256, layout=7, esum=o)) == -1
     rq_bad = b._Epilogue(None, 0, 1, 1, 0, 1, 0)                                          # ASYM codes in the operand layout
     assert lin(_act(b), _wt(b, N=32), e=rq_bad, os_=out) == -1
+    # operands in the FP6 operand layout: symmetric, one scale per row, K % 256 == 0, K >= 512, lda >= 3K/4
+    a6, w6 = _act(b, K=512, lda=384, layout=2), _wt(b, N=256, K=512, layout=2)
+    assert lin(_act(b, K=512, lda=384, layout=2, mode=1), _wt(b, N=256, K=512, layout=2, mode=1)) == -1   # unsigned codes
+    assert lin(_act(b, K=512, lda=256, layout=2), w6) == -1                               # lda < 3K/4
+    assert lin(_act(b, K=320, lda=240, layout=2), _wt(b, N=256, K=320, layout=2)) == -2   # K % 128
+    assert lin(_act(b, K=256, lda=192, layout=2), _wt(b, N=256, K=256, layout=2)) == -2   # K < 512
+    assert lin(a6, _wt(b, N=256, K=512, layout=2, group=128)) == -2                       # K-groups
+    # a requantized output in the FP6 layout: from FP6 operands only, symmetric, one range per token
+    assert lin(_act(b), _wt(b, N=256), e=b._Epilogue(None, 0, 1, 0, 0, 2, 0), os_=out) == -2
+    assert lin(a6, w6, e=b._Epilogue(None, 0, 1, 1, 0, 2, 0), os_=out) == -1
+    assert lin(a6, w6, e=b._Epilogue(None, 0, 1, 0, 128, 2, 0), os_=out) == -2
     # M == 0 is a successful no-op
     assert lin(_act(b, M=0), _wt(b)) == 0
     assert L.w4a4_gemm_i32(ctypes.byref(_act(b)), ctypes.byref(_wt(b)), None, 0, None) == -1
