@@ -95,3 +95,39 @@ def test_operand_layout_gemm_random_shapes(B, orc):
             assert np.array_equal(host(B.gemm_i32(A, Q, schedule=sch))[:, rows], wantP), (M, N, K, sch)
             got = host(B.linear(A, Q, dev(b), 0, schedule=sch))[rows]
             assert_f16(got, want, OLAY_SAME if got.size > 4000 else 0.98, str((M, N, K, sch)))
+
+
+def test_fp6_path_random_shapes(B, orc):
+    """The FP6 path on ragged M and N and every K the layout is offered for up to 4096: int32 sums of sampled rows on
+    every tile, fp16 outputs bit for bit, and - where N is a multiple of 256 - the fused requantize into the FP6 layout
+    (codes and scales bit for bit)."""
+    from tests.gpu_util import fp6_plan, fp6_schedules, fp6_to_codes
+    rng = np.random.default_rng(2028)
+    done = 0
+    while done < 10:
+        M = int(rng.integers(1, 1500))
+        K = 256 * int(rng.integers(2, 17))
+        if fp6_plan(K) is None:
+            continue
+        requant = bool(rng.integers(0, 2))
+        N = 256 * int(rng.integers(1, 7)) if requant else 8 * int(rng.integers(1, 130))
+        done += 1
+        X = (rng.standard_normal((M, K)) * rng.uniform(0.2, 3.0, size=(M, 1))).astype(np.float32).astype(np.float16)
+        W = (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
+        b = (rng.standard_normal(N) * 0.01).astype(np.float16)
+        A, Q = B.quantize_act(dev(X), 0, layout=2), B.quantize_weight(dev(W), 0, 0, layout=2)
+        rows = np.sort(rng.choice(M, min(M, 40), replace=False))
+        a, w = orc.quantize_act(np.ascontiguousarray(X[rows]), 0), orc.quantize_weight(W, 0, 0)
+        want = orc.gemm_i32(a["q"], w["q"], 0, 0)
+        for sch in fp6_schedules(B, K):
+            got = host(B.gemm_i32(A, Q, schedule=sch)).reshape(M, N)[rows]
+            assert np.array_equal(got, want.reshape(len(rows), N)), (M, N, K, B.schedule_names()[sch - 1])
+        y = host(B.linear(A, Q, dev(b), 0))[rows]
+        assert np.array_equal(y.view(np.uint16), orc.linear(a, w, 0, 0, b, 0)["out"].view(np.uint16)), (M, N, K)
+        if requant:
+            out = B.linear(A, Q, dev(b), 0, requant=True, requant_layout=2)
+            ref = orc.linear(a, w, 0, 0, b, 0, requant=True, requant_mode=0, requant_group=0)
+            assert np.array_equal(host(out.scale)[rows].view(np.uint32), ref["s"].view(np.uint32)), (M, N, K)
+            codes = fp6_to_codes(host(out.q), N, M)[rows]
+            assert np.array_equal(codes, orc.unpack(ref["q"], 0)), (M, N, K)
+    assert B.fused_fault_check() is False
