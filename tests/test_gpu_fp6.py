@@ -192,7 +192,8 @@ def _codes(want_q, N):
 
 
 @pytest.mark.parametrize("M,N,K,bias", [(128, 256, 512, False), (200, 512, 768, True), (1000, 1024, 1024, True), (77, 768, 512, True),
-                                        (2500, 3072, 1024, True)])
+                                        (2500, 3072, 1024, True), (1, 256, 512, True), (65, 256, 768, False), (64, 2560, 512, True),
+                                        (129, 512, 10240, True), (300, 8192, 512, True)])
 def test_fused_requantize_fp6(B, orc, M, N, K, bias):
     rng = np.random.default_rng(M + N + K)
     X, W = _x(rng, M, K), (rng.standard_normal((N, K)) * 0.02).astype(np.float16)
