@@ -104,8 +104,9 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  * w4a4_quantize_act, w4a4_quantize_weight, w4a4_gemm_i32 and w4a4_linear understand it (any epilogue: a
  * requantized output in the FP6 layout is written by the GEMM kernel itself, as the next layer's operand - one
  * range per token, N % 256 == 0, N / 256 column tiles co-resident, else UNSUPPORTED_SHAPE -, one in the
- * canonical or the MFMA layout goes through the fp32 rows of the workspace); the fused-producer, strategy and
- * whole-layer calls do not.  Padding rows of a matrix written by the GEMM kernel hold zeros of either sign
+ * canonical or the MFMA layout goes through the fp32 rows of the workspace), and so do w4a4_part_linear and
+ * w4a4_ffn (a fused FFN pair with both parts in it); w4a4_layernorm_quantize, w4a4_linear_f16act and
+ * w4a4_encoder_layer do not.  Padding rows of a matrix written by the GEMM kernel hold zeros of either sign
  * (the sign bit of a field may be set). */
 typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1, W4A4_LAYOUT_FP6 = 2 } w4a4_layout;
 

@@ -613,11 +613,12 @@ STRATEGY_FUSED_FFN, STRATEGY_ALL_INT4 = 16, 31
 
 class Part:
     """One linear part with its weights prepared in both precisions (w4a4_part in include/w4a4.h).
-    The INT4 weights take the layout the library prefers for M tokens."""
+    The INT4 weights take the layout the library prefers for M tokens, or the one asked for."""
 
-    def __init__(self, W: torch.Tensor, M: int, bias: Optional[torch.Tensor] = None, act=ACT_NONE, mode=SYM, group=0):
+    def __init__(self, W: torch.Tensor, M: int, bias: Optional[torch.Tensor] = None, act=ACT_NONE, mode=SYM, group=0,
+                 layout: Optional[int] = None):
         N, K = W.shape
-        self.w4 = quantize_weight(W, mode, group, preferred_layout(M, N, K, mode, group))
+        self.w4 = quantize_weight(W, mode, group, preferred_layout(M, N, K, mode, group) if layout is None else layout)
         self.w8q, self.w8s = quantize_rows8(W)
         self.bias, self.act, self.N, self.K = bias, act, N, K
 

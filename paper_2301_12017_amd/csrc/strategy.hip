@@ -37,9 +37,13 @@ int groups_of(const w4a4_weight &w) { return (w.group == 0 || w.group >= w.K) ? 
 struct ActBuffers {
     uint8_t *q; float *scale, *zero; int32_t *gsum, *osum;
 };
+// bytes of its codes: two per byte, or - FP6 operand layout - whole 64-token panels of 3/4 byte per code
+size_t act_code_bytes(int M, int K, int layout) {
+    return layout == W4A4_LAYOUT_FP6 ? (((size_t)M + 63) & ~(size_t)63) * (K / 4 * 3) : (size_t)M * (K / 2);
+}
 ActBuffers carve_act4(Carver &c, int M, int K, const w4a4_weight &w) {
     ActBuffers b;
-    b.q = c.take<uint8_t>((size_t)M * (K / 2));
+    b.q = c.take<uint8_t>(act_code_bytes(M, K, w.layout));
     b.scale = c.take<float>(M);
     b.zero = c.take<float>(M);
     b.gsum = c.take<int32_t>((size_t)M * groups_of(w));
@@ -51,7 +55,7 @@ w4a4_act view_act4(const ActBuffers &b, int M, int K, const w4a4_weight &w) {
     a.q = b.q; a.scale = b.scale;
     a.zero = w.mode == W4A4_ASYM ? b.zero : nullptr;
     a.gsum = w.mode == W4A4_ASYM ? b.gsum : nullptr;
-    a.M = M; a.K = K; a.lda = K / 2; a.group = w.group; a.mode = w.mode; a.layout = w.layout;
+    a.M = M; a.K = K; a.lda = w.layout == W4A4_LAYOUT_FP6 ? K / 4 * 3 : K / 2; a.group = w.group; a.mode = w.mode; a.layout = w.layout;
     a.osum = w.layout == W4A4_LAYOUT_MFMA ? b.osum : nullptr;
     a.ldo = 1;
     return a;
@@ -68,9 +72,7 @@ size_t part_bytes(int M, const w4a4_part &p) {
 }
 
 bool part_ok(const w4a4_part *p) {
-    // (the workspaces carved here hold nibble-packed activations: weights in the FP6 operand layout are not taken)
-    return p && p->w4.N > 0 && p->w4.K > 0 && p->w4.K % 32 == 0 && p->w4.layout != W4A4_LAYOUT_FP6 &&
-           (p->act == W4A4_ACT_NONE || p->act == W4A4_ACT_GELU);
+    return p && p->w4.N > 0 && p->w4.K > 0 && p->w4.K % 32 == 0 && (p->act == W4A4_ACT_NONE || p->act == W4A4_ACT_GELU);
 }
 
 // one launch for small token counts: symmetric per-channel weights in the canonical layout
@@ -154,6 +156,9 @@ struct LayerPlan {
 bool layer_ok(const w4a4_encoder_layer_weights *L) {
     if (!L || L->hidden <= 0 || L->heads <= 0 || L->ffn <= 0 || L->hidden != L->heads * 64) return false;
     if (!part_ok(&L->qkv) || !part_ok(&L->attn_out) || !part_ok(&L->ffn1) || !part_ok(&L->ffn2)) return false;
+    // (the layer's LayerNorm producer writes nibble layouts: weights in the FP6 operand layout are not taken here)
+    for (const w4a4_part *q : {&L->qkv, &L->attn_out, &L->ffn1, &L->ffn2})
+        if (q->w4.layout == W4A4_LAYOUT_FP6) return false;
     const int h = L->hidden, f = L->ffn;
     return L->qkv.w4.N == 3 * h && L->qkv.w4.K == h && L->attn_out.w4.N == h && L->attn_out.w4.K == h &&
            L->ffn1.w4.N == f && L->ffn1.w4.K == h && L->ffn2.w4.N == h && L->ffn2.w4.K == f &&
@@ -290,6 +295,8 @@ extern "C" int w4a4_ffn(const void *X_f16, int M, int ldx, const w4a4_part *ffn1
     const bool fused = (strategy & W4A4_STRATEGY_FUSED_FFN) != 0;
     if (fused && !(i1 && i2)) return W4A4_ERR_INVALID_ARG;
     if (fused && ffn2->w4.mode != W4A4_SYM) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    // the FP6 kernel alone writes FP6 codes: a fused pair is in that layout on both sides or on neither
+    if (fused && (ffn1->w4.layout == W4A4_LAYOUT_FP6) != (ffn2->w4.layout == W4A4_LAYOUT_FP6)) return W4A4_ERR_UNSUPPORTED_SHAPE;
     if (M == 0) return W4A4_OK;
     if (!X_f16 || !out_f16) return W4A4_ERR_INVALID_ARG;
     if (!workspace || workspace_bytes < w4a4_ffn_workspace_bytes(M, ffn1, ffn2) ||

@@ -203,3 +203,25 @@ def test_ffn_at_full_size_on_sampled_rows(B, orc, strategy):
     rt = torch.from_numpy(rows).cuda()
     want = orc.ffn(host(X[rt]), host(W1), host(b1), 0, host(W2), host(b2), strategy)
     _pair_equal(host(got[rt]), want, exact=False)
+
+
+def test_parts_in_the_fp6_layout(B, orc):
+    """Weights in the FP6 operand layout through the per-part calls: a part equals quantize_act + w4a4_linear bit for bit
+    and the oracle's part; the fused FFN pair (FFN1 requantizes into FFN2's FP6 operand in its epilogue) equals the oracle's
+    fused pair bit for bit without GELU; a pair with only one side in the layout is refused; so is the whole layer."""
+    M, h, f = 700, 512, 1024
+    X, W1, b1, W2, b2 = _ffn_inputs(21, M, h, f)
+    P1 = B.Part(dev(W1), M, dev(b1), 0, layout=B.LAYOUT_FP6)
+    P2 = B.Part(dev(W2), M, dev(b2), 0, layout=B.LAYOUT_FP6)
+    got = B.part_linear(dev(X), P1, True)
+    A = B.quantize_act(dev(X), B.SYM, layout=B.LAYOUT_FP6)
+    assert torch.equal(got, B.linear(A, P1.w4, dev(b1), 0))
+    assert np.array_equal(host(got).view(np.uint16), orc.part_linear(X, W1, True, b1, 0).view(np.uint16))
+    pair = host(B.ffn(dev(X), P1, P2, 12))                      # both parts in INT4, an fp16 tensor between them
+    assert np.array_equal(pair.view(np.uint16), orc.ffn(X, W1, b1, 0, W2, b2, 12).view(np.uint16))
+    fused = host(B.ffn(dev(X), P1, P2, 28))                     # the codes handed over in FFN1's epilogue
+    assert np.array_equal(fused.view(np.uint16), orc.ffn(X, W1, b1, 0, W2, b2, 28).view(np.uint16))
+    assert B.fused_fault_check() is False
+    Pm = B.Part(dev(W2), M, dev(b2), 0, layout=B.LAYOUT_MFMA)
+    with pytest.raises(RuntimeError):
+        B.ffn(dev(X), P1, Pm, 28)
