@@ -104,9 +104,9 @@ typedef enum { W4A4_SYM = 0, W4A4_ASYM = 1 } w4a4_mode;
  * w4a4_quantize_act, w4a4_quantize_weight, w4a4_gemm_i32 and w4a4_linear understand it (any epilogue: a
  * requantized output in the FP6 layout is written by the GEMM kernel itself, as the next layer's operand - one
  * range per token, N % 256 == 0, N / 256 column tiles co-resident, else UNSUPPORTED_SHAPE -, one in the
- * canonical or the MFMA layout goes through the fp32 rows of the workspace), and so do w4a4_part_linear and
- * w4a4_ffn (a fused FFN pair with both parts in it); w4a4_layernorm_quantize, w4a4_linear_f16act and
- * w4a4_encoder_layer do not.  Padding rows of a matrix written by the GEMM kernel hold zeros of either sign
+ * canonical or the MFMA layout goes through the fp32 rows of the workspace), and so do w4a4_layernorm_quantize,
+ * w4a4_part_linear, w4a4_ffn (a fused FFN pair with both parts in it) and w4a4_encoder_layer; the one-launch
+ * small-token call w4a4_linear_f16act does not.  Padding rows of a matrix written by the GEMM kernel hold zeros of either sign
  * (the sign bit of a field may be set). */
 typedef enum { W4A4_LAYOUT_CANONICAL = 0, W4A4_LAYOUT_MFMA = 1, W4A4_LAYOUT_FP6 = 2 } w4a4_layout;
 
@@ -463,8 +463,10 @@ int w4a4_linear_static(const w4a4_act *A, const w4a4_weight *W, const w4a4_epilo
  *   X_f16, R_f16  [M, ldx] fp16 (device; R_f16 may be NULL; 16-byte aligned, ldx*2 % 16 == 0)
  *   gamma_f16, beta_f16  [K] fp16 (device, 16-byte aligned)
  *   Y_f16  [M, K] fp16 or NULL
- *   K % 32 == 0, K <= 4096; groups as for w4a4_quantize_act.  The MFMA operand layout is produced for
- *   symmetric codes only (mode == W4A4_ASYM with layout == W4A4_LAYOUT_MFMA returns W4A4_ERR_INVALID_ARG). */
+ *   K % 32 == 0, K <= 4096; groups as for w4a4_quantize_act.  The MFMA and the FP6 operand layouts are
+ *   produced for symmetric codes and one range per token only (mode == W4A4_ASYM with either returns
+ *   W4A4_ERR_INVALID_ARG); the FP6 layout takes the row lengths w4a4_quantize_act takes in it, no gsum,
+ *   and q of ceil(M/64)*64 * 3K/4 bytes, all of them written. */
 int w4a4_layernorm_quantize(const void *X_f16, const void *R_f16, int M, int K, int ldx,
                             const void *gamma_f16, const void *beta_f16, float eps, void *Y_f16,
                             int mode, int group, uint8_t *q, float *scale, float *zero, int32_t *gsum,

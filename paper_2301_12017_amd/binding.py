@@ -704,11 +704,12 @@ def attention(QKV: torch.Tensor, batch: int, seq: int, heads: int, out=None) -> 
 class EncoderLayer:
     """The weights of one encoder layer (w4a4_encoder_layer_weights) and a workspace for `batch` x `seq` tokens."""
 
-    def __init__(self, batch, seq, heads, Wqkv, bqkv, Wao, bao, W1, b1, W2, b2, g1, be1, g2, be2, eps=1e-12):
+    def __init__(self, batch, seq, heads, Wqkv, bqkv, Wao, bao, W1, b1, W2, b2, g1, be1, g2, be2, eps=1e-12,
+                 layout: Optional[int] = None):
         M = batch * seq
         self.batch, self.seq, self.heads, self.hidden, self.ffn = batch, seq, heads, Wao.shape[0], W1.shape[0]
-        self.qkv, self.attn_out = Part(Wqkv, M, bqkv), Part(Wao, M, bao)
-        self.ffn1, self.ffn2 = Part(W1, M, b1, ACT_GELU), Part(W2, M, b2)
+        self.qkv, self.attn_out = Part(Wqkv, M, bqkv, layout=layout), Part(Wao, M, bao, layout=layout)
+        self.ffn1, self.ffn2 = Part(W1, M, b1, ACT_GELU, layout=layout), Part(W2, M, b2, layout=layout)
         self.ln = (g1, be1, g2, be2)
         self.c = _LayerWeights(self.hidden, heads, self.ffn, self.qkv.c(), self.attn_out.c(), self.ffn1.c(), self.ffn2.c(),
                                _ptr(g1), _ptr(be1), _ptr(g2), _ptr(be2), eps)

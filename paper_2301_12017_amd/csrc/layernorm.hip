@@ -13,7 +13,8 @@
 //
 // One wavefront owns one token: 16-byte loads, the row stays in registers (K <= 4096: eight
 // chunks of eight elements per lane), sums and ranges are reduced with wave shuffles, codes
-// leave as one dword per lane and step.
+// leave as one dword per lane and step (FP6 operand layout: the four lanes of a quad hold one
+// operand of 32 codes, of which three store eight bytes each).
 #include "common.hpp"
 
 namespace w4a4 {
@@ -47,13 +48,40 @@ __device__ __forceinline__ void halves8(const uint4 &raw, float (&v)[8]) {
     }
 }
 
-// LAYOUT: 0 canonical nibbles, 1 the MFMA operand layout of activations (symmetric codes only)
+// One lane's eight codes of chunk c of a row (fields 8 (c % 4) .. + 7 of operand c / 4) as 48 bits {lo, hi16}, and the
+// next lane's: the four lanes of a quad hold one operand of 24 bytes, of which lanes 0, 1 and 2 store bytes 0 .. 7,
+// 8 .. 15 (the operand's sixteen-byte part) and 16 .. 23 (its eight-byte part).  See w4a4_layout for the addresses.
+__device__ __forceinline__ void fp6_store_chunk(uint8_t *q, int K, long row, int c, uint32_t lo, uint32_t hi,
+                                                uint32_t nlo, uint32_t nhi) {
+    const int j = c & 3, o = c >> 2, b = o >> 1, e = o & 1;
+    if (j == 3) return;
+    // bytes 8j .. 8j+7 of the quad's 24: own bytes 2j .. 5, then the next lane's 0 .. 2j+1
+    uint32_t w0, w1;
+    if (j == 0) { w0 = lo; w1 = (hi & 0xFFFFu) | (nlo << 16); }
+    else if (j == 1) { w0 = (lo >> 16) | (hi << 16); w1 = nlo; }
+    else { w0 = (hi & 0xFFFFu) | (nlo << 16); w1 = (nlo >> 16) | (nhi << 16); }
+    const long r = row & 63;
+    uint8_t *blk = q + ((row >> 6) * (long)(K / 64) + b) * 3072 + r * 48;
+    uint8_t *dst = j < 2 ? blk + 16 * e + 8 * j : blk + 32 + 8 * (e ^ (int)((r >> 4) & 1));
+    *reinterpret_cast<uint2 *>(dst) = make_uint2(w0, w1);
+}
+
+// LAYOUT: 0 canonical nibbles, 1 the MFMA operand layout of activations, 2 the FP6 operand layout (both: symmetric codes only)
 template <int MODE, int ITERS, int LAYOUT>
 __global__ __launch_bounds__(kLnRowsPerBlock *kWave) void layernorm_quantize_kernel(LnArgs a) {
     const int lane = threadIdx.x % kWave;
     const long row = (long)blockIdx.x * kLnRowsPerBlock + threadIdx.x / kWave;
-    if (row >= a.M) return;                                     // whole wave leaves; no block barrier below
     const int K = a.K, nchunks = K / 8;
+    if (row >= a.M) {                                           // whole wave leaves; no block barrier below
+        if constexpr (LAYOUT == 2) {                            // the layout stores whole 64-token panels: zero rows behind M
+            if (row < (((long)a.M + 63) & ~63L)) {
+#pragma unroll
+                for (int it = 0; it < ITERS; ++it)
+                    if (lane + it * kWave < nchunks) fp6_store_chunk(a.q, K, row, lane + it * kWave, 0u, 0u, 0u, 0u);
+            }
+        }
+        return;
+    }
     const __half *xr = a.X + row * a.ldx;
     const __half *rr = a.R ? a.R + row * a.ldx : nullptr;
 
@@ -132,6 +160,34 @@ __global__ __launch_bounds__(kLnRowsPerBlock *kWave) void layernorm_quantize_ker
     // ---- codes: rne(t) is the low mantissa of t + 1.5*2^23 (the clamp of the mapping cannot bind);
     //      symmetric codes in offset binary (+8 rides in the constant) so that nibble sums are byte sums,
     //      one XOR per dword then gives the layout wanted -------------------------------------------------
+    if constexpr (LAYOUT == 2) {
+        // t = rne(y * 7/absmax) is an integer of magnitude <= 7; the FP8 E4M3 encoding of t / 64, which the pack
+        // conversion produces two at a time (the division is its scale operand), is `sign 0 0 e e m m m` with the
+        // exponent and mantissa bits of t's FP6 E2M3 encoding: a field is that byte without its two zero bits
+        typedef short v2s __attribute__((ext_vector_type(2)));
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int c = lane + it * kWave;
+            uint32_t f24[2];
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                float t[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t[e] = __builtin_rintf(v[it][4 * p + e] * r.inv);
+                v2s pk = {0, 0};
+                pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, t[0], t[1], 64.0f, false);
+                pk = __builtin_amdgcn_cvt_scalef32_pk_fp8_f32(pk, t[2], t[3], 64.0f, true);
+                const uint32_t b4 = __builtin_bit_cast(uint32_t, pk);
+                const uint32_t f4 = (b4 & 0x1F1F1F1Fu) | ((b4 >> 2) & 0x20202020u);   // four 6-bit fields, one per byte
+                const uint32_t p2 = (f4 & 0x003F003Fu) | ((f4 >> 2) & 0x0FC00FC0u);   // two 12-bit pairs, one per half
+                f24[p] = (p2 & 0x00000FFFu) | ((p2 >> 4) & 0x00FFF000u);              // 24 bits
+            }
+            const uint32_t lo = f24[0] | (f24[1] << 24), hi = f24[1] >> 8;            // 48 bits
+            const uint32_t nlo = dpp_fetch<0xF9>(lo), nhi = dpp_fetch<0xF9>(hi);      // quad permute [1,2,3,3]: the next lane's
+            if (c < nchunks) fp6_store_chunk(a.q, K, row, c, lo, hi, nlo, nhi);
+        }
+        return;
+    }
     constexpr float kMagic = MODE == W4A4_SYM ? 12582920.0f : 12582912.0f;
     constexpr uint32_t kFlip = MODE == W4A4_ASYM ? 0u : LAYOUT == 0 ? 0x88888888u : 0x80808080u;
     uint32_t *qr = reinterpret_cast<uint32_t *>(a.q + row * (long)(K / 2));
@@ -176,7 +232,8 @@ __global__ __launch_bounds__(kLnRowsPerBlock *kWave) void layernorm_quantize_ker
 template <int MODE, int LAYOUT>
 static int launch_ln(const LnArgs &a, hipStream_t st) {
     const int iters = (a.K / 8 + kWave - 1) / kWave;
-    dim3 grid((unsigned)((a.M + kLnRowsPerBlock - 1) / kLnRowsPerBlock)), block(kLnRowsPerBlock * kWave);
+    const long rows = LAYOUT == 2 ? (((long)a.M + 63) & ~63L) : a.M;     // (FP6: the zero rows that fill the last panel too)
+    dim3 grid((unsigned)((rows + kLnRowsPerBlock - 1) / kLnRowsPerBlock)), block(kLnRowsPerBlock * kWave);
 #define W4A4_LN(I) hipLaunchKernelGGL((layernorm_quantize_kernel<MODE, I, LAYOUT>), grid, block, 0, st, a)
     if (iters <= 1) W4A4_LN(1);
     else if (iters <= 2) W4A4_LN(2);
@@ -197,15 +254,20 @@ extern "C" int w4a4_layernorm_quantize(const void *X_f16, const void *R_f16, int
                                        int layout, int32_t *osum, void *stream) {
     if (M < 0 || K <= 0 || ldx < K || group < 0 || !(eps >= 0.0f)) return W4A4_ERR_INVALID_ARG;
     if (mode != W4A4_SYM && mode != W4A4_ASYM) return W4A4_ERR_INVALID_ARG;
-    if (layout != W4A4_LAYOUT_CANONICAL && layout != W4A4_LAYOUT_MFMA) return W4A4_ERR_INVALID_ARG;
-    if (layout == W4A4_LAYOUT_MFMA && mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+    if (layout != W4A4_LAYOUT_CANONICAL && layout != W4A4_LAYOUT_MFMA && layout != W4A4_LAYOUT_FP6) return W4A4_ERR_INVALID_ARG;
+    if (layout != W4A4_LAYOUT_CANONICAL && mode != W4A4_SYM) return W4A4_ERR_INVALID_ARG;
+    if (layout == W4A4_LAYOUT_FP6 && gsum) return W4A4_ERR_INVALID_ARG;        // no code sums travel with that layout
     if (M > 0 && (!X_f16 || !gamma_f16 || !beta_f16 || !q || !scale || (mode == W4A4_ASYM && !zero) ||
                   (layout == W4A4_LAYOUT_MFMA && !osum)))
         return W4A4_ERR_INVALID_ARG;
     if (K % 32 || K > 4096 || (ldx * 2) % 16) return W4A4_ERR_UNSUPPORTED_SHAPE;
     const int G = group == 0 ? K : group;
     if (G % 32 || K % G) return W4A4_ERR_UNSUPPORTED_SHAPE;
-    if (layout == W4A4_LAYOUT_MFMA && G != K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (layout != W4A4_LAYOUT_CANONICAL && G != K) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    if (layout == W4A4_LAYOUT_FP6) {                            // a row length the layout is offered for
+        int lpr = 0, opl = 0;
+        if (!fp6_plan(K, &lpr, &opl)) return W4A4_ERR_UNSUPPORTED_SHAPE;
+    }
     const int ng = K / G, cpg = G / 8;
     if (gsum && ng > 1 && (cpg > 64 || (cpg & (cpg - 1)))) return W4A4_ERR_UNSUPPORTED_SHAPE;   // segmented wave sums
     if (M == 0) return W4A4_OK;
@@ -220,5 +282,6 @@ extern "C" int w4a4_layernorm_quantize(const void *X_f16, const void *R_f16, int
     a.M = M; a.K = K;
     hipStream_t st = as_stream(stream);
     if (layout == W4A4_LAYOUT_MFMA) return launch_ln<W4A4_SYM, 1>(a, st);
+    if (layout == W4A4_LAYOUT_FP6) return launch_ln<W4A4_SYM, 2>(a, st);
     return mode == W4A4_SYM ? launch_ln<W4A4_SYM, 0>(a, st) : launch_ln<W4A4_ASYM, 0>(a, st);
 }

@@ -156,9 +156,6 @@ struct LayerPlan {
 bool layer_ok(const w4a4_encoder_layer_weights *L) {
     if (!L || L->hidden <= 0 || L->heads <= 0 || L->ffn <= 0 || L->hidden != L->heads * 64) return false;
     if (!part_ok(&L->qkv) || !part_ok(&L->attn_out) || !part_ok(&L->ffn1) || !part_ok(&L->ffn2)) return false;
-    // (the layer's LayerNorm producer writes nibble layouts: weights in the FP6 operand layout are not taken here)
-    for (const w4a4_part *q : {&L->qkv, &L->attn_out, &L->ffn1, &L->ffn2})
-        if (q->w4.layout == W4A4_LAYOUT_FP6) return false;
     const int h = L->hidden, f = L->ffn;
     return L->qkv.w4.N == 3 * h && L->qkv.w4.K == h && L->attn_out.w4.N == h && L->attn_out.w4.K == h &&
            L->ffn1.w4.N == f && L->ffn1.w4.K == h && L->ffn2.w4.N == h && L->ffn2.w4.K == f &&

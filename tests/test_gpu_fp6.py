@@ -324,9 +324,6 @@ def test_calls_that_do_not_take_the_layout_refuse_it(B):
     W = _w(rng, 768, 768)
     Q = B.quantize_weight(dev(W), SYM, 0, layout=FP6)
     X = dev(_x(rng, 64, 768))
-    with pytest.raises(RuntimeError):                          # LayerNorm + quantize writes nibble layouts only
-        B.layernorm_quantize(X, None, torch.ones(768, dtype=torch.float16, device="cuda"),
-                             torch.zeros(768, dtype=torch.float16, device="cuda"), 1e-5, SYM, 0, layout=FP6)
     with pytest.raises(RuntimeError):                          # one-launch small-token kernel: canonical weights only
         B.linear_f16act(X, Q, None, 0)
 
@@ -361,3 +358,26 @@ def test_headline_workload_at_full_size(B, orc):
         assert_f16(host(Y)[rows], want, GELU_SAME if spec.gelu else 1.0, spec.name)
         del Y, A, layer
         torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("M,K,res", [(1, 256, False), (77, 768, True), (300, 1024, True), (130, 4096, False)])
+def test_layernorm_quantize_into_the_fp6_layout(B, orc, M, K, res):
+    """The fused producer writing the FP6 operand directly: the same codes, scales and fp16 copy as the call that writes
+    canonical nibbles (one kernel, one arithmetic: bit for bit), which tests/test_gpu_layernorm.py holds against the oracle;
+    and the result feeds the FP6 GEMM."""
+    rng = np.random.default_rng(M + K)
+    x = (rng.standard_normal((M, K)) * 1.7).astype(np.float32).astype(np.float16)
+    r = rng.standard_normal((M, K)).astype(np.float16) if res else None
+    g = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float16)
+    b = (0.1 * rng.standard_normal(K)).astype(np.float16)
+    args = (dev(x), None if r is None else dev(r), dev(g), dev(b), 1e-5)
+    A6, y6 = B.layernorm_quantize(*args, SYM, 0, layout=FP6)
+    A0, y0 = B.layernorm_quantize(*args, SYM, 0, layout=0)
+    assert torch.equal(y6, y0) and torch.equal(A6.scale, A0.scale)
+    assert np.array_equal(fp6_to_codes(host(A6.q), K, M), orc.unpack(host(A0.q), 0).reshape(M, K))
+    if K >= 512:
+        W = _w(rng, 264, K)
+        Q6, Q0 = B.quantize_weight(dev(W), SYM, 0, layout=FP6), B.quantize_weight(dev(W), SYM, 0)
+        assert torch.equal(B.gemm_i32(A6, Q6), B.gemm_i32(A0, Q0))
+    with pytest.raises(RuntimeError):                          # unsigned codes do not exist in this layout
+        B.layernorm_quantize(*args, 1, 0, layout=FP6)

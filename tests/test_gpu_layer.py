@@ -38,7 +38,7 @@ def test_attention_of_peaked_scores_does_not_overflow(B, orc):
     np.testing.assert_allclose(got, want, rtol=3e-3, atol=3e-2)
 
 
-def _layer(B, seed, batch, seq, heads, h, f):
+def _layer(B, seed, batch, seq, heads, h, f, layout=None):
     rng = np.random.default_rng(seed)
     n = lambda *s, std=1.0: (rng.standard_normal(s) * std).astype(np.float16)
     t = dict(X=n(batch * seq, h), Wqkv=n(3 * h, h, std=0.05), bqkv=n(3 * h, std=0.02), Wao=n(h, h, std=0.05),
@@ -47,7 +47,7 @@ def _layer(B, seed, batch, seq, heads, h, f):
              g2=(1 + 0.1 * rng.standard_normal(h)).astype(np.float16), be2=n(h, std=0.1))
     d = {k: dev(v) for k, v in t.items()}
     L = B.EncoderLayer(batch, seq, heads, d["Wqkv"], d["bqkv"], d["Wao"], d["bao"], d["W1"], d["b1"], d["W2"], d["b2"],
-                       d["g1"], d["be1"], d["g2"], d["be2"], 1e-12)
+                       d["g1"], d["be1"], d["g2"], d["be2"], 1e-12, layout=layout)
     return t, d, L
 
 
@@ -129,3 +129,18 @@ def test_layer_replays_from_a_graph(B):
             torch.cuda.synchronize()
             assert torch.equal(out, eager), (strategy, rep)
             assert torch.isfinite(other.float()).all()
+
+
+@pytest.mark.parametrize("shape", [(1, 128, 12, 768, 3072), (5, 100, 8, 512, 1024)])
+@pytest.mark.parametrize("strategy", STRATEGIES)
+def test_layer_with_weights_in_the_fp6_layout(B, shape, strategy):
+    """Every INT4 part on the FP6 matrix instruction (LayerNorm writes the FP6 operand, the fused FFN pair hands FP6 codes
+    over): the layer equals the entry points it is made of, and - the FP6 kernels and the canonical-layout kernels both
+    follow the definition's operation order - the same layer with canonical weights, bit for bit."""
+    batch, seq, heads, h, f = shape
+    t, d, L6 = _layer(B, sum(shape), batch, seq, heads, h, f, layout=B.LAYOUT_FP6)
+    got = L6(d["X"], strategy)
+    assert torch.equal(got, _blocks(B, L6, d, strategy))
+    _, _, L0 = _layer(B, sum(shape), batch, seq, heads, h, f, layout=B.LAYOUT_CANONICAL)
+    assert torch.equal(got, L0(d["X"], strategy))
+    assert B.fused_fault_check() is False
