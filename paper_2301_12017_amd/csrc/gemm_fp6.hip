@@ -106,7 +106,8 @@ __device__ __forceinline__ void fp6_epilogue(const GemmArgs &g, v16f (&acc)[FM][
 // bind) and exactly an FP6 E2M3 number, so the hardware conversion of 32 fp32 values to 32 packed fields serves here
 // as in the token-wise quantizer: two conversions per 32 x 32 block of a lane's four channels, from whose results a
 // row's 24 bits are cut.  A lane's four adjacent channels are those 24 bits; the lanes of a quad own twelve
-// consecutive bytes of an operand, which three of them store as one dword each.  No code sums travel with this layout.
+// consecutive bytes of an operand, which three of them assemble as one dword each; the dwords of eight rows meet in
+// LDS and leave as sixteen-byte stores.  No code sums travel with this layout.
 template <int FM, int FN>
 __device__ __forceinline__ void fp6_epilogue_requant(const GemmArgs &g, v16f (&acc)[FM][FN], const ChanParams6<FN> &cp,
                                                      int n_lane, int m0, int row_w, int lane, int tid, int panel,
